@@ -1,0 +1,372 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests re-types the oracle's own formulas: each compares it with
+a hand-computed fixture, a closed form, a library routine, brute force on tiny
+inputs, or an invariant.
+"""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import crystal_kv as ok
+from paper_2601_16986_amd import workloads as wl
+
+
+# ------------------------------------------------------------------ attention
+def test_attention_equals_library_sdpa_when_nothing_is_evicted():
+    """Sec. 2.2: with a budget above the token count the path is ordinary softmax
+    attention over all tokens; torch's SDPA (float64, KV heads repeated for GQA)
+    is the library routine."""
+    import torch
+    import torch.nn.functional as F
+    cfg = wl.scaled(wl.CONFIGS["tiny"], prompt=9, decode_steps=7, budget=1000, budget_min=1, budget_max=1000)
+    st = wl.make_stream(cfg, tiny_heavy=False)
+    o = ok.CrystalKVOracle(1, 1, 8, 2, 128, np.full((1, 1, 2), 1000), lam=0.5, top_p=0.9, t0=9)
+    o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    for s in range(7):
+        out, _ = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        K = np.concatenate([st.prompt_k[0, 0], np.moveaxis(st.k_new[:s + 1, 0, 0], 0, 1)], axis=1)  # [Hkv][n][d]
+        V = np.concatenate([st.prompt_v[0, 0], np.moveaxis(st.v_new[:s + 1, 0, 0], 0, 1)], axis=1)
+        Kt = torch.from_numpy(K.astype(np.float64)).repeat_interleave(4, dim=0)[None]      # [1][Hq][n][d]
+        Vt = torch.from_numpy(V.astype(np.float64)).repeat_interleave(4, dim=0)[None]
+        qt = torch.from_numpy(st.q[s, 0, 0].astype(np.float64))[None, :, None, :]          # [1][Hq][1][d]
+        ref = F.scaled_dot_product_attention(qt, Kt, Vt, scale=o.scale)[0, :, 0, :].numpy()
+        assert np.allclose(out[0, 0], ref, rtol=1e-12, atol=1e-13)
+    assert o.lengths()[0, 0, 0] == 9 + 7
+
+
+def test_softmax_rows_sum_to_one_and_slot_order_is_irrelevant():
+    g = np.random.default_rng(1)
+    q, K, V = g.standard_normal((5, 128)), g.standard_normal((300, 128)), g.standard_normal((300, 128))
+    y, a = ok.attention(q, K, V, 0.0884)
+    assert np.all(np.abs(a.sum(axis=1) - 1.0) < 1e-12)
+    assert np.all(a >= 0)
+    perm = g.permutation(300)
+    y2, a2 = ok.attention(q, K[perm], V[perm], 0.0884)
+    assert np.allclose(y, y2, rtol=1e-12, atol=1e-14)
+    assert np.allclose(a[:, perm], a2, rtol=1e-12, atol=1e-300)
+
+
+def test_attention_single_entry_returns_its_value():
+    q, K, V = np.ones((3, 4)), np.array([[1.0, 2, 3, 4]]), np.array([[9.0, 8, 7, 6]])
+    y, a = ok.attention(q, K, V, 0.5)
+    assert np.array_equal(a, np.ones((3, 1)))
+    assert np.array_equal(y, np.tile(V, (3, 1)))
+
+
+def test_attention_two_entries_closed_form():
+    # logits 0 and ln 3 -> weights 1/4 and 3/4
+    q = np.array([[1.0, 0.0]])
+    K = np.array([[0.0, 5.0], [math.log(3.0), -2.0]])
+    V = np.array([[4.0, 0.0], [0.0, 8.0]])
+    y, a = ok.attention(q, K, V, 1.0)
+    assert np.allclose(a, [[0.25, 0.75]], rtol=1e-15)
+    assert np.allclose(y, [[1.0, 6.0]], rtol=1e-15)
+
+
+# -------------------------------------------------------------------- top-p
+def brute_force_nucleus(abar, pos, p):
+    """Smallest prefix of the (weight desc, pos asc) order whose sum exceeds p,
+    found by trying every subset size and every subset (tiny n only)."""
+    n = len(abar)
+    best = None
+    for size in range(1, n + 1):
+        cands = [s for s in itertools.combinations(range(n), size) if sum(abar[i] for i in s) > p]
+        if cands:
+            # among subsets of minimal size take the one the ordering prefers:
+            # largest weights first, lower position on equal weight
+            key = lambda s: sorted((-abar[i], pos[i]) for i in s)
+            best = min(cands, key=key)
+            break
+    return set(range(n)) if best is None else set(best)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_hit_mask_matches_subset_brute_force(seed):
+    g = np.random.default_rng(seed)
+    n = int(g.integers(1, 10))
+    abar = g.random(n) ** 3
+    if seed % 3 == 0 and n > 2:            # force exact ties
+        abar[1] = abar[0]
+    abar = abar / abar.sum()
+    pos = g.permutation(50)[:n]
+    p = float(g.choice([0.3, 0.5, 0.6, 0.9, 0.99]))
+    d = ok.hit_mask(abar, pos, p)
+    assert set(np.nonzero(d.hit)[0]) == brute_force_nucleus(list(abar), list(pos), p)
+
+
+def test_hit_mask_minimality_and_limits():
+    g = np.random.default_rng(7)
+    abar = g.random(500) ** 4
+    abar /= abar.sum()
+    pos = np.arange(500)
+    for p in (0.5, 0.9):
+        d = ok.hit_mask(abar, pos, p)
+        s = abar[d.hit].sum()
+        assert s > p
+        assert s - abar[d.hit].min() <= p          # dropping the smallest hit falls to <= p
+        assert abar[d.hit].min() >= abar[~d.hit].max()
+    # p -> 0+: only the arg-max (plus the new entry); p >= 1: everything
+    d = ok.hit_mask(abar, pos, 1e-12, new_index=499)
+    assert set(np.nonzero(d.hit)[0]) == {int(np.argmax(abar)), 499}
+    assert ok.hit_mask(abar, pos, 1.0).hit.all()
+    assert ok.hit_mask(abar, pos, 1.5).hit.all()
+
+
+def test_hit_mask_strict_threshold_and_position_tie_break():
+    # cumulative weight equal to p does not "exceed" it
+    d = ok.hit_mask(np.array([0.5, 0.25, 0.25]), np.array([0, 1, 2]), 0.5)
+    assert d.hit.tolist() == [True, True, False]
+    # equal weights: the lower position comes first whatever the slot order
+    d = ok.hit_mask(np.array([0.25, 0.5, 0.25]), np.array([9, 5, 3]), 0.5)
+    assert d.hit.tolist() == [False, True, True]
+
+
+# ---------------------------------------------------------------------- CRF
+@pytest.mark.parametrize("lam", [0.0, 0.3, 0.5, 0.7, 0.95, 1.0])
+def test_incremental_crf_equals_closed_form_from_hit_history(lam):
+    """Sec. 5.2: the incremental rule must reproduce CRF = sum_j lambda^(t - t_j)."""
+    g = np.random.default_rng(11)
+    n, T = 40, 120
+    tab = ok.decay_table(lam)
+    crf = np.zeros(n, np.float32)
+    birth = g.integers(0, 20, size=n)
+    tau = birth.copy()
+    history = [[] for _ in range(n)]
+    for t in range(T):
+        alive = birth <= t
+        hit = (g.random(n) < 0.15) & alive
+        hit |= birth == t                         # arrival is a reference
+        for i in np.nonzero(hit)[0]:
+            history[i].append(t)
+        tmp, crf2, tau2 = ok.crf_update(np.where(alive, crf, 0), np.where(alive, tau, t), t,
+                                        hit.astype(np.float32), hit, tab)
+        crf = np.where(alive, crf2, crf).astype(np.float32)
+        tau = np.where(alive, tau2, tau)
+        for i in np.nonzero(alive)[0]:
+            ref = ok.crf_closed_form(history[i], t, lam)
+            assert abs(float(tmp[i]) - ref) <= 1e-5 * max(ref, 1e-30) + 1e-37
+        if lam < 1.0:
+            assert float(tmp.max()) <= 1.0 / (1.0 - lam) * (1 + 1e-5)
+        assert float(tmp.min()) >= 0.0
+
+
+def test_unaccessed_entry_decays_geometrically():
+    tab = ok.decay_table(0.7)
+    for dt in (0, 1, 5, 40):
+        tmp, crf, tau = ok.crf_update(np.array([2.5], np.float32), np.array([10]), 10 + dt,
+                                      np.zeros(1, np.float32), np.zeros(1, bool), tab)
+        assert tmp[0] == pytest.approx(2.5 * float(np.float32(0.7)) ** dt, rel=2e-7)
+        assert crf[0] == np.float32(2.5) and tau[0] == 10       # a miss records nothing
+
+
+def test_lambda_one_is_lfu_and_lambda_zero_is_lru():
+    """Sec. 5.2: lambda = 1 counts hits exactly; lambda = 0 scores only the current hits."""
+    g = np.random.default_rng(5)
+    n, T = 30, 200
+    for lam in (1.0, 0.0):
+        tab = ok.decay_table(lam)
+        crf, tau = np.zeros(n, np.float32), np.zeros(n, np.int64)
+        count = np.zeros(n, np.int64)
+        for t in range(T):
+            hit = g.random(n) < 0.3
+            count += hit
+            tmp, crf, tau = ok.crf_update(crf, tau, t, hit.astype(np.float32), hit, tab)
+            if lam == 1.0:
+                assert np.array_equal(tmp, count.astype(np.float32))
+            else:
+                assert np.array_equal(tmp, hit.astype(np.float32))
+        if lam == 1.0:
+            # eviction with lambda = 1 drops the least frequently hit entries
+            retain, evicted = ok.evict_select(tmp, np.arange(n), 20)
+            assert count[evicted].max() <= count[retain].min()
+
+
+def test_decay_table_shape():
+    t = ok.decay_table(0.5)
+    assert t[0] == 1 and t[1] == 0.5 and t[126] == np.float32(2.0 ** -126) and t[-1] == 0 and len(t) == 128
+    assert ok.decay_table(1.0).tolist() == [1.0]
+    assert ok.decay_table(0.0).tolist() == [1.0, 0.0]
+    t = ok.decay_table(0.9)
+    assert np.all(np.diff(t) < 0) and t[-1] == 0 and t[-2] >= ok.FLT_MIN
+
+
+# ----------------------------------------------------------------- eviction
+@pytest.mark.parametrize("seed", range(10))
+def test_evict_select_against_full_sort(seed):
+    g = np.random.default_rng(100 + seed)
+    n = int(g.integers(2, 12))
+    B = int(g.integers(1, n))
+    tmp = g.choice([0.0, 0.25, 0.5, 1.0, 1.5], size=n).astype(np.float32)     # many ties
+    pos = g.permutation(100)[:n]
+    retain, evicted = ok.evict_select(tmp, pos, B)
+    assert len(retain) == B and len(evicted) == n - B
+    # brute force: every evicted key must not beat any kept key under (score, -position)
+    for i in retain:
+        for j in evicted:
+            assert (tmp[i], -pos[i]) > (tmp[j], -pos[j])
+    # python's own sort as the textbook routine
+    ranked = sorted(range(n), key=lambda i: (-float(tmp[i]), int(pos[i])))
+    assert sorted(ranked[:B]) == retain.tolist()
+
+
+def test_evict_tie_keeps_lower_position_and_noop_within_budget():
+    retain, evicted = ok.evict_select(np.array([1, 1, 1], np.float32), np.array([7, 3, 5]), 2)
+    assert retain.tolist() == [1, 2] and evicted.tolist() == [0]
+    retain, evicted = ok.evict_select(np.array([1, 2], np.float32), np.array([0, 1]), 2)
+    assert retain.tolist() == [0, 1] and evicted.size == 0
+
+
+# -------------------------------------------------------- whole Alg. 1 trace
+def test_alg1_hand_worked_trace(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "alg1_trace_8tok.json")))
+    lam, p, B = fx["lambda"], fx["top_p"], fx["budget"]
+    tab = ok.decay_table(lam)
+    pos = np.zeros(0, np.int64)
+    crf = np.zeros(0, np.float32)
+    tau = np.zeros(0, np.int64)
+    for st in fx["steps"]:
+        t = st["t"]
+        pos, crf, tau = np.append(pos, t), np.append(crf, np.float32(0)), np.append(tau, t)
+        assert pos.tolist() == st["live"]
+        d = ok.hit_mask(np.array(st["abar"]), pos, p, new_index=len(pos) - 1)
+        assert sorted(pos[d.hit].tolist()) == st["hit"]
+        tmp, crf, tau = ok.crf_update(crf, tau, t, d.hit.astype(np.float32), d.hit, tab)
+        for k, (c, tt) in st["stored"].items():
+            i = int(np.nonzero(pos == int(k))[0][0])
+            assert float(crf[i]) == c and int(tau[i]) == tt and float(tmp[i]) == c
+        for k, c in st["tmp_miss"].items():
+            i = int(np.nonzero(pos == int(k))[0][0])
+            assert float(tmp[i]) == c
+            assert float(crf[i]) != c or int(tau[i]) == t or c == 0    # a miss does not record
+        retain, evicted = ok.evict_select(tmp, pos, B)
+        assert sorted(pos[evicted].tolist()) == st["evict"]
+        pos, crf, tau = pos[retain], crf[retain], tau[retain]
+    assert pos.tolist() == fx["final_retained"]
+    # the survivors carry their stored score, not the temporary one (Alg. 1 gathers CRF)
+    assert crf.tolist() == [1.140625, 1.5, 1.0, 1.0] and tau.tolist() == [7, 6, 6, 7]
+
+
+def test_oracle_class_runs_the_same_trace_through_real_attention():
+    """The class drives append -> attend -> Alg. 1.  With d = 8 one-hot keys
+    and a query whose logits are the logs of the fixture's weights, attention
+    reproduces the fixture's weights, so the class must reproduce its evictions."""
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "alg1_trace_8tok.json")))
+    o = ok.CrystalKVOracle(1, 1, 1, 1, 8, np.full((1, 1, 1), fx["budget"]), lam=fx["lambda"],
+                           top_p=fx["top_p"], softmax_scale=1.0, t0=0)
+    for st in fx["steps"]:
+        t = st["t"]
+        k_new = np.zeros(8)
+        k_new[t] = 1.0                      # entry of position t answers on coordinate t
+        q = np.full(8, -1e4)
+        for ppos, w in zip(st["live"], st["abar"]):
+            q[ppos] = math.log(w)
+        rec = o.step_unit((0, 0, 0), q[None, :], k_new, np.arange(8.0) + t)
+        assert np.allclose(rec.abar, st["abar"], rtol=1e-12)
+        assert rec.evicted_pos.tolist() == st["evict"]
+        o.t += 1
+    assert o.units[(0, 0, 0)].pos.tolist() == fx["final_retained"]
+
+
+# -------------------------------------------------------------------- Alg. 2
+def test_alg2_hand_example(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "alg2_example.json")))
+    Bl, Bh = ok.budget_shares(fx["CRF"], fx["B"], fx["B_total"])
+    assert np.allclose(Bl, fx["B_layer"], rtol=1e-14)
+    assert np.allclose(Bh, fx["B_new"], rtol=1e-14)
+    newB = ok.rebudget(np.array(fx["CRF"], float), np.array(fx["B"]), fx["B_total"], 1, 400)
+    assert newB.tolist() == fx["B_new"]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_alg2_invariants(seed):
+    g = np.random.default_rng(seed)
+    L, H = int(g.integers(1, 7)), int(g.integers(1, 9))
+    B = g.integers(50, 500, size=(L, H))
+    C = g.random((L, H)) * 100
+    tot = int(B.sum())
+    Bl, Bh = ok.budget_shares(C, B, tot)
+    assert abs(Bh.sum() - tot) < 1e-9 * tot and np.allclose(Bh.sum(axis=1), Bl)
+    Bl2, Bh2 = ok.budget_shares(C * 37.0, B, tot)                      # scale invariance
+    assert np.allclose(Bh, Bh2, rtol=1e-12)
+    newB = ok.rebudget(C, B, tot, 10, 5000)
+    assert int(newB.sum()) == tot and newB.min() >= 10 and newB.max() <= 5000
+    # with no bound active the integers are the real shares rounded down or up
+    if Bh.min() > 11 and Bh.max() < 4999:
+        assert np.all(np.abs(newB - Bh) < 1.0 + 1e-9 + L)     # layer rounding moves heads by < 1 + L/H
+    # equal utilisation everywhere -> budgets proportional to... themselves being uniform
+    U = np.full((L, H), 123)
+    same = ok.rebudget(np.full((L, H), 5.0), U, int(U.sum()), 1, 10 ** 6)
+    assert np.array_equal(same, U)
+
+
+def test_alg2_degenerate_inputs_keep_budgets():
+    B = np.array([[100, 200], [300, 400]])
+    assert np.array_equal(ok.rebudget(np.zeros((2, 2)), B, 1000, 1, 1000), B)
+
+
+def test_apportion_properties():
+    assert ok.apportion([1, 1, 1], 10, [0] * 3, [10] * 3) == [4, 3, 3]       # remainder to the lowest index
+    assert ok.apportion([3, 1], 8, [0, 0], [8, 8]) == [6, 2]
+    assert ok.apportion([100, 1, 1], 10, [2] * 3, [5] * 3) == [5, 3, 2]       # water-filling under an upper bound
+    assert ok.apportion([0, 0], 7, [0, 0], [9, 9]) == [4, 3]                 # no weight: equal shares
+    assert ok.apportion([5, 0], 10, [2, 2], [9, 9]) == [8, 2]                # lower bound
+    g = np.random.default_rng(3)
+    for _ in range(200):
+        m = int(g.integers(1, 12))
+        lo = g.integers(0, 5, size=m)
+        hi = lo + g.integers(0, 50, size=m)
+        tot = int(g.integers(lo.sum(), hi.sum() + 1))
+        x = g.random(m) * (g.random(m) < 0.8)
+        v = ok.apportion(list(x), tot, lo, hi)
+        assert sum(v) == tot and all(lo[k] <= v[k] <= hi[k] for k in range(m))
+    with pytest.raises(ValueError):
+        ok.apportion([1, 1], 100, [0, 0], [10, 10])
+
+
+# -------------------------------------------------------------- probe classes
+def test_probe_classes_counts_and_order():
+    g = np.random.default_rng(9)
+    for n in (1, 3, 10, 57):
+        abar = g.random(n)
+        pos = g.permutation(1000)[:n]
+        cls = ok.probe_classes(abar, pos)
+        k = (3 * n) // 10
+        assert (cls == ok.CLASS_CRYSTAL).sum() == k and (cls == ok.CLASS_SLIP).sum() == k
+        ranked = sorted(range(n), key=lambda i: (-abar[i], pos[i]))
+        assert all(cls[i] == ok.CLASS_CRYSTAL for i in ranked[:k])
+        assert all(cls[i] == ok.CLASS_SLIP for i in ranked[n - k:] if k)
+
+
+# ------------------------------------------------------------ end to end tiny
+def test_tiny_workload_invariants_and_heavy_survival(golden_dir):
+    """Tiny workload, all 512 steps: per-head kept count == budget once full,
+    scores within [0, 1/(1-lambda)], and the 4 heavy positions per head, which
+    draw attention throughout, are never evicted.  The final cache size
+    reproduces Table 1's 'HBM saving' closed form 1 - budget/length."""
+    cfg = wl.CONFIGS["tiny"]
+    st = wl.make_stream(cfg)
+    o = ok.CrystalKVOracle(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                           wl.draw_budgets(cfg), lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt)
+    o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    for s in range(cfg.decode_steps):
+        out, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        for key, r in recs.items():
+            u = o.units[key]
+            assert u.n == min(cfg.prompt + s + 1, cfg.budget)
+            assert len(r.evicted_pos) == max(0, cfg.prompt + s + 1 - cfg.budget) - max(0, cfg.prompt + s - cfg.budget)
+            assert float(r.tmp.max()) <= 2.0 + 1e-6 and float(r.tmp.min()) >= 0.0
+            assert abs(r.abar.sum() - 1.0) < 1e-12
+    for (l, b, h), u in o.units.items():
+        heavy_pos = np.nonzero(st.heavy[l, b, h])[0]
+        assert set(heavy_pos.tolist()) <= set(u.pos.tolist())
+    total = cfg.prompt + cfg.decode_steps
+    saving = 100.0 * (1.0 - o.lengths()[0, 0, 0] / total)
+    assert saving == pytest.approx(100.0 * (1 - 128 / 576))
+    fx = json.load(open(os.path.join(golden_dir, "table1_hbm_saving.json")))
+    for row in fx["rows"]:
+        assert round(100.0 * (1.0 - row["budget"] / row["gen_len"]), 2) == pytest.approx(row["saving_percent"], abs=0.006)
