@@ -1,0 +1,203 @@
+/*
+ * ckv - Crystal-KV decode hot path for MI355X (gfx950): C ABI.
+ *
+ * One "unit" is the KV cache of one (layer, sequence, KV head).  Per decode
+ * step and unit the library appends the new (k, v), computes GQA decode
+ * attention over the unit's budgeted cache, updates every entry's LRFU score
+ * (CRF) from the attention weights, and, when asked, evicts the lowest-score
+ * entries down to the unit's budget and compacts the cache in place.  A
+ * separate call re-allocates the budgets across layers and heads.
+ * (arxiv 2601.16986: Sec. 2.2 attention; Sec. 5.2 and Alg. 1 attention-based
+ * LRFU; Sec. 5.3 and Alg. 2 adaptive budget allocation; Sec. 3 answer-probe
+ * classes.)
+ *
+ * Conventions
+ *  - Every call returns 0 (CKV_OK) or a negative CKV_E* code; nothing throws
+ *    or aborts across this boundary.  ckv_last_error() gives detail.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *    host memory.  All device buffers are owned by the caller and must stay
+ *    valid until ckv_destroy(); the library allocates no device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls that take a stream only enqueue work on it and return; argument
+ *    errors are reported synchronously, device-side conditions (a full cache
+ *    at append) through ckv_status().  Calls documented as "synchronous" wait
+ *    for the stream/device themselves.
+ *  - A context is not thread safe.  All work of one context must be enqueued
+ *    on streams that the caller orders; the usual case is a single stream.
+ *  - Unit order everywhere: [layer][sequence][kv_head], C order.
+ *  - Time: t is the position of the token being decoded; it starts at
+ *    ckv_lrfu_params.t0 and advances by one when a decode step has covered
+ *    the last layer.  t lives in device memory so that captured HIP graphs of
+ *    decode steps can be replayed.
+ */
+#ifndef CKV_H
+#define CKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ckv_ctx ckv_ctx;
+
+enum {
+  CKV_OK = 0,
+  CKV_EINVAL = -1,     /* bad geometry, NULL pointer, parameter out of range */
+  CKV_ECAPACITY = -2,  /* an append found a unit full (the caller skipped eviction) */
+  CKV_ESTATE = -3,     /* call not valid in the context's current state */
+  CKV_EHIP = -4,       /* a HIP runtime call or kernel launch failed */
+  CKV_EWORKSPACE = -5  /* workspace too small or misaligned */
+};
+
+enum { CKV_BF16 = 1, CKV_F32 = 2 };                 /* out_dtype */
+enum { CKV_REWARD_TOPP_HIT = 0,                      /* Alg. 1: reward 1 for entries in the top-p hit set */
+       CKV_REWARD_ATTN_WEIGHTED = 1 };               /* variant: reward = mean attention weight, every entry stored */
+enum { CKV_FLAG_HIT = 1,                             /* per-slot flag: entry was in this step's hit set */
+       CKV_FLAG_SLIP = 2 };                          /* per-slot flag: slot holds the position of an entry evicted by the last eviction */
+enum { CKV_CLASS_SLIP = 0, CKV_CLASS_POTENTIAL = 1, CKV_CLASS_CRYSTAL = 2 };
+
+#define CKV_FUSE_EVICT 1u   /* ckv_decode_step: run Alg. 1 Step 4 in the same pass */
+
+/* Geometry.  head_dim must be 128; n_q_heads = G * n_kv_heads with G <= 8;
+ * `cap` = slots per unit, a multiple of 32, at most 32768. */
+typedef struct {
+  int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t cap;
+  int32_t out_dtype;      /* CKV_F32 or CKV_BF16: element type of `out` in ckv_decode_step */
+} ckv_layout;
+
+/* Parameters of Alg. 1 / Alg. 2 (Sec. 6.4 recommends top_p = 0.9, lambda in [0.5, 0.7]). */
+typedef struct {
+  float lambda;           /* CRF decay, in [0, 1]; 0^0 = 1 */
+  float top_p;            /* hit-mask threshold p > 0 of Alg. 1 Step 1; >= 1 marks every entry */
+  float softmax_scale;    /* multiplies q.k before the softmax (1/sqrt(head_dim) usually) */
+  int32_t reward_mode;    /* CKV_REWARD_* */
+  int32_t t0;             /* time of the first decode step = number of prompt positions */
+  int32_t budget_min;     /* bounds for budgets, 1 <= budget_min <= budget_max < cap */
+  int32_t budget_max;
+} ckv_lrfu_params;
+
+/* Caller-owned device buffers.  With S = n_layers*batch*n_kv_heads*cap slots:
+ *   k_pool, v_pool : S * 128 bf16 each.  Unit u owns slots [u*cap, (u+1)*cap).
+ *                    Inside a unit, entries are stored in blocks of 32 entries
+ *                    (8 KB) in a tiled order chosen so that a 64-lane wavefront
+ *                    reads 1 KB contiguous per load and gets MFMA operands
+ *                    directly; use ckv_load_prompt / ckv_import_unit /
+ *                    ckv_export_unit to convert from and to row-major.
+ *   crf  : S float   - stored CRF score of each slot
+ *   tau  : S int32   - time the stored CRF refers to (last hit)
+ *   pos  : S int32   - position of the token the slot's entry came from
+ *   flags: S uint8   - CKV_FLAG_* bits
+ *   workspace : ckv_workspace_bytes() bytes, 256-byte aligned.
+ * ckv_init overwrites all of them. */
+typedef struct {
+  void* k_pool;
+  void* v_pool;
+  float* crf;
+  int32_t* tau;
+  int32_t* pos;
+  uint8_t* flags;
+  void* workspace;
+  size_t workspace_bytes;
+} ckv_buffers;
+
+/* Bytes of workspace ckv_init needs for this geometry and these parameters
+ * (0 if they are invalid). */
+size_t ckv_workspace_bytes(const ckv_layout* layout, const ckv_lrfu_params* params);
+
+/* Create a context.  `budgets` is a host array [n_layers][batch][n_kv_heads]
+ * with budget_min <= B <= budget_max; each sequence's total is what Alg. 2
+ * later conserves (B_total).  Clears the pools and the per-unit state on
+ * `stream` and waits for it (synchronous).  Errors: CKV_EINVAL, CKV_EWORKSPACE,
+ * CKV_EHIP. */
+int ckv_init(ckv_ctx** ctx, const ckv_layout* layout, const int32_t* budgets,
+             const ckv_lrfu_params* params, const ckv_buffers* buffers, void* stream);
+
+/* Release host-side state.  Device buffers stay the caller's. */
+void ckv_destroy(ckv_ctx* ctx);
+
+/* Fill the empty caches of one layer with a prompt.  k, v: dev bf16
+ * [batch][n_kv_heads][P][128] row-major; entries get positions 0..P-1.
+ * crf0 / tau0: dev [batch][n_kv_heads][P] or NULL (then CRF = 1, tau = P-1:
+ * referenced once, at the end of the prompt; the paper is silent on prompt
+ * scores).  Requires 0 < P < cap, P <= t0 and the layer's units empty
+ * (CKV_ESTATE otherwise). */
+int ckv_load_prompt(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, int32_t P,
+                    const float* crf0, const int32_t* tau0, void* stream);
+
+/* One decode step (Sec. 2.2 + Alg. 1 Steps 1-3, optionally Step 4) for one
+ * layer, or for all layers when layer == -1.
+ *   q      : dev bf16 [batch][n_q_heads][128]   (leading [n_layers] if layer == -1)
+ *   k_new,
+ *   v_new  : dev bf16 [batch][n_kv_heads][128]  (same)
+ *   out    : dev out_dtype [batch][n_q_heads][128] (same) - softmax(scale q K^T) V
+ * Appends (k_new, v_new) at position t (CRF 0, tau t), attends over the unit's
+ * entries, takes the mean weight over the G query heads of each KV head,
+ * builds the top-p hit set (the new entry always belongs to it), updates the
+ * hit entries' stored CRF and tau, sets CKV_FLAG_HIT, accumulates the unit's
+ * aggregated CRF for Alg. 2, and with CKV_FUSE_EVICT evicts down to the budget
+ * (as ckv_evict).  Layers must be stepped in order 0..n_layers-1; t advances
+ * after the last one.  A unit that is already full (n == cap) is not
+ * appended to: the step still runs and ckv_status() reports CKV_ECAPACITY. */
+int ckv_decode_step(ckv_ctx* ctx, int32_t layer, const void* q, const void* k_new,
+                    const void* v_new, void* out, uint32_t flags, void* stream);
+
+/* Alg. 1 Step 4 for every unit of `layer` (-1: all) holding more entries than
+ * its budget B: keep the B entries that come first by (CRF_temp descending,
+ * position ascending), where CRF_temp is the score decayed to the unit's last
+ * decode step; move survivors into slots [0, B) (slot order is unspecified);
+ * slots [B, n_old) then hold the evicted positions with CKV_FLAG_SLIP. */
+int ckv_evict(ckv_ctx* ctx, int32_t layer, void* stream);
+
+/* Alg. 2: new integer budgets for every (layer, head) of every sequence from
+ * the aggregated CRF averaged over the decode steps since the last call (or
+ * since init), keeping each sequence's total; restarts the averaging window.
+ * Budgets stay within [budget_min, budget_max].  No entries move: the next
+ * eviction brings units down to shrunken budgets. */
+int ckv_rebudget(ckv_ctx* ctx, void* stream);
+
+/* Sec. 3 answer-probe classes for one layer: attention of `q_probe` (dev bf16
+ * [batch][n_q_heads][128]) over the current caches, no state change; per slot
+ * class (CKV_CLASS_*) written to classes (dev uint8, [batch][n_kv_heads][cap]):
+ * top floor(0.3 n) by (mean weight descending, position ascending) Crystal,
+ * last floor(0.3 n) Slip, the rest Potential. */
+int ckv_probe(ckv_ctx* ctx, int32_t layer, const void* q_probe, uint8_t* classes, void* stream);
+
+/* Synchronous readers (wait for the device). Host arrays [n_layers][batch][n_kv_heads]. */
+int ckv_get_budgets(ckv_ctx* ctx, int32_t* budgets);
+int ckv_get_lengths(ckv_ctx* ctx, int32_t* lengths);
+int ckv_set_budgets(ckv_ctx* ctx, const int32_t* budgets);   /* same checks as ckv_init; B_total recomputed */
+int ckv_get_time(ckv_ctx* ctx, int32_t* t);
+int ckv_set_time(ckv_ctx* ctx, int32_t t);                   /* also restarts the Alg. 2 window */
+/* CKV_OK, or CKV_ECAPACITY if some append since the last call found its unit full. */
+int ckv_status(ckv_ctx* ctx);
+
+/* Synchronous state transfer of one unit, row-major on the host side (tests,
+ * checkpointing).  Export: *n entries, *n_evicted log slots after them; the
+ * host arrays must hold `cap` slots (K, V: cap*128 bf16 as uint16).  Any
+ * output pointer may be NULL.  Import: replaces the unit's entries (n < cap)
+ * and sets its last-step time to t_unit. */
+int ckv_export_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int32_t* n,
+                    int32_t* n_evicted, int32_t* budget, uint16_t* K, uint16_t* V, float* crf,
+                    int32_t* tau, int32_t* pos, uint8_t* flags);
+int ckv_import_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int32_t n,
+                    const uint16_t* K, const uint16_t* V, const float* crf, const int32_t* tau,
+                    const int32_t* pos, int32_t t_unit);
+
+/* Timing hook for benchmarks: while enabled, every ckv_decode_step brackets
+ * its scan kernel with HIP events on the launch stream (do not enable while
+ * the stream is being captured into a graph).  ckv_profile_read waits for the
+ * device and returns the summed scan-kernel time and launch count since
+ * enabling. */
+int ckv_profile_enable(ckv_ctx* ctx, int32_t on);
+int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
+
+const char* ckv_strerror(int code);
+const char* ckv_last_error(const ckv_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKV_H */

@@ -1,0 +1,285 @@
+"""Thin ctypes binding of libckv.so (the C ABI in include/ckv.h).
+
+Argument marshalling only: every step of the decode path runs in the HIP
+kernels of the library.  PyTorch supplies device memory and streams.  There is
+no fallback: if the shared library is missing, `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libckv.so")
+
+OK, EINVAL, ECAPACITY, ESTATE, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5
+BF16, F32 = 1, 2
+REWARD_TOPP_HIT, REWARD_ATTN_WEIGHTED = 0, 1
+FLAG_HIT, FLAG_SLIP = 1, 2
+FUSE_EVICT = 1
+
+EXPORTS = [
+    "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_decode_step", "ckv_evict",
+    "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
+    "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
+    "ckv_profile_read", "ckv_strerror", "ckv_last_error",
+]
+
+
+class Layout(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("cap", C.c_int32),
+                ("out_dtype", C.c_int32)]
+
+
+class LrfuParams(C.Structure):
+    _fields_ = [("lambda_", C.c_float), ("top_p", C.c_float), ("softmax_scale", C.c_float),
+                ("reward_mode", C.c_int32), ("t0", C.c_int32), ("budget_min", C.c_int32),
+                ("budget_max", C.c_int32)]
+
+
+class Buffers(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("crf", C.c_void_p), ("tau", C.c_void_p),
+                ("pos", C.c_void_p), ("flags", C.c_void_p), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t)]
+
+
+_lib = None
+
+
+def load():
+    """The loaded library; raises if it has not been built (no CPU fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_16986_amd.build` "
+                           "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, u32 = C.c_void_p, C.c_int32, C.c_uint32
+    lib.ckv_workspace_bytes.restype = C.c_size_t
+    lib.ckv_workspace_bytes.argtypes = [C.POINTER(Layout), C.POINTER(LrfuParams)]
+    lib.ckv_init.argtypes = [C.POINTER(vp), C.POINTER(Layout), vp, C.POINTER(LrfuParams), C.POINTER(Buffers), vp]
+    lib.ckv_destroy.restype = None
+    lib.ckv_destroy.argtypes = [vp]
+    lib.ckv_load_prompt.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp]
+    lib.ckv_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, u32, vp]
+    lib.ckv_evict.argtypes = [vp, i32, vp]
+    lib.ckv_rebudget.argtypes = [vp, vp]
+    lib.ckv_probe.argtypes = [vp, i32, vp, vp, vp]
+    lib.ckv_get_budgets.argtypes = [vp, vp]
+    lib.ckv_get_lengths.argtypes = [vp, vp]
+    lib.ckv_set_budgets.argtypes = [vp, vp]
+    lib.ckv_get_time.argtypes = [vp, C.POINTER(i32)]
+    lib.ckv_set_time.argtypes = [vp, i32]
+    lib.ckv_status.argtypes = [vp]
+    lib.ckv_export_unit.argtypes = [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32),
+                                    vp, vp, vp, vp, vp, vp]
+    lib.ckv_import_unit.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
+    lib.ckv_profile_enable.argtypes = [vp, i32]
+    lib.ckv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.ckv_strerror.restype = C.c_char_p
+    lib.ckv_strerror.argtypes = [C.c_int]
+    lib.ckv_last_error.restype = C.c_char_p
+    lib.ckv_last_error.argtypes = [vp]
+    for name in EXPORTS:
+        getattr(lib, name)
+    _lib = lib
+    return lib
+
+
+class CkvError(RuntimeError):
+    def __init__(self, code, detail=""):
+        self.code = code
+        msg = load().ckv_strerror(code).decode()
+        super().__init__(f"ckv error {code} ({msg}){': ' + detail if detail else ''}")
+
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+class CrystalKV:
+    """One ckv context plus the torch tensors that back it.
+
+    budgets: int array [L][Bz][Hkv].  All device tensors live on `device`.
+    """
+
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, budgets, *, lam=0.5, top_p=0.9,
+                 softmax_scale=None, reward_mode=REWARD_TOPP_HIT, t0=0, budget_min=1, budget_max=None,
+                 out_dtype=F32, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load()
+        self.device = torch.device(device)
+        if softmax_scale is None:
+            softmax_scale = 1.0 / float(np.sqrt(head_dim))
+        if budget_max is None:
+            budget_max = cap - 1
+        self.layout = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype)
+        self.params = LrfuParams(lam, top_p, softmax_scale, reward_mode, t0, budget_min, budget_max)
+        self.L, self.Bz, self.Hq, self.Hkv, self.d, self.cap = n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap
+        self.G = n_q_heads // max(n_kv_heads, 1)
+        self.units = n_layers * batch * n_kv_heads
+        self.out_dtype = out_dtype
+        ws = self.lib.ckv_workspace_bytes(C.byref(self.layout), C.byref(self.params))
+        if ws == 0:
+            raise CkvError(EINVAL, "layout or parameters rejected")
+        S = self.units * cap
+        dev = self.device
+        self.k_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
+        self.v_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
+        self.crf = torch.empty(S, dtype=torch.float32, device=dev)
+        self.tau = torch.empty(S, dtype=torch.int32, device=dev)
+        self.pos = torch.empty(S, dtype=torch.int32, device=dev)
+        self.flags = torch.empty(S, dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(ws + 256, dtype=torch.uint8, device=dev)
+        wptr = (self.workspace.data_ptr() + 255) // 256 * 256
+        self.buffers = Buffers(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.crf.data_ptr(),
+                               self.tau.data_ptr(), self.pos.data_ptr(), self.flags.data_ptr(), wptr, ws)
+        b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(n_layers, batch, n_kv_heads))
+        self.ctx = C.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = self.lib.ckv_init(C.byref(self.ctx), C.byref(self.layout), _np_ptr(b), C.byref(self.params),
+                                   C.byref(self.buffers), self._stream())
+        if rc != OK:
+            self.ctx = C.c_void_p()
+            raise CkvError(rc, "ckv_init")
+
+    # ------------------------------------------------------------------ plumbing
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _check(self, rc):
+        if rc != OK:
+            raise CkvError(rc, self.lib.ckv_last_error(self.ctx).decode())
+
+    def close(self):
+        if getattr(self, "ctx", None) and self.ctx.value:
+            self.torch.cuda.synchronize(self.device)
+            self.lib.ckv_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _dev_bf16(self, x, shape):
+        t = self.torch
+        if isinstance(x, np.ndarray):
+            x = t.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device).to(t.bfloat16)
+        assert x.dtype == t.bfloat16 and x.is_contiguous() and tuple(x.shape) == tuple(shape), (x.dtype, x.shape, shape)
+        return x
+
+    # ------------------------------------------------------------------ calls
+    def load_prompt(self, layer, k, v, crf0=None, tau0=None):
+        """k, v: [Bz][Hkv][P][d] (numpy float32 on the bf16 grid, or device bf16 tensors)."""
+        P = k.shape[2]
+        k = self._dev_bf16(k, (self.Bz, self.Hkv, P, self.d))
+        v = self._dev_bf16(v, (self.Bz, self.Hkv, P, self.d))
+        t = self.torch
+        c0 = t.as_tensor(crf0, dtype=t.float32, device=self.device).contiguous() if crf0 is not None else None
+        t0 = t.as_tensor(tau0, dtype=t.int32, device=self.device).contiguous() if tau0 is not None else None
+        self._check(self.lib.ckv_load_prompt(self.ctx, layer, k.data_ptr(), v.data_ptr(), P,
+                                             c0.data_ptr() if c0 is not None else None,
+                                             t0.data_ptr() if t0 is not None else None, self._stream()))
+        self._keep = (k, v, c0, t0)
+
+    def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None):
+        """q [L][Bz][Hq][d], k_new / v_new [L][Bz][Hkv][d] (no leading [L] for a single layer).
+        Returns the device tensor `out` of the same shape as q."""
+        t = self.torch
+        lead = (self.L,) if layer == -1 else ()
+        q = self._dev_bf16(q, lead + (self.Bz, self.Hq, self.d))
+        k_new = self._dev_bf16(k_new, lead + (self.Bz, self.Hkv, self.d))
+        v_new = self._dev_bf16(v_new, lead + (self.Bz, self.Hkv, self.d))
+        if out is None:
+            out = t.empty(q.shape, dtype=t.float32 if self.out_dtype == F32 else t.bfloat16, device=self.device)
+        self._check(self.lib.ckv_decode_step(self.ctx, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                             out.data_ptr(), FUSE_EVICT if evict else 0, self._stream()))
+        return out
+
+    def evict(self, layer=-1):
+        self._check(self.lib.ckv_evict(self.ctx, layer, self._stream()))
+
+    def rebudget(self):
+        self._check(self.lib.ckv_rebudget(self.ctx, self._stream()))
+
+    def probe(self, layer, q_probe):
+        """Classes [Bz][Hkv][cap] (uint8 device tensor) of the layer's entries under q_probe [Bz][Hq][d]."""
+        t = self.torch
+        q = self._dev_bf16(q_probe, (self.Bz, self.Hq, self.d))
+        cls = t.full((self.Bz, self.Hkv, self.cap), 255, dtype=t.uint8, device=self.device)
+        self._check(self.lib.ckv_probe(self.ctx, layer, q.data_ptr(), cls.data_ptr(), self._stream()))
+        return cls
+
+    def budgets(self):
+        b = np.zeros((self.L, self.Bz, self.Hkv), dtype=np.int32)
+        self._check(self.lib.ckv_get_budgets(self.ctx, _np_ptr(b)))
+        return b
+
+    def set_budgets(self, budgets):
+        b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(self.L, self.Bz, self.Hkv))
+        self._check(self.lib.ckv_set_budgets(self.ctx, _np_ptr(b)))
+
+    def lengths(self):
+        b = np.zeros((self.L, self.Bz, self.Hkv), dtype=np.int32)
+        self._check(self.lib.ckv_get_lengths(self.ctx, _np_ptr(b)))
+        return b
+
+    def time(self):
+        t = C.c_int32(0)
+        self._check(self.lib.ckv_get_time(self.ctx, C.byref(t)))
+        return t.value
+
+    def set_time(self, t):
+        self._check(self.lib.ckv_set_time(self.ctx, int(t)))
+
+    def status(self):
+        return self.lib.ckv_status(self.ctx)
+
+    def export_unit(self, layer, seq, head, with_kv=True):
+        """dict with n, n_evicted, budget and host arrays (K, V as float32) of the unit's live entries;
+        `evicted_pos` lists the positions the last eviction removed."""
+        n, nev, bud = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        cap, d = self.cap, self.d
+        K = np.zeros((cap, d), dtype=np.uint16) if with_kv else None
+        V = np.zeros((cap, d), dtype=np.uint16) if with_kv else None
+        crf = np.zeros(cap, dtype=np.float32)
+        tau = np.zeros(cap, dtype=np.int32)
+        pos = np.zeros(cap, dtype=np.int32)
+        flags = np.zeros(cap, dtype=np.uint8)
+        self._check(self.lib.ckv_export_unit(self.ctx, layer, seq, head, C.byref(n), C.byref(nev), C.byref(bud),
+                                             _np_ptr(K) if with_kv else None, _np_ptr(V) if with_kv else None,
+                                             _np_ptr(crf), _np_ptr(tau), _np_ptr(pos), _np_ptr(flags)))
+        n, nev = n.value, nev.value
+        res = dict(n=n, n_evicted=nev, budget=bud.value, crf=crf[:n].copy(), tau=tau[:n].copy(),
+                   pos=pos[:n].copy(), flags=flags[:n].copy(), evicted_pos=np.sort(pos[n:n + nev]),
+                   evicted_flags=flags[n:n + nev].copy())
+        if with_kv:
+            res["K"] = (K[:n].astype(np.uint32) << 16).view(np.float32)
+            res["V"] = (V[:n].astype(np.uint32) << 16).view(np.float32)
+        return res
+
+    def import_unit(self, layer, seq, head, K, V, crf, tau, pos, t_unit):
+        """K, V float32 arrays on the bf16 grid, [n][d]."""
+        n = int(len(pos))
+        Kb = np.ascontiguousarray((np.ascontiguousarray(K, np.float32).view(np.uint32) >> 16).astype(np.uint16))
+        Vb = np.ascontiguousarray((np.ascontiguousarray(V, np.float32).view(np.uint32) >> 16).astype(np.uint16))
+        crf = np.ascontiguousarray(crf, np.float32)
+        tau = np.ascontiguousarray(tau, np.int32)
+        pos = np.ascontiguousarray(pos, np.int32)
+        self._check(self.lib.ckv_import_unit(self.ctx, layer, seq, head, n, _np_ptr(Kb), _np_ptr(Vb), _np_ptr(crf),
+                                             _np_ptr(tau), _np_ptr(pos), int(t_unit)))
+
+    def profile_enable(self, on=True):
+        self._check(self.lib.ckv_profile_enable(self.ctx, 1 if on else 0))
+
+    def profile_read(self):
+        ms, n = C.c_double(0.0), C.c_int32(0)
+        self._check(self.lib.ckv_profile_read(self.ctx, C.byref(ms), C.byref(n)))
+        return ms.value, n.value

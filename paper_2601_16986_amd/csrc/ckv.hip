@@ -1,0 +1,554 @@
+// Host side of the C ABI declared in include/ckv.h: argument checks,
+// workspace carving, kernel launches.  No device memory is allocated here.
+#include "../../include/ckv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ckv_kernels.h"
+
+using namespace ckv;
+
+struct ckv_ctx {
+  ckv_layout lay;
+  ckv_lrfu_params par;
+  ckv_buffers buf;
+  Dev dev;
+  int units = 0;
+  int units_per_layer = 0;
+  int next_layer = 0;
+  int n_cu = 256;
+  size_t finish_lds = 0;
+  std::vector<uint8_t> prompt_loaded;
+  std::string err;
+  // scan timing
+  bool profile = false;
+  std::vector<hipEvent_t> ev;      // pairs
+  size_t ev_used = 0;
+  double scan_ms = 0.0;
+  int scan_launches = 0;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int fail(ckv_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+int hip_fail(ckv_ctx* c, hipError_t e, const char* what) {
+  std::string m = std::string(what) + ": " + hipGetErrorString(e);
+  return fail(c, CKV_EHIP, m);
+}
+
+#define CKV_HIP(ctx, call)                                   \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return hip_fail((ctx), e_, #call); \
+  } while (0)
+
+bool layout_ok(const ckv_layout* l, std::string* why) {
+  if (!l) { *why = "layout is NULL"; return false; }
+  if (l->head_dim != kDim) { *why = "head_dim must be 128"; return false; }
+  if (l->n_layers < 1 || l->n_layers > kMaxLayers) { *why = "n_layers must be in [1, 256]"; return false; }
+  if (l->batch < 1) { *why = "batch must be >= 1"; return false; }
+  if (l->n_kv_heads < 1 || l->n_kv_heads > kMaxKvHeads) { *why = "n_kv_heads must be in [1, 32]"; return false; }
+  if (l->n_q_heads < l->n_kv_heads || l->n_q_heads % l->n_kv_heads != 0) { *why = "n_q_heads must be a multiple of n_kv_heads"; return false; }
+  if (l->n_q_heads / l->n_kv_heads > kMaxGroup) { *why = "at most 8 query heads per KV head"; return false; }
+  if (l->cap < kBlk || l->cap % kBlk != 0 || l->cap > kMaxChunks * kChunk) { *why = "cap must be a multiple of 32 in [32, 32768]"; return false; }
+  if (l->out_dtype != CKV_F32 && l->out_dtype != CKV_BF16) { *why = "out_dtype must be CKV_F32 or CKV_BF16"; return false; }
+  long long units = (long long)l->n_layers * l->batch * l->n_kv_heads;
+  if (units * l->cap > (1ll << 40) || units > (1ll << 24)) { *why = "geometry too large"; return false; }
+  return true;
+}
+
+bool params_ok(const ckv_layout* l, const ckv_lrfu_params* p, std::string* why) {
+  if (!p) { *why = "params is NULL"; return false; }
+  if (!(p->lambda >= 0.0f && p->lambda <= 1.0f)) { *why = "lambda must be in [0, 1]"; return false; }
+  if (!(p->top_p > 0.0f)) { *why = "top_p must be > 0"; return false; }
+  if (!(p->softmax_scale > 0.0f) || !std::isfinite(p->softmax_scale)) { *why = "softmax_scale must be positive"; return false; }
+  if (p->reward_mode != CKV_REWARD_TOPP_HIT && p->reward_mode != CKV_REWARD_ATTN_WEIGHTED) { *why = "unknown reward_mode"; return false; }
+  if (p->t0 < 0) { *why = "t0 must be >= 0"; return false; }
+  if (p->budget_min < 1 || p->budget_min > p->budget_max || p->budget_max >= l->cap) { *why = "need 1 <= budget_min <= budget_max < cap"; return false; }
+  return true;
+}
+
+// lambda^delta as float, flushed to zero below FLT_MIN; the table ends at its
+// first zero entry (one entry for lambda = 1, capped at 2^20 + 1 entries).
+std::vector<float> make_decay_table(float lambda) {
+  std::vector<float> tab;
+  tab.push_back(1.0f);
+  const double lam = (double)lambda;
+  if (lam == 1.0) return tab;
+  for (int delta = 1; delta <= (1 << 20); ++delta) {
+    float v = (float)std::pow(lam, (double)delta);
+    if (v < FLT_MIN) v = 0.0f;
+    tab.push_back(v);
+    if (v == 0.0f) break;
+  }
+  return tab;
+}
+
+struct Carve {
+  size_t n, budget, t_unit, nev, window, sc, tab, items, partial, ml, logits, btotal, total;
+};
+
+Carve carve(const ckv_layout* l, size_t tab_len) {
+  Carve c{};
+  const size_t U = (size_t)l->n_layers * l->batch * l->n_kv_heads;
+  const size_t G = (size_t)(l->n_q_heads / l->n_kv_heads);
+  const size_t mc = (size_t)(l->cap + kChunk - 1) / kChunk;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  c.n = take(U * 4);
+  c.budget = take(U * 4);
+  c.t_unit = take(U * 4);
+  c.nev = take(U * 4);
+  c.window = take(U * 8);
+  c.sc = take(SC_COUNT * 4);
+  c.tab = take(tab_len * 4);
+  c.items = take(U * mc * 8);
+  c.partial = take(U * mc * G * kDim * 4);
+  c.ml = take(U * mc * G * 2 * 4);
+  c.logits = take(U * G * (size_t)l->cap * 4);
+  c.btotal = take((size_t)l->batch * 8);
+  c.total = off;
+  return c;
+}
+
+int check_budgets(ckv_ctx* c, const ckv_layout* l, const ckv_lrfu_params* p, const int32_t* budgets) {
+  if (!budgets) return fail(c, CKV_EINVAL, "budgets is NULL");
+  const size_t U = (size_t)l->n_layers * l->batch * l->n_kv_heads;
+  for (size_t u = 0; u < U; ++u)
+    if (budgets[u] < p->budget_min || budgets[u] > p->budget_max)
+      return fail(c, CKV_EINVAL, "a budget lies outside [budget_min, budget_max]");
+  return CKV_OK;
+}
+
+int upload_budgets(ckv_ctx* c, const int32_t* budgets, hipStream_t s) {
+  const ckv_layout& l = c->lay;
+  std::vector<long long> tot(l.batch, 0);
+  for (int i = 0; i < l.n_layers; ++i)
+    for (int b = 0; b < l.batch; ++b)
+      for (int h = 0; h < l.n_kv_heads; ++h) tot[b] += budgets[((size_t)i * l.batch + b) * l.n_kv_heads + h];
+  CKV_HIP(c, hipMemcpyAsync(c->dev.budget, budgets, (size_t)c->units * 4, hipMemcpyHostToDevice, s));
+  CKV_HIP(c, hipMemcpyAsync(c->dev.btotal, tot.data(), (size_t)l.batch * 8, hipMemcpyHostToDevice, s));
+  CKV_HIP(c, hipStreamSynchronize(s));
+  return CKV_OK;
+}
+
+int fill32(ckv_ctx* c, void* p, uint32_t v, size_t count, hipStream_t s) {
+  if (count == 0) return CKV_OK;
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint32_t*)p, v, count);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int layer_range(ckv_ctx* c, int32_t layer, int* begin, int* count) {
+  if (layer == -1) {
+    *begin = 0;
+    *count = c->units;
+  } else if (layer >= 0 && layer < c->lay.n_layers) {
+    *begin = layer * c->units_per_layer;
+    *count = c->units_per_layer;
+  } else {
+    return fail(c, CKV_EINVAL, "layer out of range");
+  }
+  return CKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ckv_workspace_bytes(const ckv_layout* layout, const ckv_lrfu_params* params) {
+  std::string why;
+  if (!layout_ok(layout, &why) || !params_ok(layout, params, &why)) return 0;
+  return carve(layout, make_decay_table(params->lambda).size()).total;
+}
+
+int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, const ckv_lrfu_params* params,
+             const ckv_buffers* b, void* stream) {
+  if (!out) return CKV_EINVAL;
+  *out = nullptr;
+  std::string why;
+  if (!layout_ok(layout, &why) || !params_ok(layout, params, &why)) return CKV_EINVAL;
+  if (!b || !b->k_pool || !b->v_pool || !b->crf || !b->tau || !b->pos || !b->flags || !b->workspace) return CKV_EINVAL;
+  if (int rc = check_budgets(nullptr, layout, params, budgets)) return rc;
+  std::vector<float> tab = make_decay_table(params->lambda);
+  const Carve cv = carve(layout, tab.size());
+  if (b->workspace_bytes < cv.total || ((uintptr_t)b->workspace % kAlign) != 0) return CKV_EWORKSPACE;
+  if (((uintptr_t)b->k_pool | (uintptr_t)b->v_pool | (uintptr_t)b->crf | (uintptr_t)b->tau | (uintptr_t)b->pos) % 16 != 0)
+    return CKV_EINVAL;
+
+  ckv_ctx* c = new (std::nothrow) ckv_ctx();
+  if (!c) return CKV_EINVAL;
+  c->lay = *layout;
+  c->par = *params;
+  c->buf = *b;
+  c->units_per_layer = layout->batch * layout->n_kv_heads;
+  c->units = layout->n_layers * c->units_per_layer;
+  c->prompt_loaded.assign(layout->n_layers, 0);
+  hipStream_t s = (hipStream_t)stream;
+
+  int devid = 0;
+  hipError_t e = hipGetDevice(&devid);
+  int max_lds = 65536;
+  if (e == hipSuccess) {
+    if (hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, devid) != hipSuccess) c->n_cu = 0;
+    if (hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, devid) != hipSuccess) max_lds = 65536;
+  }
+  if (e != hipSuccess || c->n_cu <= 0) {
+    delete c;
+    return CKV_EHIP;
+  }
+  c->finish_lds = (size_t)layout->cap * 4 + (size_t)((layout->cap + 31) / 32) * 4;
+  if (c->finish_lds + 8192 > (size_t)max_lds) {   // static LDS of the kernels stays below 8 KB
+    delete c;
+    return CKV_EINVAL;
+  }
+  const void* lds_kernels[3] = {reinterpret_cast<const void*>(finish_kernel), reinterpret_cast<const void*>(evict_kernel),
+                                reinterpret_cast<const void*>(probe_kernel)};
+  for (const void* fn : lds_kernels) {
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->finish_lds) != hipSuccess) {
+      delete c;
+      return CKV_EHIP;
+    }
+  }
+
+  Dev& d = c->dev;
+  d.L = layout->n_layers;
+  d.Bz = layout->batch;
+  d.Hq = layout->n_q_heads;
+  d.Hkv = layout->n_kv_heads;
+  d.G = layout->n_q_heads / layout->n_kv_heads;
+  d.cap = layout->cap;
+  d.units = c->units;
+  d.max_chunks = (layout->cap + kChunk - 1) / kChunk;
+  d.out_bf16 = layout->out_dtype == CKV_BF16;
+  d.scale_log2e = params->softmax_scale * 1.44269504088896340736f;
+  d.top_p = params->top_p;
+  d.reward_mode = params->reward_mode;
+  d.bmin = params->budget_min;
+  d.bmax = params->budget_max;
+  d.tab_last = (int32_t)tab.size() - 1;
+  d.K = (uint16_t*)b->k_pool;
+  d.V = (uint16_t*)b->v_pool;
+  d.crf = b->crf;
+  d.tau = b->tau;
+  d.pos = b->pos;
+  d.flags = b->flags;
+  uint8_t* ws = (uint8_t*)b->workspace;
+  d.n = (int32_t*)(ws + cv.n);
+  d.budget = (int32_t*)(ws + cv.budget);
+  d.t_unit = (int32_t*)(ws + cv.t_unit);
+  d.nev = (int32_t*)(ws + cv.nev);
+  d.window = (u64*)(ws + cv.window);
+  d.sc = (int32_t*)(ws + cv.sc);
+  d.tab = (const float*)(ws + cv.tab);
+  d.items = (int2*)(ws + cv.items);
+  d.partial = (float*)(ws + cv.partial);
+  d.ml = (float*)(ws + cv.ml);
+  d.logits = (float*)(ws + cv.logits);
+  d.btotal = (long long*)(ws + cv.btotal);
+
+  auto bail = [&](int rc) {
+    delete c;
+    return rc;
+  };
+  const size_t S = (size_t)c->units * layout->cap;
+  int rc;
+  if ((rc = fill32(c, d.K, 0u, S * kDim / 2, s))) return bail(rc);
+  if ((rc = fill32(c, d.V, 0u, S * kDim / 2, s))) return bail(rc);
+  if ((rc = fill32(c, d.crf, 0u, S, s))) return bail(rc);
+  if ((rc = fill32(c, d.tau, 0u, S, s))) return bail(rc);
+  if ((rc = fill32(c, d.pos, 0u, S, s))) return bail(rc);
+  if ((rc = fill32(c, d.flags, 0u, S / 4, s))) return bail(rc);
+  // per-unit state and scalars (everything up to the decay table)
+  if ((rc = fill32(c, ws, 0u, cv.tab / 4, s))) return bail(rc);
+  if ((rc = fill32(c, d.t_unit, (uint32_t)(params->t0 - 1), (size_t)c->units, s))) return bail(rc);
+  if ((rc = fill32(c, d.sc + SC_T, (uint32_t)params->t0, 1, s))) return bail(rc);
+  if (hipMemcpyAsync((void*)d.tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) return bail(CKV_EHIP);
+  if ((rc = upload_budgets(c, budgets, s))) return bail(rc);
+  if (hipStreamSynchronize(s) != hipSuccess) return bail(CKV_EHIP);
+  *out = c;
+  return CKV_OK;
+}
+
+void ckv_destroy(ckv_ctx* c) {
+  if (!c) return;
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+int ckv_load_prompt(ckv_ctx* c, int32_t layer, const void* k, const void* v, int32_t P, const float* crf0,
+                    const int32_t* tau0, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (layer < 0 || layer >= c->lay.n_layers) return fail(c, CKV_EINVAL, "layer out of range");
+  if (!k || !v) return fail(c, CKV_EINVAL, "k or v is NULL");
+  if (P <= 0 || P >= c->lay.cap || P > c->par.t0) return fail(c, CKV_EINVAL, "need 0 < P < cap and P <= t0");
+  if (c->prompt_loaded[layer]) return fail(c, CKV_ESTATE, "layer already holds entries");
+  c->prompt_loaded[layer] = 1;
+  dim3 grid((unsigned)((P + kBlk - 1) / kBlk), (unsigned)c->units_per_layer);
+  hipLaunchKernelGGL(load_prompt_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, c->dev,
+                     layer * c->units_per_layer, (const uint16_t*)k, (const uint16_t*)v, (int)P, crf0, tau0);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new, const void* v_new, void* out,
+                    uint32_t flags, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (!q || !k_new || !v_new || !out) return fail(c, CKV_EINVAL, "q, k_new, v_new or out is NULL");
+  if (flags & ~CKV_FUSE_EVICT) return fail(c, CKV_EINVAL, "unknown flag bits");
+  int begin, count;
+  if (int rc = layer_range(c, layer, &begin, &count)) return rc;
+  if (layer == -1) {
+    if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  } else {
+    if (layer != c->next_layer) return fail(c, CKV_ESTATE, "layers must be stepped in order");
+  }
+  const int advance = (layer == -1 || layer == c->lay.n_layers - 1) ? 1 : 0;
+  c->next_layer = advance ? 0 : layer + 1;
+  for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_loaded[l] = 1;
+  hipStream_t s = (hipStream_t)stream;
+
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + 3) / 4)), dim3(kThreads), 0, s, c->dev, begin, count,
+                     (const uint16_t*)k_new, (const uint16_t*)v_new, 1);
+  CKV_HIP(c, hipGetLastError());
+
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (c->profile) {
+    if (c->ev_used + 2 > c->ev.size()) {
+      for (int i = 0; i < 2; ++i) {
+        hipEvent_t e;
+        CKV_HIP(c, hipEventCreate(&e));
+        c->ev.push_back(e);
+      }
+    }
+    e0 = c->ev[c->ev_used];
+    e1 = c->ev[c->ev_used + 1];
+    c->ev_used += 2;
+    CKV_HIP(c, hipEventRecord(e0, s));
+  }
+  const long long max_items = (long long)count * c->dev.max_chunks;
+  long long blocks = 2ll * c->n_cu;
+  if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
+  hipLaunchKernelGGL(scan_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q);
+  CKV_HIP(c, hipGetLastError());
+  if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
+
+  hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out,
+                     flags & CKV_FUSE_EVICT, advance);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_evict(ckv_ctx* c, int32_t layer, void* stream) {
+  if (!c) return CKV_EINVAL;
+  int begin, count;
+  if (int rc = layer_range(c, layer, &begin, &count)) return rc;
+  hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_rebudget(ckv_ctx* c, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  hipLaunchKernelGGL(rebudget_kernel, dim3((unsigned)c->lay.batch), dim3(kThreads), 0, (hipStream_t)stream, c->dev);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (!q_probe || !classes) return fail(c, CKV_EINVAL, "q_probe or classes is NULL");
+  if (layer < 0 || layer >= c->lay.n_layers) return fail(c, CKV_EINVAL, "layer out of range");
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  const int begin = layer * c->units_per_layer, count = c->units_per_layer;
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + 3) / 4)), dim3(kThreads), 0, s, c->dev, begin, count,
+                     (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0);
+  CKV_HIP(c, hipGetLastError());
+  const long long max_items = (long long)count * c->dev.max_chunks;
+  long long blocks = 2ll * c->n_cu;
+  if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
+  hipLaunchKernelGGL(scan_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q_probe);
+  CKV_HIP(c, hipGetLastError());
+  hipLaunchKernelGGL(probe_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, classes);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_get_budgets(ckv_ctx* c, int32_t* budgets) {
+  if (!c || !budgets) return CKV_EINVAL;
+  CKV_HIP(c, hipDeviceSynchronize());
+  CKV_HIP(c, hipMemcpy(budgets, c->dev.budget, (size_t)c->units * 4, hipMemcpyDeviceToHost));
+  return CKV_OK;
+}
+
+int ckv_get_lengths(ckv_ctx* c, int32_t* lengths) {
+  if (!c || !lengths) return CKV_EINVAL;
+  CKV_HIP(c, hipDeviceSynchronize());
+  CKV_HIP(c, hipMemcpy(lengths, c->dev.n, (size_t)c->units * 4, hipMemcpyDeviceToHost));
+  return CKV_OK;
+}
+
+int ckv_set_budgets(ckv_ctx* c, const int32_t* budgets) {
+  if (!c) return CKV_EINVAL;
+  if (int rc = check_budgets(c, &c->lay, &c->par, budgets)) return rc;
+  CKV_HIP(c, hipDeviceSynchronize());
+  return upload_budgets(c, budgets, nullptr);
+}
+
+int ckv_get_time(ckv_ctx* c, int32_t* t) {
+  if (!c || !t) return CKV_EINVAL;
+  CKV_HIP(c, hipDeviceSynchronize());
+  CKV_HIP(c, hipMemcpy(t, c->dev.sc + SC_T, 4, hipMemcpyDeviceToHost));
+  return CKV_OK;
+}
+
+int ckv_set_time(ckv_ctx* c, int32_t t) {
+  if (!c || t < 0) return CKV_EINVAL;
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  CKV_HIP(c, hipDeviceSynchronize());
+  int32_t zero = 0;
+  CKV_HIP(c, hipMemcpy(c->dev.sc + SC_T, &t, 4, hipMemcpyHostToDevice));
+  CKV_HIP(c, hipMemcpy(c->dev.sc + SC_WINDOW_STEPS, &zero, 4, hipMemcpyHostToDevice));
+  if (int rc = fill32(c, c->dev.window, 0u, (size_t)c->units * 2, nullptr)) return rc;
+  CKV_HIP(c, hipDeviceSynchronize());
+  return CKV_OK;
+}
+
+int ckv_status(ckv_ctx* c) {
+  if (!c) return CKV_EINVAL;
+  CKV_HIP(c, hipDeviceSynchronize());
+  int32_t st = 0, zero = 0;
+  CKV_HIP(c, hipMemcpy(&st, c->dev.sc + SC_STATUS, 4, hipMemcpyDeviceToHost));
+  if (st) {
+    CKV_HIP(c, hipMemcpy(c->dev.sc + SC_STATUS, &zero, 4, hipMemcpyHostToDevice));
+    return fail(c, CKV_ECAPACITY, "an append found its unit full");
+  }
+  return CKV_OK;
+}
+
+int ckv_export_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_t* n_out, int32_t* nev_out,
+                    int32_t* budget_out, uint16_t* K, uint16_t* V, float* crf, int32_t* tau, int32_t* pos,
+                    uint8_t* flags) {
+  if (!c) return CKV_EINVAL;
+  if (layer < 0 || layer >= c->lay.n_layers || seq < 0 || seq >= c->lay.batch || head < 0 || head >= c->lay.n_kv_heads)
+    return fail(c, CKV_EINVAL, "unit index out of range");
+  const size_t u = ((size_t)layer * c->lay.batch + seq) * c->lay.n_kv_heads + head;
+  const size_t cap = (size_t)c->lay.cap, base = u * cap;
+  CKV_HIP(c, hipDeviceSynchronize());
+  int32_t n = 0, nev = 0, bud = 0;
+  CKV_HIP(c, hipMemcpy(&n, c->dev.n + u, 4, hipMemcpyDeviceToHost));
+  CKV_HIP(c, hipMemcpy(&nev, c->dev.nev + u, 4, hipMemcpyDeviceToHost));
+  CKV_HIP(c, hipMemcpy(&bud, c->dev.budget + u, 4, hipMemcpyDeviceToHost));
+  if (n_out) *n_out = n;
+  if (nev_out) *nev_out = nev;
+  if (budget_out) *budget_out = bud;
+  std::vector<uint16_t> tmp;
+  for (int which = 0; which < 2; ++which) {
+    uint16_t* dst = which == 0 ? K : V;
+    if (!dst) continue;
+    tmp.resize(cap * kDim);
+    CKV_HIP(c, hipMemcpy(tmp.data(), (which == 0 ? c->dev.K : c->dev.V) + base * kDim, cap * kDim * 2, hipMemcpyDeviceToHost));
+    for (int r = 0; r < (int)cap; ++r)
+      for (int col = 0; col < kDim; ++col)
+        dst[(size_t)r * kDim + col] = tmp[which == 0 ? k_offset(r, col) : v_offset(r, col)];
+  }
+  if (crf) CKV_HIP(c, hipMemcpy(crf, c->dev.crf + base, cap * 4, hipMemcpyDeviceToHost));
+  if (tau) CKV_HIP(c, hipMemcpy(tau, c->dev.tau + base, cap * 4, hipMemcpyDeviceToHost));
+  if (pos) CKV_HIP(c, hipMemcpy(pos, c->dev.pos + base, cap * 4, hipMemcpyDeviceToHost));
+  if (flags) CKV_HIP(c, hipMemcpy(flags, c->dev.flags + base, cap, hipMemcpyDeviceToHost));
+  return CKV_OK;
+}
+
+int ckv_import_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_t n, const uint16_t* K,
+                    const uint16_t* V, const float* crf, const int32_t* tau, const int32_t* pos, int32_t t_unit) {
+  if (!c) return CKV_EINVAL;
+  if (layer < 0 || layer >= c->lay.n_layers || seq < 0 || seq >= c->lay.batch || head < 0 || head >= c->lay.n_kv_heads)
+    return fail(c, CKV_EINVAL, "unit index out of range");
+  if (n < 0 || n >= c->lay.cap) return fail(c, CKV_EINVAL, "need 0 <= n < cap");
+  if (n > 0 && (!K || !V || !crf || !tau || !pos)) return fail(c, CKV_EINVAL, "NULL state array");
+  const size_t u = ((size_t)layer * c->lay.batch + seq) * c->lay.n_kv_heads + head;
+  const size_t cap = (size_t)c->lay.cap, base = u * cap;
+  CKV_HIP(c, hipDeviceSynchronize());
+  const int nblk = (n + kBlk - 1) / kBlk;
+  std::vector<uint16_t> tmp((size_t)nblk * kBlkElems);
+  for (int which = 0; which < 2 && n > 0; ++which) {
+    const uint16_t* src = which == 0 ? K : V;
+    std::fill(tmp.begin(), tmp.end(), (uint16_t)0);
+    for (int r = 0; r < n; ++r)
+      for (int col = 0; col < kDim; ++col)
+        tmp[which == 0 ? k_offset(r, col) : v_offset(r, col)] = src[(size_t)r * kDim + col];
+    CKV_HIP(c, hipMemcpy((which == 0 ? c->dev.K : c->dev.V) + base * kDim, tmp.data(), tmp.size() * 2, hipMemcpyHostToDevice));
+  }
+  if (n > 0) {
+    std::vector<uint8_t> zf(n, 0);
+    CKV_HIP(c, hipMemcpy(c->dev.crf + base, crf, (size_t)n * 4, hipMemcpyHostToDevice));
+    CKV_HIP(c, hipMemcpy(c->dev.tau + base, tau, (size_t)n * 4, hipMemcpyHostToDevice));
+    CKV_HIP(c, hipMemcpy(c->dev.pos + base, pos, (size_t)n * 4, hipMemcpyHostToDevice));
+    CKV_HIP(c, hipMemcpy(c->dev.flags + base, zf.data(), (size_t)n, hipMemcpyHostToDevice));
+  }
+  int32_t zero = 0;
+  CKV_HIP(c, hipMemcpy(c->dev.n + u, &n, 4, hipMemcpyHostToDevice));
+  CKV_HIP(c, hipMemcpy(c->dev.nev + u, &zero, 4, hipMemcpyHostToDevice));
+  CKV_HIP(c, hipMemcpy(c->dev.t_unit + u, &t_unit, 4, hipMemcpyHostToDevice));
+  c->prompt_loaded[layer] = 1;
+  return CKV_OK;
+}
+
+int ckv_profile_enable(ckv_ctx* c, int32_t on) {
+  if (!c) return CKV_EINVAL;
+  CKV_HIP(c, hipDeviceSynchronize());
+  c->profile = on != 0;
+  c->ev_used = 0;
+  c->scan_ms = 0.0;
+  c->scan_launches = 0;
+  return CKV_OK;
+}
+
+int ckv_profile_read(ckv_ctx* c, double* scan_ms, int32_t* launches) {
+  if (!c) return CKV_EINVAL;
+  CKV_HIP(c, hipDeviceSynchronize());
+  for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+    float ms = 0.f;
+    CKV_HIP(c, hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]));
+    c->scan_ms += ms;
+    c->scan_launches += 1;
+  }
+  c->ev_used = 0;
+  if (scan_ms) *scan_ms = c->scan_ms;
+  if (launches) *launches = c->scan_launches;
+  return CKV_OK;
+}
+
+const char* ckv_strerror(int code) {
+  switch (code) {
+    case CKV_OK: return "ok";
+    case CKV_EINVAL: return "invalid argument";
+    case CKV_ECAPACITY: return "unit full at append";
+    case CKV_ESTATE: return "call not valid in this state";
+    case CKV_EHIP: return "HIP runtime error";
+    case CKV_EWORKSPACE: return "workspace too small or misaligned";
+    default: return "unknown error";
+  }
+}
+
+const char* ckv_last_error(const ckv_ctx* c) { return c ? c->err.c_str() : ""; }
+
+}  // extern "C"

@@ -1,0 +1,919 @@
+// Device code of the Crystal-KV decode path for gfx950 (64-lane wavefronts,
+// v_mfma_f32_16x16x32_bf16).  Kernels, in launch order of one decode step:
+//
+//   prep_kernel    append (k_new, v_new) into the tiled cache, build the list
+//                  of scan work items (unit, chunk of 256 entries)
+//   scan_kernel    the HBM-bound pass: stream K and V once, QK^T and PV on the
+//                  matrix cores, online softmax per work item; leaves the
+//                  scaled logits and one partial (max, sum, acc) per item
+//   finish_kernel  one workgroup per unit: merge partials -> out, mean
+//                  attention weight per entry, top-p hit mask, CRF update,
+//                  aggregated CRF, and (optionally) eviction + compaction
+//   evict_kernel   eviction + compaction on its own
+//   rebudget_kernel  Alg. 2 with integer apportionment, one workgroup/sequence
+//
+// All floating-point code is compiled with -ffp-contract=off: the CRF update
+// and Alg. 2 must round exactly as their definitions say.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "ckv_layout.h"
+
+namespace ckv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_N_ITEMS = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_COUNT = 64 };
+enum { FLAG_HIT = 1, FLAG_SLIP = 2 };
+constexpr int kThreads = 256;
+constexpr int kMaxChunks = 128;           // cap <= 32768
+constexpr float kFixedOne = 1048576.0f;   // 2^20: resolution of the aggregated-CRF accumulator
+
+struct Dev {
+  int32_t L, Bz, Hq, Hkv, G, cap, units, max_chunks, out_bf16;
+  float scale_log2e;     // softmax_scale * log2(e): logits are kept in the base-2 domain
+  float top_p;
+  int32_t reward_mode, bmin, bmax, tab_last;
+  uint16_t* K;
+  uint16_t* V;
+  float* crf;
+  int32_t* tau;
+  int32_t* pos;
+  uint8_t* flags;
+  int32_t* n;            // [units] entries held
+  int32_t* budget;       // [units]
+  int32_t* t_unit;       // [units] time of the unit's last decode step
+  int32_t* nev;          // [units] entries evicted by the last eviction
+  u64* window;           // [units] fixed-point sum of aggregated CRF since the last re-allocation
+  int32_t* sc;           // scalars, SC_*
+  const float* tab;      // lambda^delta, delta = 0..tab_last
+  int2* items;           // scan work list
+  float* partial;        // [units*max_chunks][G][128]
+  float* ml;             // [units*max_chunks][G][2] (running max, sum)
+  float* logits;         // [units][G][cap] scaled logits (base-2 domain)
+  long long* btotal;     // [Bz] budget total per sequence
+};
+
+// ------------------------------------------------------------------ helpers
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <class T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Block-wide reductions with a fixed combination order (deterministic).  `buf`
+// is a [2][4] LDS array used alternately, so one barrier per call suffices.
+struct RedBuf {
+  u64 v[2][4];
+};
+
+__device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int tid) {
+  v = wave_sum(v);
+  if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
+  __syncthreads();
+  u64 r = rb.v[phase][0] + rb.v[phase][1] + rb.v[phase][2] + rb.v[phase][3];
+  phase ^= 1;
+  return r;
+}
+
+__device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int tid) {
+  return (int)block_sum_u64((u64)(uint32_t)v, rb, phase, tid);
+}
+
+__device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, int tid) {
+  v = wave_sum(v);
+  if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)__float_as_uint(v);
+  __syncthreads();
+  float r = __uint_as_float((uint32_t)rb.v[phase][0]);
+  r += __uint_as_float((uint32_t)rb.v[phase][1]);
+  r += __uint_as_float((uint32_t)rb.v[phase][2]);
+  r += __uint_as_float((uint32_t)rb.v[phase][3]);
+  phase ^= 1;
+  return r;
+}
+
+__device__ __forceinline__ u64 block_min_u64(u64 v, RedBuf& rb, int& phase, int tid) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    u64 y = __shfl_xor(v, o);
+    v = y < v ? y : v;
+  }
+  if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
+  __syncthreads();
+  u64 r = rb.v[phase][0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) r = rb.v[phase][w] < r ? rb.v[phase][w] : r;
+  phase ^= 1;
+  return r;
+}
+
+// ------------------------------------------------------------------ fill
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t v, size_t count) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) p[i] = v;
+}
+
+// ------------------------------------------------------------------ prompt load
+// grid: (ceil(P/32), units of the layer); converts 32 row-major rows to one tiled block.
+__global__ __launch_bounds__(kThreads) void load_prompt_kernel(Dev d, int unit_begin, const uint16_t* k,
+                                                               const uint16_t* v, int P, const float* crf0,
+                                                               const int32_t* tau0) {
+  __shared__ uint16_t vt[kBlk][kDim + 8];
+  const int tid = threadIdx.x;
+  const int urel = blockIdx.y, u = unit_begin + urel;
+  const int blk = blockIdx.x, r0 = blk * kBlk;
+  const uint16_t* ksrc = k + (size_t)urel * P * kDim;
+  const uint16_t* vsrc = v + (size_t)urel * P * kDim;
+  uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
+  uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+  // K: 32 rows x 16 pieces of 16 bytes
+  for (int p = tid; p < kBlk * 16; p += kThreads) {
+    int rr = p >> 4, piece = p & 15, r = r0 + rr;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (r < P) x = *reinterpret_cast<const u32x4*>(ksrc + (size_t)r * kDim + piece * 8);
+    *reinterpret_cast<u32x4*>(kdst + k_offset(r, piece * 8)) = x;
+  }
+  // V: stage the rows, then write 16-byte pieces of the entry-interleaved order
+  for (int p = tid; p < kBlk * 16; p += kThreads) {
+    int rr = p >> 4, piece = p & 15, r = r0 + rr;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (r < P) x = *reinterpret_cast<const u32x4*>(vsrc + (size_t)r * kDim + piece * 8);
+    *reinterpret_cast<u32x4*>(&vt[rr][piece * 8]) = x;
+  }
+  __syncthreads();
+  for (int p = tid; p < 8 * 64; p += kThreads) {
+    int dt = p >> 6, kg = (p >> 4) & 3, j = p & 15;
+    uint16_t e8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      int rr = (e < 4) ? (4 * kg + e) : (16 + 4 * kg + (e - 4));
+      e8[e] = vt[rr][16 * dt + j];
+    }
+    u32x4 x;
+    x.x = e8[0] | ((uint32_t)e8[1] << 16);
+    x.y = e8[2] | ((uint32_t)e8[3] << 16);
+    x.z = e8[4] | ((uint32_t)e8[5] << 16);
+    x.w = e8[6] | ((uint32_t)e8[7] << 16);
+    *reinterpret_cast<u32x4*>(vdst + (size_t)blk * kBlkElems + (size_t)p * 8) = x;
+  }
+  // per-slot state
+  const size_t base = (size_t)u * d.cap;
+  for (int rr = tid; rr < kBlk; rr += kThreads) {
+    int r = r0 + rr;
+    if (r < P) {
+      d.pos[base + r] = r;
+      d.crf[base + r] = crf0 ? crf0[(size_t)urel * P + r] : 1.0f;
+      d.tau[base + r] = tau0 ? tau0[(size_t)urel * P + r] : (P - 1);
+      d.flags[base + r] = 0;
+    }
+  }
+  if (blk == 0 && tid == 0) {
+    d.n[u] = P;
+    d.nev[u] = 0;
+  }
+}
+
+// ------------------------------------------------------------------ prep
+// One wavefront per unit: append the new entry (unless `append` is 0) and
+// publish the unit's scan work items.
+__global__ __launch_bounds__(kThreads) void prep_kernel(Dev d, int unit_begin, int unit_count, const uint16_t* k_new,
+                                                        const uint16_t* v_new, int append) {
+  const int lane = threadIdx.x & 63;
+  const int w = (blockIdx.x * kThreads + threadIdx.x) >> 6;
+  if (w >= unit_count) return;
+  const int u = unit_begin + w;
+  int n = d.n[u];
+  if (append) {
+    const int t = d.sc[SC_T];
+    if (n >= d.cap) {
+      if (lane == 0) atomicOr(&d.sc[SC_STATUS], 1);
+    } else {
+      uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
+      uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+      if (lane < 16)
+        *reinterpret_cast<u32x4*>(kdst + k_offset(n, lane * 8)) =
+            *reinterpret_cast<const u32x4*>(k_new + (size_t)w * kDim + lane * 8);
+      vdst[v_offset(n, lane)] = v_new[(size_t)w * kDim + lane];
+      vdst[v_offset(n, lane + 64)] = v_new[(size_t)w * kDim + lane + 64];
+      if (lane == 0) {
+        const size_t s = (size_t)u * d.cap + n;
+        d.crf[s] = 0.0f;
+        d.tau[s] = t;
+        d.pos[s] = t;
+        d.flags[s] = 0;
+        d.n[u] = n + 1;
+      }
+      n += 1;
+    }
+  }
+  const int nch = (n + kChunk - 1) / kChunk;
+  int base = 0;
+  if (lane == 0) base = atomicAdd(&d.sc[SC_N_ITEMS], nch);
+  base = __shfl(base, 0);
+  for (int c = lane; c < nch; c += 64) d.items[base + c] = make_int2(u, c);
+}
+
+// ------------------------------------------------------------------ scan
+struct KFrag {
+  u32x4 k[8];
+};
+struct VFrag {
+  u32x4 v[8];
+};
+
+__device__ __forceinline__ void load_k(KFrag& f, const uint16_t* kb, int lane) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) f.k[i] = *reinterpret_cast<const u32x4*>(kb + i * 512 + lane * 8);
+}
+
+__device__ __forceinline__ void load_v(VFrag& f, const uint16_t* vb, int lane) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) f.v[i] = *reinterpret_cast<const u32x4*>(vb + i * 512 + lane * 8);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+
+// One block of 32 entries: logits on the matrix cores, online softmax update,
+// probabilities (split into two bf16 terms) times V on the matrix cores.
+__device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, const bf16x8 (&qv)[4], f32x4 (&acc)[8], float& m_run,
+                                           float& l_run, float c_scale, int e_base, int n_valid, float* lg,
+                                           bool store_lg, int lane) {
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < 4; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[s]), qv[s], s0, 0, 0, 0);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[4 + s]), qv[s], s1, 0, 0, 0);
+  float sv[8];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    sv[v] = (e_base + v < n_valid) ? s0[v] * c_scale : -INFINITY;
+    sv[4 + v] = (e_base + 16 + v < n_valid) ? s1[v] * c_scale : -INFINITY;
+  }
+  if (store_lg) {
+    *reinterpret_cast<f32x4*>(lg + e_base) = f32x4{sv[0], sv[1], sv[2], sv[3]};
+    *reinterpret_cast<f32x4*>(lg + e_base + 16) = f32x4{sv[4], sv[5], sv[6], sv[7]};
+  }
+  float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+  bm = fmaxf(bm, __shfl_xor(bm, 16));
+  bm = fmaxf(bm, __shfl_xor(bm, 32));
+  if (__any(bm > m_run)) {
+    const float m_new = fmaxf(m_run, bm);
+    const float sc = fast_exp2(m_run - m_new);
+    l_run *= sc;
+    m_run = m_new;
+    const int h4 = (lane >> 4) << 2;
+    const float c0 = __shfl(sc, h4), c1 = __shfl(sc, h4 + 1), c2 = __shfl(sc, h4 + 2), c3 = __shfl(sc, h4 + 3);
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      acc[dt][0] *= c0;
+      acc[dt][1] *= c1;
+      acc[dt][2] *= c2;
+      acc[dt][3] *= c3;
+    }
+  }
+  bf16x8 ph, pl;
+  float ps = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float p = fast_exp2(sv[i] - m_run);
+    ps += p;
+    const __bf16 h = (__bf16)p;
+    ph[i] = h;
+    pl[i] = (__bf16)(p - (float)h);
+  }
+  l_run += ps;
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) {
+    acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ph, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
+    acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
+  }
+}
+
+// Persistent grid; every wavefront strides over the work list.  `q` holds the
+// query rows of the units [unit_begin, ...) of this call: row (u - unit_begin) * G + g.
+__global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin, const uint16_t* q) {
+  const int lane = threadIdx.x & 63;
+  const int gw = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  const int nw = gridDim.x * (kThreads / 64);
+  const int n_items = d.sc[SC_N_ITEMS];
+  const int j = lane & 15, kg = lane >> 4;
+  const int G = d.G;
+  for (int it = gw; it < n_items; it += nw) {
+    const int2 item = d.items[it];
+    const int u = item.x, c = item.y;
+    const int n = d.n[u];
+    const int e0 = c * kChunk;
+    const int n_valid = n - e0;                       // entries of this item (>= 1)
+    const int nblk = min(kChunkBlocks, (n_valid + kBlk - 1) / kBlk);
+    bf16x8 qv[4];
+    {
+      const uint16_t* qrow = q + ((size_t)(u - unit_begin) * G + j) * kDim + 8 * kg;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        u32x4 x = {0u, 0u, 0u, 0u};
+        if (j < G) x = *reinterpret_cast<const u32x4*>(qrow + 32 * s);
+        qv[s] = as_bf16x8(x);
+      }
+    }
+    const uint16_t* kb = d.K + ((size_t)u * d.cap + e0) * kDim;
+    const uint16_t* vb = d.V + ((size_t)u * d.cap + e0) * kDim;
+    float* lg = d.logits + ((size_t)u * G + (j < G ? j : 0)) * d.cap + e0;
+    const bool store_lg = j < G;
+    f32x4 acc[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+    KFrag ka, kb2;
+    VFrag va;
+    load_k(ka, kb, lane);
+    load_v(va, vb, lane);
+    int blk = 0;
+    while (true) {
+      const bool more = blk + 1 < nblk;
+      if (more) load_k(kb2, kb + (size_t)(blk + 1) * kBlkElems, lane);
+      scan_block(ka, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk + 4 * kg, n_valid, lg, store_lg, lane);
+      if (!more) break;
+      ++blk;
+      load_v(va, vb + (size_t)blk * kBlkElems, lane);
+      const bool more2 = blk + 1 < nblk;
+      if (more2) load_k(ka, kb + (size_t)(blk + 1) * kBlkElems, lane);
+      scan_block(kb2, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk + 4 * kg, n_valid, lg, store_lg, lane);
+      if (!more2) break;
+      ++blk;
+      load_v(va, vb + (size_t)blk * kBlkElems, lane);
+    }
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    const size_t slot = (size_t)u * d.max_chunks + c;
+    if (j < G && kg == 0) {
+      d.ml[(slot * G + j) * 2] = m_run;
+      d.ml[(slot * G + j) * 2 + 1] = l_run;
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int head = 4 * kg + v;
+      if (head < G) {
+        float* dst = d.partial + (slot * G + head) * kDim + j;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) dst[16 * dt] = acc[dt][v];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ eviction
+__device__ __forceinline__ u64 evict_key(float tmp, int pos) {
+  // ascending key order = eviction order: lower score first, then higher position
+  return ((u64)__float_as_uint(tmp) << 32) | (u64)(uint32_t)(~pos);
+}
+
+// One wavefront moves the entry in slot `src` to slot `dst` (both of unit
+// base slot `base`); dst's position goes to src, flagged as evicted.
+__device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, int dst, int lane) {
+  uint16_t* K = d.K + base * kDim;
+  uint16_t* V = d.V + base * kDim;
+  if (lane < 16)
+    *reinterpret_cast<u32x4*>(K + k_offset(dst, lane * 8)) = *reinterpret_cast<const u32x4*>(K + k_offset(src, lane * 8));
+  V[v_offset(dst, lane)] = V[v_offset(src, lane)];
+  V[v_offset(dst, lane + 64)] = V[v_offset(src, lane + 64)];
+  if (lane == 0) {
+    d.crf[base + dst] = d.crf[base + src];
+    d.tau[base + dst] = d.tau[base + src];
+    const int ps = d.pos[base + src], pd = d.pos[base + dst];
+    d.pos[base + dst] = ps;
+    d.pos[base + src] = pd;
+    d.flags[base + dst] = d.flags[base + src];
+    d.flags[base + src] = FLAG_SLIP;
+  }
+}
+
+// Alg. 1 Step 4 for one unit with n > B.  val[i] = CRF_temp of slot i (LDS,
+// `cap` floats, reused as scratch afterwards), evm = LDS bit mask of cap bits.
+__device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint32_t* evm, RedBuf& rb, int& phase,
+                            int* sh, int tid) {
+  const size_t base = (size_t)u * d.cap;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int k = n - B;
+  if (k == 1) {
+    u64 best = ~0ull;
+    int best_i = -1;
+    for (int i = tid; i < n; i += kThreads) {
+      const u64 key = evict_key(val[i], d.pos[base + i]);
+      if (key < best) {
+        best = key;
+        best_i = i;
+      }
+    }
+    const u64 gbest = block_min_u64(best, rb, phase, tid);
+    if (best == gbest && best_i >= 0) sh[0] = best_i;     // keys are unique: one writer
+    __syncthreads();
+    const int e = sh[0];
+    if (wave == 0) {
+      if (e != n - 1) {
+        move_entry(d, base, n - 1, e, lane);
+      } else if (lane == 0) {
+        d.flags[base + e] = FLAG_SLIP;
+      }
+    }
+  } else {
+    // k-th smallest key, most significant bit first (bit 63 is the score's sign: 0)
+    u64 X = 0;
+    for (int bit = 62; bit >= 0; --bit) {
+      const u64 trial = X | (1ull << bit);
+      int cnt = 0;
+      for (int i = tid; i < n; i += kThreads) cnt += evict_key(val[i], d.pos[base + i]) < trial ? 1 : 0;
+      cnt = block_sum_int(cnt, rb, phase, tid);
+      if (cnt < k) X = trial;
+    }
+    const int words = (n + 31) >> 5;
+    for (int w = tid; w < words; w += kThreads) evm[w] = 0u;
+    __syncthreads();
+    for (int i = tid; i < n; i += kThreads)
+      if (evict_key(val[i], d.pos[base + i]) <= X) atomicOr(&evm[i >> 5], 1u << (i & 31));
+    __syncthreads();
+    // holes = evicted slots below B, movers = surviving slots at or above B (equal counts)
+    const int wpt = (words + kThreads - 1) / kThreads;
+    const int w0 = min(words, tid * wpt), w1 = min(words, w0 + wpt);
+    uint32_t holes = 0, movers = 0;
+    for (int w = w0; w < w1; ++w) {
+      const uint32_t e = evm[w];
+      const int s0 = w << 5;
+      const uint32_t below = (B >= s0 + 32) ? 0xFFFFFFFFu : (B <= s0 ? 0u : ((1u << (B - s0)) - 1u));
+      const uint32_t valid = (n >= s0 + 32) ? 0xFFFFFFFFu : ((1u << (n - s0)) - 1u);
+      holes += __popc(e & below);
+      movers += __popc(~e & ~below & valid);
+    }
+    const uint32_t packed = holes | (movers << 16);
+    uint32_t incl = packed;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    if (lane == 63) sh[4 + wave] = (int)incl;
+    __syncthreads();
+    uint32_t prefix = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (w < wave) prefix += (uint32_t)sh[4 + w];
+      total += (uint32_t)sh[4 + w];
+    }
+    const uint32_t excl = incl - packed + prefix;
+    int hrank = (int)(excl & 0xFFFFu), mrank = (int)(excl >> 16);
+    const int h = (int)(total & 0xFFFFu);
+    int* lst = reinterpret_cast<int*>(val);               // CRF_temp no longer needed
+    for (int w = w0; w < w1; ++w) {
+      const uint32_t e = evm[w];
+      const int s0 = w << 5;
+      const uint32_t below = (B >= s0 + 32) ? 0xFFFFFFFFu : (B <= s0 ? 0u : ((1u << (B - s0)) - 1u));
+      const uint32_t valid = (n >= s0 + 32) ? 0xFFFFFFFFu : ((1u << (n - s0)) - 1u);
+      uint32_t hm = e & below, mm = ~e & ~below & valid;
+      while (hm) {
+        lst[hrank++] = s0 + __builtin_ctz(hm);
+        hm &= hm - 1;
+      }
+      while (mm) {
+        lst[d.cap - 1 - (mrank++)] = s0 + __builtin_ctz(mm);
+        mm &= mm - 1;
+      }
+    }
+    __syncthreads();
+    // evicted entries that already sit at or above B just get their flag
+    for (int i = B + tid; i < n; i += kThreads)
+      if ((evm[i >> 5] >> (i & 31)) & 1u) d.flags[base + i] = FLAG_SLIP;
+    for (int r = wave; r < h; r += kThreads / 64) move_entry(d, base, lst[d.cap - 1 - r], lst[r], lane);
+  }
+  if (tid == 0) {
+    d.n[u] = B;
+    d.nev[u] = k;
+  }
+}
+
+// ------------------------------------------------------------------ finish
+// Ends a kernel that must leave the step scalars consistent: the last block
+// to arrive resets the work list and, if asked, advances time.
+__device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, int tid) {
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const int prev = atomicAdd(&d.sc[SC_DONE], 1);
+    if (prev == (int)gridDim.x - 1) {
+      d.sc[SC_DONE] = 0;
+      d.sc[SC_N_ITEMS] = 0;
+      if (advance) {
+        d.sc[SC_T] = t + 1;
+        d.sc[SC_WINDOW_STEPS] = d.sc[SC_WINDOW_STEPS] + 1;
+      }
+      __threadfence();
+    }
+  }
+}
+
+// Merge the scan partials of unit u.  Leaves sM[g] (global max), sInv[g]
+// (1 / softmax denominator) in LDS and, if `out` is given, the attention output.
+__device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, int nch, float* sM, float* sInv, float* sW,
+                                               void* out, int tid) {
+  const int G = d.G;
+  const size_t slot0 = (size_t)u * d.max_chunks;
+  if (tid < G) {
+    const int g = tid;
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, d.ml[((slot0 + c) * G + g) * 2]);
+    float Lsum = 0.f;
+    for (int c = 0; c < nch; ++c) {
+      const float w = fast_exp2(d.ml[((slot0 + c) * G + g) * 2] - M);
+      sW[c * kMaxGroup + g] = w;
+      Lsum += d.ml[((slot0 + c) * G + g) * 2 + 1] * w;
+    }
+    sM[g] = M;
+    sInv[g] = 1.0f / Lsum;
+  }
+  __syncthreads();
+  if (out) {
+    for (int idx = tid; idx < G * kDim; idx += kThreads) {
+      const int g = idx >> 7, dim = idx & 127;
+      float o = 0.f;
+      for (int c = 0; c < nch; ++c) o += d.partial[((slot0 + c) * G + g) * kDim + dim] * sW[c * kMaxGroup + g];
+      o *= sInv[g];
+      const size_t oi = ((size_t)urel * G + g) * kDim + dim;
+      if (d.out_bf16)
+        reinterpret_cast<__bf16*>(out)[oi] = (__bf16)o;
+      else
+        reinterpret_cast<float*>(out)[oi] = o;
+    }
+  }
+}
+
+// Mean attention weight of every entry of unit u into val[0..n).
+__device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const float* sM, const float* sInv, float* val,
+                                             int tid) {
+  const int G = d.G;
+  const float invG = 1.0f / (float)G;
+  const float* lg = d.logits + (size_t)u * G * d.cap;
+  for (int i = tid; i < n; i += kThreads) {
+    float a = 0.f;
+    for (int g = 0; g < G; ++g) a += fast_exp2(lg[(size_t)g * d.cap + i] - sM[g]) * sInv[g];
+    val[i] = a * invG;
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin, void* out, uint32_t call_flags,
+                                                          int advance) {
+  extern __shared__ unsigned char smem[];
+  float* val = reinterpret_cast<float*>(smem);
+  uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
+  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[kMaxChunks * kMaxGroup];
+  __shared__ RedBuf rb;
+  __shared__ int sh[8];
+  const int tid = threadIdx.x;
+  const int urel = blockIdx.x, u = unit_begin + urel;
+  const int n = d.n[u];
+  const int t = d.sc[SC_T];
+  const int B = d.budget[u];
+  const size_t base = (size_t)u * d.cap;
+  int phase = 0;
+  if (n > 0) {
+    const int nch = (n + kChunk - 1) / kChunk;
+    merge_partials(d, u, urel, nch, sM, sInv, sW, out, tid);
+    mean_weights(d, u, n, sM, sInv, val, tid);
+
+    // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
+    uint32_t theta = 0;
+    bool ties_all = true;
+    int pos_cut = 0x7FFFFFFF;
+    if (d.reward_mode == 0) {
+      for (int bit = 30; bit >= 0; --bit) {
+        const uint32_t cand = theta | (1u << bit);
+        float part = 0.f;
+        for (int i = tid; i < n; i += kThreads) {
+          const float a = val[i];
+          part += (__float_as_uint(a) >= cand) ? a : 0.f;
+        }
+        const float tot = block_sum_f32(part, rb, phase, tid);
+        if (tot > d.top_p) theta = cand;
+      }
+      if (theta != 0) {
+        // entries equal to the threshold: only as many as needed, lower positions first
+        float above = 0.f;
+        int ties = 0;
+        for (int i = tid; i < n; i += kThreads) {
+          const float a = val[i];
+          const uint32_t b = __float_as_uint(a);
+          above += (b > theta) ? a : 0.f;
+          ties += (b == theta) ? 1 : 0;
+        }
+        above = block_sum_f32(above, rb, phase, tid);
+        ties = block_sum_int(ties, rb, phase, tid);
+        if (ties > 1) {
+          const float th = __uint_as_float(theta);
+          float c = above;
+          int r = 0;
+          do {
+            c += th;
+            ++r;
+          } while (c <= d.top_p && r < ties);
+          if (r < ties) {
+            ties_all = false;
+            int X = 0;   // r-th smallest position among the ties
+            for (int bit = 30; bit >= 0; --bit) {
+              const int trial = X | (1 << bit);
+              int cnt = 0;
+              for (int i = tid; i < n; i += kThreads)
+                cnt += (__float_as_uint(val[i]) == theta && d.pos[base + i] < trial) ? 1 : 0;
+              cnt = block_sum_int(cnt, rb, phase, tid);
+              if (cnt < r) X = trial;
+            }
+            pos_cut = X;
+          }
+        }
+      }
+    }
+
+    // ---- Alg. 1 Steps 2-3: scores
+    const bool has_new = d.pos[base + n - 1] == t;
+    u64 sfix = 0;
+    for (int i = tid; i < n; i += kThreads) {
+      const float a = val[i];
+      bool hit, store;
+      float reward;
+      if (d.reward_mode == 0) {
+        const uint32_t b = __float_as_uint(a);
+        hit = (b > theta) || (b == theta && (ties_all || d.pos[base + i] <= pos_cut));
+        if (i == n - 1 && has_new) hit = true;
+        store = hit;
+        reward = hit ? 1.0f : 0.0f;
+      } else {
+        hit = false;
+        store = true;
+        reward = a;
+      }
+      const float crf = d.crf[base + i];
+      int delta = t - d.tau[base + i];
+      delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+      float tmp = __fadd_rn(__fmul_rn(d.tab[delta], crf), reward);
+      if (tmp < FLT_MIN) tmp = 0.0f;
+      if (store) {
+        d.crf[base + i] = tmp;
+        d.tau[base + i] = t;
+      }
+      d.flags[base + i] = hit ? FLAG_HIT : 0;
+      val[i] = tmp;
+      sfix += (u64)floorf(tmp * kFixedOne);
+    }
+    sfix = block_sum_u64(sfix, rb, phase, tid);   // barrier: val[] and the stores above are complete
+    if (tid == 0) {
+      d.window[u] += sfix;
+      d.t_unit[u] = t;
+    }
+    // ---- Alg. 1 Step 4
+    if ((call_flags & 1u) && n > B)
+      evict_phase(d, u, n, B, val, evm, rb, phase, sh, tid);
+    else if (tid == 0)
+      d.nev[u] = 0;
+  }
+  step_epilogue(d, t, advance, tid);
+}
+
+// Alg. 1 Step 4 on its own: scores decayed to the unit's last step, no update.
+__global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin) {
+  extern __shared__ unsigned char smem[];
+  float* val = reinterpret_cast<float*>(smem);
+  uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
+  __shared__ RedBuf rb;
+  __shared__ int sh[8];
+  const int tid = threadIdx.x;
+  const int u = unit_begin + blockIdx.x;
+  const int n = d.n[u], B = d.budget[u];
+  const size_t base = (size_t)u * d.cap;
+  int phase = 0;
+  if (n <= B) {
+    if (tid == 0) d.nev[u] = 0;
+    return;
+  }
+  const int t = d.t_unit[u];
+  for (int i = tid; i < n; i += kThreads) {
+    int delta = t - d.tau[base + i];
+    delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+    float tmp = __fmul_rn(d.tab[delta], d.crf[base + i]);
+    if (tmp < FLT_MIN) tmp = 0.0f;
+    val[i] = tmp;
+  }
+  __syncthreads();
+  evict_phase(d, u, n, B, val, evm, rb, phase, sh, tid);
+}
+
+// ------------------------------------------------------------------ probe
+// Sec. 3: classes of the entries of unit u under the probe query's weights.
+__global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, uint8_t* classes) {
+  extern __shared__ unsigned char smem[];
+  float* val = reinterpret_cast<float*>(smem);
+  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[kMaxChunks * kMaxGroup];
+  __shared__ RedBuf rb;
+  const int tid = threadIdx.x;
+  const int urel = blockIdx.x, u = unit_begin + urel;
+  const int n = d.n[u];
+  const size_t base = (size_t)u * d.cap;
+  int phase = 0;
+  if (n > 0) {
+    merge_partials(d, u, urel, (n + kChunk - 1) / kChunk, sM, sInv, sW, nullptr, tid);
+    mean_weights(d, u, n, sM, sInv, val, tid);
+    const int kq = (3 * n) / 10;
+    // order key: ascending = (weight asc, position desc); Crystal = kq largest, Slip = kq smallest
+    u64 lo_cut = 0, hi_cut = ~0ull;
+    if (kq > 0) {
+      for (int pass = 0; pass < 2; ++pass) {
+        const int k = pass == 0 ? kq : (n - kq + 1);      // k-th smallest key
+        u64 X = 0;
+        for (int bit = 62; bit >= 0; --bit) {
+          const u64 trial = X | (1ull << bit);
+          int cnt = 0;
+          for (int i = tid; i < n; i += kThreads) cnt += evict_key(val[i], d.pos[base + i]) < trial ? 1 : 0;
+          cnt = block_sum_int(cnt, rb, phase, tid);
+          if (cnt < k) X = trial;
+        }
+        if (pass == 0) lo_cut = X; else hi_cut = X;
+      }
+    }
+    for (int i = tid; i < n; i += kThreads) {
+      const u64 key = evict_key(val[i], d.pos[base + i]);
+      uint8_t c = 1;
+      if (kq > 0) {
+        if (key >= hi_cut) c = 2;
+        else if (key <= lo_cut) c = 0;
+      }
+      classes[(size_t)urel * d.cap + i] = c;
+    }
+  }
+  step_epilogue(d, 0, 0, tid);
+}
+
+// ------------------------------------------------------------------ Alg. 2
+// Integers val[k] in [lo, hi] summing to `total`, proportional to x[k] >= 0 as
+// far as the bounds allow: water-filling on the reals, floor, remainder by
+// largest fractional part (lower index first on ties), final spill in index order.
+__device__ void apportion(const double* x, int m, long long total, long long lo, long long hi, long long* val, double* y,
+                          unsigned char* fixed) {
+  for (int k = 0; k < m; ++k) {
+    fixed[k] = 0;
+    val[k] = 0;
+    y[k] = 0.0;
+  }
+  for (int iter = 0; iter < m + 1; ++iter) {
+    long long R = total;
+    int n_free = 0;
+    double X = 0.0;
+    for (int k = 0; k < m; ++k) {
+      if (fixed[k]) R -= val[k];
+      else {
+        ++n_free;
+        X += x[k];
+      }
+    }
+    if (n_free == 0) break;
+    double over = 0.0, under = 0.0;
+    for (int k = 0; k < m; ++k) {
+      if (fixed[k]) continue;
+      y[k] = (X > 0.0) ? (double)R * (x[k] / X) : (double)R / (double)n_free;
+      if (y[k] > (double)hi) over += y[k] - (double)hi;
+      if (y[k] < (double)lo) under += (double)lo - y[k];
+    }
+    if (over == 0.0 && under == 0.0) break;
+    if (over >= under) {
+      for (int k = 0; k < m; ++k)
+        if (!fixed[k] && y[k] > (double)hi) {
+          fixed[k] = 1;
+          val[k] = hi;
+        }
+    } else {
+      for (int k = 0; k < m; ++k)
+        if (!fixed[k] && y[k] < (double)lo) {
+          fixed[k] = 1;
+          val[k] = lo;
+        }
+    }
+  }
+  long long sum = 0;
+  for (int k = 0; k < m; ++k) {
+    if (!fixed[k]) {
+      const double f = floor(y[k]);
+      long long fi = (long long)f;
+      fi = fi < lo ? lo : (fi > hi ? hi : fi);
+      val[k] = fi;
+      y[k] = y[k] - f;         // fractional part
+    }
+    sum += val[k];
+  }
+  long long rem = total - sum;
+  // fixed[k]: 0 = free and not yet visited, 1 = fixed at a bound, 2 = free and visited
+  while (rem > 0) {
+    int best = -1;
+    for (int k = 0; k < m; ++k)
+      if (fixed[k] == 0 && (best < 0 || y[k] > y[best])) best = k;
+    if (best < 0) break;
+    fixed[best] = 2;
+    if (val[best] < hi) {
+      val[best] += 1;
+      rem -= 1;
+    }
+  }
+  while (rem < 0) {
+    int best = -1;
+    for (int k = 0; k < m; ++k)
+      if (fixed[k] == 0 && (best < 0 || y[k] <= y[best])) best = k;
+    if (best < 0) break;
+    fixed[best] = 2;
+    if (val[best] > lo) {
+      val[best] -= 1;
+      rem += 1;
+    }
+  }
+  while (rem != 0) {
+    bool moved = false;
+    for (int k = 0; k < m; ++k) {
+      if (rem > 0 && val[k] < hi) {
+        val[k] += 1;
+        rem -= 1;
+        moved = true;
+      } else if (rem < 0 && val[k] > lo) {
+        val[k] -= 1;
+        rem += 1;
+        moved = true;
+      }
+      if (rem == 0) break;
+    }
+    if (!moved) break;
+  }
+}
+
+constexpr int kMaxLayers = 256;
+constexpr int kMaxKvHeads = 32;
+
+// One workgroup per sequence.
+__global__ __launch_bounds__(kThreads) void rebudget_kernel(Dev d) {
+  __shared__ double eta_l[kMaxLayers], y_l[kMaxLayers];
+  __shared__ long long tot_l[kMaxLayers];
+  __shared__ unsigned char fx_l[kMaxLayers];
+  __shared__ int ok;
+  const int tid = threadIdx.x, b = blockIdx.x;
+  const int L = d.L, H = d.Hkv;
+  const int steps = d.sc[SC_WINDOW_STEPS];
+  if (steps > 0) {
+    const double denom = 1048576.0 * (double)steps;
+    if (tid < L) {
+      double sc = 0.0, sb = 0.0;
+      for (int j = 0; j < H; ++j) {
+        const int u = (tid * d.Bz + b) * H + j;
+        sc += (double)d.window[u] / denom;
+        sb += (double)d.budget[u];
+      }
+      eta_l[tid] = sc / sb;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      double sum_eta = 0.0;
+      for (int i = 0; i < L; ++i) sum_eta += eta_l[i];
+      if (!(sum_eta > 0.0) || !isfinite(sum_eta)) {
+        ok = 0;
+      } else {
+        apportion(eta_l, L, d.btotal[b], (long long)H * d.bmin, (long long)H * d.bmax, tot_l, y_l, fx_l);
+        ok = 1;
+      }
+    }
+    __syncthreads();
+    if (ok && tid < L) {
+      double eta_h[kMaxKvHeads], y_h[kMaxKvHeads];
+      long long val_h[kMaxKvHeads];
+      unsigned char fx_h[kMaxKvHeads];
+      for (int j = 0; j < H; ++j) {
+        const int u = (tid * d.Bz + b) * H + j;
+        eta_h[j] = ((double)d.window[u] / denom) / (double)d.budget[u];
+      }
+      apportion(eta_h, H, tot_l[tid], d.bmin, d.bmax, val_h, y_h, fx_h);
+      for (int j = 0; j < H; ++j) d.budget[(tid * d.Bz + b) * H + j] = (int32_t)val_h[j];
+    }
+    __syncthreads();
+    for (int i = tid; i < L * H; i += kThreads) d.window[((i / H) * d.Bz + b) * H + (i % H)] = 0ull;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const int prev = atomicAdd(&d.sc[SC_DONE_RB], 1);
+    if (prev == (int)gridDim.x - 1) {
+      d.sc[SC_DONE_RB] = 0;
+      d.sc[SC_WINDOW_STEPS] = 0;
+    }
+  }
+}
+
+}  // namespace ckv

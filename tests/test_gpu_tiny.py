@@ -1,0 +1,45 @@
+"""GPU parity on the tiny workload: every decode step, every unit, against the oracle."""
+import numpy as np
+import pytest
+
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(cfg, cap, **kw):
+    from oracle import crystal_kv as ok
+    from paper_2601_16986_amd import ckv, workloads as wl
+    st = wl.make_stream(cfg)
+    budgets = wl.draw_budgets(cfg)
+    o = ok.CrystalKVOracle(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, budgets,
+                           lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, **kw)
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
+                      lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=1, budget_max=cap - 1, **kw)
+    for l in range(cfg.n_layers):
+        o.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+        g.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+    return st, o, g
+
+
+def test_tiny_lockstep_all_512_steps():
+    """Tiny workload (1 layer, 8 q / 2 kv heads, 64 prompt + 512 steps, budget 128):
+    outputs within 2e-3, hit flags / CRF bits / tau / eviction sets identical at every step."""
+    from paper_2601_16986_amd import workloads as wl
+    cfg = wl.CONFIGS["tiny"]
+    st, o, g = _pair(cfg, cap=160)
+    # the prompt itself must round-trip through the tiled layout
+    for key, u in o.units.items():
+        e = g.export_unit(*key)
+        assert np.array_equal(e["K"], u.K.astype(np.float32)) and np.array_equal(e["V"], u.V.astype(np.float32))
+        assert np.array_equal(e["pos"], u.pos) and np.array_equal(e["crf"], u.crf) and np.array_equal(e["tau"], u.tau)
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=64)
+    print(f"tiny lock-step: {stats.unit_steps} unit-steps, resynced {stats.resynced}, "
+          f"max out err {stats.max_out_err:.2e}, notes {stats.notes[:5]}")
+    assert stats.resynced <= max(2, stats.unit_steps // 200)
+    assert g.status() == 0
+    assert g.time() == cfg.prompt + cfg.decode_steps
+    for (l, b, h), u in o.units.items():
+        heavy_pos = set(np.nonzero(st.heavy[l, b, h])[0].tolist())
+        assert heavy_pos <= set(g.export_unit(l, b, h, with_kv=False)["pos"].tolist())
+    g.close()
