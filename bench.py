@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the Crystal-KV decode hot path on one MI355X.
+
+A "step" is one decode step over ALL layers x sequences x KV heads of the
+workload: append, GQA attention over the budgeted caches, top-p hit mask, CRF
+update, eviction + compaction (every step), and, for workloads that re-allocate
+budgets, Alg. 2 at its interval.  Inputs are synthetic and resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+  value        decode steps/s from HIP-graph replays of the all-layers call
+  roofline     scan kernel (the dominant one): algorithmic K/V bytes per launch
+               over its average duration, measured with HIP events around each
+               launch in a separate eager pass
+  cpu_baseline the numpy oracle timed on the host on a bounded sample
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+RING = 8                      # distinct synthetic step inputs, replayed cyclically
+
+
+def build_workload(cfg, device):
+    import numpy as np
+    import torch
+    from paper_2601_16986_amd import ckv, workloads as wl
+
+    budgets = wl.draw_budgets(cfg)
+    cap = (cfg.budget_max + 1 + 31) // 32 * 32
+    t_now = cfg.prompt + cfg.decode_steps // 2
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
+                      lam=cfg.lam, top_p=cfg.top_p, t0=t_now, budget_min=cfg.budget_min,
+                      budget_max=cfg.budget_max, device=device)
+    m = wl.torch_mean_query(cfg, device)
+    gen = wl.torch_generator(cfg, 9, device)
+    r_now = math.sqrt(wl.DRIFT_VAR) * torch.randn(m.shape, generator=gen, device=device)
+    for layer in range(cfg.n_layers):
+        k, v, n, crf, tau, pos = wl.torch_steady_layer(cfg, layer, budgets[layer], t_now, m[layer], r_now[layer], device)
+        g.load_cache(layer, k, v, n, crf, tau, pos)
+        torch.cuda.synchronize()
+        del k, v, n, crf, tau, pos
+    ring = wl.torch_step_ring(cfg, RING, m, r_now, device)
+    return g, budgets, ring
+
+
+def algorithmic_bytes(cfg, budgets):
+    """Per decode step.  Scan kernel: K and V rows of every cached entry once
+    (512 B) plus the query group; whole step: 524 B per entry (K, V, CRF and
+    tau reads) plus per-unit q, out (fp32), new k/v and one evicted row move."""
+    import numpy as np
+    n = np.asarray(budgets, dtype=np.int64) + 1          # entries attended: budget + the new one
+    U, G = n.size, cfg.group
+    scan = int(n.sum()) * 512 + U * G * 256
+    step = int(n.sum()) * 524 + U * (G * 256 + G * 512 + 512 + 2 * 524)
+    return scan, step, int(n.sum())
+
+
+def cpu_baseline(cfg, budgets, seconds=15.0):
+    """Time the numpy oracle on a few units of the same workload; scale by entries."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import crystal_kv as ok
+    from paper_2601_16986_amd import workloads as wl
+
+    flat = np.asarray(budgets).reshape(-1)
+    t_now = cfg.prompt + cfg.decode_steps // 2
+    m = wl.mean_query(wl.scaled(cfg, n_layers=1, batch=1))      # one layer/sequence worth of directions
+    sample = [int(u) for u in np.linspace(0, flat.size - 1, 6).astype(int)]
+    o = ok.CrystalKVOracle(1, 1, cfg.group * len(sample), len(sample), cfg.head_dim,
+                           np.asarray([flat[u] for u in sample]).reshape(1, 1, -1), lam=cfg.lam, top_p=cfg.top_p, t0=t_now)
+    rng = np.random.default_rng(0)
+    for i, u in enumerate(sample):
+        c = wl.steady_unit(cfg, u, int(flat[u]), t_now, m[0, 0, i % m.shape[2]])
+        o.set_unit((0, 0, i), c.K, c.V, c.pos, c.crf, c.tau)
+    entries = 0
+    steps = 0
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for i in range(len(sample)):
+                q = wl.bf16_round(rng.standard_normal((cfg.group, cfg.head_dim)).astype(np.float32))
+                k = wl.bf16_round(rng.standard_normal(cfg.head_dim).astype(np.float32))
+                v = wl.bf16_round(rng.standard_normal(cfg.head_dim).astype(np.float32))
+                o.step_unit((0, 0, i), q, k, v)
+                entries += o.units[(0, 0, i)].n + 1
+            o.t += 1
+            steps += 1
+        dt = time.perf_counter() - t0
+    total_entries = int((flat.astype(np.int64) + 1).sum())
+    steps_per_s = (entries / dt) / total_entries
+    return {"value": steps_per_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(sample)} units spread over the workload x {steps} decode steps "
+                      f"({entries} cached entries in {dt:.1f} s), scaled by entries to all {flat.size} units"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", default="qwen14b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-layer", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (units are independent; nothing is sharded); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_16986_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.config]
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+    g, budgets, (rq, rk, rv) = build_workload(cfg, device)
+    out = torch.empty(rq.shape[1:], dtype=torch.float32, device=device)
+    steps = max(RING, args.steps // RING * RING)
+    warm = max(RING, (args.warmup + RING - 1) // RING * RING)
+    R = cfg.rebudget_interval
+
+    def eager_steps(k):
+        for i in range(k):
+            g.decode_step(rq[i % RING], rk[i % RING], rv[i % RING], out=out)
+
+    eager_steps(warm)
+    torch.cuda.synchronize()
+    assert g.status() == 0, "a unit overflowed during warm-up"
+
+    # ---- timed region: graph replays of RING consecutive steps
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_steps(RING)
+        torch.cuda.synchronize()
+    done_since_rebudget = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps // RING):
+        if graph is not None:
+            graph.replay()
+        else:
+            eager_steps(RING)
+        done_since_rebudget += RING
+        if R and done_since_rebudget >= R:
+            g.rebudget()
+            done_since_rebudget = 0
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / steps
+    assert g.status() == 0
+
+    # ---- roofline pass: eager, HIP events around every scan launch
+    g.profile_enable(True)
+    eager_steps(RING * 2)
+    scan_ms, launches = g.profile_read()
+    g.profile_enable(False)
+    scan_bytes, step_bytes, entries = algorithmic_bytes(cfg, g.budgets())
+    scan_avg_ms = scan_ms / max(launches, 1)
+    achieved = scan_bytes / (scan_avg_ms * 1e-3) / 1e9
+
+    # ---- secondary: the shape a real model imposes, one call per layer
+    per_layer = None
+    if not args.no_per_layer and not args.no_graph:
+        outl = out[0]
+
+        def layer_steps(k):
+            for i in range(k):
+                for l in range(cfg.n_layers):
+                    g.decode_step(rq[i % RING, l], rk[i % RING, l], rv[i % RING, l], layer=l, out=outl)
+
+        layer_steps(1)
+        torch.cuda.synchronize()
+        gl = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gl):
+            layer_steps(RING)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        reps = max(1, steps // RING // 2)
+        for _ in range(reps):
+            gl.replay()
+        torch.cuda.synchronize()
+        per_layer = (time.perf_counter() - t1) * 1e3 / (reps * RING)
+
+    lengths = g.lengths()
+    assert np.array_equal(lengths, g.budgets()), "caches are not at their budgets after the run"
+
+    res = {
+        "metric": "decode steps/s (attention + LRFU + evict, all layers per step)",
+        "value": 1e3 / ms_per_step,
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warm,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, "
+                               f"batch {cfg.batch}, mean budget {cfg.budget} "
+                               f"({cfg.budget_min}..{cfg.budget_max}), evict every step, steady state at t={cfg.prompt + cfg.decode_steps // 2}",
+                   "units": int(cfg.n_units), "entries_per_step": entries, "launch": "all layers per call, HIP graph of 8 steps"
+                   if graph is not None else "all layers per call, eager"},
+        "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "per_layer_graph_ms_per_step": per_layer,
+        "roofline": {"bound": "hbm", "kernel": "scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "bytes_per_launch": scan_bytes, "avg_launch_ms": scan_avg_ms, "launches": launches},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, budgets)
+    g.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

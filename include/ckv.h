@@ -127,6 +127,17 @@ void ckv_destroy(ckv_ctx* ctx);
 int ckv_load_prompt(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, int32_t P,
                     const float* crf0, const int32_t* tau0, void* stream);
 
+/* Fill the empty caches of one layer with entries from the middle of a
+ * sequence (restoring a checkpoint, or building a steady-state cache for
+ * measurements).  k, v as in ckv_load_prompt with row stride P; unit (b, h)
+ * takes its first lengths[b][h] rows (dev int32 [batch][n_kv_heads], NULL = P);
+ * pos0: dev int32 [batch][n_kv_heads][P], the entries' positions, which must be
+ * distinct within a unit and below the current time (NULL = 0..P-1); crf0 /
+ * tau0 as in ckv_load_prompt.  Nothing about the values is checked. */
+int ckv_load_cache(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, int32_t P,
+                   const int32_t* lengths, const float* crf0, const int32_t* tau0, const int32_t* pos0,
+                   void* stream);
+
 /* One decode step (Sec. 2.2 + Alg. 1 Steps 1-3, optionally Step 4) for one
  * layer, or for all layers when layer == -1.
  *   q      : dev bf16 [batch][n_q_heads][128]   (leading [n_layers] if layer == -1)

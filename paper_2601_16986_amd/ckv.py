@@ -21,7 +21,7 @@ FLAG_HIT, FLAG_SLIP = 1, 2
 FUSE_EVICT = 1
 
 EXPORTS = [
-    "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_decode_step", "ckv_evict",
+    "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_load_cache", "ckv_decode_step", "ckv_evict",
     "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
     "ckv_profile_read", "ckv_strerror", "ckv_last_error",
@@ -65,6 +65,7 @@ def load():
     lib.ckv_destroy.restype = None
     lib.ckv_destroy.argtypes = [vp]
     lib.ckv_load_prompt.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp]
+    lib.ckv_load_cache.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.ckv_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, u32, vp]
     lib.ckv_evict.argtypes = [vp, i32, vp]
     lib.ckv_rebudget.argtypes = [vp, vp]
@@ -188,6 +189,17 @@ class CrystalKV:
                                              c0.data_ptr() if c0 is not None else None,
                                              t0.data_ptr() if t0 is not None else None, self._stream()))
         self._keep = (k, v, c0, t0)
+
+    def load_cache(self, layer, k, v, lengths, crf0, tau0, pos0):
+        """Device tensors: k, v bf16 [Bz][Hkv][P][d]; lengths int32 [Bz][Hkv]; crf0 f32, tau0 / pos0 int32 [Bz][Hkv][P]."""
+        t = self.torch
+        P = k.shape[2]
+        k = self._dev_bf16(k, (self.Bz, self.Hkv, P, self.d))
+        v = self._dev_bf16(v, (self.Bz, self.Hkv, P, self.d))
+        for x, dt in ((lengths, t.int32), (crf0, t.float32), (tau0, t.int32), (pos0, t.int32)):
+            assert x.dtype == dt and x.is_contiguous() and x.device == k.device
+        self._check(self.lib.ckv_load_cache(self.ctx, layer, k.data_ptr(), v.data_ptr(), P, lengths.data_ptr(),
+                                            crf0.data_ptr(), tau0.data_ptr(), pos0.data_ptr(), self._stream()))
 
     def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None):
         """q [L][Bz][Hq][d], k_new / v_new [L][Bz][Hkv][d] (no leading [L] for a single layer).

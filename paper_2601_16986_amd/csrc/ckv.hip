@@ -292,19 +292,28 @@ void ckv_destroy(ckv_ctx* c) {
   delete c;
 }
 
-int ckv_load_prompt(ckv_ctx* c, int32_t layer, const void* k, const void* v, int32_t P, const float* crf0,
-                    const int32_t* tau0, void* stream) {
+int ckv_load_cache(ckv_ctx* c, int32_t layer, const void* k, const void* v, int32_t P, const int32_t* lengths,
+                   const float* crf0, const int32_t* tau0, const int32_t* pos0, void* stream) {
   if (!c) return CKV_EINVAL;
   if (layer < 0 || layer >= c->lay.n_layers) return fail(c, CKV_EINVAL, "layer out of range");
   if (!k || !v) return fail(c, CKV_EINVAL, "k or v is NULL");
-  if (P <= 0 || P >= c->lay.cap || P > c->par.t0) return fail(c, CKV_EINVAL, "need 0 < P < cap and P <= t0");
+  if (P <= 0 || P >= c->lay.cap) return fail(c, CKV_EINVAL, "need 0 < P < cap");
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
   if (c->prompt_loaded[layer]) return fail(c, CKV_ESTATE, "layer already holds entries");
   c->prompt_loaded[layer] = 1;
   dim3 grid((unsigned)((P + kBlk - 1) / kBlk), (unsigned)c->units_per_layer);
-  hipLaunchKernelGGL(load_prompt_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, c->dev,
-                     layer * c->units_per_layer, (const uint16_t*)k, (const uint16_t*)v, (int)P, crf0, tau0);
+  hipLaunchKernelGGL(load_cache_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, c->dev,
+                     layer * c->units_per_layer, (const uint16_t*)k, (const uint16_t*)v, (int)P, lengths, crf0, tau0,
+                     pos0);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
+}
+
+int ckv_load_prompt(ckv_ctx* c, int32_t layer, const void* k, const void* v, int32_t P, const float* crf0,
+                    const int32_t* tau0, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (P > c->par.t0) return fail(c, CKV_EINVAL, "need P <= t0");
+  return ckv_load_cache(c, layer, k, v, P, nullptr, crf0, tau0, nullptr, stream);
 }
 
 int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new, const void* v_new, void* out,

@@ -123,15 +123,24 @@ __global__ void fill_u32_kernel(uint32_t* p, uint32_t v, size_t count) {
   for (; i < count; i += stride) p[i] = v;
 }
 
-// ------------------------------------------------------------------ prompt load
-// grid: (ceil(P/32), units of the layer); converts 32 row-major rows to one tiled block.
-__global__ __launch_bounds__(kThreads) void load_prompt_kernel(Dev d, int unit_begin, const uint16_t* k,
-                                                               const uint16_t* v, int P, const float* crf0,
-                                                               const int32_t* tau0) {
+// ------------------------------------------------------------------ cache load
+// grid: (ceil(P/32), units of the layer); converts 32 row-major rows to one
+// tiled block.  k, v: [units][P][128]; unit `urel` holds len[urel] (or P)
+// entries; rows beyond that become zero.
+__global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_begin, const uint16_t* k,
+                                                              const uint16_t* v, int P, const int32_t* len,
+                                                              const float* crf0, const int32_t* tau0,
+                                                              const int32_t* pos0) {
   __shared__ uint16_t vt[kBlk][kDim + 8];
   const int tid = threadIdx.x;
   const int urel = blockIdx.y, u = unit_begin + urel;
   const int blk = blockIdx.x, r0 = blk * kBlk;
+  const int n = len ? min(max(len[urel], 0), P) : P;
+  if (blk == 0 && tid == 0) {
+    d.n[u] = n;
+    d.nev[u] = 0;
+  }
+  if (r0 >= n) return;
   const uint16_t* ksrc = k + (size_t)urel * P * kDim;
   const uint16_t* vsrc = v + (size_t)urel * P * kDim;
   uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
@@ -140,14 +149,14 @@ __global__ __launch_bounds__(kThreads) void load_prompt_kernel(Dev d, int unit_b
   for (int p = tid; p < kBlk * 16; p += kThreads) {
     int rr = p >> 4, piece = p & 15, r = r0 + rr;
     u32x4 x = {0u, 0u, 0u, 0u};
-    if (r < P) x = *reinterpret_cast<const u32x4*>(ksrc + (size_t)r * kDim + piece * 8);
+    if (r < n) x = *reinterpret_cast<const u32x4*>(ksrc + (size_t)r * kDim + piece * 8);
     *reinterpret_cast<u32x4*>(kdst + k_offset(r, piece * 8)) = x;
   }
   // V: stage the rows, then write 16-byte pieces of the entry-interleaved order
   for (int p = tid; p < kBlk * 16; p += kThreads) {
     int rr = p >> 4, piece = p & 15, r = r0 + rr;
     u32x4 x = {0u, 0u, 0u, 0u};
-    if (r < P) x = *reinterpret_cast<const u32x4*>(vsrc + (size_t)r * kDim + piece * 8);
+    if (r < n) x = *reinterpret_cast<const u32x4*>(vsrc + (size_t)r * kDim + piece * 8);
     *reinterpret_cast<u32x4*>(&vt[rr][piece * 8]) = x;
   }
   __syncthreads();
@@ -170,16 +179,12 @@ __global__ __launch_bounds__(kThreads) void load_prompt_kernel(Dev d, int unit_b
   const size_t base = (size_t)u * d.cap;
   for (int rr = tid; rr < kBlk; rr += kThreads) {
     int r = r0 + rr;
-    if (r < P) {
-      d.pos[base + r] = r;
+    if (r < n) {
+      d.pos[base + r] = pos0 ? pos0[(size_t)urel * P + r] : r;
       d.crf[base + r] = crf0 ? crf0[(size_t)urel * P + r] : 1.0f;
       d.tau[base + r] = tau0 ? tau0[(size_t)urel * P + r] : (P - 1);
       d.flags[base + r] = 0;
     }
-  }
-  if (blk == 0 && tid == 0) {
-    d.n[u] = P;
-    d.nev[u] = 0;
   }
 }
 

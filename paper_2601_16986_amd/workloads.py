@@ -266,3 +266,87 @@ def decode_inputs(cfg: Config, step: int, m, r_last=None):
     q = (g.standard_normal((L, Bz, Hq, d)).astype(np.float32)
          + np.repeat(m, G, axis=2) + np.repeat(r, G, axis=2))
     return bf16_round(q), bf16_round(k), bf16_round(v), r
+
+
+# ------------------------------------------- steady-state caches (device, bulk)
+def torch_generator(cfg: Config, stream: int, device):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(cfg.seed) * 1000003 + int(stream))
+    return g
+
+
+def torch_mean_query(cfg: Config, device):
+    """m[L][Bz][Hkv][d], norm 4, drawn on the device (bulk workloads)."""
+    import torch
+    g = torch_generator(cfg, 1, device)
+    m = torch.randn((cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.head_dim), generator=g, device=device)
+    return m * (M_NORM / m.norm(dim=-1, keepdim=True))
+
+
+def torch_steady_layer(cfg: Config, layer: int, lengths, t_now: int, m_layer, r_now, device):
+    """Caches of one layer mid-way through the think stage, built on the device.
+
+    lengths: int array [Bz][Hkv] (entries per unit).  Same recipe as
+    `steady_unit` (most recent quarter contiguous, older positions spread over
+    the past, 1 % heavy keys, plausible scores), except that the drift of an
+    entry is tied only to the current drift state r_now [Bz][Hkv][d]
+    (r_pos = rho^age r_now + sqrt(1 - rho^(2 age)) sigma xi): that gives every
+    entry the right logit bonus against the coming queries without a
+    sequential pass over 10^4 entries.
+    Returns bf16 k, v [Bz][Hkv][P][d], int32 lengths, f32 crf, int32 tau, pos.
+    """
+    import torch
+    g = torch_generator(cfg, 100 + layer, device)
+    Bz, Hkv, d = cfg.batch, cfg.n_kv_heads, cfg.head_dim
+    n = torch.as_tensor(np.asarray(lengths, dtype=np.int64), device=device).reshape(Bz, Hkv, 1)
+    P = int(n.max().item())
+    i = torch.arange(P, device=device).reshape(1, 1, P)
+    n_recent = torch.clamp(n // 4, min=1)
+    n_old = n - n_recent
+    t_old = t_now - n_recent                                   # older positions live in [0, t_old)
+    stride = t_old.double() / torch.clamp(n_old, min=1).double()
+    jitter = torch.rand((Bz, Hkv, P), generator=g, device=device, dtype=torch.float64)
+    lo = torch.floor(i.double() * stride).long()
+    hi = torch.floor((i + 1).double() * stride).long()          # cell [lo, hi) of entry i: cells are disjoint
+    pos_old = lo + torch.floor(jitter * (hi - lo).double()).long()
+    pos_old = torch.minimum(pos_old, torch.clamp(hi - 1, min=0))
+    pos = torch.where(i < n_old, pos_old, t_old + (i - n_old))
+    pos = torch.where(i < n, pos, torch.zeros_like(pos))
+    age = (t_now - 1 - pos).clamp(min=0)
+    k = torch.randn((Bz, Hkv, P, d), generator=g, device=device)
+    v = torch.randn((Bz, Hkv, P, d), generator=g, device=device)
+    heavy = torch.rand((Bz, Hkv, P), generator=g, device=device) < HEAVY_FRACTION
+    k += HEAVY_GAIN * heavy.unsqueeze(-1) * m_layer.unsqueeze(2)
+    a = torch.pow(torch.tensor(RHO, device=device, dtype=torch.float64), (age + 1).double()).float().unsqueeze(-1)
+    xi = torch.randn((Bz, Hkv, P, d), generator=g, device=device)
+    k += a * r_now.unsqueeze(2) + torch.sqrt(1 - a * a) * float(np.sqrt(DRIFT_VAR)) * xi
+    since = torch.minimum(age, torch.floor(-torch.log(torch.rand((Bz, Hkv, P), generator=g, device=device)
+                                                      .clamp(min=1e-9)) * 5.0).long())
+    tau = (t_now - 1 - since).int()
+    crf = 1.0 + torch.rand((Bz, Hkv, P), generator=g, device=device)
+    return (k.to(torch.bfloat16).contiguous(), v.to(torch.bfloat16).contiguous(),
+            n.reshape(Bz, Hkv).int().contiguous(), crf.contiguous(), tau.contiguous(), pos.int().contiguous())
+
+
+def torch_step_ring(cfg: Config, n_slots: int, m, r_now, device):
+    """Inputs of `n_slots` consecutive decode steps for all layers, on the
+    device: q [S][L][Bz][Hq][d], k_new, v_new [S][L][Bz][Hkv][d] (bf16).  The
+    drift continues from r_now [L][Bz][Hkv][d]."""
+    import torch
+    g = torch_generator(cfg, 7, device)
+    L, Bz, Hq, Hkv, d, G = cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.group
+    sig = float(np.sqrt(DRIFT_VAR))
+    qs, ks, vs = [], [], []
+    r = r_now
+    for _ in range(n_slots):
+        r = RHO * r + float(np.sqrt(1 - RHO * RHO)) * sig * torch.randn((L, Bz, Hkv, d), generator=g, device=device)
+        heavy = torch.rand((L, Bz, Hkv), generator=g, device=device) < HEAVY_FRACTION
+        k = torch.randn((L, Bz, Hkv, d), generator=g, device=device) + HEAVY_GAIN * heavy.unsqueeze(-1) * m + r
+        v = torch.randn((L, Bz, Hkv, d), generator=g, device=device)
+        q = (torch.randn((L, Bz, Hq, d), generator=g, device=device)
+             + m.repeat_interleave(G, dim=2) + r.repeat_interleave(G, dim=2))
+        qs.append(q.to(torch.bfloat16))
+        ks.append(k.to(torch.bfloat16))
+        vs.append(v.to(torch.bfloat16))
+    return torch.stack(qs).contiguous(), torch.stack(ks).contiguous(), torch.stack(vs).contiguous()
