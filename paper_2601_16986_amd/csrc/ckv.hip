@@ -99,7 +99,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, tab, items, partial, ml, logits, btotal, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -115,10 +115,11 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.nev = take(U * 4);
   c.window = take(U * 8);
   c.sc = take(SC_COUNT * 4);
+  c.stamp = take(U * (mc + 1) * 4);
   c.tab = take(tab_len * 4);
-  c.items = take(U * mc * 8);
-  c.partial = take(U * mc * G * kDim * 4);
-  c.ml = take(U * mc * G * 2 * 4);
+  c.items = take(U * mc * 16);
+  c.partial = take(U * (mc + 1) * G * kDim * 4);
+  c.ml = take(U * (mc + 1) * G * 2 * 4);
   c.logits = take(U * G * (size_t)l->cap * 4);
   c.btotal = take((size_t)l->batch * 8);
   c.total = off;
@@ -236,6 +237,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.cap = layout->cap;
   d.units = c->units;
   d.max_chunks = (layout->cap + kChunk - 1) / kChunk;
+  d.slots = d.max_chunks + 1;
   d.out_bf16 = layout->out_dtype == CKV_BF16;
   d.scale_log2e = params->softmax_scale * 1.44269504088896340736f;
   d.top_p = params->top_p;
@@ -257,9 +259,10 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.window = (u64*)(ws + cv.window);
   d.sc = (int32_t*)(ws + cv.sc);
   d.tab = (const float*)(ws + cv.tab);
-  d.items = (int2*)(ws + cv.items);
+  d.items = (int4*)(ws + cv.items);
   d.partial = (float*)(ws + cv.partial);
   d.ml = (float*)(ws + cv.ml);
+  d.stamp = (int32_t*)(ws + cv.stamp);
   d.logits = (float*)(ws + cv.logits);
   d.btotal = (long long*)(ws + cv.btotal);
 
@@ -279,6 +282,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   if ((rc = fill32(c, ws, 0u, cv.tab / 4, s))) return bail(rc);
   if ((rc = fill32(c, d.t_unit, (uint32_t)(params->t0 - 1), (size_t)c->units, s))) return bail(rc);
   if ((rc = fill32(c, d.sc + SC_T, (uint32_t)params->t0, 1, s))) return bail(rc);
+  if ((rc = fill32(c, d.sc + SC_SEQ, 1u, 1, s))) return bail(rc);
   if (hipMemcpyAsync((void*)d.tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) return bail(CKV_EHIP);
   if ((rc = upload_budgets(c, budgets, s))) return bail(rc);
   if (hipStreamSynchronize(s) != hipSuccess) return bail(CKV_EHIP);
@@ -333,7 +337,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_loaded[l] = 1;
   hipStream_t s = (hipStream_t)stream;
 
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + 3) / 4)), dim3(kThreads), 0, s, c->dev, begin, count,
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)k_new, (const uint16_t*)v_new, 1);
   CKV_HIP(c, hipGetLastError());
 
@@ -388,7 +392,7 @@ int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, 
   if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
   const int begin = layer * c->units_per_layer, count = c->units_per_layer;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + 3) / 4)), dim3(kThreads), 0, s, c->dev, begin, count,
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0);
   CKV_HIP(c, hipGetLastError());
   const long long max_items = (long long)count * c->dev.max_chunks;
@@ -559,5 +563,6 @@ const char* ckv_strerror(int code) {
 }
 
 const char* ckv_last_error(const ckv_ctx* c) { return c ? c->err.c_str() : ""; }
+
 
 }  // extern "C"

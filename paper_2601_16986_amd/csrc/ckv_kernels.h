@@ -29,14 +29,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
-enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_N_ITEMS = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_COUNT = 64 };
+// SC_CLAIM is a 64-bit counter (8-byte aligned): low word = work items published, high word = their blocks
+enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_SEQ = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_CLAIM = 8, SC_COUNT = 64 };
 enum { FLAG_HIT = 1, FLAG_SLIP = 2 };
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 128;           // cap <= 32768
 constexpr float kFixedOne = 1048576.0f;   // 2^20: resolution of the aggregated-CRF accumulator
 
 struct Dev {
-  int32_t L, Bz, Hq, Hkv, G, cap, units, max_chunks, out_bf16;
+  int32_t L, Bz, Hq, Hkv, G, cap, units, max_chunks, slots, out_bf16;   // slots = partial slots per unit
   float scale_log2e;     // softmax_scale * log2(e): logits are kept in the base-2 domain
   float top_p;
   int32_t reward_mode, bmin, bmax, tab_last;
@@ -53,12 +54,15 @@ struct Dev {
   u64* window;           // [units] fixed-point sum of aggregated CRF since the last re-allocation
   int32_t* sc;           // scalars, SC_*
   const float* tab;      // lambda^delta, delta = 0..tab_last
-  int2* items;           // scan work list
-  float* partial;        // [units*max_chunks][G][128]
-  float* ml;             // [units*max_chunks][G][2] (running max, sum)
-  float* logits;         // [units][G][cap] scaled logits (base-2 domain)
+  int4* items;           // scan work list: {unit, chunk, entries from the chunk's start, blocks before this item}
+  float* partial;        // [units*slots][G][128]
+  float* ml;             // [units*slots][G][2] (running max, sum)
+  int32_t* stamp;        // [units*slots] launch sequence number that last wrote the slot
+  float* logits;         // [units][cap/32][G][32] scaled logits (base-2 domain)
   long long* btotal;     // [Bz] budget total per sequence
 };
+
+
 
 // ------------------------------------------------------------------ helpers
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -68,6 +72,39 @@ __device__ __forceinline__ T wave_sum(T v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
   return v;
+}
+
+// Cross-lane moves inside a row of 16 lanes without going through LDS.
+template <int kCtrl>
+__device__ __forceinline__ int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xF, 0xF, true);
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+// Sum over the 64 lanes, same fixed order in every lane: butterfly inside each
+// row of 16 lanes, then the four row sums are read out and added.
+__device__ __forceinline__ float wave_sum_f32(float v) {
+  v += __int_as_float(dpp_i32<kDppQuadSwap1>(__float_as_int(v)));
+  v += __int_as_float(dpp_i32<kDppQuadSwap2>(__float_as_int(v)));
+  v += __int_as_float(dpp_i32<kDppRowHalfMirror>(__float_as_int(v)));
+  v += __int_as_float(dpp_i32<kDppRowMirror>(__float_as_int(v)));
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v) {
+  v += dpp_i32<kDppQuadSwap1>(v);
+  v += dpp_i32<kDppQuadSwap2>(v);
+  v += dpp_i32<kDppRowHalfMirror>(v);
+  v += dpp_i32<kDppRowMirror>(v);
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+         __builtin_amdgcn_readlane(v, 48);
 }
 
 // Block-wide reductions with a fixed combination order (deterministic).  `buf`
@@ -86,11 +123,17 @@ __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int 
 }
 
 __device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int tid) {
-  return (int)block_sum_u64((u64)(uint32_t)v, rb, phase, tid);
+  v = wave_sum_i32(v);
+  if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)(uint32_t)v;
+  __syncthreads();
+  const int r = (int)(uint32_t)rb.v[phase][0] + (int)(uint32_t)rb.v[phase][1] + (int)(uint32_t)rb.v[phase][2] +
+                (int)(uint32_t)rb.v[phase][3];
+  phase ^= 1;
+  return r;
 }
 
 __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, int tid) {
-  v = wave_sum(v);
+  v = wave_sum_f32(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)__float_as_uint(v);
   __syncthreads();
   float r = __uint_as_float((uint32_t)rb.v[phase][0]);
@@ -189,43 +232,74 @@ __global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_be
 }
 
 // ------------------------------------------------------------------ prep
-// One wavefront per unit: append the new entry (unless `append` is 0) and
-// publish the unit's scan work items.
-__global__ __launch_bounds__(kThreads) void prep_kernel(Dev d, int unit_begin, int unit_count, const uint16_t* k_new,
-                                                        const uint16_t* v_new, int append) {
-  const int lane = threadIdx.x & 63;
-  const int w = (blockIdx.x * kThreads + threadIdx.x) >> 6;
-  if (w >= unit_count) return;
+// 32 threads per unit, 32 units per workgroup: append the new entry (unless
+// `append` is 0) and publish the unit's scan work items {unit, chunk, entries
+// from the chunk's start to the unit's end, blocks in the list before this
+// item}.  One 64-bit atomic per workgroup claims the list range and the block
+// range together, so the list is sorted by block offset and unit-major (its
+// order only affects scheduling, never results).
+constexpr int kPrepThreads = 1024;
+constexpr int kPrepUnits = 32;
+
+__global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begin, int unit_count, const uint16_t* k_new,
+                                                            const uint16_t* v_new, int append) {
+  __shared__ int s_nch[kPrepUnits], s_nblk[kPrepUnits];
+  __shared__ u64 s_base;
+  const int tid = threadIdx.x, sub = tid & 31, slot = tid >> 5;
+  const int w = blockIdx.x * kPrepUnits + slot;
+  const bool active = w < unit_count;
   const int u = unit_begin + w;
-  int n = d.n[u];
-  if (append) {
-    const int t = d.sc[SC_T];
-    if (n >= d.cap) {
-      if (lane == 0) atomicOr(&d.sc[SC_STATUS], 1);
-    } else {
-      uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
-      uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
-      if (lane < 16)
-        *reinterpret_cast<u32x4*>(kdst + k_offset(n, lane * 8)) =
-            *reinterpret_cast<const u32x4*>(k_new + (size_t)w * kDim + lane * 8);
-      vdst[v_offset(n, lane)] = v_new[(size_t)w * kDim + lane];
-      vdst[v_offset(n, lane + 64)] = v_new[(size_t)w * kDim + lane + 64];
-      if (lane == 0) {
-        const size_t s = (size_t)u * d.cap + n;
-        d.crf[s] = 0.0f;
-        d.tau[s] = t;
-        d.pos[s] = t;
-        d.flags[s] = 0;
-        d.n[u] = n + 1;
+  int n = 0;
+  if (active) {
+    n = d.n[u];
+    if (append) {
+      const int t = d.sc[SC_T];
+      if (n >= d.cap) {
+        if (sub == 0) atomicOr(&d.sc[SC_STATUS], 1);
+      } else {
+        uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
+        uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+        if (sub < 16)
+          *reinterpret_cast<u32x4*>(kdst + k_offset(n, sub * 8)) =
+              *reinterpret_cast<const u32x4*>(k_new + (size_t)w * kDim + sub * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vdst[v_offset(n, sub * 4 + e)] = v_new[(size_t)w * kDim + sub * 4 + e];
+        if (sub == 0) {
+          const size_t s = (size_t)u * d.cap + n;
+          d.crf[s] = 0.0f;
+          d.tau[s] = t;
+          d.pos[s] = t;
+          d.flags[s] = 0;
+          d.n[u] = n + 1;
+        }
+        n += 1;
       }
-      n += 1;
     }
   }
-  const int nch = (n + kChunk - 1) / kChunk;
-  int base = 0;
-  if (lane == 0) base = atomicAdd(&d.sc[SC_N_ITEMS], nch);
-  base = __shfl(base, 0);
-  for (int c = lane; c < nch; c += 64) d.items[base + c] = make_int2(u, c);
+  const int nch = active ? (n + kChunk - 1) / kChunk : 0;
+  const int nblk = active ? (n + kBlk - 1) / kBlk : 0;
+  if (sub == 0) {
+    s_nch[slot] = nch;
+    s_nblk[slot] = nblk;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int tot = 0, totb = 0;
+    for (int i = 0; i < kPrepUnits; ++i) {
+      const int c = s_nch[i], b = s_nblk[i];
+      s_nch[i] = tot;
+      s_nblk[i] = totb;
+      tot += c;
+      totb += b;
+    }
+    s_base = atomicAdd(reinterpret_cast<u64*>(&d.sc[SC_CLAIM]), (u64)(uint32_t)tot | ((u64)(uint32_t)totb << 32));
+  }
+  __syncthreads();
+  if (active) {
+    const int base = (int)(uint32_t)s_base + s_nch[slot];
+    const int bbase = (int)(uint32_t)(s_base >> 32) + s_nblk[slot];
+    for (int c = sub; c < nch; c += 32) d.items[base + c] = make_int4(u, c, n - c * kChunk, bbase + c * kChunkBlocks);
+  }
 }
 
 // ------------------------------------------------------------------ scan
@@ -236,23 +310,35 @@ struct VFrag {
   u32x4 v[8];
 };
 
-__device__ __forceinline__ void load_k(KFrag& f, const uint16_t* kb, int lane) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) f.k[i] = *reinterpret_cast<const u32x4*>(kb + i * 512 + lane * 8);
+// K and V are read once per step and never reused: non-temporal loads keep
+// them from displacing the partials and logits that the finish kernel re-reads.
+__device__ __forceinline__ u32x4 stream_load(const uint16_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
 
-__device__ __forceinline__ void load_v(VFrag& f, const uint16_t* vb, int lane) {
+// `kb` / `vb` already include the lane's offset (8 bf16 per lane).
+__device__ __forceinline__ void load_k(KFrag& f, const uint16_t* kb) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) f.v[i] = *reinterpret_cast<const u32x4*>(vb + i * 512 + lane * 8);
+  for (int i = 0; i < 8; ++i) f.k[i] = stream_load(kb + i * 512);
+}
+
+__device__ __forceinline__ void load_v(VFrag& f, const uint16_t* vb) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) f.v[i] = stream_load(vb + i * 512);
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 
 // One block of 32 entries: logits on the matrix cores, online softmax update,
 // probabilities (split into two bf16 terms) times V on the matrix cores.
-__device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, const bf16x8 (&qv)[4], f32x4 (&acc)[8], float& m_run,
-                                           float& l_run, float c_scale, int e_base, int n_valid, float* lg,
-                                           bool store_lg, int lane) {
+// The scaled logits leave through a wave-private LDS tile so that each head's
+// 32 values go to memory as one full 128-byte line.
+constexpr int kLgRow = 36;     // floats per head row in the LDS tile (32 + pad against bank conflicts)
+
+__device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, const bf16x8 (&qv)[4], f32x4 (&acc)[8],
+                                           float& m_run, float& l_run, float c_scale, int e_base, int n_valid,
+                                           float* lds_lg, float* lg_dst, int G, int lane) {
+  const int j = lane & 15, kg = lane >> 4;
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int s = 0; s < 4; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[s]), qv[s], s0, 0, 0, 0);
@@ -261,13 +347,19 @@ __device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, cons
   float sv[8];
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
-    sv[v] = (e_base + v < n_valid) ? s0[v] * c_scale : -INFINITY;
-    sv[4 + v] = (e_base + 16 + v < n_valid) ? s1[v] * c_scale : -INFINITY;
+    sv[v] = (e_base + 4 * kg + v < n_valid) ? s0[v] * c_scale : -INFINITY;
+    sv[4 + v] = (e_base + 4 * kg + 16 + v < n_valid) ? s1[v] * c_scale : -INFINITY;
   }
-  if (store_lg) {
-    *reinterpret_cast<f32x4*>(lg + e_base) = f32x4{sv[0], sv[1], sv[2], sv[3]};
-    *reinterpret_cast<f32x4*>(lg + e_base + 16) = f32x4{sv[4], sv[5], sv[6], sv[7]};
+  if (j < G) {
+    *reinterpret_cast<f32x4*>(lds_lg + j * kLgRow + 4 * kg) = f32x4{sv[0], sv[1], sv[2], sv[3]};
+    *reinterpret_cast<f32x4*>(lds_lg + j * kLgRow + 16 + 4 * kg) = f32x4{sv[4], sv[5], sv[6], sv[7]};
   }
+  __builtin_amdgcn_wave_barrier();
+  if (lane < 8 * G) {
+    const f32x4 row = *reinterpret_cast<const f32x4*>(lds_lg + (lane >> 3) * kLgRow + 4 * (lane & 7));
+    *reinterpret_cast<f32x4*>(lg_dst + e_base * G) = row;
+  }
+  __builtin_amdgcn_wave_barrier();
   float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
   bm = fmaxf(bm, __shfl_xor(bm, 16));
   bm = fmaxf(bm, __shfl_xor(bm, 32));
@@ -304,66 +396,135 @@ __device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, cons
   }
 }
 
-// Persistent grid; every wavefront strides over the work list.  `q` holds the
-// query rows of the units [unit_begin, ...) of this call: row (u - unit_begin) * G + g.
-__global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin, const uint16_t* q) {
+struct Item {
+  int u, c, n_valid, blk_off;
+};
+
+__device__ __forceinline__ Item fetch_item(const Dev& d, int it) {
+  const int4 r = d.items[it];
+  Item m;
+  m.u = __builtin_amdgcn_readfirstlane(r.x);
+  m.c = __builtin_amdgcn_readfirstlane(r.y);
+  m.n_valid = __builtin_amdgcn_readfirstlane(r.z);
+  m.blk_off = __builtin_amdgcn_readfirstlane(r.w);
+  return m;
+}
+
+// Index of the work item that holds global block `b` (largest i with
+// items[i].blk_off <= b): 64-way search, one probe per lane and round.
+__device__ __forceinline__ int find_item(const Dev& d, int n_items, int b, int lane) {
+  int lo = 0, hi = n_items;
+  while (hi - lo > 1) {
+    const int step = (hi - lo + 63) >> 6;
+    const int idx = lo + lane * step;
+    const int off = idx < hi ? d.items[idx].w : 0x7FFFFFFF;
+    const u64 mask = __ballot(off <= b);
+    const int k = __popcll(mask) - 1;            // lane 0 always qualifies
+    lo += k * step;
+    hi = min(hi, lo + step);
+  }
+  return __builtin_amdgcn_readfirstlane(lo);
+}
+
+// Persistent grid.  The blocks (32 entries) of all work items form one
+// sequence, sorted unit-major; every wavefront takes an equal contiguous share
+// of it.  Its share is a few long RUNS: consecutive blocks of one unit,
+// contiguous in memory, over which the online softmax simply continues.  A run
+// is streamed block by block: while block b is computed the K tile of block
+// b+1 (the next run's first block at the end of a run) is in flight, and V
+// follows as soon as the previous V has been consumed.  All loads in the loop
+// are unconditional, so the waits the compiler inserts are exact.  A run
+// leaves one partial (max, sum, acc), stamped with the launch sequence number,
+// in slot 0 of its unit if it starts the unit, else in slot 1 + chunk of its
+// first block (shares are at least one chunk long, so no two runs collide).
+// `q` holds the query rows of the units [unit_begin, ...) of this call:
+// row (u - unit_begin) * G + g.
+__global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q) {
+  __shared__ float s_lg[kThreads / 64][kMaxGroup * kLgRow];
   const int lane = threadIdx.x & 63;
-  const int gw = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
   const int nw = gridDim.x * (kThreads / 64);
-  const int n_items = d.sc[SC_N_ITEMS];
+  const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6));
+  const int n_items = d.sc[SC_CLAIM];
+  const int n_blocks = d.sc[SC_CLAIM + 1];
+  const int seq = d.sc[SC_SEQ];
+  const int per = max(kChunkBlocks, (n_blocks + nw - 1) / nw);
+  int b_cur = gw * per;                                  // global block index
+  const int b_end = min(n_blocks, b_cur + per);
+  if (b_cur >= b_end) return;
+  float* lds_lg = s_lg[threadIdx.x >> 6];
   const int j = lane & 15, kg = lane >> 4;
   const int G = d.G;
-  for (int it = gw; it < n_items; it += nw) {
-    const int2 item = d.items[it];
-    const int u = item.x, c = item.y;
-    const int n = d.n[u];
-    const int e0 = c * kChunk;
-    const int n_valid = n - e0;                       // entries of this item (>= 1)
-    const int nblk = min(kChunkBlocks, (n_valid + kBlk - 1) / kBlk);
+  const bool head_lane = j < G;
+  const int jq = head_lane ? j : 0;
+  const size_t unit_elems = (size_t)d.cap * kDim;
+
+  int it = find_item(d, n_items, b_cur, lane);
+  Item cur = fetch_item(d, it);
+  KFrag ka, kb;
+  VFrag va;
+  {
+    const size_t off = (size_t)cur.u * unit_elems + ((size_t)cur.c * kChunk + (size_t)(b_cur - cur.blk_off) * kBlk) * kDim + lane * 8;
+    load_k(ka, d.K + off);
+    load_v(va, d.V + off);
+  }
+  while (true) {
+    // ---- one run: blocks [fb, fb + nblk) of unit cur.u, fb counted from the unit's start
+    const int fb_item = b_cur - cur.blk_off;                                   // first block, inside item `it`
+    const int fb = cur.c * kChunkBlocks + fb_item;
+    const int run_valid = cur.n_valid - fb_item * kBlk;                        // entries from the run's start to the unit's end
+    const int nblk = min((run_valid + kBlk - 1) / kBlk, b_end - b_cur);
+    const int b_next = b_cur + nblk;
+    const bool have_next = b_next < b_end;
+    const int it_next = it + (fb_item + nblk + kChunkBlocks - 1) / kChunkBlocks;   // next unit's first item
+    const Item nxt = have_next ? fetch_item(d, it_next) : cur;
     bf16x8 qv[4];
     {
-      const uint16_t* qrow = q + ((size_t)(u - unit_begin) * G + j) * kDim + 8 * kg;
+      const uint16_t* qrow = q + ((size_t)(cur.u - unit_begin) * G + jq) * kDim + 8 * kg;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        u32x4 x = {0u, 0u, 0u, 0u};
-        if (j < G) x = *reinterpret_cast<const u32x4*>(qrow + 32 * s);
+        u32x4 x = *reinterpret_cast<const u32x4*>(qrow + 32 * s);
+        if (!head_lane) x = u32x4{0u, 0u, 0u, 0u};
         qv[s] = as_bf16x8(x);
       }
     }
-    const uint16_t* kb = d.K + ((size_t)u * d.cap + e0) * kDim;
-    const uint16_t* vb = d.V + ((size_t)u * d.cap + e0) * kDim;
-    float* lg = d.logits + ((size_t)u * G + (j < G ? j : 0)) * d.cap + e0;
-    const bool store_lg = j < G;
+    const size_t run_off = (size_t)cur.u * unit_elems + (size_t)fb * kBlkElems + lane * 8;
+    const uint16_t* kcur = d.K + run_off;
+    const uint16_t* vcur = d.V + run_off;
+    // after the run's last block the stream continues with the next run, or re-reads this block at the very end
+    const size_t tail_off = have_next ? (size_t)nxt.u * unit_elems + (size_t)nxt.c * kChunk * kDim + lane * 8
+                                      : run_off + (size_t)(nblk - 1) * kBlkElems;
+    // logits of a block are stored as [head][32 entries]: 128 G contiguous bytes, 16 per lane
+    float* lg_dst = d.logits + ((size_t)cur.u * d.cap + (size_t)fb * kBlk) * G + 4 * min(lane, 8 * G - 1);
     f32x4 acc[8];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
-    KFrag ka, kb2;
-    VFrag va;
-    load_k(ka, kb, lane);
-    load_v(va, vb, lane);
     int blk = 0;
+
+    auto step = [&](const KFrag& kc, KFrag& kn) -> bool {
+      const bool last = blk + 1 == nblk;
+      const uint16_t* kn_ptr = last ? d.K + tail_off : kcur + (size_t)(blk + 1) * kBlkElems;
+      const uint16_t* vn_ptr = last ? d.V + tail_off : vcur + (size_t)(blk + 1) * kBlkElems;
+      load_k(kn, kn_ptr);
+      scan_block(kc, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk, run_valid, lds_lg, lg_dst, G, lane);
+      load_v(va, vn_ptr);
+      ++blk;
+      return last;
+    };
+    bool in_a = true;       // which K buffer holds the block to compute next
     while (true) {
-      const bool more = blk + 1 < nblk;
-      if (more) load_k(kb2, kb + (size_t)(blk + 1) * kBlkElems, lane);
-      scan_block(ka, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk + 4 * kg, n_valid, lg, store_lg, lane);
-      if (!more) break;
-      ++blk;
-      load_v(va, vb + (size_t)blk * kBlkElems, lane);
-      const bool more2 = blk + 1 < nblk;
-      if (more2) load_k(ka, kb + (size_t)(blk + 1) * kBlkElems, lane);
-      scan_block(kb2, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk + 4 * kg, n_valid, lg, store_lg, lane);
-      if (!more2) break;
-      ++blk;
-      load_v(va, vb + (size_t)blk * kBlkElems, lane);
+      if (step(ka, kb)) { in_a = false; break; }
+      if (step(kb, ka)) { in_a = true; break; }
     }
+    // ---- publish the run's partial
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
-    const size_t slot = (size_t)u * d.max_chunks + c;
-    if (j < G && kg == 0) {
+    const size_t slot = (size_t)cur.u * d.slots + (fb == 0 ? 0 : 1 + fb / kChunkBlocks);
+    if (head_lane && kg == 0) {
       d.ml[(slot * G + j) * 2] = m_run;
       d.ml[(slot * G + j) * 2 + 1] = l_run;
     }
+    if (lane == 0) d.stamp[slot] = seq;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int head = 4 * kg + v;
@@ -372,6 +533,14 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) dst[16 * dt] = acc[dt][v];
       }
+    }
+    if (!have_next) break;
+    b_cur = b_next;
+    it = it_next;
+    cur = nxt;
+    if (!in_a) {        // keep the invariant "next block to compute is in ka"
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ka.k[i] = kb.k[i];
     }
   }
 }
@@ -412,11 +581,23 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
   if (k == 1) {
     u64 best = ~0ull;
     int best_i = -1;
-    for (int i = tid; i < n; i += kThreads) {
-      const u64 key = evict_key(val[i], d.pos[base + i]);
-      if (key < best) {
-        best = key;
-        best_i = i;
+    for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+      int ps[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + r * kThreads;
+        ps[r] = i < n ? d.pos[base + i] : 0;
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + r * kThreads;
+        if (i < n) {
+          const u64 key = evict_key(val[i], ps[r]);
+          if (key < best) {
+            best = key;
+            best_i = i;
+          }
+        }
       }
     }
     const u64 gbest = block_min_u64(best, rb, phase, tid);
@@ -514,7 +695,9 @@ __device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, 
     const int prev = atomicAdd(&d.sc[SC_DONE], 1);
     if (prev == (int)gridDim.x - 1) {
       d.sc[SC_DONE] = 0;
-      d.sc[SC_N_ITEMS] = 0;
+      d.sc[SC_CLAIM] = 0;
+      d.sc[SC_CLAIM + 1] = 0;
+      d.sc[SC_SEQ] = d.sc[SC_SEQ] + 1;
       if (advance) {
         d.sc[SC_T] = t + 1;
         d.sc[SC_WINDOW_STEPS] = d.sc[SC_WINDOW_STEPS] + 1;
@@ -524,23 +707,42 @@ __device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, 
   }
 }
 
-// Merge the scan partials of unit u.  Leaves sM[g] (global max), sInv[g]
-// (1 / softmax denominator) in LDS and, if `out` is given, the attention output.
-__device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, int nch, float* sM, float* sInv, float* sW,
-                                               void* out, int tid) {
+// Merge the scan partials of unit u (the slots stamped by this launch).  Leaves
+// sM[g] (global max) and sInv[g] (1 / softmax denominator) in LDS and, if `out`
+// is given, writes the attention output.
+__device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, int nch, int seq, float* sM, float* sInv,
+                                               float* sW, void* out, int tid) {
   const int G = d.G;
-  const size_t slot0 = (size_t)u * d.max_chunks;
+  const size_t slot0 = (size_t)u * d.slots;
+  const int ns = nch + 1;
+  // weights: sW[s * 8 + g] = exp2(m_s - M) for live slots, 0 for the others
+  for (int i = tid; i < ns * kMaxGroup; i += kThreads) {
+    const int sidx = i >> 3, g = i & 7;
+    float m = -INFINITY;
+    if (g < G && d.stamp[slot0 + sidx] == seq) m = d.ml[((slot0 + sidx) * G + g) * 2];
+    sW[i] = m;
+  }
+  __syncthreads();
   if (tid < G) {
     const int g = tid;
     float M = -INFINITY;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, d.ml[((slot0 + c) * G + g) * 2]);
-    float Lsum = 0.f;
-    for (int c = 0; c < nch; ++c) {
-      const float w = fast_exp2(d.ml[((slot0 + c) * G + g) * 2] - M);
-      sW[c * kMaxGroup + g] = w;
-      Lsum += d.ml[((slot0 + c) * G + g) * 2 + 1] * w;
-    }
+    for (int sidx = 0; sidx < ns; ++sidx) M = fmaxf(M, sW[sidx * kMaxGroup + g]);
     sM[g] = M;
+  }
+  __syncthreads();
+  for (int i = tid; i < ns * kMaxGroup; i += kThreads) {
+    const int g = i & 7;
+    const float m = sW[i];
+    sW[i] = (g < G && m > -INFINITY) ? fast_exp2(m - sM[g]) : 0.f;
+  }
+  __syncthreads();
+  if (tid < G) {
+    const int g = tid;
+    float Lsum = 0.f;
+    for (int sidx = 0; sidx < ns; ++sidx) {
+      const float w = sW[sidx * kMaxGroup + g];
+      if (w != 0.f) Lsum += d.ml[((slot0 + sidx) * G + g) * 2 + 1] * w;
+    }
     sInv[g] = 1.0f / Lsum;
   }
   __syncthreads();
@@ -548,7 +750,10 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
     for (int idx = tid; idx < G * kDim; idx += kThreads) {
       const int g = idx >> 7, dim = idx & 127;
       float o = 0.f;
-      for (int c = 0; c < nch; ++c) o += d.partial[((slot0 + c) * G + g) * kDim + dim] * sW[c * kMaxGroup + g];
+      for (int sidx = 0; sidx < ns; ++sidx) {
+        const float w = sW[sidx * kMaxGroup + g];
+        if (w != 0.f) o += d.partial[((slot0 + sidx) * G + g) * kDim + dim] * w;   // dead slots hold stale data
+      }
       o *= sInv[g];
       const size_t oi = ((size_t)urel * G + g) * kDim + dim;
       if (d.out_bf16)
@@ -564,11 +769,25 @@ __device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const f
                                              int tid) {
   const int G = d.G;
   const float invG = 1.0f / (float)G;
-  const float* lg = d.logits + (size_t)u * G * d.cap;
-  for (int i = tid; i < n; i += kThreads) {
-    float a = 0.f;
-    for (int g = 0; g < G; ++g) a += fast_exp2(lg[(size_t)g * d.cap + i] - sM[g]) * sInv[g];
-    val[i] = a * invG;
+  const float* lg = d.logits + (size_t)u * G * d.cap;      // per block of 32 entries: [head][32]
+  for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+    float x[4][kMaxGroup];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + r * kThreads;
+      const float* row = lg + (size_t)(i >> 5) * (G * kBlk) + (i & 31);
+#pragma unroll
+      for (int g = 0; g < kMaxGroup; ++g) x[r][g] = (i < n && g < G) ? row[g * kBlk] : -INFINITY;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + r * kThreads;
+      float a = 0.f;
+#pragma unroll
+      for (int g = 0; g < kMaxGroup; ++g)
+        if (g < G) a += fast_exp2(x[r][g] - sM[g]) * sInv[g];
+      if (i < n) val[i] = a * invG;
+    }
   }
   __syncthreads();
 }
@@ -578,7 +797,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
-  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[kMaxChunks * kMaxGroup];
+  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[(kMaxChunks + 1) * kMaxGroup];
   __shared__ RedBuf rb;
   __shared__ int sh[8];
   const int tid = threadIdx.x;
@@ -590,7 +809,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   int phase = 0;
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
-    merge_partials(d, u, urel, nch, sM, sInv, sW, out, tid);
+    merge_partials(d, u, urel, nch, d.sc[SC_SEQ], sM, sInv, sW, out, tid);
     mean_weights(d, u, n, sM, sInv, val, tid);
 
     // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
@@ -645,36 +864,56 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
       }
     }
 
-    // ---- Alg. 1 Steps 2-3: scores
+    // ---- Alg. 1 Steps 2-3: scores (4 entries per thread and round: loads, table lookups, then stores)
     const bool has_new = d.pos[base + n - 1] == t;
+    const bool need_pos = d.reward_mode == 0 && !ties_all;
     u64 sfix = 0;
-    for (int i = tid; i < n; i += kThreads) {
-      const float a = val[i];
-      bool hit, store;
-      float reward;
-      if (d.reward_mode == 0) {
-        const uint32_t b = __float_as_uint(a);
-        hit = (b > theta) || (b == theta && (ties_all || d.pos[base + i] <= pos_cut));
-        if (i == n - 1 && has_new) hit = true;
-        store = hit;
-        reward = hit ? 1.0f : 0.0f;
-      } else {
-        hit = false;
-        store = true;
-        reward = a;
+    for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+      float crf[4], dec[4];
+      int tau[4], ps[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + r * kThreads;
+        const bool ok = i < n;
+        crf[r] = ok ? d.crf[base + i] : 0.f;
+        tau[r] = ok ? d.tau[base + i] : t;
+        ps[r] = (ok && need_pos) ? d.pos[base + i] : 0;
       }
-      const float crf = d.crf[base + i];
-      int delta = t - d.tau[base + i];
-      delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
-      float tmp = __fadd_rn(__fmul_rn(d.tab[delta], crf), reward);
-      if (tmp < FLT_MIN) tmp = 0.0f;
-      if (store) {
-        d.crf[base + i] = tmp;
-        d.tau[base + i] = t;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        int delta = t - tau[r];
+        delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+        dec[r] = d.tab[delta];
       }
-      d.flags[base + i] = hit ? FLAG_HIT : 0;
-      val[i] = tmp;
-      sfix += (u64)floorf(tmp * kFixedOne);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + r * kThreads;
+        if (i < n) {
+          const float a = val[i];
+          bool hit, store;
+          float reward;
+          if (d.reward_mode == 0) {
+            const uint32_t b = __float_as_uint(a);
+            hit = (b > theta) || (b == theta && (ties_all || ps[r] <= pos_cut));
+            if (i == n - 1 && has_new) hit = true;
+            store = hit;
+            reward = hit ? 1.0f : 0.0f;
+          } else {
+            hit = false;
+            store = true;
+            reward = a;
+          }
+          float tmp = __fadd_rn(__fmul_rn(dec[r], crf[r]), reward);
+          if (tmp < FLT_MIN) tmp = 0.0f;
+          if (store) {
+            d.crf[base + i] = tmp;
+            d.tau[base + i] = t;
+          }
+          d.flags[base + i] = hit ? FLAG_HIT : 0;
+          val[i] = tmp;
+          sfix += (u64)floorf(tmp * kFixedOne);
+        }
+      }
     }
     sfix = block_sum_u64(sfix, rb, phase, tid);   // barrier: val[] and the stores above are complete
     if (tid == 0) {
@@ -723,7 +962,7 @@ __global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin) 
 __global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, uint8_t* classes) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
-  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[kMaxChunks * kMaxGroup];
+  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[(kMaxChunks + 1) * kMaxGroup];
   __shared__ RedBuf rb;
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
@@ -731,7 +970,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, 
   const size_t base = (size_t)u * d.cap;
   int phase = 0;
   if (n > 0) {
-    merge_partials(d, u, urel, (n + kChunk - 1) / kChunk, sM, sInv, sW, nullptr, tid);
+    merge_partials(d, u, urel, (n + kChunk - 1) / kChunk, d.sc[SC_SEQ], sM, sInv, sW, nullptr, tid);
     mean_weights(d, u, n, sM, sInv, val, tid);
     const int kq = (3 * n) / 10;
     // order key: ascending = (weight asc, position desc); Crystal = kq largest, Slip = kq smallest
