@@ -172,7 +172,7 @@ def make_stream(cfg: Config, n_steps=None, *, tiny_heavy=None, drift=True) -> St
         for l in range(L):
             for b in range(Bz):
                 for h in range(Hkv):
-                    hp = np.concatenate([g.choice(P, 2, replace=False),
+                    hp = np.concatenate([g.choice(P, 2, replace=False) if P >= 2 else np.zeros(0, dtype=np.int64),
                                          P + g.choice(max(T // 2, 2), 2, replace=False)])
                     heavy[l, b, h, hp] = True
                     k_all[l, b, h, hp] = HEAVY_GAIN * m[l, b, h]

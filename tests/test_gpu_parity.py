@@ -1,0 +1,317 @@
+"""GPU parity of the HIP path against the CPU oracle on small workloads: geometries,
+call shapes (all layers / per layer), eviction on its own, re-budgeting, probe classes,
+the attention-weighted variant, bf16 output, edge cases, determinism, graph replay."""
+import numpy as np
+import pytest
+
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _mods():
+    from oracle import crystal_kv as ok
+    from paper_2601_16986_amd import ckv, workloads as wl
+    return ok, ckv, wl
+
+
+def _pair(cfg, cap, budgets=None, stream=None, n_steps=None, load=True, **kw):
+    ok, ckv, wl = _mods()
+    st = stream if stream is not None else wl.make_stream(cfg, n_steps)
+    budgets = wl.draw_budgets(cfg) if budgets is None else budgets
+    okw = {k: v for k, v in kw.items() if k != "out_dtype"}
+    o = ok.CrystalKVOracle(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, budgets,
+                           lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min,
+                           budget_max=cfg.budget_max, **okw)
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
+                      lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min,
+                      budget_max=cfg.budget_max, **kw)
+    if load and cfg.prompt > 0:
+        for l in range(cfg.n_layers):
+            o.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+            g.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+    return st, o, g
+
+
+def _small(name, **kw):
+    _, _, wl = _mods()
+    base = dict(n_layers=2, batch=2, prompt=45, decode_steps=40, budget=56, budget_min=1, budget_max=95,
+                adaptive=False, rebudget_interval=0)
+    base.update(kw)
+    return wl.scaled(wl.CONFIGS[name], **base)
+
+
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 2), (10, 2), (14, 2), (16, 2), (6, 2)])
+def test_lockstep_every_group_size(hq, hkv):
+    """G = 1, 4, 5, 7, 8, 3 query heads per KV head; prompt length not a multiple of the 32-entry block;
+    two layers and two sequences through the all-layers call; K/V rows checked after compaction."""
+    cfg = _small("tiny", n_q_heads=hq, n_kv_heads=hkv, seed=77 + hq)
+    st, o, g = _pair(cfg, cap=96)
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=10)
+    assert stats.resynced <= 2, stats.notes
+    assert g.status() == 0 and g.time() == cfg.prompt + cfg.decode_steps
+    g.close()
+
+
+def test_units_longer_than_a_chunk_and_ragged_tails():
+    """Budgets 300..700 so units span several 256-entry chunks with ragged last blocks, and the
+    scan's runs start in the middle of chunks; 7B-like group size 7."""
+    _, _, wl = _mods()
+    cfg = _small("qwen7b", n_layers=1, batch=3, n_q_heads=14, n_kv_heads=2, prompt=333, decode_steps=24,
+                 budget=500, budget_min=300, budget_max=735, seed=5)
+    budgets = np.array([[[300, 700], [513, 333], [641, 352]]], dtype=np.int32)
+    st, o, g = _pair(cfg, cap=736, budgets=budgets)
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=8)
+    assert stats.resynced <= 2, stats.notes
+    assert np.array_equal(g.lengths(), o.lengths())
+    g.close()
+
+
+def test_per_layer_calls():
+    """The shape a real model imposes: one call per layer, t advancing after the last layer."""
+    cfg = _small("llama8b", n_layers=3, n_q_heads=8, n_kv_heads=2, seed=11)
+    st, o, g = _pair(cfg, cap=96)
+    stats = parity.LockstepStats()
+    import torch
+    for s in range(20):
+        ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        outs = [g.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l) for l in range(cfg.n_layers)]
+        assert g.time() == cfg.prompt + s + 1
+        out = torch.stack(outs).cpu().numpy()
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+        for key, rec in recs.items():
+            parity.compare_unit(g, o, key, rec, stats)
+    assert stats.resynced <= 2
+    # layers out of order are refused, and so is a second prompt for a layer that holds entries
+    _, ckv, _ = _mods()
+    with pytest.raises(ckv.CkvError) as e1:
+        g.decode_step(st.q[20, 1], st.k_new[20, 1], st.v_new[20, 1], layer=1)
+    assert e1.value.code == ckv.ESTATE
+    with pytest.raises(ckv.CkvError) as e2:
+        g.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    assert e2.value.code == ckv.ESTATE
+    g.close()
+
+
+def test_eviction_on_its_own_and_after_a_budget_cut():
+    """Steps without eviction let caches grow past their budgets; ckv_evict then removes many entries
+    at once (the general select + compaction path), also after budgets were cut."""
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, prompt=40, decode_steps=60, budget=50, seed=3)
+    st, o, g = _pair(cfg, cap=128)
+    stats = parity.LockstepStats()
+    s = 0
+    for rnd in range(3):
+        for _ in range(12):
+            ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+            out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False).cpu().numpy()
+            assert parity.out_error(out, ref) <= parity.OUT_TOL
+            for key, rec in recs.items():
+                parity.compare_unit(g, o, key, rec, stats)
+            s += 1
+        if rnd == 1:                      # cut budgets: k becomes large
+            newb = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), 23, dtype=np.int32)
+            newb[0, 0, 0] = 7
+            g.set_budgets(newb)
+            for key, u in o.units.items():
+                u.budget = int(newb[key])
+        ev = o.evict()
+        g.evict()
+        for key in o.units:
+            e = g.export_unit(*key)
+            u = o.units[key]
+            assert e["n"] == u.n == u.budget
+            assert np.array_equal(e["evicted_pos"], ev[key])
+            assert np.all(e["evicted_flags"] == 2)
+            og, oo = np.argsort(e["pos"]), np.argsort(u.pos)
+            assert np.array_equal(e["pos"][og], u.pos[oo])
+            assert np.array_equal(e["crf"][og], u.crf[oo]) and np.array_equal(e["tau"][og], u.tau[oo])
+            assert np.array_equal(e["K"][og], u.K[oo].astype(np.float32))
+            assert np.array_equal(e["V"][og], u.V[oo].astype(np.float32))
+    assert stats.resynced <= 2
+    g.close()
+
+
+def test_rebudget_matches_alg2_oracle():
+    """Alg. 2 on the device: budgets bit-identical to the oracle's, totals conserved, bounds kept;
+    the next fused eviction brings the caches down to the new budgets."""
+    _, _, wl = _mods()
+    cfg = wl.scaled(wl.CONFIGS["qwen14b"], n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, prompt=70,
+                    decode_steps=48, budget=64, budget_min=16, budget_max=120, seed=9)
+    st, o, g = _pair(cfg, cap=160)
+    total0 = o.budgets().sum(axis=(0, 2))
+    stats = parity.LockstepStats()
+    s = 0
+    for rnd in range(3):
+        for _ in range(12):
+            ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+            g.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+            for key, rec in recs.items():
+                parity.compare_unit(g, o, key, rec, stats)
+            s += 1
+        assert stats.resynced == 0, "window sums are only comparable without re-synchronised units"
+        nb = o.rebudget()
+        g.rebudget()
+        gb = g.budgets()
+        assert np.array_equal(gb, nb), (gb - nb)
+        assert np.array_equal(gb.sum(axis=(0, 2)), total0)
+        assert gb.min() >= cfg.budget_min and gb.max() <= cfg.budget_max
+        assert not np.array_equal(gb, wl.draw_budgets(cfg)) or rnd > 0
+    g.close()
+
+
+def test_probe_classes():
+    """Sec. 3 classes under the answer-probe query: counts floor(0.3 n) and the same entries as the oracle."""
+    _, _, wl = _mods()
+    cfg = wl.scaled(wl.CONFIGS["tiny"], decode_steps=100)
+    st, o, g = _pair(cfg, cap=160)
+    parity.lockstep(g, o, st, 100)
+    cls = g.probe(0, st.probe_q[0]).cpu().numpy()
+    t_before = g.time()
+    for (l, b, h), u in o.units.items():
+        ref, abar = o.probe((l, b, h), st.probe_q[l, b, h * o.G:(h + 1) * o.G])
+        e = g.export_unit(l, b, h, with_kv=False)
+        got = cls[b, h, :e["n"]]
+        by_pos_g = dict(zip(e["pos"].tolist(), got.tolist()))
+        by_pos_o = dict(zip(u.pos.tolist(), ref.tolist()))
+        # entries whose weight is within rounding of a class boundary may fall either way
+        srt = np.sort(abar)
+        k = (3 * u.n) // 10
+        edges = [srt[k - 1], srt[k], srt[u.n - k - 1], srt[u.n - k]]
+        for p_, a in zip(u.pos.tolist(), abar.tolist()):
+            if by_pos_g[p_] != by_pos_o[p_]:
+                assert min(abs(a - x) / x for x in edges) < 1e-5, (p_, a)
+        assert (got == 2).sum() == k and (got == 0).sum() == k
+    assert g.time() == t_before and np.array_equal(g.lengths(), o.lengths())
+    g.close()
+
+
+def test_attention_weighted_reward_variant():
+    """reward = mean attention weight (labelled variant): scores within 1e-5 relative of the oracle's,
+    same evictions unless the last kept and first evicted scores are closer than that."""
+    ok, ckv, _ = _mods()
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=30, seed=21)
+    st, o, g = _pair(cfg, cap=96, reward_mode=ok.REWARD_ATTN_WEIGHTED)
+    for s in range(cfg.decode_steps):
+        ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).cpu().numpy()
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+        for key, rec in recs.items():
+            u = o.units[key]
+            e = g.export_unit(*key, with_kv=False)
+            if set(e["pos"].tolist()) != set(u.pos.tolist()):
+                assert rec.evict_gap < 1e-5, (key, s, rec.evict_gap)
+                parity.sync_unit_to_gpu(g, o, key)
+                continue
+            og, oo = np.argsort(e["pos"]), np.argsort(u.pos)
+            assert np.allclose(e["crf"][og], u.crf[oo], rtol=1e-5, atol=1e-30)
+            assert np.array_equal(e["tau"][og], u.tau[oo])
+            parity.sync_unit_to_gpu(g, o, key)        # keep both sides on the oracle's exact scores
+    g.close()
+
+
+def test_bf16_output():
+    """out_dtype bf16: within one bf16 ulp of the oracle's output rounded to bf16."""
+    _, ckv, wl = _mods()
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=8, seed=31)
+    st, o, g = _pair(cfg, cap=96, out_dtype=ckv.BF16)
+    for s in range(cfg.decode_steps):
+        ref, _ = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).float().cpu().numpy()
+        ref16 = wl.bf16_round(ref.astype(np.float32))
+        ulp = np.maximum(np.abs(ref16), 2.0 ** -126) * 2.0 ** -7
+        assert np.all(np.abs(out - ref16) <= ulp + parity.OUT_TOL * 1e-2 * np.abs(ref).max())
+    g.close()
+
+
+@pytest.mark.parametrize("lam,top_p", [(0.0, 0.9), (1.0, 0.9), (0.7, 1.0), (0.5, 0.5), (0.99, 0.9)])
+def test_parameter_corners(lam, top_p):
+    """lambda = 0 (LRU) and 1 (LFU), p >= 1 (every entry hit), a low p, and a decay table of ~9000 entries."""
+    _, _, wl = _mods()
+    cfg = wl.scaled(_small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=30, seed=41), lam=lam, top_p=top_p)
+    st, o, g = _pair(cfg, cap=96)
+    stats = parity.lockstep(g, o, st, cfg.decode_steps)
+    assert stats.resynced <= 2, stats.notes
+    if top_p >= 1.0:
+        for key in o.units:
+            assert np.all(g.export_unit(*key, with_kv=False)["flags"] & 1)
+    g.close()
+
+
+def test_empty_start_capacity_and_argument_errors():
+    ok, ckv, wl = _mods()
+    cfg = _small("tiny", n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, prompt=0, decode_steps=40, budget=20,
+                 budget_max=31, seed=51)
+    st, o, g = _pair(cfg, cap=32, load=False)
+    # no prompt: the first step attends over the new entry alone
+    stats = parity.lockstep(g, o, st, 10)
+    assert np.array_equal(g.lengths(), o.lengths()) and o.lengths().max() == 10
+    # without eviction the caches fill; an append to a full unit is reported, nothing is written out of bounds
+    for s in range(10, 36):
+        g.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+    assert g.status() == ckv.ECAPACITY and g.status() == 0      # reported once, then cleared
+    assert g.lengths().max() == 32
+    # argument errors
+    with pytest.raises(ckv.CkvError) as e1:
+        g.decode_step(st.q[0, 0], st.k_new[0, 0], st.v_new[0, 0], layer=5)
+    assert e1.value.code == ckv.EINVAL
+    with pytest.raises(ckv.CkvError) as e2:
+        g.load_prompt(0, np.zeros((1, 2, 4, 128), np.float32), np.zeros((1, 2, 4, 128), np.float32))
+    assert e2.value.code == ckv.EINVAL                          # a prompt longer than t0
+    with pytest.raises(ckv.CkvError):
+        g.set_budgets(np.full((1, 1, 2), 32))                   # budget must stay below cap
+    with pytest.raises(ckv.CkvError):
+        ckv.CrystalKV(1, 1, 8, 2, 64, 32, np.full((1, 1, 2), 8))   # head_dim 64
+    g.close()
+
+
+def test_runs_are_deterministic():
+    """Same inputs twice: outputs and state bit-identical (no atomics on floating-point data)."""
+    cfg = _small("qwen14b", n_layers=2, batch=2, n_q_heads=10, n_kv_heads=2, prompt=300, decode_steps=12,
+                 budget=320, budget_max=351, seed=61)
+    res = []
+    for _ in range(2):
+        st, o, g = _pair(cfg, cap=352)
+        outs = [g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).cpu().numpy().copy() for s in range(cfg.decode_steps)]
+        state = [g.export_unit(*key) for key in o.units]
+        res.append((outs, state))
+        g.close()
+    for a, b in zip(res[0][0], res[1][0]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for a, b in zip(res[0][1], res[1][1]):
+        for f in ("pos", "crf", "tau", "flags", "K", "V"):
+            assert np.array_equal(a[f], b[f]), f
+
+
+def test_hip_graph_replay_matches_eager():
+    """Four decode steps captured into one HIP graph (time lives in device memory) and replayed three
+    times, with eager work between the replays; every replay must equal the eager run."""
+    import torch
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=12, seed=71)
+    st, o, g = _pair(cfg, cap=96)
+    _, _, g2 = _pair(cfg, cap=96)
+    dev = g.device
+    as_dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(torch.bfloat16)
+    q, k, v = as_dev(st.q), as_dev(st.k_new), as_dev(st.v_new)
+    eager = [g2.decode_step(q[s], k[s], v[s]).clone() for s in range(12)]
+    torch.cuda.synchronize()
+    sq, sk, sv = q[:4].clone(), k[:4].clone(), v[:4].clone()          # static input buffers of the graph
+    outs = [torch.empty_like(eager[0]) for _ in range(4)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(4):
+            g.decode_step(sq[i], sk[i], sv[i], out=outs[i])
+    for rep in range(3):
+        sq.copy_(q[4 * rep:4 * rep + 4]); sk.copy_(k[4 * rep:4 * rep + 4]); sv.copy_(v[4 * rep:4 * rep + 4])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        scratch = (torch.randn(1 << 16, device=dev) * 2).sum().item()   # unrelated eager work between replays
+        assert np.isfinite(scratch)
+        for i in range(4):
+            assert torch.equal(outs[i], eager[4 * rep + i]), (rep, i)
+    assert g.time() == cfg.prompt + 12
+    for key in o.units:
+        a, b = g.export_unit(*key), g2.export_unit(*key)
+        for f in ("pos", "crf", "tau", "flags"):
+            assert np.array_equal(a[f], b[f])
+    g.close(); g2.close()
