@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-layer", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    ap.add_argument("--probe-only", action="store_true",
+                    help="only run the plain streaming-read and copy kernels (4 GiB each): counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (units are independent; nothing is sharded); use --gpus 1",
@@ -125,6 +127,12 @@ def main():
     cfg = wl.CONFIGS[args.config]
     device = torch.device("cuda:0")
     torch.cuda.set_device(device)
+    from paper_2601_16986_amd import ckv
+    read_gbps = ckv.bandwidth_probe(4 << 30, copy=False)
+    copy_gbps = ckv.bandwidth_probe(4 << 30, copy=True)
+    if args.probe_only:
+        print(json.dumps({"stream_read_gbps": read_gbps, "copy_gbps": copy_gbps, "bytes": 4 << 30}))
+        return
     g, budgets, (rq, rk, rv) = build_workload(cfg, device)
     out = torch.empty(rq.shape[1:], dtype=torch.float32, device=device)
     steps = max(RING, args.steps // RING * RING)
@@ -219,9 +227,12 @@ def main():
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "per_layer_graph_ms_per_step": per_layer,
+        "stream_read_gbps": read_gbps,          # plain non-temporal streaming read measured on this machine
+        "copy_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "bytes_per_launch": scan_bytes, "avg_launch_ms": scan_avg_ms, "launches": launches},
+                     "bytes_per_launch": scan_bytes, "avg_launch_ms": scan_avg_ms, "launches": launches,
+                     "frac_of_stream_read": achieved / read_gbps},
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, budgets)

@@ -205,6 +205,14 @@ int ckv_import_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int3
 int ckv_profile_enable(ckv_ctx* ctx, int32_t on);
 int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
 
+/* Measurement aid, independent of any context: streams `bytes` (a multiple of
+ * 16 KiB is read completely; at least 1 MiB) from dev `src` with plain 16-byte
+ * non-temporal loads (dst == NULL; `sink` is a dev uint32 that is never
+ * actually written) or copies them to dev `dst`.  Gives the on-box bandwidth
+ * ceiling next to which the scan kernel is reported, and kernels of known size
+ * for calibrating profiler byte counters.  Pointers 16-byte aligned. */
+int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, void* stream);
+
 const char* ckv_strerror(int code);
 const char* ckv_last_error(const ckv_ctx* ctx);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_load_cache", "ckv_decode_step", "ckv_evict",
     "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
-    "ckv_profile_read", "ckv_strerror", "ckv_last_error",
+    "ckv_profile_read", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
 ]
 
 
@@ -81,6 +81,7 @@ def load():
     lib.ckv_import_unit.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
     lib.ckv_profile_enable.argtypes = [vp, i32]
     lib.ckv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.ckv_bandwidth_probe.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.ckv_strerror.restype = C.c_char_p
     lib.ckv_strerror.argtypes = [C.c_int]
     lib.ckv_last_error.restype = C.c_char_p
@@ -295,3 +296,30 @@ class CrystalKV:
         ms, n = C.c_double(0.0), C.c_int32(0)
         self._check(self.lib.ckv_profile_read(self.ctx, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+
+def bandwidth_probe(n_bytes=4 << 30, copy=False, reps=5, device="cuda:0"):
+    """GB/s of the library's plain streaming-read (or copy: read + written bytes) kernel on this machine."""
+    import torch
+    lib = load()
+    dev = torch.device(device)
+    with torch.cuda.device(dev):
+        src = torch.ones(n_bytes // 4, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src) if copy else None
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        stream = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def launch():
+            rc = lib.ckv_bandwidth_probe(src.data_ptr(), dst.data_ptr() if copy else None, n_bytes, sink.data_ptr(), stream)
+            if rc != OK:
+                raise CkvError(rc, "ckv_bandwidth_probe")
+
+        launch()
+        a.record()
+        for _ in range(reps):
+            launch()
+        b.record()
+        torch.cuda.synchronize(dev)
+        ms = a.elapsed_time(b) / reps
+    return n_bytes * (2 if copy else 1) / (ms * 1e-3) / 1e9

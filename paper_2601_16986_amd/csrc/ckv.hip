@@ -550,6 +550,22 @@ int ckv_profile_read(ckv_ctx* c, double* scan_ms, int32_t* launches) {
   return CKV_OK;
 }
 
+int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes < (1u << 20) || ((uintptr_t)src % 16) != 0 || ((uintptr_t)dst % 16) != 0) return CKV_EINVAL;
+  int devid = 0, n_cu = 0;
+  if (hipGetDevice(&devid) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, devid) != hipSuccess || n_cu <= 0)
+    return CKV_EHIP;
+  const size_t n_vec = bytes / 16;
+  if (dst)
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)(n_cu * 32)), dim3(kThreads), 0, (hipStream_t)stream,
+                       (const u32x4*)src, (u32x4*)dst, n_vec);
+  else
+    hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)n_cu), dim3(kThreads), 0, (hipStream_t)stream,
+                       (const u32x4*)src, n_vec, (uint32_t*)sink);
+  return hipGetLastError() == hipSuccess ? CKV_OK : CKV_EHIP;
+}
+
 const char* ckv_strerror(int code) {
   switch (code) {
     case CKV_OK: return "ok";

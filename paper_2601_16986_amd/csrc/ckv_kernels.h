@@ -166,6 +166,29 @@ __global__ void fill_u32_kernel(uint32_t* p, uint32_t v, size_t count) {
   for (; i < count; i += stride) p[i] = v;
 }
 
+// ------------------------------------------------------------------ bandwidth probes
+// Plain streaming kernels of known size: the on-box ceiling the scan kernel is
+// compared with, and the calibration of the profiler's fetch/write counters.
+__global__ __launch_bounds__(kThreads) void probe_read_kernel(const u32x4* __restrict__ src, size_t n_vec, uint32_t* sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t nw = (size_t)gridDim.x * (kThreads / 64), gw = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (size_t base = gw * 1024; base + 1024 <= n_vec; base += nw * 1024) {     // 16 KB per wavefront and round
+    u32x4 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = __builtin_nontemporal_load(src + base + i * 64 + lane);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc ^= v[i];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = 1u;          // keeps the loads alive
+}
+
+__global__ __launch_bounds__(kThreads) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n_vec) {
+  size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (; i < n_vec; i += stride) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------ cache load
 // grid: (ceil(P/32), units of the layer); converts 32 row-major rows to one
 // tiled block.  k, v: [units][P][128]; unit `urel` holds len[urel] (or P)
