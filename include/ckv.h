@@ -205,6 +205,14 @@ int ckv_import_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int3
 int ckv_profile_enable(ckv_ctx* ctx, int32_t on);
 int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
 
+/* Which kernels ckv_decode_step(layer = -1) uses: 0 = choose by unit count
+ * (default), 1 = separate scan and finish kernels (always used for single-layer
+ * calls), 2 = the fused per-unit kernel, which keeps the logits in LDS; it needs
+ * 4 * cap bytes of LDS per workgroup (CKV_EINVAL otherwise).  Results do not
+ * depend on the choice beyond floating-point summation order. */
+int ckv_set_path(ckv_ctx* ctx, int32_t mode);
+int ckv_path_info(ckv_ctx* ctx, int32_t* fused_available, int32_t* lds_main_bytes);
+
 /* Measurement aid, independent of any context: streams `bytes` (a multiple of
  * 16 KiB is read completely; at least 1 MiB) from dev `src` with plain 16-byte
  * non-temporal loads (dst == NULL; `sink` is a dev uint32 that is never

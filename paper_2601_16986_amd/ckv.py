@@ -24,7 +24,7 @@ EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_load_cache", "ckv_decode_step", "ckv_evict",
     "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
-    "ckv_profile_read", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
+    "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
 ]
 
 
@@ -81,6 +81,8 @@ def load():
     lib.ckv_import_unit.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
     lib.ckv_profile_enable.argtypes = [vp, i32]
     lib.ckv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.ckv_set_path.argtypes = [vp, i32]
+    lib.ckv_path_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
     lib.ckv_bandwidth_probe.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.ckv_strerror.restype = C.c_char_p
     lib.ckv_strerror.argtypes = [C.c_int]
@@ -288,6 +290,15 @@ class CrystalKV:
         pos = np.ascontiguousarray(pos, np.int32)
         self._check(self.lib.ckv_import_unit(self.ctx, layer, seq, head, n, _np_ptr(Kb), _np_ptr(Vb), _np_ptr(crf),
                                              _np_ptr(tau), _np_ptr(pos), int(t_unit)))
+
+    def set_path(self, mode):
+        """0 = auto, 1 = separate scan/finish kernels, 2 = fused per-unit kernel."""
+        self._check(self.lib.ckv_set_path(self.ctx, int(mode)))
+
+    def path_info(self):
+        ok_, lds = C.c_int32(0), C.c_int32(0)
+        self._check(self.lib.ckv_path_info(self.ctx, C.byref(ok_), C.byref(lds)))
+        return bool(ok_.value), lds.value
 
     def profile_enable(self, on=True):
         self._check(self.lib.ckv_profile_enable(self.ctx, 1 if on else 0))

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "ckv_kernels.h"
+#include "ckv_unit_kernel.h"
 
 using namespace ckv;
 
@@ -25,6 +26,12 @@ struct ckv_ctx {
   int next_layer = 0;
   int n_cu = 256;
   size_t finish_lds = 0;
+  // fused path (unit_kernel)
+  int path_mode = 0;            // 0 auto, 1 separate kernels, 2 fused kernel
+  bool fused_ok = false;
+  int fused_grid = 0;
+  int lds_main = 0;
+  size_t fused_lds = 0;
   std::vector<uint8_t> prompt_loaded;
   std::string err;
   // scan timing
@@ -99,7 +106,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -122,6 +129,7 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.ml = take(U * (mc + 1) * G * 2 * 4);
   c.logits = take(U * G * (size_t)l->cap * 4);
   c.btotal = take((size_t)l->batch * 8);
+  c.order = take(U * 4);
   c.total = off;
   return c;
 }
@@ -143,6 +151,8 @@ int upload_budgets(ckv_ctx* c, const int32_t* budgets, hipStream_t s) {
       for (int h = 0; h < l.n_kv_heads; ++h) tot[b] += budgets[((size_t)i * l.batch + b) * l.n_kv_heads + h];
   CKV_HIP(c, hipMemcpyAsync(c->dev.budget, budgets, (size_t)c->units * 4, hipMemcpyHostToDevice, s));
   CKV_HIP(c, hipMemcpyAsync(c->dev.btotal, tot.data(), (size_t)l.batch * 8, hipMemcpyHostToDevice, s));
+  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, s, c->dev);
+  CKV_HIP(c, hipGetLastError());
   CKV_HIP(c, hipStreamSynchronize(s));
   return CKV_OK;
 }
@@ -228,6 +238,21 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     }
   }
 
+  // fused kernel: two workgroups per CU, each with half of the CU's LDS at most
+  {
+    const int static_lds = 12 * 1024;                          // upper bound of unit_kernel's static LDS
+    const int evm_bytes = ((layout->cap + 31) / 32) * 4;
+    int per_wg = max_lds < 80 * 1024 ? max_lds : 80 * 1024;
+    int main_bytes = (per_wg - static_lds - evm_bytes) & ~127;
+    c->fused_ok = main_bytes >= 4 * layout->cap;                // every entry's value must fit
+    c->lds_main = main_bytes;
+    c->fused_lds = (size_t)main_bytes + evm_bytes;
+    c->fused_grid = 2 * c->n_cu;
+    if (c->fused_ok && hipFuncSetAttribute(reinterpret_cast<const void*>(unit_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds) != hipSuccess)
+      c->fused_ok = false;
+  }
+
   Dev& d = c->dev;
   d.L = layout->n_layers;
   d.Bz = layout->batch;
@@ -265,6 +290,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.stamp = (int32_t*)(ws + cv.stamp);
   d.logits = (float*)(ws + cv.logits);
   d.btotal = (long long*)(ws + cv.btotal);
+  d.order = (int32_t*)(ws + cv.order);
 
   auto bail = [&](int rc) {
     delete c;
@@ -283,6 +309,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   if ((rc = fill32(c, d.t_unit, (uint32_t)(params->t0 - 1), (size_t)c->units, s))) return bail(rc);
   if ((rc = fill32(c, d.sc + SC_T, (uint32_t)params->t0, 1, s))) return bail(rc);
   if ((rc = fill32(c, d.sc + SC_SEQ, 1u, 1, s))) return bail(rc);
+  if ((rc = fill32(c, d.sc + SC_QUEUE, (uint32_t)c->fused_grid, 1, s))) return bail(rc);
   if (hipMemcpyAsync((void*)d.tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) return bail(CKV_EHIP);
   if ((rc = upload_budgets(c, budgets, s))) return bail(rc);
   if (hipStreamSynchronize(s) != hipSuccess) return bail(CKV_EHIP);
@@ -337,8 +364,10 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_loaded[l] = 1;
   hipStream_t s = (hipStream_t)stream;
 
+  const bool fused = c->fused_ok && layer == -1 &&
+                     (c->path_mode == 2 || (c->path_mode == 0 && count >= 4 * c->fused_grid));
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)k_new, (const uint16_t*)v_new, 1);
+                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1);
   CKV_HIP(c, hipGetLastError());
 
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -354,6 +383,13 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     e1 = c->ev[c->ev_used + 1];
     c->ev_used += 2;
     CKV_HIP(c, hipEventRecord(e0, s));
+  }
+  if (fused) {
+    hipLaunchKernelGGL(unit_kernel, dim3((unsigned)c->fused_grid), dim3(kThreads), c->fused_lds, s, c->dev,
+                       (const uint16_t*)q, out, flags & CKV_FUSE_EVICT, advance, c->lds_main);
+    CKV_HIP(c, hipGetLastError());
+    if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
+    return CKV_OK;
   }
   const long long max_items = (long long)count * c->dev.max_chunks;
   long long blocks = 2ll * c->n_cu;
@@ -381,6 +417,8 @@ int ckv_rebudget(ckv_ctx* c, void* stream) {
   if (!c) return CKV_EINVAL;
   if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
   hipLaunchKernelGGL(rebudget_kernel, dim3((unsigned)c->lay.batch), dim3(kThreads), 0, (hipStream_t)stream, c->dev);
+  CKV_HIP(c, hipGetLastError());
+  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, c->dev);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
 }
@@ -564,6 +602,20 @@ int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, vo
     hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)n_cu), dim3(kThreads), 0, (hipStream_t)stream,
                        (const u32x4*)src, n_vec, (uint32_t*)sink);
   return hipGetLastError() == hipSuccess ? CKV_OK : CKV_EHIP;
+}
+
+int ckv_set_path(ckv_ctx* c, int32_t mode) {
+  if (!c || mode < 0 || mode > 2) return CKV_EINVAL;
+  if (mode == 2 && !c->fused_ok) return fail(c, CKV_EINVAL, "cap too large for the fused kernel's LDS");
+  c->path_mode = mode;
+  return CKV_OK;
+}
+
+int ckv_path_info(ckv_ctx* c, int32_t* fused_available, int32_t* lds_main_bytes) {
+  if (!c) return CKV_EINVAL;
+  if (fused_available) *fused_available = c->fused_ok ? 1 : 0;
+  if (lds_main_bytes) *lds_main_bytes = c->lds_main;
+  return CKV_OK;
 }
 
 const char* ckv_strerror(int code) {

@@ -30,11 +30,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
 // SC_CLAIM is a 64-bit counter (8-byte aligned): low word = work items published, high word = their blocks
-enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_SEQ = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_CLAIM = 8, SC_COUNT = 64 };
+enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_SEQ = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_QUEUE = 6, SC_CLAIM = 8, SC_COUNT = 64 };
 enum { FLAG_HIT = 1, FLAG_SLIP = 2 };
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 128;           // cap <= 32768
 constexpr float kFixedOne = 1048576.0f;   // 2^20: resolution of the aggregated-CRF accumulator
+constexpr int kTabLds = 256;              // decay-table entries kept in LDS by the LRFU kernels
 
 struct Dev {
   int32_t L, Bz, Hq, Hkv, G, cap, units, max_chunks, slots, out_bf16;   // slots = partial slots per unit
@@ -60,6 +61,7 @@ struct Dev {
   int32_t* stamp;        // [units*slots] launch sequence number that last wrote the slot
   float* logits;         // [units][cap/32][G][32] scaled logits (base-2 domain)
   long long* btotal;     // [Bz] budget total per sequence
+  int32_t* order;        // [units] unit indices by descending budget (schedule of the fused kernel)
 };
 
 
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_be
 
 // ------------------------------------------------------------------ prep
 // 32 threads per unit, 32 units per workgroup: append the new entry (unless
-// `append` is 0) and publish the unit's scan work items {unit, chunk, entries
+// bit 0 of `append` is clear) and, unless bit 1 is set, publish the unit's scan work items {unit, chunk, entries
 // from the chunk's start to the unit's end, blocks in the list before this
 // item}.  One 64-bit atomic per workgroup claims the list range and the block
 // range together, so the list is sorted by block offset and unit-major (its
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
   int n = 0;
   if (active) {
     n = d.n[u];
-    if (append) {
+    if (append & 1) {
       const int t = d.sc[SC_T];
       if (n >= d.cap) {
         if (sub == 0) atomicOr(&d.sc[SC_STATUS], 1);
@@ -299,6 +301,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
       }
     }
   }
+  if (append & 2) return;                 // the fused kernel schedules whole units: no work list
   const int nch = active ? (n + kChunk - 1) / kChunk : 0;
   const int nblk = active ? (n + kBlk - 1) / kBlk : 0;
   if (sub == 0) {
@@ -360,7 +363,7 @@ constexpr int kLgRow = 36;     // floats per head row in the LDS tile (32 + pad 
 
 __device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, const bf16x8 (&qv)[4], f32x4 (&acc)[8],
                                            float& m_run, float& l_run, float c_scale, int e_base, int n_valid,
-                                           float* lds_lg, float* lg_dst, int G, int lane) {
+                                           float* lds_lg, int lds_row, float* lg_dst, int G, int lane) {
   const int j = lane & 15, kg = lane >> 4;
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -373,16 +376,21 @@ __device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, cons
     sv[v] = (e_base + 4 * kg + v < n_valid) ? s0[v] * c_scale : -INFINITY;
     sv[4 + v] = (e_base + 4 * kg + 16 + v < n_valid) ? s1[v] * c_scale : -INFINITY;
   }
+  // logits: row j of the LDS buffer (a wave-private staging tile, or the block's
+  // place in a resident logits tile); with lg_dst the tile is forwarded to memory
+  // as one contiguous 128 G-byte store
   if (j < G) {
-    *reinterpret_cast<f32x4*>(lds_lg + j * kLgRow + 4 * kg) = f32x4{sv[0], sv[1], sv[2], sv[3]};
-    *reinterpret_cast<f32x4*>(lds_lg + j * kLgRow + 16 + 4 * kg) = f32x4{sv[4], sv[5], sv[6], sv[7]};
+    *reinterpret_cast<f32x4*>(lds_lg + j * lds_row + 4 * kg) = f32x4{sv[0], sv[1], sv[2], sv[3]};
+    *reinterpret_cast<f32x4*>(lds_lg + j * lds_row + 16 + 4 * kg) = f32x4{sv[4], sv[5], sv[6], sv[7]};
   }
-  __builtin_amdgcn_wave_barrier();
-  if (lane < 8 * G) {
-    const f32x4 row = *reinterpret_cast<const f32x4*>(lds_lg + (lane >> 3) * kLgRow + 4 * (lane & 7));
-    *reinterpret_cast<f32x4*>(lg_dst + e_base * G) = row;
+  if (lg_dst) {
+    __builtin_amdgcn_wave_barrier();
+    if (lane < 8 * G) {
+      const f32x4 row = *reinterpret_cast<const f32x4*>(lds_lg + (lane >> 3) * lds_row + 4 * (lane & 7));
+      *reinterpret_cast<f32x4*>(lg_dst + e_base * G) = row;
+    }
+    __builtin_amdgcn_wave_barrier();
   }
-  __builtin_amdgcn_wave_barrier();
   float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
   bm = fmaxf(bm, __shfl_xor(bm, 16));
   bm = fmaxf(bm, __shfl_xor(bm, 32));
@@ -529,7 +537,7 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
       const uint16_t* kn_ptr = last ? d.K + tail_off : kcur + (size_t)(blk + 1) * kBlkElems;
       const uint16_t* vn_ptr = last ? d.V + tail_off : vcur + (size_t)(blk + 1) * kBlkElems;
       load_k(kn, kn_ptr);
-      scan_block(kc, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk, run_valid, lds_lg, lg_dst, G, lane);
+      scan_block(kc, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk, run_valid, lds_lg, kLgRow, lg_dst, G, lane);
       load_v(va, vn_ptr);
       ++blk;
       return last;
@@ -594,10 +602,20 @@ __device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, i
   }
 }
 
-// Alg. 1 Step 4 for one unit with n > B.  val[i] = CRF_temp of slot i (LDS,
-// `cap` floats, reused as scratch afterwards), evm = LDS bit mask of cap bits.
-__device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint32_t* evm, RedBuf& rb, int& phase,
-                            int* sh, int tid) {
+// Per-entry LDS values (mean weight, then CRF_temp) are reached through an
+// accessor: a plain array in the finish kernel, a view into the logits tile in
+// the fused unit kernel.
+struct ValLinear {
+  float* p;
+  __device__ __forceinline__ float& operator()(int i) const { return p[i]; }
+};
+
+// Alg. 1 Step 4 for one unit with n > B.  val(i) = CRF_temp of slot i (LDS),
+// evm = LDS bit mask of n bits, lst = LDS scratch of lst_cap >= n ints that may
+// overlap the storage behind `val` (the scores are dead by the time it is used).
+template <class Val>
+__device__ void evict_phase(const Dev& d, int u, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
+                            int& phase, int* sh, int tid) {
   const size_t base = (size_t)u * d.cap;
   const int lane = tid & 63, wave = tid >> 6;
   const int k = n - B;
@@ -615,7 +633,7 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
       for (int r = 0; r < 4; ++r) {
         const int i = i0 + r * kThreads;
         if (i < n) {
-          const u64 key = evict_key(val[i], ps[r]);
+          const u64 key = evict_key(val(i), ps[r]);
           if (key < best) {
             best = key;
             best_i = i;
@@ -640,7 +658,7 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
     for (int bit = 62; bit >= 0; --bit) {
       const u64 trial = X | (1ull << bit);
       int cnt = 0;
-      for (int i = tid; i < n; i += kThreads) cnt += evict_key(val[i], d.pos[base + i]) < trial ? 1 : 0;
+      for (int i = tid; i < n; i += kThreads) cnt += evict_key(val(i), d.pos[base + i]) < trial ? 1 : 0;
       cnt = block_sum_int(cnt, rb, phase, tid);
       if (cnt < k) X = trial;
     }
@@ -648,7 +666,7 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
     for (int w = tid; w < words; w += kThreads) evm[w] = 0u;
     __syncthreads();
     for (int i = tid; i < n; i += kThreads)
-      if (evict_key(val[i], d.pos[base + i]) <= X) atomicOr(&evm[i >> 5], 1u << (i & 31));
+      if (evict_key(val(i), d.pos[base + i]) <= X) atomicOr(&evm[i >> 5], 1u << (i & 31));
     __syncthreads();
     // holes = evicted slots below B, movers = surviving slots at or above B (equal counts)
     const int wpt = (words + kThreads - 1) / kThreads;
@@ -680,7 +698,6 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
     const uint32_t excl = incl - packed + prefix;
     int hrank = (int)(excl & 0xFFFFu), mrank = (int)(excl >> 16);
     const int h = (int)(total & 0xFFFFu);
-    int* lst = reinterpret_cast<int*>(val);               // CRF_temp no longer needed
     for (int w = w0; w < w1; ++w) {
       const uint32_t e = evm[w];
       const int s0 = w << 5;
@@ -692,7 +709,7 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
         hm &= hm - 1;
       }
       while (mm) {
-        lst[d.cap - 1 - (mrank++)] = s0 + __builtin_ctz(mm);
+        lst[lst_cap - 1 - (mrank++)] = s0 + __builtin_ctz(mm);
         mm &= mm - 1;
       }
     }
@@ -700,7 +717,7 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
     // evicted entries that already sit at or above B just get their flag
     for (int i = B + tid; i < n; i += kThreads)
       if ((evm[i >> 5] >> (i & 31)) & 1u) d.flags[base + i] = FLAG_SLIP;
-    for (int r = wave; r < h; r += kThreads / 64) move_entry(d, base, lst[d.cap - 1 - r], lst[r], lane);
+    for (int r = wave; r < h; r += kThreads / 64) move_entry(d, base, lst[lst_cap - 1 - r], lst[r], lane);
   }
   if (tid == 0) {
     d.n[u] = B;
@@ -711,7 +728,7 @@ __device__ void evict_phase(const Dev& d, int u, int n, int B, float* val, uint3
 // ------------------------------------------------------------------ finish
 // Ends a kernel that must leave the step scalars consistent: the last block
 // to arrive resets the work list and, if asked, advances time.
-__device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, int tid) {
+__device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, int tid, int queue_reset = -1) {
   __syncthreads();
   if (tid == 0) {
     __threadfence();
@@ -721,6 +738,7 @@ __device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, 
       d.sc[SC_CLAIM] = 0;
       d.sc[SC_CLAIM + 1] = 0;
       d.sc[SC_SEQ] = d.sc[SC_SEQ] + 1;
+      if (queue_reset >= 0) d.sc[SC_QUEUE] = queue_reset;
       if (advance) {
         d.sc[SC_T] = t + 1;
         d.sc[SC_WINDOW_STEPS] = d.sc[SC_WINDOW_STEPS] + 1;
@@ -815,6 +833,120 @@ __device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const f
   __syncthreads();
 }
 
+// Alg. 1 Steps 1-3 for one unit: top-p hit set from the mean weights val(i),
+// score update, flags.  Leaves CRF_temp in val(i) and returns the unit's
+// aggregated CRF (2^-20 fixed point), summed over the block.  s_tab: the first
+// s_tab_n entries of the decay table in LDS.
+template <class Val>
+__device__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
+                           int& phase, int tid) {
+  const size_t base = (size_t)u * d.cap;
+  // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
+  uint32_t theta = 0;
+  bool ties_all = true;
+  int pos_cut = 0x7FFFFFFF;
+  if (d.reward_mode == 0) {
+    for (int bit = 30; bit >= 0; --bit) {
+      const uint32_t cand = theta | (1u << bit);
+      float part = 0.f;
+      for (int i = tid; i < n; i += kThreads) {
+        const float a = val(i);
+        part += (__float_as_uint(a) >= cand) ? a : 0.f;
+      }
+      const float tot = block_sum_f32(part, rb, phase, tid);
+      if (tot > d.top_p) theta = cand;
+    }
+    if (theta != 0) {
+      // entries equal to the threshold: only as many as needed, lower positions first
+      float above = 0.f;
+      int ties = 0;
+      for (int i = tid; i < n; i += kThreads) {
+        const float a = val(i);
+        const uint32_t b = __float_as_uint(a);
+        above += (b > theta) ? a : 0.f;
+        ties += (b == theta) ? 1 : 0;
+      }
+      above = block_sum_f32(above, rb, phase, tid);
+      ties = block_sum_int(ties, rb, phase, tid);
+      if (ties > 1) {
+        const float th = __uint_as_float(theta);
+        float c = above;
+        int r = 0;
+        do {
+          c += th;
+          ++r;
+        } while (c <= d.top_p && r < ties);
+        if (r < ties) {
+          ties_all = false;
+          int X = 0;   // r-th smallest position among the ties
+          for (int bit = 30; bit >= 0; --bit) {
+            const int trial = X | (1 << bit);
+            int cnt = 0;
+            for (int i = tid; i < n; i += kThreads)
+              cnt += (__float_as_uint(val(i)) == theta && d.pos[base + i] < trial) ? 1 : 0;
+            cnt = block_sum_int(cnt, rb, phase, tid);
+            if (cnt < r) X = trial;
+          }
+          pos_cut = X;
+        }
+      }
+    }
+  }
+
+  // ---- Alg. 1 Steps 2-3: scores (4 entries per thread and round: loads, table lookups, then stores)
+  const bool has_new = d.pos[base + n - 1] == t;
+  const bool need_pos = d.reward_mode == 0 && !ties_all;
+  u64 sfix = 0;
+  for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+    float crf[4], dec[4];
+    int tau[4], ps[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + r * kThreads;
+      const bool ok = i < n;
+      crf[r] = ok ? d.crf[base + i] : 0.f;
+      tau[r] = ok ? d.tau[base + i] : t;
+      ps[r] = (ok && need_pos) ? d.pos[base + i] : 0;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int delta = t - tau[r];
+      delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+      dec[r] = delta < s_tab_n ? s_tab[delta] : d.tab[delta];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + r * kThreads;
+      if (i < n) {
+        const float a = val(i);
+        bool hit, store;
+        float reward;
+        if (d.reward_mode == 0) {
+          const uint32_t b = __float_as_uint(a);
+          hit = (b > theta) || (b == theta && (ties_all || ps[r] <= pos_cut));
+          if (i == n - 1 && has_new) hit = true;
+          store = hit;
+          reward = hit ? 1.0f : 0.0f;
+        } else {
+          hit = false;
+          store = true;
+          reward = a;
+        }
+        float tmp = __fadd_rn(__fmul_rn(dec[r], crf[r]), reward);
+        if (tmp < FLT_MIN) tmp = 0.0f;
+        if (store) {
+          d.crf[base + i] = tmp;
+          d.tau[base + i] = t;
+        }
+        d.flags[base + i] = hit ? FLAG_HIT : 0;
+        val(i) = tmp;
+        sfix += (u64)floorf(tmp * kFixedOne);
+      }
+    }
+  }
+  return block_sum_u64(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
+}
+
 __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin, void* out, uint32_t call_flags,
                                                           int advance) {
   extern __shared__ unsigned char smem[];
@@ -823,129 +955,28 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[(kMaxChunks + 1) * kMaxGroup];
   __shared__ RedBuf rb;
   __shared__ int sh[8];
+  __shared__ float s_tab[kTabLds];
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
   const int n = d.n[u];
   const int t = d.sc[SC_T];
   const int B = d.budget[u];
-  const size_t base = (size_t)u * d.cap;
+  const int s_tab_n = min(kTabLds, d.tab_last + 1);
+  if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
   int phase = 0;
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
     merge_partials(d, u, urel, nch, d.sc[SC_SEQ], sM, sInv, sW, out, tid);
     mean_weights(d, u, n, sM, sInv, val, tid);
 
-    // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
-    uint32_t theta = 0;
-    bool ties_all = true;
-    int pos_cut = 0x7FFFFFFF;
-    if (d.reward_mode == 0) {
-      for (int bit = 30; bit >= 0; --bit) {
-        const uint32_t cand = theta | (1u << bit);
-        float part = 0.f;
-        for (int i = tid; i < n; i += kThreads) {
-          const float a = val[i];
-          part += (__float_as_uint(a) >= cand) ? a : 0.f;
-        }
-        const float tot = block_sum_f32(part, rb, phase, tid);
-        if (tot > d.top_p) theta = cand;
-      }
-      if (theta != 0) {
-        // entries equal to the threshold: only as many as needed, lower positions first
-        float above = 0.f;
-        int ties = 0;
-        for (int i = tid; i < n; i += kThreads) {
-          const float a = val[i];
-          const uint32_t b = __float_as_uint(a);
-          above += (b > theta) ? a : 0.f;
-          ties += (b == theta) ? 1 : 0;
-        }
-        above = block_sum_f32(above, rb, phase, tid);
-        ties = block_sum_int(ties, rb, phase, tid);
-        if (ties > 1) {
-          const float th = __uint_as_float(theta);
-          float c = above;
-          int r = 0;
-          do {
-            c += th;
-            ++r;
-          } while (c <= d.top_p && r < ties);
-          if (r < ties) {
-            ties_all = false;
-            int X = 0;   // r-th smallest position among the ties
-            for (int bit = 30; bit >= 0; --bit) {
-              const int trial = X | (1 << bit);
-              int cnt = 0;
-              for (int i = tid; i < n; i += kThreads)
-                cnt += (__float_as_uint(val[i]) == theta && d.pos[base + i] < trial) ? 1 : 0;
-              cnt = block_sum_int(cnt, rb, phase, tid);
-              if (cnt < r) X = trial;
-            }
-            pos_cut = X;
-          }
-        }
-      }
-    }
-
-    // ---- Alg. 1 Steps 2-3: scores (4 entries per thread and round: loads, table lookups, then stores)
-    const bool has_new = d.pos[base + n - 1] == t;
-    const bool need_pos = d.reward_mode == 0 && !ties_all;
-    u64 sfix = 0;
-    for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
-      float crf[4], dec[4];
-      int tau[4], ps[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int i = i0 + r * kThreads;
-        const bool ok = i < n;
-        crf[r] = ok ? d.crf[base + i] : 0.f;
-        tau[r] = ok ? d.tau[base + i] : t;
-        ps[r] = (ok && need_pos) ? d.pos[base + i] : 0;
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        int delta = t - tau[r];
-        delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
-        dec[r] = d.tab[delta];
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int i = i0 + r * kThreads;
-        if (i < n) {
-          const float a = val[i];
-          bool hit, store;
-          float reward;
-          if (d.reward_mode == 0) {
-            const uint32_t b = __float_as_uint(a);
-            hit = (b > theta) || (b == theta && (ties_all || ps[r] <= pos_cut));
-            if (i == n - 1 && has_new) hit = true;
-            store = hit;
-            reward = hit ? 1.0f : 0.0f;
-          } else {
-            hit = false;
-            store = true;
-            reward = a;
-          }
-          float tmp = __fadd_rn(__fmul_rn(dec[r], crf[r]), reward);
-          if (tmp < FLT_MIN) tmp = 0.0f;
-          if (store) {
-            d.crf[base + i] = tmp;
-            d.tau[base + i] = t;
-          }
-          d.flags[base + i] = hit ? FLAG_HIT : 0;
-          val[i] = tmp;
-          sfix += (u64)floorf(tmp * kFixedOne);
-        }
-      }
-    }
-    sfix = block_sum_u64(sfix, rb, phase, tid);   // barrier: val[] and the stores above are complete
+    u64 sfix = lrfu_update(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
     if (tid == 0) {
       d.window[u] += sfix;
       d.t_unit[u] = t;
     }
     // ---- Alg. 1 Step 4
     if ((call_flags & 1u) && n > B)
-      evict_phase(d, u, n, B, val, evm, rb, phase, sh, tid);
+      evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
     else if (tid == 0)
       d.nev[u] = 0;
   }
@@ -977,7 +1008,7 @@ __global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin) 
     val[i] = tmp;
   }
   __syncthreads();
-  evict_phase(d, u, n, B, val, evm, rb, phase, sh, tid);
+  evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
 }
 
 // ------------------------------------------------------------------ probe

@@ -15,7 +15,7 @@ def _mods():
     return ok, ckv, wl
 
 
-def _pair(cfg, cap, budgets=None, stream=None, n_steps=None, load=True, **kw):
+def _pair(cfg, cap, budgets=None, stream=None, n_steps=None, load=True, path=0, **kw):
     ok, ckv, wl = _mods()
     st = stream if stream is not None else wl.make_stream(cfg, n_steps)
     budgets = wl.draw_budgets(cfg) if budgets is None else budgets
@@ -26,6 +26,7 @@ def _pair(cfg, cap, budgets=None, stream=None, n_steps=None, load=True, **kw):
     g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
                       lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min,
                       budget_max=cfg.budget_max, **kw)
+    g.set_path(path)          # 1 = separate scan/finish kernels, 2 = fused per-unit kernel
     if load and cfg.prompt > 0:
         for l in range(cfg.n_layers):
             o.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
@@ -41,29 +42,50 @@ def _small(name, **kw):
     return wl.scaled(wl.CONFIGS[name], **base)
 
 
+PATHS = [1, 2]
+
+
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 2), (10, 2), (14, 2), (16, 2), (6, 2)])
-def test_lockstep_every_group_size(hq, hkv):
+def test_lockstep_every_group_size(hq, hkv, path):
     """G = 1, 4, 5, 7, 8, 3 query heads per KV head; prompt length not a multiple of the 32-entry block;
     two layers and two sequences through the all-layers call; K/V rows checked after compaction."""
     cfg = _small("tiny", n_q_heads=hq, n_kv_heads=hkv, seed=77 + hq)
-    st, o, g = _pair(cfg, cap=96)
+    st, o, g = _pair(cfg, cap=96, path=path)
     stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=10)
     assert stats.resynced <= 2, stats.notes
     assert g.status() == 0 and g.time() == cfg.prompt + cfg.decode_steps
     g.close()
 
 
-def test_units_longer_than_a_chunk_and_ragged_tails():
+@pytest.mark.parametrize("path", PATHS)
+def test_units_longer_than_a_chunk_and_ragged_tails(path):
     """Budgets 300..700 so units span several 256-entry chunks with ragged last blocks, and the
     scan's runs start in the middle of chunks; 7B-like group size 7."""
     _, _, wl = _mods()
     cfg = _small("qwen7b", n_layers=1, batch=3, n_q_heads=14, n_kv_heads=2, prompt=333, decode_steps=24,
                  budget=500, budget_min=300, budget_max=735, seed=5)
     budgets = np.array([[[300, 700], [513, 333], [641, 352]]], dtype=np.int32)
-    st, o, g = _pair(cfg, cap=736, budgets=budgets)
+    st, o, g = _pair(cfg, cap=736, budgets=budgets, path=path)
     stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=8)
     assert stats.resynced <= 2, stats.notes
     assert np.array_equal(g.lengths(), o.lengths())
+    g.close()
+
+
+def test_fused_kernel_with_logits_spilling_out_of_lds():
+    """A unit of ~3000 entries with 8 query heads per KV head needs 96 KB of logits: more than the fused
+    kernel's LDS tile, so the logits of its last blocks take the global-memory route; a second, small
+    unit in the same call stays resident.  Also exercises several blocks per wavefront."""
+    _, _, wl = _mods()
+    cfg = _small("qwen7b", n_layers=1, batch=1, n_q_heads=16, n_kv_heads=2, prompt=2890, decode_steps=6,
+                 budget=1800, budget_min=600, budget_max=3071, seed=15)
+    budgets = np.array([[[2900, 700]]], dtype=np.int32)
+    st, o, g = _pair(cfg, cap=3072, budgets=budgets, path=2)
+    avail, lds_main = g.path_info()
+    assert avail and 3000 * 8 * 4 > lds_main
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=3)
+    assert stats.resynced <= 1, stats.notes
     g.close()
 
 
@@ -93,11 +115,12 @@ def test_per_layer_calls():
     g.close()
 
 
-def test_eviction_on_its_own_and_after_a_budget_cut():
+@pytest.mark.parametrize("path", PATHS)
+def test_eviction_on_its_own_and_after_a_budget_cut(path):
     """Steps without eviction let caches grow past their budgets; ckv_evict then removes many entries
     at once (the general select + compaction path), also after budgets were cut."""
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, prompt=40, decode_steps=60, budget=50, seed=3)
-    st, o, g = _pair(cfg, cap=128)
+    st, o, g = _pair(cfg, cap=128, path=path)
     stats = parity.LockstepStats()
     s = 0
     for rnd in range(3):
@@ -131,13 +154,14 @@ def test_eviction_on_its_own_and_after_a_budget_cut():
     g.close()
 
 
-def test_rebudget_matches_alg2_oracle():
+@pytest.mark.parametrize("path", PATHS)
+def test_rebudget_matches_alg2_oracle(path):
     """Alg. 2 on the device: budgets bit-identical to the oracle's, totals conserved, bounds kept;
     the next fused eviction brings the caches down to the new budgets."""
     _, _, wl = _mods()
     cfg = wl.scaled(wl.CONFIGS["qwen14b"], n_layers=3, batch=2, n_q_heads=10, n_kv_heads=2, prompt=70,
                     decode_steps=48, budget=64, budget_min=16, budget_max=120, seed=9)
-    st, o, g = _pair(cfg, cap=160)
+    st, o, g = _pair(cfg, cap=160, path=path)
     total0 = o.budgets().sum(axis=(0, 2))
     stats = parity.LockstepStats()
     s = 0
@@ -185,12 +209,13 @@ def test_probe_classes():
     g.close()
 
 
-def test_attention_weighted_reward_variant():
+@pytest.mark.parametrize("path", PATHS)
+def test_attention_weighted_reward_variant(path):
     """reward = mean attention weight (labelled variant): scores within 1e-5 relative of the oracle's,
     same evictions unless the last kept and first evicted scores are closer than that."""
     ok, ckv, _ = _mods()
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=30, seed=21)
-    st, o, g = _pair(cfg, cap=96, reward_mode=ok.REWARD_ATTN_WEIGHTED)
+    st, o, g = _pair(cfg, cap=96, reward_mode=ok.REWARD_ATTN_WEIGHTED, path=path)
     for s in range(cfg.decode_steps):
         ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
         out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).cpu().numpy()
@@ -209,11 +234,12 @@ def test_attention_weighted_reward_variant():
     g.close()
 
 
-def test_bf16_output():
+@pytest.mark.parametrize("path", PATHS)
+def test_bf16_output(path):
     """out_dtype bf16: within one bf16 ulp of the oracle's output rounded to bf16."""
     _, ckv, wl = _mods()
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=8, seed=31)
-    st, o, g = _pair(cfg, cap=96, out_dtype=ckv.BF16)
+    st, o, g = _pair(cfg, cap=96, out_dtype=ckv.BF16, path=path)
     for s in range(cfg.decode_steps):
         ref, _ = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
         out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).float().cpu().numpy()
@@ -223,12 +249,13 @@ def test_bf16_output():
     g.close()
 
 
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("lam,top_p", [(0.0, 0.9), (1.0, 0.9), (0.7, 1.0), (0.5, 0.5), (0.99, 0.9)])
-def test_parameter_corners(lam, top_p):
+def test_parameter_corners(lam, top_p, path):
     """lambda = 0 (LRU) and 1 (LFU), p >= 1 (every entry hit), a low p, and a decay table of ~9000 entries."""
     _, _, wl = _mods()
     cfg = wl.scaled(_small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=30, seed=41), lam=lam, top_p=top_p)
-    st, o, g = _pair(cfg, cap=96)
+    st, o, g = _pair(cfg, cap=96, path=path)
     stats = parity.lockstep(g, o, st, cfg.decode_steps)
     assert stats.resynced <= 2, stats.notes
     if top_p >= 1.0:
@@ -264,13 +291,14 @@ def test_empty_start_capacity_and_argument_errors():
     g.close()
 
 
-def test_runs_are_deterministic():
+@pytest.mark.parametrize("path", PATHS)
+def test_runs_are_deterministic(path):
     """Same inputs twice: outputs and state bit-identical (no atomics on floating-point data)."""
     cfg = _small("qwen14b", n_layers=2, batch=2, n_q_heads=10, n_kv_heads=2, prompt=300, decode_steps=12,
                  budget=320, budget_max=351, seed=61)
     res = []
     for _ in range(2):
-        st, o, g = _pair(cfg, cap=352)
+        st, o, g = _pair(cfg, cap=352, path=path)
         outs = [g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).cpu().numpy().copy() for s in range(cfg.decode_steps)]
         state = [g.export_unit(*key) for key in o.units]
         res.append((outs, state))
@@ -282,13 +310,14 @@ def test_runs_are_deterministic():
             assert np.array_equal(a[f], b[f]), f
 
 
-def test_hip_graph_replay_matches_eager():
+@pytest.mark.parametrize("path", PATHS)
+def test_hip_graph_replay_matches_eager(path):
     """Four decode steps captured into one HIP graph (time lives in device memory) and replayed three
     times, with eager work between the replays; every replay must equal the eager run."""
     import torch
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, decode_steps=12, seed=71)
-    st, o, g = _pair(cfg, cap=96)
-    _, _, g2 = _pair(cfg, cap=96)
+    st, o, g = _pair(cfg, cap=96, path=path)
+    _, _, g2 = _pair(cfg, cap=96, path=path)
     dev = g.device
     as_dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(torch.bfloat16)
     q, k, v = as_dev(st.q), as_dev(st.k_new), as_dev(st.v_new)
