@@ -240,7 +240,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
 
   // fused kernel: two workgroups per CU, each with half of the CU's LDS at most
   {
-    const int static_lds = 12 * 1024;                          // upper bound of unit_kernel's static LDS
+    const int static_lds = 16 * 1024;                          // upper bound of unit_kernel's static LDS
     const int evm_bytes = ((layout->cap + 31) / 32) * 4;
     int per_wg = max_lds < 80 * 1024 ? max_lds : 80 * 1024;
     int main_bytes = (per_wg - static_lds - evm_bytes) & ~127;

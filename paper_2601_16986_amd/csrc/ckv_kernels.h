@@ -109,6 +109,37 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
          __builtin_amdgcn_readlane(v, 48);
 }
 
+template <int kCtrl>
+__device__ __forceinline__ u64 dpp_u64(u64 v) {
+  const uint32_t lo = (uint32_t)dpp_i32<kCtrl>((int)(uint32_t)v);
+  const uint32_t hi = (uint32_t)dpp_i32<kCtrl>((int)(uint32_t)(v >> 32));
+  return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
+  return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 wave_sum_u64(u64 v) {
+  v += dpp_u64<kDppQuadSwap1>(v);
+  v += dpp_u64<kDppQuadSwap2>(v);
+  v += dpp_u64<kDppRowHalfMirror>(v);
+  v += dpp_u64<kDppRowMirror>(v);
+  return (readlane_u64(v, 0) + readlane_u64(v, 16)) + (readlane_u64(v, 32) + readlane_u64(v, 48));
+}
+
+__device__ __forceinline__ u64 min_u64(u64 a, u64 b) { return a < b ? a : b; }
+
+__device__ __forceinline__ u64 wave_min_u64(u64 v) {
+  v = min_u64(v, dpp_u64<kDppQuadSwap1>(v));
+  v = min_u64(v, dpp_u64<kDppQuadSwap2>(v));
+  v = min_u64(v, dpp_u64<kDppRowHalfMirror>(v));
+  v = min_u64(v, dpp_u64<kDppRowMirror>(v));
+  return min_u64(min_u64(readlane_u64(v, 0), readlane_u64(v, 16)), min_u64(readlane_u64(v, 32), readlane_u64(v, 48)));
+}
+
 // Block-wide reductions with a fixed combination order (deterministic).  `buf`
 // is a [2][4] LDS array used alternately, so one barrier per call suffices.
 struct RedBuf {
@@ -116,7 +147,7 @@ struct RedBuf {
 };
 
 __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int tid) {
-  v = wave_sum(v);
+  v = wave_sum_u64(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
   __syncthreads();
   u64 r = rb.v[phase][0] + rb.v[phase][1] + rb.v[phase][2] + rb.v[phase][3];
@@ -147,11 +178,7 @@ __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, 
 }
 
 __device__ __forceinline__ u64 block_min_u64(u64 v, RedBuf& rb, int& phase, int tid) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    u64 y = __shfl_xor(v, o);
-    v = y < v ? y : v;
-  }
+  v = wave_min_u64(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
   __syncthreads();
   u64 r = rb.v[phase][0];
@@ -355,22 +382,23 @@ __device__ __forceinline__ void load_v(VFrag& f, const uint16_t* vb) {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 
-// One block of 32 entries: logits on the matrix cores, online softmax update,
-// probabilities (split into two bf16 terms) times V on the matrix cores.
-// The scaled logits leave through a wave-private LDS tile so that each head's
-// 32 values go to memory as one full 128-byte line.
+// One block of 32 entries is processed in two halves so that each fragment's
+// registers can be refilled as soon as it has been consumed.  The scaled logits
+// leave through a wave-private LDS tile so that each block's values go to memory
+// as one contiguous store.
 constexpr int kLgRow = 36;     // floats per head row in the LDS tile (32 + pad against bank conflicts)
 
-__device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, const bf16x8 (&qv)[4], f32x4 (&acc)[8],
-                                           float& m_run, float& l_run, float c_scale, int e_base, int n_valid,
-                                           float* lds_lg, int lds_row, float* lg_dst, int G, int lane) {
+// First half of a block of 32 entries: logits on the matrix cores, masked and
+// scaled into sv[8] (this lane's 4 + 4 entries), and sent on their way to the
+// finish phase.  The K fragment is dead afterwards.
+__device__ __forceinline__ void scan_qk(const KFrag& f, const bf16x8 (&qv)[4], float (&sv)[8], float c_scale, int e_base,
+                                        int n_valid, float* lds_lg, int lds_row, float* lg_dst, int G, int lane) {
   const int j = lane & 15, kg = lane >> 4;
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int s = 0; s < 4; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[s]), qv[s], s0, 0, 0, 0);
 #pragma unroll
   for (int s = 0; s < 4; ++s) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[4 + s]), qv[s], s1, 0, 0, 0);
-  float sv[8];
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     sv[v] = (e_base + 4 * kg + v < n_valid) ? s0[v] * c_scale : -INFINITY;
@@ -391,6 +419,12 @@ __device__ __forceinline__ void scan_block(const KFrag& f, const VFrag& fv, cons
     }
     __builtin_amdgcn_wave_barrier();
   }
+}
+
+// Second half: online softmax update and probabilities (split into two bf16
+// terms) times V on the matrix cores.  The V fragment is dead afterwards.
+__device__ __forceinline__ void scan_pv(const float (&sv)[8], const VFrag& fv, f32x4 (&acc)[8], float& m_run, float& l_run,
+                                        int lane) {
   float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
   bm = fmaxf(bm, __shfl_xor(bm, 16));
   bm = fmaxf(bm, __shfl_xor(bm, 32));
@@ -491,7 +525,7 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
 
   int it = find_item(d, n_items, b_cur, lane);
   Item cur = fetch_item(d, it);
-  KFrag ka, kb;
+  KFrag ka;
   VFrag va;
   {
     const size_t off = (size_t)cur.u * unit_elems + ((size_t)cur.c * kChunk + (size_t)(b_cur - cur.blk_off) * kBlk) * kDim + lane * 8;
@@ -532,20 +566,19 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
     float m_run = -INFINITY, l_run = 0.f;
     int blk = 0;
 
-    auto step = [&](const KFrag& kc, KFrag& kn) -> bool {
+    // stream: the K tile of block b+1 is requested right after block b's logits are done, the V tile
+    // right after block b's PV; at the end of the run both continue with the next run's first block
+    while (true) {
       const bool last = blk + 1 == nblk;
       const uint16_t* kn_ptr = last ? d.K + tail_off : kcur + (size_t)(blk + 1) * kBlkElems;
       const uint16_t* vn_ptr = last ? d.V + tail_off : vcur + (size_t)(blk + 1) * kBlkElems;
-      load_k(kn, kn_ptr);
-      scan_block(kc, va, qv, acc, m_run, l_run, d.scale_log2e, blk * kBlk, run_valid, lds_lg, kLgRow, lg_dst, G, lane);
+      float sv[8];
+      scan_qk(ka, qv, sv, d.scale_log2e, blk * kBlk, run_valid, lds_lg, kLgRow, lg_dst, G, lane);
+      load_k(ka, kn_ptr);
+      scan_pv(sv, va, acc, m_run, l_run, lane);
       load_v(va, vn_ptr);
       ++blk;
-      return last;
-    };
-    bool in_a = true;       // which K buffer holds the block to compute next
-    while (true) {
-      if (step(ka, kb)) { in_a = false; break; }
-      if (step(kb, ka)) { in_a = true; break; }
+      if (last) break;
     }
     // ---- publish the run's partial
     l_run += __shfl_xor(l_run, 16);
@@ -569,10 +602,6 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
     b_cur = b_next;
     it = it_next;
     cur = nxt;
-    if (!in_a) {        // keep the invariant "next block to compute is in ka"
-#pragma unroll
-      for (int i = 0; i < 8; ++i) ka.k[i] = kb.k[i];
-    }
   }
 }
 
@@ -614,7 +643,7 @@ struct ValLinear {
 // evm = LDS bit mask of n bits, lst = LDS scratch of lst_cap >= n ints that may
 // overlap the storage behind `val` (the scores are dead by the time it is used).
 template <class Val>
-__device__ void evict_phase(const Dev& d, int u, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
+__device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
                             int& phase, int* sh, int tid) {
   const size_t base = (size_t)u * d.cap;
   const int lane = tid & 63, wave = tid >> 6;
@@ -838,7 +867,7 @@ __device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const f
 // aggregated CRF (2^-20 fixed point), summed over the block.  s_tab: the first
 // s_tab_n entries of the decay table in LDS.
 template <class Val>
-__device__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
+__device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
                            int& phase, int tid) {
   const size_t base = (size_t)u * d.cap;
   // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
@@ -947,6 +976,187 @@ __device__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const flo
   return block_sum_u64(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
 }
 
+// Mean attention weight of the entries tid + 256 k of unit u (global logits) into registers.
+template <int R>
+__device__ __forceinline__ void mean_weights_regs(const Dev& d, int u, int n, const float* sM, const float* sInv,
+                                                  float (&a)[R], int tid) {
+  const int G = d.G;
+  const float invG = 1.0f / (float)G;
+  const float* lg = d.logits + (size_t)u * G * d.cap;      // per block of 32 entries: [head][32]
+#pragma unroll
+  for (int k0 = 0; k0 < R; k0 += 4) {
+    float x[4][kMaxGroup];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = tid + (k0 + r) * kThreads;
+      const float* row = lg + (size_t)(i >> 5) * (G * kBlk) + (i & 31);
+#pragma unroll
+      for (int g = 0; g < kMaxGroup; ++g) x[r][g] = (i < n && g < G) ? row[g * kBlk] : -INFINITY;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float acc = 0.f;
+#pragma unroll
+      for (int g = 0; g < kMaxGroup; ++g)
+        if (g < G) acc += fast_exp2(x[r][g] - sM[g]) * sInv[g];
+      a[k0 + r] = (tid + (k0 + r) * kThreads < n) ? acc * invG : 0.f;
+    }
+  }
+}
+
+// Alg. 1 Steps 1-4 for a unit of n <= 256 R entries with everything in
+// registers: thread tid owns entries tid + 256 k, a[k] holds their mean
+// weights on entry (0 beyond n).  Same decisions and arithmetic as
+// lrfu_update + evict_phase, without re-reading LDS in the 31 bisection rounds;
+// the entries' CRF, tau and position are loaded up front so that their latency
+// hides behind the bisection.  Evicting more than one entry falls back to
+// evict_phase (the scores are then left in val()).
+template <int R, class Val>
+__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], Val val, bool evict, uint32_t* evm,
+                          int* lst, int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
+                          int tid) {
+  const size_t base = (size_t)u * d.cap;
+  float crf[R];
+  int tau[R], ps[R];
+#pragma unroll
+  for (int k = 0; k < R; ++k) {
+    const int i = tid + k * kThreads;
+    const bool ok = i < n;
+    crf[k] = ok ? d.crf[base + i] : 0.f;
+    tau[k] = ok ? d.tau[base + i] : t;
+    ps[k] = ok ? d.pos[base + i] : 0x7FFFFFFF;
+  }
+  // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
+  uint32_t theta = 0;
+  bool ties_all = true;
+  int pos_cut = 0x7FFFFFFF;
+  if (d.reward_mode == 0) {
+    for (int bit = 30; bit >= 0; --bit) {
+      const uint32_t cand = theta | (1u << bit);
+      float part = 0.f;
+#pragma unroll
+      for (int k = 0; k < R; ++k) part += (__float_as_uint(a[k]) >= cand) ? a[k] : 0.f;
+      const float tot = block_sum_f32(part, rb, phase, tid);
+      if (tot > d.top_p) theta = cand;
+    }
+    if (theta != 0) {
+      float above = 0.f;
+      int ties = 0;
+#pragma unroll
+      for (int k = 0; k < R; ++k) {
+        const uint32_t b = __float_as_uint(a[k]);
+        above += (b > theta) ? a[k] : 0.f;
+        ties += (b == theta) ? 1 : 0;
+      }
+      above = block_sum_f32(above, rb, phase, tid);
+      ties = block_sum_int(ties, rb, phase, tid);
+      if (ties > 1) {
+        const float th = __uint_as_float(theta);
+        float c = above;
+        int r = 0;
+        do {
+          c += th;
+          ++r;
+        } while (c <= d.top_p && r < ties);
+        if (r < ties) {
+          ties_all = false;
+          int X = 0;   // r-th smallest position among the ties
+          for (int bit = 30; bit >= 0; --bit) {
+            const int trial = X | (1 << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int k = 0; k < R; ++k) cnt += (__float_as_uint(a[k]) == theta && ps[k] < trial) ? 1 : 0;
+            cnt = block_sum_int(cnt, rb, phase, tid);
+            if (cnt < r) X = trial;
+          }
+          pos_cut = X;
+        }
+      }
+    }
+  }
+  // ---- Steps 2-3: scores; a[k] becomes CRF_temp
+  u64 sfix = 0;
+#pragma unroll
+  for (int k = 0; k < R; ++k) {
+    const int i = tid + k * kThreads;
+    if (i < n) {
+      int delta = t - tau[k];
+      delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+      const float dec = delta < s_tab_n ? s_tab[delta] : d.tab[delta];
+      bool hit, store;
+      float reward;
+      if (d.reward_mode == 0) {
+        const uint32_t b = __float_as_uint(a[k]);
+        hit = (b > theta) || (b == theta && (ties_all || ps[k] <= pos_cut));
+        if (i == n - 1 && ps[k] == t) hit = true;          // the entry appended this step
+        store = hit;
+        reward = hit ? 1.0f : 0.0f;
+      } else {
+        hit = false;
+        store = true;
+        reward = a[k];
+      }
+      float tmp = __fadd_rn(__fmul_rn(dec, crf[k]), reward);
+      if (tmp < FLT_MIN) tmp = 0.0f;
+      if (store) {
+        d.crf[base + i] = tmp;
+        d.tau[base + i] = t;
+      }
+      d.flags[base + i] = hit ? FLAG_HIT : 0;
+      a[k] = tmp;
+      sfix += (u64)floorf(tmp * kFixedOne);
+    }
+  }
+  sfix = block_sum_u64(sfix, rb, phase, tid);
+  if (tid == 0) {
+    d.window[u] += sfix;
+    d.t_unit[u] = t;
+  }
+  // ---- Step 4
+  if (!(evict && n > B)) {
+    if (tid == 0) d.nev[u] = 0;
+    return;
+  }
+  if (n - B == 1) {
+    u64 best = ~0ull;
+    int best_i = -1;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const int i = tid + k * kThreads;
+      if (i < n) {
+        const u64 key = evict_key(a[k], ps[k]);
+        if (key < best) {
+          best = key;
+          best_i = i;
+        }
+      }
+    }
+    const u64 gbest = block_min_u64(best, rb, phase, tid);
+    if (best == gbest && best_i >= 0) sh[0] = best_i;     // keys are unique: one writer
+    __syncthreads();
+    const int e = sh[0];
+    if ((tid >> 6) == 0) {
+      if (e != n - 1) {
+        move_entry(d, base, n - 1, e, tid & 63);
+      } else if (tid == 0) {
+        d.flags[base + e] = FLAG_SLIP;
+      }
+    }
+    if (tid == 0) {
+      d.n[u] = B;
+      d.nev[u] = 1;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const int i = tid + k * kThreads;
+      if (i < n) val(i) = a[k];
+    }
+    __syncthreads();
+    evict_phase(d, u, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin, void* out, uint32_t call_flags,
                                                           int advance) {
   extern __shared__ unsigned char smem[];
@@ -967,18 +1177,24 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
     merge_partials(d, u, urel, nch, d.sc[SC_SEQ], sM, sInv, sW, out, tid);
-    mean_weights(d, u, n, sM, sInv, val, tid);
-
-    u64 sfix = lrfu_update(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
-    if (tid == 0) {
-      d.window[u] += sfix;
-      d.t_unit[u] = t;
+    const bool evict = (call_flags & 1u) != 0;
+    if (n <= 8 * kThreads) {
+      float a[8];
+      mean_weights_regs(d, u, n, sM, sInv, a, tid);
+      lrfu_regs<8>(d, u, n, B, t, a, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap, s_tab, s_tab_n, rb,
+                   phase, sh, tid);
+    } else {
+      mean_weights(d, u, n, sM, sInv, val, tid);
+      const u64 sfix = lrfu_update(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
+      if (tid == 0) {
+        d.window[u] += sfix;
+        d.t_unit[u] = t;
+      }
+      if (evict && n > B)
+        evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
+      else if (tid == 0)
+        d.nev[u] = 0;
     }
-    // ---- Alg. 1 Step 4
-    if ((call_flags & 1u) && n > B)
-      evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
-    else if (tid == 0)
-      d.nev[u] = 0;
   }
   step_epilogue(d, t, advance, tid);
 }
@@ -1060,7 +1276,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, 
 // Integers val[k] in [lo, hi] summing to `total`, proportional to x[k] >= 0 as
 // far as the bounds allow: water-filling on the reals, floor, remainder by
 // largest fractional part (lower index first on ties), final spill in index order.
-__device__ void apportion(const double* x, int m, long long total, long long lo, long long hi, long long* val, double* y,
+__device__ __forceinline__ void apportion(const double* x, int m, long long total, long long lo, long long hi, long long* val, double* y,
                           unsigned char* fixed) {
   for (int k = 0; k < m; ++k) {
     fixed[k] = 0;

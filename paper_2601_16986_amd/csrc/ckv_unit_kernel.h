@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
   float* lg = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + lds_main);
   __shared__ float s_stage[kThreads / 64][kMaxGroup * kLgRow];   // staging tiles for spilled logits
-  __shared__ float s_out[kMaxGroup * kDim];
+  __shared__ float s_out[2][kMaxGroup * kDim];
   __shared__ float s_ml[kThreads / 64][kMaxGroup][2];
   __shared__ float sM[kMaxGroup], sInv[kMaxGroup];
   __shared__ float s_tab[kTabLds];
@@ -102,18 +102,9 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
   }
   __syncthreads();
   int idx = s_idx[0], idx_next = s_idx[1];
-  int phase = 0;
 
-  KFrag ka, kb;
-  VFrag va;
   int u = idx < n_units ? d.order[idx] : 0;
   int n = idx < n_units ? d.n[u] : 0;
-  if (idx < n_units) {
-    const int nblk0 = (n + kBlk - 1) / kBlk;
-    const size_t off = (size_t)u * unit_elems + (size_t)min(wave, max(nblk0 - 1, 0)) * kBlkElems + lane * 8;
-    load_k(ka, d.K + off);
-    load_v(va, d.V + off);
-  }
 
   while (idx < n_units) {
     // ---- claim the unit after next; look at the next one (its first blocks get prefetched)
@@ -122,8 +113,6 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
     const bool have_next = idx_next < n_units;
     const int u_next = have_next ? d.order[idx_next] : u;
     const int n_next = have_next ? d.n[u_next] : n;
-    const int nblk_next = max((n_next + kBlk - 1) / kBlk, 1);
-    const size_t next_off = (size_t)u_next * unit_elems + (size_t)min(wave, nblk_next - 1) * kBlkElems + lane * 8;
 
     const int B = d.budget[u];
     const int nblk = (n + kBlk - 1) / kBlk;
@@ -132,6 +121,8 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
     const int my_cnt = wave < nblk ? (nblk - wave + 3) / 4 : 0;
 
     // ---- stream this wave's blocks
+    int slane = lane;
+    asm volatile("" : "+v"(slane));
     f32x4 acc[8];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -147,37 +138,29 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
           qv[s] = as_bf16x8(x);
         }
       }
-      const uint16_t* kcur = d.K + (size_t)u * unit_elems + lane * 8;
-      const uint16_t* vcur = d.V + (size_t)u * unit_elems + lane * 8;
-      float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(lane, 8 * G - 1);
-      int i = 0;
-      auto step = [&](const KFrag& kc, KFrag& kn) -> bool {
+      const uint16_t* kcur = d.K + (size_t)u * unit_elems + slane * 8;
+      const uint16_t* vcur = d.V + (size_t)u * unit_elems + slane * 8;
+      float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(slane, 8 * G - 1);
+      KFrag ka;
+      VFrag va;
+      load_k(ka, kcur + (size_t)wave * kBlkElems);
+      load_v(va, vcur + (size_t)wave * kBlkElems);
+      for (int i = 0; i < my_cnt; ++i) {
         const int blk = wave + 4 * i;
-        const bool last = i + 1 == my_cnt;
-        const uint16_t* kn_ptr = last ? d.K + next_off : kcur + (size_t)(blk + 4) * kBlkElems;
-        const uint16_t* vn_ptr = last ? d.V + next_off : vcur + (size_t)(blk + 4) * kBlkElems;
-        load_k(kn, kn_ptr);
+        const int nb = (i + 1 == my_cnt) ? blk : blk + 4;     // after the last block: read it once more (keeps the loads unconditional)
         const bool resident = blk < res_blk;
         float* lds_dst = resident ? lg + (size_t)blk * (G * kBlk) : s_stage[wave];
-        scan_block(kc, va, qv, acc, m_run, l_run, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
-                   resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, lane);
-        load_v(va, vn_ptr);
-        ++i;
-        return last;
-      };
-      bool in_a = true;
-      while (true) {
-        if (step(ka, kb)) { in_a = false; break; }
-        if (step(kb, ka)) { in_a = true; break; }
+        float sv[8];
+        scan_qk(ka, qv, sv, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
+                resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
+        load_k(ka, kcur + (size_t)nb * kBlkElems);
+        scan_pv(sv, va, acc, m_run, l_run, slane);
+        load_v(va, vcur + (size_t)nb * kBlkElems);
       }
-      if (!in_a) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) ka.k[r] = kb.k[r];
-      }
-    } else {
-      load_k(ka, d.K + next_off);       // idle for this unit: just move the prefetch on
-      load_v(va, d.V + next_off);
     }
+    // the bookkeeping below is short and latency-bound: let it win the issue slots over the other
+    // workgroup's streaming wavefronts, which mostly wait on memory anyway
+    __builtin_amdgcn_s_setprio(3);
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     if (head_lane && kg == 0) {
@@ -186,7 +169,9 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
     }
     __syncthreads();
 
-    // ---- merge the four online-softmax states -> out
+    // ---- merge the four online-softmax states -> out.  Every thread derives the global max and
+    // denominator of the heads it needs from s_ml (same fixed order everywhere); waves 0 and 1 deposit
+    // their rescaled accumulators in two LDS slices, waves 2 and 3 add theirs on top.
     if (tid < G) {
       float M = -INFINITY;
       for (int w = 0; w < 4; ++w) M = fmaxf(M, s_ml[w][tid][0]);
@@ -198,29 +183,39 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
       sM[tid] = M;
       sInv[tid] = 1.0f / L;
     }
-    __syncthreads();
-    for (int w = 0; w < 4; ++w) {
-      if (wave == w) {
+    {
+      float sc[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int head = 4 * kg + v;
-          if (head < G) {
-            const float m = s_ml[w][head][0];
-            const float sc = m > -INFINITY ? fast_exp2(m - sM[head]) : 0.f;
+      for (int v = 0; v < 4; ++v) {
+        const int head = min(4 * kg + v, kMaxGroup - 1);
+        float M = -INFINITY;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-              const float x = acc[dt][v] * sc;
-              float* dst = &s_out[head * kDim + 16 * dt + j];
-              *dst = (w == 0) ? x : *dst + x;
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, s_ml[w][head][0]);
+        const float m = s_ml[wave][head][0];
+        sc[v] = m > -INFINITY ? fast_exp2(m - M) : 0.f;
+      }
+      float* slice = s_out[wave & 1];
+      for (int half = 0; half < 2; ++half) {
+        if ((wave >> 1) == half) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int head = 4 * kg + v;
+            if (head < G) {
+#pragma unroll
+              for (int dt = 0; dt < 8; ++dt) {
+                float* dst = &slice[head * kDim + 16 * dt + j];
+                const float x = acc[dt][v] * sc[v];
+                *dst = half == 0 ? x : *dst + x;
+              }
             }
           }
         }
+        __syncthreads();
       }
-      __syncthreads();
     }
     for (int o = tid; o < G * kDim; o += kThreads) {
       const int g = o >> 7;
-      const float y = s_out[o] * sInv[g];
+      const float y = (s_out[0][o] + s_out[1][o]) * sInv[g];
       const size_t oi = (size_t)u * G * kDim + o;
       if (d.out_bf16)
         reinterpret_cast<__bf16*>(out)[oi] = (__bf16)y;
@@ -228,33 +223,72 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
         reinterpret_cast<float*>(out)[oi] = y;
     }
 
-    // ---- mean attention weight of every entry
+    // ---- mean attention weights, then Alg. 1 Steps 1-4.  The thread index is laundered so that the
+    // compiler derives this phase's per-lane addresses here instead of keeping them alive, in
+    // registers the streaming loop needs, across the whole unit loop.
+    int ftid = tid;
+    asm volatile("" : "+v"(ftid));
+    int phase = 0;      // block reductions of different units are separated by barriers
     const ValFused val{lg, lg + (size_t)n_res * G, n_res, G * kBlk};
-    {
-      const float invG = 1.0f / (float)G;
-      const float* lgg = d.logits + (size_t)u * d.cap * G;
-      for (int i = tid; i < n; i += kThreads) {
-        const int off = (i >> 5) * (G * kBlk) + (i & 31);
-        const float* row = i < n_res ? lg + off : lgg + off;
-        float a = 0.f;
-        for (int g = 0; g < G; ++g) a += fast_exp2(row[g * kBlk] - sM[g]) * sInv[g];
-        val(i) = a * invG;
+    const bool evict = (call_flags & 1u) != 0;
+    const float invG = 1.0f / (float)G;
+    const float* lgg = d.logits + (size_t)u * d.cap * G;
+    auto weight_of = [&](int i) -> float {
+      const int off = (i >> 5) * (G * kBlk) + (i & 31);
+      float a = 0.f;
+      if (i < n_res) {
+        for (int g = 0; g < G; ++g) a += fast_exp2(lg[off + g * kBlk] - sM[g]) * sInv[g];
+      } else {
+        for (int g = 0; g < G; ++g) a += fast_exp2(lgg[off + g * kBlk] - sM[g]) * sInv[g];
       }
+      return a * invG;
+    };
+    // four entries at a time with all their logits in flight together
+    auto weights4 = [&](int i0, float* a4) {
+      float x[4][kMaxGroup];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + r * kThreads;
+        const int off = (i >> 5) * (G * kBlk) + (i & 31);
+        if (i < n_res) {
+#pragma unroll
+          for (int g = 0; g < kMaxGroup; ++g) x[r][g] = g < G ? lg[off + g * kBlk] : -INFINITY;
+        } else {
+#pragma unroll
+          for (int g = 0; g < kMaxGroup; ++g) x[r][g] = (g < G && i < n) ? lgg[off + g * kBlk] : -INFINITY;
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float a = 0.f;
+#pragma unroll
+        for (int g = 0; g < kMaxGroup; ++g)
+          if (g < G) a += fast_exp2(x[r][g] - sM[g]) * sInv[g];
+        a4[r] = (i0 + r * kThreads < n) ? a * invG : 0.f;
+      }
+    };
+    if (n <= 8 * kThreads) {
+      float a[8];
+      weights4(ftid, a);
+      weights4(ftid + 4 * kThreads, a + 4);
+      lrfu_regs<8>(d, u, n, B, t, a, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4, s_tab, s_tab_n, rb, phase,
+                   sh, ftid);
+    } else {
+      for (int i = ftid; i < n; i += kThreads) val(i) = weight_of(i);
+      __syncthreads();
+      const u64 sfix = lrfu_update(d, u, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
+      if (ftid == 0) {
+        d.window[u] += sfix;
+        d.t_unit[u] = t;
+      }
+      if (evict && n > B)
+        evict_phase(d, u, n, B, val, evm, reinterpret_cast<int*>(smem), lds_main / 4, rb, phase, sh, ftid);
+      else if (ftid == 0)
+        d.nev[u] = 0;
     }
-    __syncthreads();
-
-    // ---- Alg. 1 Steps 1-3, then Step 4
-    const u64 sfix = lrfu_update(d, u, n, t, val, s_tab, s_tab_n, rb, phase, tid);
-    if (tid == 0) {
-      d.window[u] += sfix;
-      d.t_unit[u] = t;
-    }
-    if ((call_flags & 1u) && n > B)
-      evict_phase(d, u, n, B, val, evm, reinterpret_cast<int*>(smem), lds_main / 4, rb, phase, sh, tid);
-    else if (tid == 0)
-      d.nev[u] = 0;
 
     // ---- next unit
+    __builtin_amdgcn_s_setprio(0);
     if (tid == 0) {
       s_idx[0] = idx_next;
       s_idx[1] = claimed;
