@@ -13,6 +13,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
     "-ffp-contract=off",                       # CRF update and Alg. 2 must round as written
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep the fused kernel's queue atomic a plain atomic: the wave-level rewrite of atomics reads the
+    # result back at once, and that wait is a wait for every load in flight
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wno-unused-function",
 ]
 

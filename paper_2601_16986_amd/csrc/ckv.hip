@@ -27,11 +27,14 @@ struct ckv_ctx {
   int n_cu = 256;
   size_t finish_lds = 0;
   // fused path (unit_kernel)
-  int path_mode = 0;            // 0 auto, 1 separate kernels, 2 fused kernel
-  bool fused_ok = false;
-  int fused_grid = 0;
-  int lds_main = 0;
-  size_t fused_lds = 0;
+  int path_mode = 0;            // 0 auto, 1 separate kernels, 2 fused kernel, 3 / 4 fused with 4 / 2 wavefronts per unit
+  struct Fused {                // one variant of the fused kernel
+    bool ok = false;
+    int waves = 0;              // wavefronts per workgroup (= per unit)
+    int grid = 0;
+    int lds_main = 0;           // bytes of the logits / values tile
+    size_t lds = 0;             // dynamic LDS per workgroup
+  } fused[2];                   // [0]: 4 wavefronts, 2 workgroups per CU; [1]: 2 wavefronts, 4 workgroups per CU
   std::vector<uint8_t> prompt_loaded;
   std::string err;
   // scan timing
@@ -106,7 +109,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -130,6 +133,8 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.logits = take(U * G * (size_t)l->cap * 4);
   c.btotal = take((size_t)l->batch * 8);
   c.order = take(U * 4);
+  c.rank = take(U * 4);
+  c.sched = take(U * 16);
   c.total = off;
   return c;
 }
@@ -143,6 +148,21 @@ int check_budgets(ckv_ctx* c, const ckv_layout* l, const ckv_lrfu_params* p, con
   return CKV_OK;
 }
 
+// The variant of the fused kernel the current path mode selects (nullptr: none fits or separate kernels).
+const ckv_ctx::Fused* fused_variant(const ckv_ctx* c) {
+  if (c->path_mode == 1) return nullptr;
+  const ckv_ctx::Fused* f = c->path_mode == 3 ? &c->fused[0] : c->path_mode == 4 ? &c->fused[1]
+                            : c->fused[0].ok ? &c->fused[0] : &c->fused[1];
+  return f->ok ? f : nullptr;
+}
+
+// (Re)build the fused kernel's schedule (units by descending budget) from the budgets in device memory.
+int launch_schedule(ckv_ctx* c, hipStream_t s) {
+  hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(1024), 0, s, c->dev);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
 int upload_budgets(ckv_ctx* c, const int32_t* budgets, hipStream_t s) {
   const ckv_layout& l = c->lay;
   std::vector<long long> tot(l.batch, 0);
@@ -151,8 +171,7 @@ int upload_budgets(ckv_ctx* c, const int32_t* budgets, hipStream_t s) {
       for (int h = 0; h < l.n_kv_heads; ++h) tot[b] += budgets[((size_t)i * l.batch + b) * l.n_kv_heads + h];
   CKV_HIP(c, hipMemcpyAsync(c->dev.budget, budgets, (size_t)c->units * 4, hipMemcpyHostToDevice, s));
   CKV_HIP(c, hipMemcpyAsync(c->dev.btotal, tot.data(), (size_t)l.batch * 8, hipMemcpyHostToDevice, s));
-  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, s, c->dev);
-  CKV_HIP(c, hipGetLastError());
+  if (int rc = launch_schedule(c, s)) return rc;
   CKV_HIP(c, hipStreamSynchronize(s));
   return CKV_OK;
 }
@@ -238,19 +257,22 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     }
   }
 
-  // fused kernel: two workgroups per CU, each with half of the CU's LDS at most
-  {
-    const int static_lds = 16 * 1024;                          // upper bound of unit_kernel's static LDS
+  // fused kernel: 8 / W workgroups of W wavefronts per CU, each with its share of the CU's 160 KB of LDS
+  for (int v = 0; v < 2; ++v) {
+    ckv_ctx::Fused& f = c->fused[v];
+    f.waves = v == 0 ? 4 : 2;
+    const int wgs = 8 / f.waves;
+    const int static_lds = v == 0 ? 11 * 1024 : 6 * 1024;      // upper bounds of unit_kernel<W>'s static LDS
     const int evm_bytes = ((layout->cap + 31) / 32) * 4;
-    int per_wg = max_lds < 80 * 1024 ? max_lds : 80 * 1024;
-    int main_bytes = (per_wg - static_lds - evm_bytes) & ~127;
-    c->fused_ok = main_bytes >= 4 * layout->cap;                // every entry's value must fit
-    c->lds_main = main_bytes;
-    c->fused_lds = (size_t)main_bytes + evm_bytes;
-    c->fused_grid = 2 * c->n_cu;
-    if (c->fused_ok && hipFuncSetAttribute(reinterpret_cast<const void*>(unit_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds) != hipSuccess)
-      c->fused_ok = false;
+    const int share = (160 * 1024 / wgs) & ~1023;
+    const int per_wg = max_lds < share ? max_lds : share;
+    const int main_bytes = (per_wg - static_lds - evm_bytes) & ~127;
+    f.grid = wgs * c->n_cu;
+    f.ok = main_bytes >= 4 * layout->cap;                       // every entry's value must fit
+    f.lds_main = main_bytes;
+    f.lds = (size_t)main_bytes + evm_bytes;
+    const void* fn = v == 0 ? reinterpret_cast<const void*>(unit_kernel<4>) : reinterpret_cast<const void*>(unit_kernel<2>);
+    if (f.ok && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)f.lds) != hipSuccess) f.ok = false;
   }
 
   Dev& d = c->dev;
@@ -291,6 +313,8 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.logits = (float*)(ws + cv.logits);
   d.btotal = (long long*)(ws + cv.btotal);
   d.order = (int32_t*)(ws + cv.order);
+  d.rank = (int32_t*)(ws + cv.rank);
+  d.sched = (int4*)(ws + cv.sched);
 
   auto bail = [&](int rc) {
     delete c;
@@ -309,7 +333,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   if ((rc = fill32(c, d.t_unit, (uint32_t)(params->t0 - 1), (size_t)c->units, s))) return bail(rc);
   if ((rc = fill32(c, d.sc + SC_T, (uint32_t)params->t0, 1, s))) return bail(rc);
   if ((rc = fill32(c, d.sc + SC_SEQ, 1u, 1, s))) return bail(rc);
-  if ((rc = fill32(c, d.sc + SC_QUEUE, (uint32_t)c->fused_grid, 1, s))) return bail(rc);
+  if ((rc = fill32(c, d.sc + SC_QUEUE, 0u, 1, s))) return bail(rc);
   if (hipMemcpyAsync((void*)d.tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) return bail(CKV_EHIP);
   if ((rc = upload_budgets(c, budgets, s))) return bail(rc);
   if (hipStreamSynchronize(s) != hipSuccess) return bail(CKV_EHIP);
@@ -364,8 +388,9 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_loaded[l] = 1;
   hipStream_t s = (hipStream_t)stream;
 
-  const bool fused = c->fused_ok && layer == -1 &&
-                     (c->path_mode == 2 || (c->path_mode == 0 && count >= 4 * c->fused_grid));
+  const ckv_ctx::Fused* fv = layer == -1 ? fused_variant(c) : nullptr;
+  if (fv && c->path_mode == 0 && count < 4 * fv->grid) fv = nullptr;
+  const bool fused = fv != nullptr;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1);
   CKV_HIP(c, hipGetLastError());
@@ -385,8 +410,12 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     CKV_HIP(c, hipEventRecord(e0, s));
   }
   if (fused) {
-    hipLaunchKernelGGL(unit_kernel, dim3((unsigned)c->fused_grid), dim3(kThreads), c->fused_lds, s, c->dev,
-                       (const uint16_t*)q, out, flags & CKV_FUSE_EVICT, advance, c->lds_main);
+    if (fv->waves == 4)
+      hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, c->dev, (const uint16_t*)q, out,
+                         flags & CKV_FUSE_EVICT, advance, fv->lds_main);
+    else
+      hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, c->dev, (const uint16_t*)q, out,
+                         flags & CKV_FUSE_EVICT, advance, fv->lds_main);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
     return CKV_OK;
@@ -418,9 +447,7 @@ int ckv_rebudget(ckv_ctx* c, void* stream) {
   if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
   hipLaunchKernelGGL(rebudget_kernel, dim3((unsigned)c->lay.batch), dim3(kThreads), 0, (hipStream_t)stream, c->dev);
   CKV_HIP(c, hipGetLastError());
-  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, c->dev);
-  CKV_HIP(c, hipGetLastError());
-  return CKV_OK;
+  return launch_schedule(c, (hipStream_t)stream);
 }
 
 int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, void* stream) {
@@ -524,7 +551,18 @@ int ckv_export_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
   if (crf) CKV_HIP(c, hipMemcpy(crf, c->dev.crf + base, cap * 4, hipMemcpyDeviceToHost));
   if (tau) CKV_HIP(c, hipMemcpy(tau, c->dev.tau + base, cap * 4, hipMemcpyDeviceToHost));
   if (pos) CKV_HIP(c, hipMemcpy(pos, c->dev.pos + base, cap * 4, hipMemcpyDeviceToHost));
-  if (flags) CKV_HIP(c, hipMemcpy(flags, c->dev.flags + base, cap, hipMemcpyDeviceToHost));
+  if (flags) {
+    CKV_HIP(c, hipMemcpy(flags, c->dev.flags + base, cap, hipMemcpyDeviceToHost));
+    // the hit mark is not stored: in the top-p mode an entry was hit in the unit's last step iff its tau is that step
+    int32_t tu = 0;
+    CKV_HIP(c, hipMemcpy(&tu, c->dev.t_unit + u, 4, hipMemcpyDeviceToHost));
+    if (c->dev.reward_mode == 0 && tu >= c->par.t0 && n > 0) {
+      std::vector<int32_t> th((size_t)n);
+      CKV_HIP(c, hipMemcpy(th.data(), c->dev.tau + base, (size_t)n * 4, hipMemcpyDeviceToHost));
+      for (int i = 0; i < n; ++i)
+        if (th[i] == tu) flags[i] |= CKV_FLAG_HIT;
+    }
+  }
   return CKV_OK;
 }
 
@@ -605,16 +643,20 @@ int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, vo
 }
 
 int ckv_set_path(ckv_ctx* c, int32_t mode) {
-  if (!c || mode < 0 || mode > 2) return CKV_EINVAL;
-  if (mode == 2 && !c->fused_ok) return fail(c, CKV_EINVAL, "cap too large for the fused kernel's LDS");
+  if (!c || mode < 0 || mode > 4) return CKV_EINVAL;
+  const bool any = c->fused[0].ok || c->fused[1].ok;
+  if ((mode == 2 && !any) || (mode == 3 && !c->fused[0].ok) || (mode == 4 && !c->fused[1].ok))
+    return fail(c, CKV_EINVAL, "cap too large for the fused kernel's LDS");
   c->path_mode = mode;
   return CKV_OK;
 }
 
 int ckv_path_info(ckv_ctx* c, int32_t* fused_available, int32_t* lds_main_bytes) {
   if (!c) return CKV_EINVAL;
-  if (fused_available) *fused_available = c->fused_ok ? 1 : 0;
-  if (lds_main_bytes) *lds_main_bytes = c->lds_main;
+  const ckv_ctx::Fused* f = c->path_mode == 3 ? &c->fused[0] : c->path_mode == 4 ? &c->fused[1]
+                            : c->fused[0].ok ? &c->fused[0] : &c->fused[1];
+  if (fused_available) *fused_available = f->ok ? f->waves : 0;
+  if (lds_main_bytes) *lds_main_bytes = f->lds_main;
   return CKV_OK;
 }
 

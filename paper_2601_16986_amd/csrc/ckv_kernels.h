@@ -62,6 +62,8 @@ struct Dev {
   float* logits;         // [units][cap/32][G][32] scaled logits (base-2 domain)
   long long* btotal;     // [Bz] budget total per sequence
   int32_t* order;        // [units] unit indices by descending budget (schedule of the fused kernel)
+  int32_t* rank;         // [units] inverse of `order`
+  int4* sched;           // [units] schedule entry i: {unit order[i], its entry count after this step's append, its budget, 0}
 };
 
 
@@ -140,50 +142,57 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
   return min_u64(min_u64(readlane_u64(v, 0), readlane_u64(v, 16)), min_u64(readlane_u64(v, 32), readlane_u64(v, 48)));
 }
 
-// Block-wide reductions with a fixed combination order (deterministic).  `buf`
-// is a [2][4] LDS array used alternately, so one barrier per call suffices.
+// Block-wide reductions over NT threads with a fixed combination order
+// (deterministic).  `rb` is a [2][NT/64] LDS array used alternately, so one
+// barrier per call suffices.
 struct RedBuf {
   u64 v[2][4];
 };
 
+template <int NT = kThreads>
 __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_u64(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
   __syncthreads();
-  u64 r = rb.v[phase][0] + rb.v[phase][1] + rb.v[phase][2] + rb.v[phase][3];
+  u64 r = rb.v[phase][0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r += rb.v[phase][w];
   phase ^= 1;
   return r;
 }
 
+template <int NT = kThreads>
 __device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_i32(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)(uint32_t)v;
   __syncthreads();
-  const int r = (int)(uint32_t)rb.v[phase][0] + (int)(uint32_t)rb.v[phase][1] + (int)(uint32_t)rb.v[phase][2] +
-                (int)(uint32_t)rb.v[phase][3];
+  int r = (int)(uint32_t)rb.v[phase][0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r += (int)(uint32_t)rb.v[phase][w];
   phase ^= 1;
   return r;
 }
 
+template <int NT = kThreads>
 __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_f32(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)__float_as_uint(v);
   __syncthreads();
   float r = __uint_as_float((uint32_t)rb.v[phase][0]);
-  r += __uint_as_float((uint32_t)rb.v[phase][1]);
-  r += __uint_as_float((uint32_t)rb.v[phase][2]);
-  r += __uint_as_float((uint32_t)rb.v[phase][3]);
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r += __uint_as_float((uint32_t)rb.v[phase][w]);
   phase ^= 1;
   return r;
 }
 
+template <int NT = kThreads>
 __device__ __forceinline__ u64 block_min_u64(u64 v, RedBuf& rb, int& phase, int tid) {
   v = wave_min_u64(v);
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
   __syncthreads();
   u64 r = rb.v[phase][0];
 #pragma unroll
-  for (int w = 1; w < 4; ++w) r = rb.v[phase][w] < r ? rb.v[phase][w] : r;
+  for (int w = 1; w < NT / 64; ++w) r = rb.v[phase][w] < r ? rb.v[phase][w] : r;
   phase ^= 1;
   return r;
 }
@@ -328,7 +337,10 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
       }
     }
   }
-  if (append & 2) return;                 // the fused kernel schedules whole units: no work list
+  if (append & 2) {                       // the fused kernel schedules whole units: one schedule entry per unit, no work list
+    if (active && sub == 0) d.sched[d.rank[u]] = make_int4(u, n, d.budget[u], 0);
+    return;
+  }
   const int nch = active ? (n + kChunk - 1) / kChunk : 0;
   const int nblk = active ? (n + kBlk - 1) / kBlk : 0;
   if (sub == 0) {
@@ -631,6 +643,37 @@ __device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, i
   }
 }
 
+// Eviction of exactly one entry: the last slot's entry moves into the victim's
+// slot `dst`, whose position goes to the last slot, flagged as evicted.  The K
+// row, the V row and the per-slot state are handled by different wavefronts;
+// the state comes from sh[1..4] = {CRF bits, tau, position} of the last slot's
+// entry and the victim's position, so no per-slot array is read.
+template <int NT = kThreads>
+__device__ __forceinline__ void evict_one(const Dev& d, size_t base, int src, int dst, const int* sh, int tid) {
+  const int wave = tid >> 6, lane = tid & 63;
+  constexpr int W = NT / 64;
+  uint16_t* K = d.K + base * kDim;
+  uint16_t* V = d.V + base * kDim;
+  if (dst != src) {
+    if (wave == 0 && lane < 16)
+      *reinterpret_cast<u32x4*>(K + k_offset(dst, lane * 8)) = *reinterpret_cast<const u32x4*>(K + k_offset(src, lane * 8));
+    if (wave == (W > 1 ? 1 : 0)) {
+      const uint16_t v0 = V[v_offset(src, lane)], v1 = V[v_offset(src, lane + 64)];
+      V[v_offset(dst, lane)] = v0;
+      V[v_offset(dst, lane + 64)] = v1;
+    }
+  }
+  if (wave == (W > 2 ? 2 : 0) && lane == 32) {
+    if (dst != src) {
+      d.crf[base + dst] = __int_as_float(sh[1]);
+      d.tau[base + dst] = sh[2];
+      d.pos[base + dst] = sh[3];
+      d.pos[base + src] = sh[4];
+    }
+    d.flags[base + src] = FLAG_SLIP;
+  }
+}
+
 // Per-entry LDS values (mean weight, then CRF_temp) are reached through an
 // accessor: a plain array in the finish kernel, a view into the logits tile in
 // the fused unit kernel.
@@ -642,7 +685,7 @@ struct ValLinear {
 // Alg. 1 Step 4 for one unit with n > B.  val(i) = CRF_temp of slot i (LDS),
 // evm = LDS bit mask of n bits, lst = LDS scratch of lst_cap >= n ints that may
 // overlap the storage behind `val` (the scores are dead by the time it is used).
-template <class Val>
+template <class Val, int NT = kThreads>
 __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
                             int& phase, int* sh, int tid) {
   const size_t base = (size_t)u * d.cap;
@@ -651,16 +694,16 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
   if (k == 1) {
     u64 best = ~0ull;
     int best_i = -1;
-    for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+    for (int i0 = tid; i0 < n; i0 += 4 * NT) {
       int ps[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int i = i0 + r * kThreads;
+        const int i = i0 + r * NT;
         ps[r] = i < n ? d.pos[base + i] : 0;
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int i = i0 + r * kThreads;
+        const int i = i0 + r * NT;
         if (i < n) {
           const u64 key = evict_key(val(i), ps[r]);
           if (key < best) {
@@ -670,7 +713,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
         }
       }
     }
-    const u64 gbest = block_min_u64(best, rb, phase, tid);
+    const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
     if (best == gbest && best_i >= 0) sh[0] = best_i;     // keys are unique: one writer
     __syncthreads();
     const int e = sh[0];
@@ -687,18 +730,18 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
     for (int bit = 62; bit >= 0; --bit) {
       const u64 trial = X | (1ull << bit);
       int cnt = 0;
-      for (int i = tid; i < n; i += kThreads) cnt += evict_key(val(i), d.pos[base + i]) < trial ? 1 : 0;
-      cnt = block_sum_int(cnt, rb, phase, tid);
+      for (int i = tid; i < n; i += NT) cnt += evict_key(val(i), d.pos[base + i]) < trial ? 1 : 0;
+      cnt = block_sum_int<NT>(cnt, rb, phase, tid);
       if (cnt < k) X = trial;
     }
     const int words = (n + 31) >> 5;
-    for (int w = tid; w < words; w += kThreads) evm[w] = 0u;
+    for (int w = tid; w < words; w += NT) evm[w] = 0u;
     __syncthreads();
-    for (int i = tid; i < n; i += kThreads)
+    for (int i = tid; i < n; i += NT)
       if (evict_key(val(i), d.pos[base + i]) <= X) atomicOr(&evm[i >> 5], 1u << (i & 31));
     __syncthreads();
     // holes = evicted slots below B, movers = surviving slots at or above B (equal counts)
-    const int wpt = (words + kThreads - 1) / kThreads;
+    const int wpt = (words + NT - 1) / NT;
     const int w0 = min(words, tid * wpt), w1 = min(words, w0 + wpt);
     uint32_t holes = 0, movers = 0;
     for (int w = w0; w < w1; ++w) {
@@ -720,7 +763,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
     __syncthreads();
     uint32_t prefix = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NT / 64; ++w) {
       if (w < wave) prefix += (uint32_t)sh[4 + w];
       total += (uint32_t)sh[4 + w];
     }
@@ -744,9 +787,9 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
     }
     __syncthreads();
     // evicted entries that already sit at or above B just get their flag
-    for (int i = B + tid; i < n; i += kThreads)
+    for (int i = B + tid; i < n; i += NT)
       if ((evm[i >> 5] >> (i & 31)) & 1u) d.flags[base + i] = FLAG_SLIP;
-    for (int r = wave; r < h; r += kThreads / 64) move_entry(d, base, lst[lst_cap - 1 - r], lst[r], lane);
+    for (int r = wave; r < h; r += NT / 64) move_entry(d, base, lst[lst_cap - 1 - r], lst[r], lane);
   }
   if (tid == 0) {
     d.n[u] = B;
@@ -866,7 +909,7 @@ __device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const f
 // score update, flags.  Leaves CRF_temp in val(i) and returns the unit's
 // aggregated CRF (2^-20 fixed point), summed over the block.  s_tab: the first
 // s_tab_n entries of the decay table in LDS.
-template <class Val>
+template <class Val, int NT = kThreads>
 __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
                            int& phase, int tid) {
   const size_t base = (size_t)u * d.cap;
@@ -878,25 +921,25 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
     for (int bit = 30; bit >= 0; --bit) {
       const uint32_t cand = theta | (1u << bit);
       float part = 0.f;
-      for (int i = tid; i < n; i += kThreads) {
+      for (int i = tid; i < n; i += NT) {
         const float a = val(i);
         part += (__float_as_uint(a) >= cand) ? a : 0.f;
       }
-      const float tot = block_sum_f32(part, rb, phase, tid);
+      const float tot = block_sum_f32<NT>(part, rb, phase, tid);
       if (tot > d.top_p) theta = cand;
     }
     if (theta != 0) {
       // entries equal to the threshold: only as many as needed, lower positions first
       float above = 0.f;
       int ties = 0;
-      for (int i = tid; i < n; i += kThreads) {
+      for (int i = tid; i < n; i += NT) {
         const float a = val(i);
         const uint32_t b = __float_as_uint(a);
         above += (b > theta) ? a : 0.f;
         ties += (b == theta) ? 1 : 0;
       }
-      above = block_sum_f32(above, rb, phase, tid);
-      ties = block_sum_int(ties, rb, phase, tid);
+      above = block_sum_f32<NT>(above, rb, phase, tid);
+      ties = block_sum_int<NT>(ties, rb, phase, tid);
       if (ties > 1) {
         const float th = __uint_as_float(theta);
         float c = above;
@@ -911,9 +954,9 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
           for (int bit = 30; bit >= 0; --bit) {
             const int trial = X | (1 << bit);
             int cnt = 0;
-            for (int i = tid; i < n; i += kThreads)
+            for (int i = tid; i < n; i += NT)
               cnt += (__float_as_uint(val(i)) == theta && d.pos[base + i] < trial) ? 1 : 0;
-            cnt = block_sum_int(cnt, rb, phase, tid);
+            cnt = block_sum_int<NT>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
           }
           pos_cut = X;
@@ -926,12 +969,12 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
   const bool has_new = d.pos[base + n - 1] == t;
   const bool need_pos = d.reward_mode == 0 && !ties_all;
   u64 sfix = 0;
-  for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+  for (int i0 = tid; i0 < n; i0 += 4 * NT) {
     float crf[4], dec[4];
     int tau[4], ps[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int i = i0 + r * kThreads;
+      const int i = i0 + r * NT;
       const bool ok = i < n;
       crf[r] = ok ? d.crf[base + i] : 0.f;
       tau[r] = ok ? d.tau[base + i] : t;
@@ -945,7 +988,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int i = i0 + r * kThreads;
+      const int i = i0 + r * NT;
       if (i < n) {
         const float a = val(i);
         bool hit, store;
@@ -957,7 +1000,6 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
           store = hit;
           reward = hit ? 1.0f : 0.0f;
         } else {
-          hit = false;
           store = true;
           reward = a;
         }
@@ -967,65 +1009,83 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
           d.crf[base + i] = tmp;
           d.tau[base + i] = t;
         }
-        d.flags[base + i] = hit ? FLAG_HIT : 0;
         val(i) = tmp;
         sfix += (u64)floorf(tmp * kFixedOne);
       }
     }
   }
-  return block_sum_u64(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
+  return block_sum_u64<NT>(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
 }
 
-// Mean attention weight of the entries tid + 256 k of unit u (global logits) into registers.
-template <int R>
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Register-resident bookkeeping: thread tid of NT owns R = 4 C entries, in C
+// groups of four consecutive entries 4 (tid + c NT) .. + 3 (group c), so that
+// every access to the per-entry arrays is a 16-byte one: the memory pipeline of
+// a CU is shared with the streaming loads of the other workgroup and every
+// instruction queues behind them, so the number of memory instructions, not
+// their size, is what the latency of this phase depends on.
+
+// Mean attention weights of this thread's groups from logits in global memory
+// (per block of 32 entries: [head][32]); 0 beyond n.
+template <int R, int NT = kThreads>
 __device__ __forceinline__ void mean_weights_regs(const Dev& d, int u, int n, const float* sM, const float* sInv,
                                                   float (&a)[R], int tid) {
   const int G = d.G;
   const float invG = 1.0f / (float)G;
-  const float* lg = d.logits + (size_t)u * G * d.cap;      // per block of 32 entries: [head][32]
+  const float* lg = d.logits + (size_t)u * G * d.cap;
 #pragma unroll
-  for (int k0 = 0; k0 < R; k0 += 4) {
-    float x[4][kMaxGroup];
+  for (int c = 0; c < R / 4; ++c) {
+    const int e0 = 4 * (tid + c * NT);
+    f32x4 x[kMaxGroup];
+    const float* row = lg + (size_t)(e0 >> 5) * (G * kBlk) + (e0 & 31);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int i = tid + (k0 + r) * kThreads;
-      const float* row = lg + (size_t)(i >> 5) * (G * kBlk) + (i & 31);
+    for (int g = 0; g < kMaxGroup; ++g)
+      x[g] = (e0 < n && g < G) ? *reinterpret_cast<const f32x4*>(row + g * kBlk) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
-      for (int g = 0; g < kMaxGroup; ++g) x[r][g] = (i < n && g < G) ? row[g * kBlk] : -INFINITY;
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int e = 0; e < 4; ++e) {
       float acc = 0.f;
 #pragma unroll
       for (int g = 0; g < kMaxGroup; ++g)
-        if (g < G) acc += fast_exp2(x[r][g] - sM[g]) * sInv[g];
-      a[k0 + r] = (tid + (k0 + r) * kThreads < n) ? acc * invG : 0.f;
+        if (g < G) acc += fast_exp2(x[g][e] - sM[g]) * sInv[g];
+      a[4 * c + e] = (e0 + e < n) ? acc * invG : 0.f;
     }
   }
 }
 
-// Alg. 1 Steps 1-4 for a unit of n <= 256 R entries with everything in
-// registers: thread tid owns entries tid + 256 k, a[k] holds their mean
-// weights on entry (0 beyond n).  Same decisions and arithmetic as
-// lrfu_update + evict_phase, without re-reading LDS in the 31 bisection rounds;
-// the entries' CRF, tau and position are loaded up front so that their latency
-// hides behind the bisection.  Evicting more than one entry falls back to
-// evict_phase (the scores are then left in val()).
-template <int R, class Val>
-__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], Val val, bool evict, uint32_t* evm,
-                          int* lst, int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
-                          int tid) {
+// CRF, tau and position of group c of thread tid.  The loads are unconditional
+// (a select on their result would wait for them on the spot): a group beyond
+// the unit reads the unit's last group instead (the arrays hold cap entries, a
+// multiple of 4), and nothing looks at the values of entries >= n.
+template <int NT = kThreads>
+__device__ __forceinline__ void load_meta(const Dev& d, size_t base, int n, int t, int c, int tid, f32x4& crf, i32x4& tau, i32x4& ps) {
+  const int e0 = min(4 * (tid + c * NT), d.cap - 4);
+  crf = *reinterpret_cast<const f32x4*>(d.crf + base + e0);
+  tau = *reinterpret_cast<const i32x4*>(d.tau + base + e0);
+  ps = *reinterpret_cast<const i32x4*>(d.pos + base + e0);
+}
+
+// Alg. 1 Steps 1-4 for a unit of n <= R NT entries with the weights in
+// registers (a[4 c + e] = mean weight of entry 4 (tid + c NT) + e, 0 beyond n).
+// Same decisions and arithmetic as lrfu_update + evict_phase.  The groups'
+// CRF, tau and position pass through register arrays of CH groups: the caller
+// has loaded the first CP of them (early enough that they have arrived), the
+// rest of the first CH groups are loaded here, before the bisection, whose 31
+// rounds hide their latency; further chunks of CH groups (large units only, to
+// bound the registers) are loaded when their turn comes.  The hit mark of an entry is not stored: in the
+// top-p mode it equals tau == t.  Evicting exactly one entry is done in place
+// (the owners of the two entries involved pass their registers through `sh`);
+// evicting more falls back to evict_phase (scores then go to val()).
+template <int R, int CH, int CP, class Val, int NT = kThreads>
+__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
+                                          i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
+                                          int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
+                                          int tid) {
+  constexpr int C = R / 4;
+  static_assert(C % CH == 0 && CP <= CH, "groups come in chunks of CH");
   const size_t base = (size_t)u * d.cap;
-  float crf[R];
-  int tau[R], ps[R];
 #pragma unroll
-  for (int k = 0; k < R; ++k) {
-    const int i = tid + k * kThreads;
-    const bool ok = i < n;
-    crf[k] = ok ? d.crf[base + i] : 0.f;
-    tau[k] = ok ? d.tau[base + i] : t;
-    ps[k] = ok ? d.pos[base + i] : 0x7FFFFFFF;
-  }
+  for (int c = CP; c < CH; ++c) load_meta<NT>(d, base, n, t, c, tid, crf[c], tau[c], ps[c]);
   // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
   uint32_t theta = 0;
   bool ties_all = true;
@@ -1036,7 +1096,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       float part = 0.f;
 #pragma unroll
       for (int k = 0; k < R; ++k) part += (__float_as_uint(a[k]) >= cand) ? a[k] : 0.f;
-      const float tot = block_sum_f32(part, rb, phase, tid);
+      const float tot = block_sum_f32<NT>(part, rb, phase, tid);
       if (tot > d.top_p) theta = cand;
     }
     if (theta != 0) {
@@ -1048,8 +1108,8 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
         above += (b > theta) ? a[k] : 0.f;
         ties += (b == theta) ? 1 : 0;
       }
-      above = block_sum_f32(above, rb, phase, tid);
-      ties = block_sum_int(ties, rb, phase, tid);
+      above = block_sum_f32<NT>(above, rb, phase, tid);
+      ties = block_sum_int<NT>(ties, rb, phase, tid);
       if (ties > 1) {
         const float th = __uint_as_float(theta);
         float c = above;
@@ -1060,13 +1120,15 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
         } while (c <= d.top_p && r < ties);
         if (r < ties) {
           ties_all = false;
-          int X = 0;   // r-th smallest position among the ties
+          int X = 0;   // r-th smallest position among the ties (rare: positions are re-read from memory)
           for (int bit = 30; bit >= 0; --bit) {
             const int trial = X | (1 << bit);
             int cnt = 0;
-#pragma unroll
-            for (int k = 0; k < R; ++k) cnt += (__float_as_uint(a[k]) == theta && ps[k] < trial) ? 1 : 0;
-            cnt = block_sum_int(cnt, rb, phase, tid);
+            for (int k = 0; k < R; ++k) {
+              const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
+              if (__float_as_uint(a[k]) == theta && i < n && d.pos[base + i] < trial) ++cnt;
+            }
+            cnt = block_sum_int<NT>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
           }
           pos_cut = X;
@@ -1074,40 +1136,79 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       }
     }
   }
-  // ---- Steps 2-3: scores; a[k] becomes CRF_temp
+  // ---- Steps 2-3: scores; a[k] becomes CRF_temp.  The candidate for Step 4 (lowest score, then
+  // highest position) is tracked on the way.
   u64 sfix = 0;
+  u64 best = ~0ull;
+  int best_i = -1;
 #pragma unroll
-  for (int k = 0; k < R; ++k) {
-    const int i = tid + k * kThreads;
-    if (i < n) {
-      int delta = t - tau[k];
-      delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
-      const float dec = delta < s_tab_n ? s_tab[delta] : d.tab[delta];
-      bool hit, store;
-      float reward;
-      if (d.reward_mode == 0) {
-        const uint32_t b = __float_as_uint(a[k]);
-        hit = (b > theta) || (b == theta && (ties_all || ps[k] <= pos_cut));
-        if (i == n - 1 && ps[k] == t) hit = true;          // the entry appended this step
-        store = hit;
-        reward = hit ? 1.0f : 0.0f;
-      } else {
-        hit = false;
-        store = true;
-        reward = a[k];
+  for (int cc = 0; cc < C; ++cc) {
+    const int c = cc % CH;                  // register slot of group cc
+    if (cc >= CH && c == 0) {               // next chunk of groups: its state is requested only now
+#pragma unroll
+      for (int k = 0; k < CH; ++k) load_meta<NT>(d, base, n, t, cc + k, tid, crf[k], tau[k], ps[k]);
+    }
+    const int e0 = 4 * (tid + cc * NT);
+    if (e0 < n) {
+      f32x4 ncrf = crf[c];
+      i32x4 ntau = tau[c];
+      uint32_t stored = 0;                  // bit e: entry e0 + e gets a new (CRF, tau)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = e0 + e;
+        if (i < n) {
+          int delta = t - tau[c][e];
+          delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+          const float dec = delta < s_tab_n ? s_tab[delta] : d.tab[delta];
+          bool hit, store;
+          float reward;
+          if (d.reward_mode == 0) {
+            const uint32_t b = __float_as_uint(a[4 * cc + e]);
+            hit = (b > theta) || (b == theta && (ties_all || ps[c][e] <= pos_cut));
+            if (i == n - 1 && ps[c][e] == t) hit = true;          // the entry appended this step
+            store = hit;
+            reward = hit ? 1.0f : 0.0f;
+          } else {
+            store = true;
+            reward = a[4 * cc + e];
+          }
+          float tmp = __fadd_rn(__fmul_rn(dec, crf[c][e]), reward);
+          if (tmp < FLT_MIN) tmp = 0.0f;
+          if (store) {
+            ncrf[e] = tmp;
+            ntau[e] = t;
+            stored |= 1u << e;
+          }
+          a[4 * cc + e] = tmp;
+          sfix += (u64)floorf(tmp * kFixedOne);
+          const u64 key = evict_key(tmp, ps[c][e]);
+          if (key < best) {
+            best = key;
+            best_i = i;
+          }
+          if (i == n - 1) {                  // the last slot's final state, for the in-place eviction
+            sh[1] = __float_as_int(ncrf[e]);
+            sh[2] = ntau[e];
+            sh[3] = ps[c][e];
+          }
+        }
       }
-      float tmp = __fadd_rn(__fmul_rn(dec, crf[k]), reward);
-      if (tmp < FLT_MIN) tmp = 0.0f;
-      if (store) {
-        d.crf[base + i] = tmp;
-        d.tau[base + i] = t;
+      if (e0 + 3 < n) {
+        if (stored) {
+          *reinterpret_cast<f32x4*>(d.crf + base + e0) = ncrf;
+          *reinterpret_cast<i32x4*>(d.tau + base + e0) = ntau;
+        }
+      } else {                               // the unit's last, partial group: entry by entry
+        for (int e = 0; e < 4 && e0 + e < n; ++e) {
+          if ((stored >> e) & 1u) {
+            d.crf[base + e0 + e] = ncrf[e];
+            d.tau[base + e0 + e] = t;
+          }
+        }
       }
-      d.flags[base + i] = hit ? FLAG_HIT : 0;
-      a[k] = tmp;
-      sfix += (u64)floorf(tmp * kFixedOne);
     }
   }
-  sfix = block_sum_u64(sfix, rb, phase, tid);
+  sfix = block_sum_u64<NT>(sfix, rb, phase, tid);
   if (tid == 0) {
     d.window[u] += sfix;
     d.t_unit[u] = t;
@@ -1118,30 +1219,13 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     return;
   }
   if (n - B == 1) {
-    u64 best = ~0ull;
-    int best_i = -1;
-#pragma unroll
-    for (int k = 0; k < R; ++k) {
-      const int i = tid + k * kThreads;
-      if (i < n) {
-        const u64 key = evict_key(a[k], ps[k]);
-        if (key < best) {
-          best = key;
-          best_i = i;
-        }
-      }
+    const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
+    if (best == gbest && best_i >= 0) {     // keys are unique: one writer
+      sh[0] = best_i;
+      sh[4] = ~(int)(uint32_t)best;         // the victim's position
     }
-    const u64 gbest = block_min_u64(best, rb, phase, tid);
-    if (best == gbest && best_i >= 0) sh[0] = best_i;     // keys are unique: one writer
     __syncthreads();
-    const int e = sh[0];
-    if ((tid >> 6) == 0) {
-      if (e != n - 1) {
-        move_entry(d, base, n - 1, e, tid & 63);
-      } else if (tid == 0) {
-        d.flags[base + e] = FLAG_SLIP;
-      }
-    }
+    evict_one<NT>(d, base, n - 1, sh[0], sh, tid);
     if (tid == 0) {
       d.n[u] = B;
       d.nev[u] = 1;
@@ -1149,11 +1233,11 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   } else {
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-      const int i = tid + k * kThreads;
+      const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
       if (i < n) val(i) = a[k];
     }
     __syncthreads();
-    evict_phase(d, u, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
+    evict_phase<Val, NT>(d, u, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
   }
 }
 
@@ -1181,8 +1265,27 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
     if (n <= 8 * kThreads) {
       float a[8];
       mean_weights_regs(d, u, n, sM, sInv, a, tid);
-      lrfu_regs<8>(d, u, n, B, t, a, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap, s_tab, s_tab_n, rb,
+      f32x4 crf[2];
+      i32x4 tau[2], ps[2];
+      lrfu_regs<8, 2, 0, ValLinear>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+                  s_tab, s_tab_n, rb,
                    phase, sh, tid);
+    } else if (n <= 16 * kThreads) {
+      float a[16];
+      mean_weights_regs(d, u, n, sM, sInv, a, tid);
+      f32x4 crf[4];
+      i32x4 tau[4], ps[4];
+      lrfu_regs<16, 4, 0, ValLinear>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+                   s_tab, s_tab_n, rb,
+                    phase, sh, tid);
+    } else if (n <= 32 * kThreads) {
+      float a[32];
+      mean_weights_regs(d, u, n, sM, sInv, a, tid);
+      f32x4 crf[8];
+      i32x4 tau[8], ps[8];
+      lrfu_regs<32, 8, 0, ValLinear>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+                   s_tab, s_tab_n, rb,
+                    phase, sh, tid);
     } else {
       mean_weights(d, u, n, sM, sInv, val, tid);
       const u64 sfix = lrfu_update(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);

@@ -23,6 +23,8 @@
 // follow the tile.  Units whose logits do not fit spill the logits of their
 // last blocks to the global logits buffer (same layout as the scan kernel's).
 #pragma once
+#include <type_traits>
+
 #include "ckv_kernels.h"
 
 namespace ckv {
@@ -47,9 +49,12 @@ __device__ __forceinline__ int resident_entries(int n, int G, int lds_main_bytes
   return r < n_pad ? r : n_pad;
 }
 
-// Unit indices by descending budget: counting sort over budget / 32, one
-// workgroup.  The order inside a class is arbitrary; it only affects scheduling.
-__global__ __launch_bounds__(1024) void order_kernel(Dev d) {
+// Schedule of the fused kernel: the units sorted by descending budget (counting
+// sort over budget / 32, one workgroup; the order inside a class is arbitrary,
+// it only affects scheduling).  Unit u gets slot rank[u] of `sched`, whose
+// entries {unit, entries, budget} prep_kernel refreshes every step.  Workgroups
+// take the slots in order, largest units first.
+__global__ __launch_bounds__(1024) void schedule_kernel(Dev d) {
   __shared__ int hist[1025];
   const int tid = threadIdx.x;
   for (int i = tid; i < 1025; i += 1024) hist[i] = 0;
@@ -68,102 +73,162 @@ __global__ __launch_bounds__(1024) void order_kernel(Dev d) {
   for (int u = tid; u < d.units; u += 1024) {
     const int slot = atomicAdd(&hist[1023 - min(1023, d.budget[u] >> 5)], 1);
     d.order[slot] = u;
+    d.rank[u] = slot;
   }
 }
 
-__global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t* __restrict__ q, void* out,
-                                                           uint32_t call_flags, int advance, int lds_main) {
+// W wavefronts per workgroup (and per unit), 8 / W workgroups per CU.
+template <int W>
+__global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* __restrict__ q, void* out,
+                                                             uint32_t call_flags, int advance, int lds_main) {
+  constexpr int NT = 64 * W;
+  constexpr int kSlices = W / 2;             // LDS slices the accumulators are merged through, two waves each
   extern __shared__ unsigned char smem[];
   float* lg = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + lds_main);
-  __shared__ float s_stage[kThreads / 64][kMaxGroup * kLgRow];   // staging tiles for spilled logits
-  __shared__ float s_out[2][kMaxGroup * kDim];
-  __shared__ float s_ml[kThreads / 64][kMaxGroup][2];
+  // staging tiles for spilled logits while streaming, accumulator slices afterwards
+  constexpr int kStageFloats = W * kMaxGroup * kLgRow, kOutFloats = kSlices * kMaxGroup * kDim;
+  __shared__ float s_buf[kStageFloats > kOutFloats ? kStageFloats : kOutFloats];
+  float* s_out = s_buf;
+  __shared__ float s_ml[W][kMaxGroup][2];
   __shared__ float sM[kMaxGroup], sInv[kMaxGroup];
   __shared__ float s_tab[kTabLds];
   __shared__ RedBuf rb;
   __shared__ int sh[8];
-  __shared__ int s_idx[2];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j = lane & 15, kg = lane >> 4;
   const int G = d.G;
-  const bool head_lane = j < G;
-  const int jq = head_lane ? j : 0;
   const size_t unit_elems = (size_t)d.cap * kDim;
   const int n_units = d.units;
   const int t = d.sc[SC_T];
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
-  if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
-  if (tid == 0) {
-    s_idx[0] = blockIdx.x;
-    s_idx[1] = atomicAdd(&d.sc[SC_QUEUE], 1);
-  }
+  for (int i = tid; i < s_tab_n; i += NT) s_tab[i] = d.tab[i];
   __syncthreads();
-  int idx = s_idx[0], idx_next = s_idx[1];
 
-  int u = idx < n_units ? d.order[idx] : 0;
-  int n = idx < n_units ? d.n[u] : 0;
+  // Work distribution: schedule slots (units by descending budget) are taken from a shared queue, except
+  // for the first three rounds, which are static (slot = round * grid + workgroup).  A slot is claimed
+  // three units ahead and its entry fetched two units ahead, so that neither the atomic's return
+  // value nor the entry is ever waited for: the claim made while unit r streams is picked up during
+  // unit r's bookkeeping, when everything requested before it has long arrived (a wait for one
+  // result of the vector memory pipeline is a wait for all results requested before it).
+  __shared__ int s_claim;
+  const int grid = (int)gridDim.x, wg = (int)blockIdx.x;
+  auto fetch = [&](int slot, int& uu, int& nn, int& bb) {      // uniform slot: scalar loads
+    const int4 e = d.sched[min(slot, n_units - 1)];
+    uu = slot < n_units ? e.x : -1;
+    nn = e.y;
+    bb = e.z;
+  };
+  int u, n, B, u1, n1, B1;
+  fetch(wg, u, n, B);
+  fetch(grid + wg, u1, n1, B1);
+  int slot2 = 2 * grid + wg;                                   // slot of the unit after next
+  // Per-lane values are re-derived, from a copy of the lane index the compiler cannot see through, at
+  // the start of every phase that needs them: otherwise they are computed once, kept alive across the
+  // whole unit loop, and spilled, and every reload of a spilled register waits for all loads in flight.
+  int slane = lane;
+  asm volatile("" : "+v"(slane));
+  KFrag ka;
+  VFrag va;
+  bf16x8 qv[4];
+  // first block of wave `wave` in a unit of nb blocks (any valid block if the wave has none there)
+  auto first_off = [&](int uu, int nn) -> size_t {
+    const int nb = (nn + kBlk - 1) / kBlk;
+    return (size_t)uu * unit_elems + (size_t)min(wave, max(nb - 1, 0)) * kBlkElems + slane * 8;
+  };
+  auto load_q = [&](int uu) {
+    const int jh = slane & 15;
+    const uint16_t* qrow = q + ((size_t)uu * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      // lanes beyond the group read head 0's row: the columns they produce are never looked at, and
+      // selecting zeros here would wait for the load on the spot
+      qv[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * s));
+    }
+  };
+  if (u >= 0) {
+    const size_t o = first_off(u, n);
+    load_k(ka, d.K + o);
+    load_v(va, d.V + o);
+    load_q(u);
+  }
 
-  while (idx < n_units) {
-    // ---- claim the unit after next; look at the next one (its first blocks get prefetched)
-    int claimed = 0;
-    if (tid == 0) claimed = atomicAdd(&d.sc[SC_QUEUE], 1);
-    const bool have_next = idx_next < n_units;
-    const int u_next = have_next ? d.order[idx_next] : u;
-    const int n_next = have_next ? d.n[u_next] : n;
-
-    const int B = d.budget[u];
+  while (u >= 0) {
     const int nblk = (n + kBlk - 1) / kBlk;
     const int n_res = resident_entries(n, G, lds_main);
     const int res_blk = n_res / kBlk;
-    const int my_cnt = wave < nblk ? (nblk - wave + 3) / 4 : 0;
+    const int my_cnt = wave < nblk ? (nblk - wave + W - 1) / W : 0;
 
-    // ---- stream this wave's blocks
-    int slane = lane;
     asm volatile("" : "+v"(slane));
+    // ---- schedule entry of the unit after next: scalar loads, waited for with the first LDS access
+    // below, a unit before they are needed
+    int u2, n2, B2;
+    fetch(slot2, u2, n2, B2);
+
+    // ---- stream this wave's blocks (wave + W i, i < my_cnt): while block i is computed, block i + 1 is
+    // in flight; the last block's successor is the wave's first block of the next unit, so the loads
+    // never stop and every load in the loop is unconditional.  (Two blocks ahead was measured too:
+    // it lowers the achieved bandwidth.)
     f32x4 acc[8];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
-    if (my_cnt > 0) {
-      bf16x8 qv[4];
-      {
-        const uint16_t* qrow = q + ((size_t)u * G + jq) * kDim + 8 * kg;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          u32x4 x = *reinterpret_cast<const u32x4*>(qrow + 32 * s);
-          if (!head_lane) x = u32x4{0u, 0u, 0u, 0u};
-          qv[s] = as_bf16x8(x);
-        }
-      }
-      const uint16_t* kcur = d.K + (size_t)u * unit_elems + slane * 8;
-      const uint16_t* vcur = d.V + (size_t)u * unit_elems + slane * 8;
-      float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(slane, 8 * G - 1);
-      KFrag ka;
-      VFrag va;
-      load_k(ka, kcur + (size_t)wave * kBlkElems);
-      load_v(va, vcur + (size_t)wave * kBlkElems);
-      for (int i = 0; i < my_cnt; ++i) {
-        const int blk = wave + 4 * i;
-        const int nb = (i + 1 == my_cnt) ? blk : blk + 4;     // after the last block: read it once more (keeps the loads unconditional)
-        const bool resident = blk < res_blk;
-        float* lds_dst = resident ? lg + (size_t)blk * (G * kBlk) : s_stage[wave];
-        float sv[8];
-        scan_qk(ka, qv, sv, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
-                resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
-        load_k(ka, kcur + (size_t)nb * kBlkElems);
-        scan_pv(sv, va, acc, m_run, l_run, slane);
-        load_v(va, vcur + (size_t)nb * kBlkElems);
-      }
+    const uint16_t* kcur = d.K + (size_t)u * unit_elems + slane * 8;
+    const uint16_t* vcur = d.V + (size_t)u * unit_elems + slane * 8;
+    float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(slane, 8 * G - 1);
+    auto qk = [&](int blk, float (&sv)[8]) {
+      const bool resident = blk < res_blk;
+      float* lds_dst = resident ? lg + (size_t)blk * (G * kBlk) : s_buf + wave * (kMaxGroup * kLgRow);
+      scan_qk(ka, qv, sv, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
+              resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
+    };
+    for (int i = 0; i + 1 < my_cnt; ++i) {
+      const int blk = wave + W * i;
+      float sv[8];
+      qk(blk, sv);
+      load_k(ka, kcur + (size_t)(blk + W) * kBlkElems);
+      scan_pv(sv, va, acc, m_run, l_run, slane);
+      load_v(va, vcur + (size_t)(blk + W) * kBlkElems);
     }
+    // without a next unit the prefetch reads this unit's first block again and is ignored
+    const bool have_next = u1 >= 0;
+    const int u_next = have_next ? u1 : u;
+    const int n_next = have_next ? n1 : n;
+    const size_t o_next = first_off(u_next, n_next);
+    if (my_cnt > 0) {
+      float sv[8];
+      qk(wave + W * (my_cnt - 1), sv);
+      load_k(ka, d.K + o_next);
+      scan_pv(sv, va, acc, m_run, l_run, slane);
+      load_v(va, d.V + o_next);
+    } else {
+      load_k(ka, d.K + o_next);
+      load_v(va, d.V + o_next);
+    }
+    load_q(u_next);
+    // claim the slot of the unit three ahead; the result is picked up after the weights phase below
+    int claimed = 0;
+    if (tid == 0) claimed = atomicAdd(&d.sc[SC_QUEUE], 1);
+
+    // ---- CRF, tau and position of this thread's first groups of entries: requested now, behind the
+    // next unit's first block, so that they arrive during the merge and the bisection below
+    int ftid = tid;
+    asm volatile("" : "+v"(ftid));
+    constexpr int CP = 4;
+    f32x4 crf_p[CP];
+    i32x4 tau_p[CP], pos_p[CP];
+#pragma unroll
+    for (int c = 0; c < CP; ++c) load_meta<NT>(d, (size_t)u * d.cap, n, t, c, ftid, crf_p[c], tau_p[c], pos_p[c]);
+
     // the bookkeeping below is short and latency-bound: let it win the issue slots over the other
     // workgroup's streaming wavefronts, which mostly wait on memory anyway
     __builtin_amdgcn_s_setprio(3);
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
-    if (head_lane && kg == 0) {
+    asm volatile("" : "+v"(slane));
+    const int j = slane & 15, kg = slane >> 4;
+    if (j < G && kg == 0) {
       s_ml[wave][j][0] = m_run;
       s_ml[wave][j][1] = l_run;
     }
@@ -172,16 +237,17 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
     // ---- merge the four online-softmax states -> out.  Every thread derives the global max and
     // denominator of the heads it needs from s_ml (same fixed order everywhere); waves 0 and 1 deposit
     // their rescaled accumulators in two LDS slices, waves 2 and 3 add theirs on top.
-    if (tid < G) {
+    asm volatile("" : "+v"(ftid));
+    if (ftid < G) {
       float M = -INFINITY;
-      for (int w = 0; w < 4; ++w) M = fmaxf(M, s_ml[w][tid][0]);
+      for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][ftid][0]);
       float L = 0.f;
-      for (int w = 0; w < 4; ++w) {
-        const float m = s_ml[w][tid][0];
-        L += m > -INFINITY ? s_ml[w][tid][1] * fast_exp2(m - M) : 0.f;
+      for (int w = 0; w < W; ++w) {
+        const float m = s_ml[w][ftid][0];
+        L += m > -INFINITY ? s_ml[w][ftid][1] * fast_exp2(m - M) : 0.f;
       }
-      sM[tid] = M;
-      sInv[tid] = 1.0f / L;
+      sM[ftid] = M;
+      sInv[ftid] = 1.0f / L;
     }
     {
       float sc[4];
@@ -190,13 +256,13 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
         const int head = min(4 * kg + v, kMaxGroup - 1);
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) M = fmaxf(M, s_ml[w][head][0]);
+        for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][head][0]);
         const float m = s_ml[wave][head][0];
         sc[v] = m > -INFINITY ? fast_exp2(m - M) : 0.f;
       }
-      float* slice = s_out[wave & 1];
+      float* slice = s_out + (wave % kSlices) * (kMaxGroup * kDim);
       for (int half = 0; half < 2; ++half) {
-        if ((wave >> 1) == half) {
+        if ((wave / kSlices) == half) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const int head = 4 * kg + v;
@@ -213,9 +279,11 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
         __syncthreads();
       }
     }
-    for (int o = tid; o < G * kDim; o += kThreads) {
+    for (int o = ftid; o < G * kDim; o += NT) {
       const int g = o >> 7;
-      const float y = (s_out[0][o] + s_out[1][o]) * sInv[g];
+      float y = s_out[o];
+      if (kSlices == 2) y += s_out[kMaxGroup * kDim + o];
+      y *= sInv[g];
       const size_t oi = (size_t)u * G * kDim + o;
       if (d.out_bf16)
         reinterpret_cast<__bf16*>(out)[oi] = (__bf16)y;
@@ -226,7 +294,6 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
     // ---- mean attention weights, then Alg. 1 Steps 1-4.  The thread index is laundered so that the
     // compiler derives this phase's per-lane addresses here instead of keeping them alive, in
     // registers the streaming loop needs, across the whole unit loop.
-    int ftid = tid;
     asm volatile("" : "+v"(ftid));
     int phase = 0;      // block reductions of different units are separated by barriers
     const ValFused val{lg, lg + (size_t)n_res * G, n_res, G * kBlk};
@@ -243,64 +310,82 @@ __global__ __launch_bounds__(kThreads, 2) void unit_kernel(Dev d, const uint16_t
       }
       return a * invG;
     };
-    // four entries at a time with all their logits in flight together
-    auto weights4 = [&](int i0, float* a4) {
-      float x[4][kMaxGroup];
+    // mean weights of the four consecutive entries e0 .. e0 + 3 (one 16-byte read per head)
+    auto weights4 = [&](int e0, float* a4) {
+      f32x4 x[kMaxGroup];
+      const int off = (e0 >> 5) * (G * kBlk) + (e0 & 31);
+      const f32x4 ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      if (e0 < n_res) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int i = i0 + r * kThreads;
-        const int off = (i >> 5) * (G * kBlk) + (i & 31);
-        if (i < n_res) {
+        for (int g = 0; g < kMaxGroup; ++g) x[g] = g < G ? *reinterpret_cast<const f32x4*>(lg + off + g * kBlk) : ninf;
+      } else {
 #pragma unroll
-          for (int g = 0; g < kMaxGroup; ++g) x[r][g] = g < G ? lg[off + g * kBlk] : -INFINITY;
-        } else {
-#pragma unroll
-          for (int g = 0; g < kMaxGroup; ++g) x[r][g] = (g < G && i < n) ? lgg[off + g * kBlk] : -INFINITY;
-        }
+        for (int g = 0; g < kMaxGroup; ++g)
+          x[g] = (g < G && e0 < n) ? *reinterpret_cast<const f32x4*>(lgg + off + g * kBlk) : ninf;
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int e = 0; e < 4; ++e) {
         float a = 0.f;
 #pragma unroll
         for (int g = 0; g < kMaxGroup; ++g)
-          if (g < G) a += fast_exp2(x[r][g] - sM[g]) * sInv[g];
-        a4[r] = (i0 + r * kThreads < n) ? a * invG : 0.f;
+          if (g < G) a += fast_exp2(x[g][e] - sM[g]) * sInv[g];
+        a4[e] = (e0 + e < n) ? a * invG : 0.f;
       }
     };
-    if (n <= 8 * kThreads) {
-      float a[8];
-      weights4(ftid, a);
-      weights4(ftid + 4 * kThreads, a + 4);
-      lrfu_regs<8>(d, u, n, B, t, a, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4, s_tab, s_tab_n, rb, phase,
-                   sh, ftid);
+    // R entries per thread.  The groups' state that was not requested at the unit's start is requested
+    // after the weights have been computed (fewer live registers) and arrives during the bisection.
+    auto regs_path = [&](auto rc) {
+      constexpr int R = decltype(rc)::value, C = R / 4;
+      float a[R];
+#pragma unroll
+      for (int c = 0; c < C; ++c) {
+        weights4(4 * (ftid + c * NT), a + 4 * c);
+        __builtin_amdgcn_sched_barrier(0);      // one group's logits at a time: keeps the register need flat
+      }
+      if (ftid == 0) s_claim = 3 * grid + claimed;
+      constexpr int CH = C < CP ? C : CP;   // register slots for the groups' state; CP of them were requested early
+      f32x4 crf[CH];
+      i32x4 tau[CH], ps[CH];
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        crf[c] = crf_p[c];
+        tau[c] = tau_p[c];
+        ps[c] = pos_p[c];
+      }
+      lrfu_regs<R, CH, CH, ValFused, NT>(d, u, n, B, t, a, crf, tau, ps, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4,
+                                         s_tab, s_tab_n, rb, phase, sh, ftid);
+    };
+    if (n <= 8 * NT) {
+      regs_path(std::integral_constant<int, 8>{});
+    } else if (n <= 16 * NT) {
+      regs_path(std::integral_constant<int, 16>{});
     } else {
-      for (int i = ftid; i < n; i += kThreads) val(i) = weight_of(i);
+      for (int i = ftid; i < n; i += NT) val(i) = weight_of(i);
+      if (ftid == 0) s_claim = 3 * grid + claimed;
       __syncthreads();
-      const u64 sfix = lrfu_update(d, u, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
+      const u64 sfix = lrfu_update<ValFused, NT>(d, u, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
       if (ftid == 0) {
         d.window[u] += sfix;
         d.t_unit[u] = t;
       }
       if (evict && n > B)
-        evict_phase(d, u, n, B, val, evm, reinterpret_cast<int*>(smem), lds_main / 4, rb, phase, sh, ftid);
+        evict_phase<ValFused, NT>(d, u, n, B, val, evm, reinterpret_cast<int*>(smem), lds_main / 4, rb, phase, sh, ftid);
       else if (ftid == 0)
         d.nev[u] = 0;
     }
 
     // ---- next unit
     __builtin_amdgcn_s_setprio(0);
-    if (tid == 0) {
-      s_idx[0] = idx_next;
-      s_idx[1] = claimed;
-    }
-    __syncthreads();
-    idx = s_idx[0];
-    idx_next = s_idx[1];
-    u = u_next;
-    n = n_next;
-    __syncthreads();          // everyone has read s_idx before the next round overwrites it
+    __syncthreads();          // LDS of this unit is dead before the next unit's logits overwrite it; s_claim is set
+    u = u1;
+    n = n1;
+    B = B1;
+    u1 = u2;
+    n1 = n2;
+    B1 = B2;
+    slot2 = __builtin_amdgcn_readfirstlane(s_claim);
   }
-  step_epilogue(d, t, advance, tid, (int)gridDim.x);
+  step_epilogue(d, t, advance, tid, 0);
 }
 
 }  // namespace ckv

@@ -26,7 +26,7 @@ def _pair(cfg, cap, budgets=None, stream=None, n_steps=None, load=True, path=0, 
     g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
                       lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min,
                       budget_max=cfg.budget_max, **kw)
-    g.set_path(path)          # 1 = separate scan/finish kernels, 2 = fused per-unit kernel
+    g.set_path(path)          # 1 = separate scan/finish kernels, 2 = fused per-unit kernel (3, 4: its two variants)
     if load and cfg.prompt > 0:
         for l in range(cfg.n_layers):
             o.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
@@ -42,7 +42,7 @@ def _small(name, **kw):
     return wl.scaled(wl.CONFIGS[name], **base)
 
 
-PATHS = [1, 2]
+PATHS = [1, 3, 4]     # separate kernels; fused kernel with 4 and with 2 wavefronts per unit
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -73,7 +73,8 @@ def test_units_longer_than_a_chunk_and_ragged_tails(path):
     g.close()
 
 
-def test_fused_kernel_with_logits_spilling_out_of_lds():
+@pytest.mark.parametrize("path", [3, 4])
+def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     """A unit of ~3000 entries with 8 query heads per KV head needs 96 KB of logits: more than the fused
     kernel's LDS tile, so the logits of its last blocks take the global-memory route; a second, small
     unit in the same call stays resident.  Also exercises several blocks per wavefront."""
@@ -81,7 +82,7 @@ def test_fused_kernel_with_logits_spilling_out_of_lds():
     cfg = _small("qwen7b", n_layers=1, batch=1, n_q_heads=16, n_kv_heads=2, prompt=2890, decode_steps=6,
                  budget=1800, budget_min=600, budget_max=3071, seed=15)
     budgets = np.array([[[2900, 700]]], dtype=np.int32)
-    st, o, g = _pair(cfg, cap=3072, budgets=budgets, path=2)
+    st, o, g = _pair(cfg, cap=3072, budgets=budgets, path=path)
     avail, lds_main = g.path_info()
     assert avail and 3000 * 8 * 4 > lds_main
     stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=3)
