@@ -8,7 +8,8 @@ budgets, Alg. 2 at its interval.  Inputs are synthetic and resident in HBM
 before the timed region.  Prints ONE JSON line.
 
   value        decode steps/s from HIP-graph replays of the all-layers call
-  roofline     scan kernel (the dominant one): algorithmic K/V bytes per launch
+  roofline     the dominant kernel (the fused per-unit kernel, or the scan kernel
+               when the separate kernels are used): algorithmic bytes per launch
                over its average duration, measured with HIP events around each
                launch in a separate eager pass
   cpu_baseline the numpy oracle timed on the host on a bounded sample
@@ -62,7 +63,23 @@ def algorithmic_bytes(cfg, budgets):
     U, G = n.size, cfg.group
     scan = int(n.sum()) * 512 + U * G * 256
     step = int(n.sum()) * 524 + U * (G * 256 + G * 512 + 512 + 2 * 524)
-    return scan, step, int(n.sum())
+    fused = step - U * 512                               # the fused kernel does everything but the append
+    return scan, step, int(n.sum()), fused
+
+
+def measured_traffic(kernel_name, workload):
+    """HBM bytes per launch of the dominant kernel as counted by the profiler (FETCH_SIZE + WRITE_SIZE,
+    calibrated against plain read/copy kernels): a figure taken from the committed counter summary of
+    this kernel and workload, or None if there is none (the counters cannot be read from inside a run)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == kernel_name and f[1] == workload:
+                return int(f[2])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(cfg, budgets, seconds=15.0):
@@ -112,6 +129,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-layer", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    ap.add_argument("--path", type=int, default=0,
+                    help="kernels of the all-layers step: 0 default, 1 separate scan/finish, 3 / 4 fused with 4 / 2 wavefronts per unit")
     ap.add_argument("--probe-only", action="store_true",
                     help="only run the plain streaming-read and copy kernels (4 GiB each): counter calibration")
     args = ap.parse_args()
@@ -134,6 +153,8 @@ def main():
         print(json.dumps({"stream_read_gbps": read_gbps, "copy_gbps": copy_gbps, "bytes": 4 << 30}))
         return
     g, budgets, (rq, rk, rv) = build_workload(cfg, device)
+    if args.path:
+        g.set_path(args.path)
     out = torch.empty(rq.shape[1:], dtype=torch.float32, device=device)
     steps = max(RING, args.steps // RING * RING)
     warm = max(RING, (args.warmup + RING - 1) // RING * RING)
@@ -176,9 +197,14 @@ def main():
     eager_steps(RING * 2)
     scan_ms, launches = g.profile_read()
     g.profile_enable(False)
-    scan_bytes, step_bytes, entries = algorithmic_bytes(cfg, g.budgets())
+    scan_bytes, step_bytes, entries, fused_bytes = algorithmic_bytes(cfg, g.budgets())
+    fused_waves, _ = g.path_info()
+    # dominant kernel of an all-layers step: the fused per-unit kernel if the context uses it, else the scan kernel
+    kernel_name = f"unit_kernel<{fused_waves}>" if fused_waves else "scan_kernel"
+    kernel_bytes = fused_bytes if fused_waves else scan_bytes
     scan_avg_ms = scan_ms / max(launches, 1)
-    achieved = scan_bytes / (scan_avg_ms * 1e-3) / 1e9
+    achieved = kernel_bytes / (scan_avg_ms * 1e-3) / 1e9
+    traffic = measured_traffic(kernel_name, cfg.name)
 
     # ---- secondary: the shape a real model imposes, one call per layer
     per_layer = None
@@ -229,9 +255,9 @@ def main():
         "per_layer_graph_ms_per_step": per_layer,
         "stream_read_gbps": read_gbps,          # plain non-temporal streaming read measured on this machine
         "copy_gbps": copy_gbps,
-        "roofline": {"bound": "hbm", "kernel": "scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "bytes_per_launch": scan_bytes, "avg_launch_ms": scan_avg_ms, "launches": launches,
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "bytes_per_launch": kernel_bytes, "avg_launch_ms": scan_avg_ms, "launches": launches,
                      "frac_of_stream_read": achieved / read_gbps},
     }
     if not args.no_cpu_baseline:

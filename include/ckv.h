@@ -54,7 +54,7 @@ enum {
 enum { CKV_BF16 = 1, CKV_F32 = 2 };                 /* out_dtype */
 enum { CKV_REWARD_TOPP_HIT = 0,                      /* Alg. 1: reward 1 for entries in the top-p hit set */
        CKV_REWARD_ATTN_WEIGHTED = 1 };               /* variant: reward = mean attention weight, every entry stored */
-enum { CKV_FLAG_HIT = 1,                             /* per-slot flag: entry was in this step's hit set */
+enum { CKV_FLAG_HIT = 1,                             /* per-slot flag as exported: entry was in the last step's hit set */
        CKV_FLAG_SLIP = 2 };                          /* per-slot flag: slot holds the position of an entry evicted by the last eviction */
 enum { CKV_CLASS_SLIP = 0, CKV_CLASS_POTENTIAL = 1, CKV_CLASS_CRYSTAL = 2 };
 
@@ -89,7 +89,10 @@ typedef struct {
  *   crf  : S float   - stored CRF score of each slot
  *   tau  : S int32   - time the stored CRF refers to (last hit)
  *   pos  : S int32   - position of the token the slot's entry came from
- *   flags: S uint8   - CKV_FLAG_* bits
+ *   flags: S uint8   - CKV_FLAG_SLIP marks.  The hit mark is not stored per
+ *                      step: in the top-p mode an entry was hit in its unit's
+ *                      last step iff its tau equals that step's time;
+ *                      ckv_export_unit adds CKV_FLAG_HIT accordingly.
  *   workspace : ckv_workspace_bytes() bytes, 256-byte aligned.
  * ckv_init overwrites all of them. */
 typedef struct {
@@ -147,7 +150,7 @@ int ckv_load_cache(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, in
  * Appends (k_new, v_new) at position t (CRF 0, tau t), attends over the unit's
  * entries, takes the mean weight over the G query heads of each KV head,
  * builds the top-p hit set (the new entry always belongs to it), updates the
- * hit entries' stored CRF and tau, sets CKV_FLAG_HIT, accumulates the unit's
+ * hit entries' stored CRF and tau (tau = t marks the hit), accumulates the unit's
  * aggregated CRF for Alg. 2, and with CKV_FUSE_EVICT evicts down to the budget
  * (as ckv_evict).  Layers must be stepped in order 0..n_layers-1; t advances
  * after the last one.  A unit that is already full (n == cap) is not
@@ -207,11 +210,17 @@ int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
 
 /* Which kernels ckv_decode_step(layer = -1) uses: 0 = choose by unit count
  * (default), 1 = separate scan and finish kernels (always used for single-layer
- * calls), 2 = the fused per-unit kernel, which keeps the logits in LDS; it needs
- * 4 * cap bytes of LDS per workgroup (CKV_EINVAL otherwise).  Results do not
- * depend on the choice beyond floating-point summation order. */
+ * calls), 2 = the fused per-unit kernel, which keeps the logits in LDS, in the
+ * widest variant that fits; 3 / 4 = the fused kernel with 4 / 2 wavefronts per
+ * unit (2 / 4 workgroups per compute unit).  A variant needs 4 * cap bytes of
+ * LDS in its workgroup's share (CKV_EINVAL otherwise).  Results do not depend
+ * on the choice beyond floating-point summation order.
+ * ckv_path_info reports what all-layer steps use under the current mode:
+ * *fused_waves = wavefronts per unit of the fused variant (0: separate
+ * kernels), *lds_main_bytes = bytes of its LDS tile for logits and per-entry
+ * values. */
 int ckv_set_path(ckv_ctx* ctx, int32_t mode);
-int ckv_path_info(ckv_ctx* ctx, int32_t* fused_available, int32_t* lds_main_bytes);
+int ckv_path_info(ckv_ctx* ctx, int32_t* fused_waves, int32_t* lds_main_bytes);
 
 /* Measurement aid, independent of any context: streams `bytes` (a multiple of
  * 16 KiB is read completely; at least 1 MiB) from dev `src` with plain 16-byte

@@ -296,9 +296,9 @@ class CrystalKV:
         self._check(self.lib.ckv_set_path(self.ctx, int(mode)))
 
     def path_info(self):
-        ok_, lds = C.c_int32(0), C.c_int32(0)
-        self._check(self.lib.ckv_path_info(self.ctx, C.byref(ok_), C.byref(lds)))
-        return bool(ok_.value), lds.value
+        waves, lds = C.c_int32(0), C.c_int32(0)
+        self._check(self.lib.ckv_path_info(self.ctx, C.byref(waves), C.byref(lds)))
+        return waves.value, lds.value
 
     def profile_enable(self, on=True):
         self._check(self.lib.ckv_profile_enable(self.ctx, 1 if on else 0))

@@ -651,12 +651,12 @@ int ckv_set_path(ckv_ctx* c, int32_t mode) {
   return CKV_OK;
 }
 
-int ckv_path_info(ckv_ctx* c, int32_t* fused_available, int32_t* lds_main_bytes) {
+int ckv_path_info(ckv_ctx* c, int32_t* fused_waves, int32_t* lds_main_bytes) {
   if (!c) return CKV_EINVAL;
-  const ckv_ctx::Fused* f = c->path_mode == 3 ? &c->fused[0] : c->path_mode == 4 ? &c->fused[1]
-                            : c->fused[0].ok ? &c->fused[0] : &c->fused[1];
-  if (fused_available) *fused_available = f->ok ? f->waves : 0;
-  if (lds_main_bytes) *lds_main_bytes = f->lds_main;
+  const ckv_ctx::Fused* f = fused_variant(c);
+  if (f && c->path_mode == 0 && c->units < 4 * f->grid) f = nullptr;
+  if (fused_waves) *fused_waves = f ? f->waves : 0;
+  if (lds_main_bytes) *lds_main_bytes = f ? f->lds_main : 0;
   return CKV_OK;
 }
 

@@ -145,8 +145,9 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
 // Block-wide reductions over NT threads with a fixed combination order
 // (deterministic).  `rb` is a [2][NT/64] LDS array used alternately, so one
 // barrier per call suffices.
-struct RedBuf {
+struct alignas(16) RedBuf {
   u64 v[2][4];
+  float t[2][4][4];
 };
 
 template <int NT = kThreads>
@@ -183,6 +184,28 @@ __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, 
   for (int w = 1; w < NT / 64; ++w) r += __uint_as_float((uint32_t)rb.v[phase][w]);
   phase ^= 1;
   return r;
+}
+
+// Three sums at once (one barrier).
+template <int NT = kThreads>
+__device__ __forceinline__ void block_sum3_f32(float& x, float& y, float& z, RedBuf& rb, int& phase, int tid) {
+  x = wave_sum_f32(x);
+  y = wave_sum_f32(y);
+  z = wave_sum_f32(z);
+  if ((tid & 63) == 0) *reinterpret_cast<f32x4*>(rb.t[phase][tid >> 6]) = f32x4{x, y, z, 0.f};
+  __syncthreads();
+  f32x4 r = *reinterpret_cast<const f32x4*>(rb.t[phase][0]);
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) {
+    const f32x4 q = *reinterpret_cast<const f32x4*>(rb.t[phase][w]);
+    r[0] += q[0];
+    r[1] += q[1];
+    r[2] += q[2];
+  }
+  x = r[0];
+  y = r[1];
+  z = r[2];
+  phase ^= 1;
 }
 
 template <int NT = kThreads>
@@ -1076,11 +1099,17 @@ __device__ __forceinline__ void load_meta(const Dev& d, size_t base, int n, int 
 // top-p mode it equals tau == t.  Evicting exactly one entry is done in place
 // (the owners of the two entries involved pass their registers through `sh`);
 // evicting more falls back to evict_phase (scores then go to val()).
-template <int R, int CH, int CP, class Val, int NT = kThreads>
+struct NoHook {
+  __device__ __forceinline__ void operator()() const {}
+};
+
+// `after_step1` runs once between Step 1 and the score update (the fused kernel
+// picks up its queue claim there).
+template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook>
 __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
                                           i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
                                           int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
-                                          int tid) {
+                                          int tid, Hook after_step1 = Hook{}) {
   constexpr int C = R / 4;
   static_assert(C % CH == 0 && CP <= CH, "groups come in chunks of CH");
   const size_t base = (size_t)u * d.cap;
@@ -1091,13 +1120,21 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   bool ties_all = true;
   int pos_cut = 0x7FFFFFFF;
   if (d.reward_mode == 0) {
-    for (int bit = 30; bit >= 0; --bit) {
-      const uint32_t cand = theta | (1u << bit);
-      float part = 0.f;
+    // largest pattern theta with sum{a >= theta} > p, two bits per round (one barrier each): the three
+    // candidates' sums are nested, so the largest candidate that passes is what bit-by-bit bisection
+    // would reach.  Bit 30 is never set: the weights are <= 1.
+    for (int bit = 29; bit >= 1; bit -= 2) {
+      const uint32_t c1 = theta | (1u << (bit - 1)), c2 = theta | (1u << bit), c3 = c1 | c2;
+      float p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
-      for (int k = 0; k < R; ++k) part += (__float_as_uint(a[k]) >= cand) ? a[k] : 0.f;
-      const float tot = block_sum_f32<NT>(part, rb, phase, tid);
-      if (tot > d.top_p) theta = cand;
+      for (int k = 0; k < R; ++k) {
+        const uint32_t b = __float_as_uint(a[k]);
+        p1 += (b >= c1) ? a[k] : 0.f;
+        p2 += (b >= c2) ? a[k] : 0.f;
+        p3 += (b >= c3) ? a[k] : 0.f;
+      }
+      block_sum3_f32<NT>(p1, p2, p3, rb, phase, tid);
+      theta = p3 > d.top_p ? c3 : p2 > d.top_p ? c2 : p1 > d.top_p ? c1 : theta;
     }
     if (theta != 0) {
       float above = 0.f;
@@ -1136,6 +1173,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       }
     }
   }
+  after_step1();
   // ---- Steps 2-3: scores; a[k] becomes CRF_temp.  The candidate for Step 4 (lowest score, then
   // highest position) is tracked on the way.
   u64 sfix = 0;

@@ -221,9 +221,6 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
 #pragma unroll
     for (int c = 0; c < CP; ++c) load_meta<NT>(d, (size_t)u * d.cap, n, t, c, ftid, crf_p[c], tau_p[c], pos_p[c]);
 
-    // the bookkeeping below is short and latency-bound: let it win the issue slots over the other
-    // workgroup's streaming wavefronts, which mostly wait on memory anyway
-    __builtin_amdgcn_s_setprio(3);
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     asm volatile("" : "+v"(slane));
@@ -300,16 +297,6 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     const bool evict = (call_flags & 1u) != 0;
     const float invG = 1.0f / (float)G;
     const float* lgg = d.logits + (size_t)u * d.cap * G;
-    auto weight_of = [&](int i) -> float {
-      const int off = (i >> 5) * (G * kBlk) + (i & 31);
-      float a = 0.f;
-      if (i < n_res) {
-        for (int g = 0; g < G; ++g) a += fast_exp2(lg[off + g * kBlk] - sM[g]) * sInv[g];
-      } else {
-        for (int g = 0; g < G; ++g) a += fast_exp2(lgg[off + g * kBlk] - sM[g]) * sInv[g];
-      }
-      return a * invG;
-    };
     // mean weights of the four consecutive entries e0 .. e0 + 3 (one 16-byte read per head)
     auto weights4 = [&](int e0, float* a4) {
       f32x4 x[kMaxGroup];
@@ -342,7 +329,6 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         weights4(4 * (ftid + c * NT), a + 4 * c);
         __builtin_amdgcn_sched_barrier(0);      // one group's logits at a time: keeps the register need flat
       }
-      if (ftid == 0) s_claim = 3 * grid + claimed;
       constexpr int CH = C < CP ? C : CP;   // register slots for the groups' state; CP of them were requested early
       f32x4 crf[CH];
       i32x4 tau[CH], ps[CH];
@@ -352,15 +338,25 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         tau[c] = tau_p[c];
         ps[c] = pos_p[c];
       }
+      // the queue claim is picked up after the bisection: by then everything requested before it has arrived
+      auto publish = [&]() {
+        if (ftid == 0) s_claim = 3 * grid + claimed;
+      };
       lrfu_regs<R, CH, CH, ValFused, NT>(d, u, n, B, t, a, crf, tau, ps, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4,
-                                         s_tab, s_tab_n, rb, phase, sh, ftid);
+                                         s_tab, s_tab_n, rb, phase, sh, ftid, publish);
     };
     if (n <= 8 * NT) {
       regs_path(std::integral_constant<int, 8>{});
     } else if (n <= 16 * NT) {
       regs_path(std::integral_constant<int, 16>{});
     } else {
-      for (int i = ftid; i < n; i += NT) val(i) = weight_of(i);
+      for (int e0 = 4 * ftid; e0 < n; e0 += 4 * NT) {
+        float a4[4];
+        weights4(e0, a4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (e0 + e < n) val(e0 + e) = a4[e];
+      }
       if (ftid == 0) s_claim = 3 * grid + claimed;
       __syncthreads();
       const u64 sfix = lrfu_update<ValFused, NT>(d, u, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
@@ -375,7 +371,6 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     }
 
     // ---- next unit
-    __builtin_amdgcn_s_setprio(0);
     __syncthreads();          // LDS of this unit is dead before the next unit's logits overwrite it; s_claim is set
     u = u1;
     n = n1;
