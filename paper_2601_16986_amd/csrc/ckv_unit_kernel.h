@@ -8,14 +8,14 @@
 // Here two workgroups share a CU, so while one does a unit's bookkeeping the
 // other keeps the memory pipeline busy.
 //
-// Work: units are taken from a queue in order of descending budget (`d.order`),
-// first round statically (unit index = blockIdx.x), then by one atomic per unit.
-// The four wavefronts of a workgroup split a unit's 32-entry blocks round robin
-// (wave w takes blocks w, w+4, ...), each with its own online softmax state;
-// the states are merged through LDS at the end of the unit.  As in the scan
-// kernel every load in the streaming loop is unconditional: after a wave's last
-// block of a unit the stream continues with its first block of the next unit,
-// which therefore is in flight during the bookkeeping.
+// Work: schedule slots (units in order of descending budget, `d.sched`) are
+// taken three rounds statically, then from a shared queue.  The W wavefronts of
+// a workgroup split a unit's 32-entry blocks round robin (wave w takes blocks
+// w, w+W, ...), each with its own online softmax state; the states are merged
+// through LDS at the end of the unit.  As in the scan kernel every load in the
+// streaming loop is unconditional: after a wave's last block of a unit the
+// stream continues with its first block of the next unit, which therefore is
+// in flight during the bookkeeping.
 //
 // LDS (dynamic, `lds_main` bytes + mask): the logits tile [block][head][32] f32
 // of the first n_res entries; the per-entry value (mean weight, then CRF_temp)
