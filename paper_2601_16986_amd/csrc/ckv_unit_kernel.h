@@ -199,27 +199,21 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     if (my_cnt > 0) {
       float sv[8];
       qk(wave + W * (my_cnt - 1), sv);
-      load_k(ka, d.K + o_next);
       scan_pv(sv, va, acc, m_run, l_run, slane);
-      load_v(va, d.V + o_next);
-    } else {
+    }
+    // The next unit's first block, its queries and the claim of the slot three units ahead are requested
+    // once this unit's weights sit in registers (the block's 64 registers are free until then, which is
+    // what lets units of up to 32 entries per thread stay in registers); they arrive during the
+    // bisection.  The claim's result is picked up after the bisection.
+    int claimed = 0;
+    auto request_next = [&]() {
       load_k(ka, d.K + o_next);
       load_v(va, d.V + o_next);
-    }
-    load_q(u_next);
-    // claim the slot of the unit three ahead; the result is picked up after the weights phase below
-    int claimed = 0;
-    if (tid == 0) claimed = atomicAdd(&d.sc[SC_QUEUE], 1);
-
-    // ---- CRF, tau and position of this thread's first groups of entries: requested now, behind the
-    // next unit's first block, so that they arrive during the merge and the bisection below
+      load_q(u_next);
+      if (tid == 0) claimed = atomicAdd(&d.sc[SC_QUEUE], 1);
+    };
     int ftid = tid;
     asm volatile("" : "+v"(ftid));
-    constexpr int CP = 4;
-    f32x4 crf_p[CP];
-    i32x4 tau_p[CP], pos_p[CP];
-#pragma unroll
-    for (int c = 0; c < CP; ++c) load_meta<NT>(d, (size_t)u * d.cap, n, t, c, ftid, crf_p[c], tau_p[c], pos_p[c]);
 
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
@@ -329,15 +323,14 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         weights4(4 * (ftid + c * NT), a + 4 * c);
         __builtin_amdgcn_sched_barrier(0);      // one group's logits at a time: keeps the register need flat
       }
-      constexpr int CH = C < CP ? C : CP;   // register slots for the groups' state; CP of them were requested early
+      request_next();
+      // CRF, tau and position of the thread's groups (in chunks of four groups for the largest units):
+      // requested behind the next unit's block, first used after the bisection
+      constexpr int CH = C < 4 ? C : 4;
       f32x4 crf[CH];
       i32x4 tau[CH], ps[CH];
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        crf[c] = crf_p[c];
-        tau[c] = tau_p[c];
-        ps[c] = pos_p[c];
-      }
+      for (int c = 0; c < CH; ++c) load_meta<NT>(d, (size_t)u * d.cap, n, t, c, ftid, crf[c], tau[c], ps[c]);
       // the queue claim is picked up after the bisection: by then everything requested before it has arrived
       auto publish = [&]() {
         if (ftid == 0) s_claim = 3 * grid + claimed;
@@ -349,6 +342,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       regs_path(std::integral_constant<int, 8>{});
     } else if (n <= 16 * NT) {
       regs_path(std::integral_constant<int, 16>{});
+    } else if (n <= 32 * NT) {
+      regs_path(std::integral_constant<int, 32>{});
     } else {
       for (int e0 = 4 * ftid; e0 < n; e0 += 4 * NT) {
         float a4[4];
@@ -357,6 +352,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         for (int e = 0; e < 4; ++e)
           if (e0 + e < n) val(e0 + e) = a4[e];
       }
+      request_next();
       if (ftid == 0) s_claim = 3 * grid + claimed;
       __syncthreads();
       const u64 sfix = lrfu_update<ValFused, NT>(d, u, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
