@@ -900,6 +900,17 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
   }
 }
 
+// lambda^delta from the decay table: its first s_tab_n entries sit in LDS, the rest (long tables: lambda
+// close to 1) in global memory.  Written as two loads in two address spaces on purpose: a conditional
+// expression over the two pointers becomes one flat load, which waits for every vector-memory
+// operation in flight.
+__device__ __forceinline__ float decay_of(const Dev& d, int delta, const float* s_tab, int s_tab_n) {
+  float dec = s_tab[min(delta, s_tab_n - 1)];
+  asm volatile("" : "+v"(dec));          // pins the LDS load: otherwise the two loads are merged again
+  if (delta >= s_tab_n) dec = d.tab[delta];
+  return dec;
+}
+
 // Mean attention weight of every entry of unit u into val[0..n).
 __device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const float* sM, const float* sInv, float* val,
                                              int tid) {
@@ -1007,7 +1018,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
     for (int r = 0; r < 4; ++r) {
       int delta = t - tau[r];
       delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
-      dec[r] = delta < s_tab_n ? s_tab[delta] : d.tab[delta];
+      dec[r] = decay_of(d, delta, s_tab, s_tab_n);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -1186,62 +1197,57 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
 #pragma unroll
       for (int k = 0; k < CH; ++k) load_meta<NT>(d, base, n, t, cc + k, tid, crf[k], tau[k], ps[k]);
     }
+    // Straight-line, predicated code (selects instead of branches; entries beyond n compute on
+    // whatever was loaded and are masked out of every result): branchy per-entry code ran at a small
+    // fraction of the issue rate.
     const int e0 = 4 * (tid + cc * NT);
-    if (e0 < n) {
-      f32x4 ncrf = crf[c];
-      i32x4 ntau = tau[c];
-      uint32_t stored = 0;                  // bit e: entry e0 + e gets a new (CRF, tau)
+    f32x4 ncrf = crf[c];
+    i32x4 ntau = tau[c];
+    uint32_t stored = 0;                    // bit e: entry e0 + e gets a new (CRF, tau)
+    const bool topp = d.reward_mode == 0;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int i = e0 + e;
-        if (i < n) {
-          int delta = t - tau[c][e];
-          delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
-          const float dec = delta < s_tab_n ? s_tab[delta] : d.tab[delta];
-          bool hit, store;
-          float reward;
-          if (d.reward_mode == 0) {
-            const uint32_t b = __float_as_uint(a[4 * cc + e]);
-            hit = (b > theta) || (b == theta && (ties_all || ps[c][e] <= pos_cut));
-            if (i == n - 1 && ps[c][e] == t) hit = true;          // the entry appended this step
-            store = hit;
-            reward = hit ? 1.0f : 0.0f;
-          } else {
-            store = true;
-            reward = a[4 * cc + e];
-          }
-          float tmp = __fadd_rn(__fmul_rn(dec, crf[c][e]), reward);
-          if (tmp < FLT_MIN) tmp = 0.0f;
-          if (store) {
-            ncrf[e] = tmp;
-            ntau[e] = t;
-            stored |= 1u << e;
-          }
-          a[4 * cc + e] = tmp;
-          sfix += (u64)floorf(tmp * kFixedOne);
-          const u64 key = evict_key(tmp, ps[c][e]);
-          if (key < best) {
-            best = key;
-            best_i = i;
-          }
-          if (i == n - 1) {                  // the last slot's final state, for the in-place eviction
-            sh[1] = __float_as_int(ncrf[e]);
-            sh[2] = ntau[e];
-            sh[3] = ps[c][e];
-          }
-        }
+    for (int e = 0; e < 4; ++e) {
+      const int i = e0 + e;
+      const bool ok = i < n;
+      const int pe = ps[c][e];
+      const float w = a[4 * cc + e];
+      const int delta = min(max(t - tau[c][e], 0), d.tab_last);
+      const float dec = decay_of(d, delta, s_tab, s_tab_n);
+      const uint32_t b = __float_as_uint(w);
+      const bool hit = topp & ((b > theta) | ((b == theta) & (ties_all | (pe <= pos_cut))) |
+                               ((i == n - 1) & (pe == t)));          // the entry appended this step is always hit
+      const bool store = ok & (hit | !topp);
+      const float reward = topp ? (hit ? 1.0f : 0.0f) : w;
+      float tmp = __fadd_rn(__fmul_rn(dec, crf[c][e]), reward);
+      tmp = tmp < FLT_MIN ? 0.0f : tmp;
+      ncrf[e] = store ? tmp : ncrf[e];
+      ntau[e] = store ? t : ntau[e];
+      stored |= (store ? 1u : 0u) << e;
+      a[4 * cc + e] = ok ? tmp : 0.0f;
+      // 2^-20 fixed point of the score: the scaling is exact, the split into two 32-bit halves too
+      const float fx = floorf(tmp * kFixedOne);
+      const uint32_t fhi = (uint32_t)(fx * 2.3283064365386963e-10f);
+      const uint32_t flo = (uint32_t)(fx - (float)fhi * 4294967296.0f);
+      sfix += ok ? (((u64)fhi << 32) | flo) : 0ull;
+      const u64 key = ok ? evict_key(tmp, pe) : ~0ull;
+      best_i = key < best ? i : best_i;
+      best = key < best ? key : best;
+      if (i == n - 1) {                     // the last slot's final state, for the in-place eviction
+        sh[1] = __float_as_int(ncrf[e]);
+        sh[2] = ntau[e];
+        sh[3] = pe;
       }
-      if (e0 + 3 < n) {
-        if (stored) {
-          *reinterpret_cast<f32x4*>(d.crf + base + e0) = ncrf;
-          *reinterpret_cast<i32x4*>(d.tau + base + e0) = ntau;
-        }
-      } else {                               // the unit's last, partial group: entry by entry
-        for (int e = 0; e < 4 && e0 + e < n; ++e) {
-          if ((stored >> e) & 1u) {
-            d.crf[base + e0 + e] = ncrf[e];
-            d.tau[base + e0 + e] = t;
-          }
+    }
+    if (e0 + 3 < n) {
+      if (stored) {
+        *reinterpret_cast<f32x4*>(d.crf + base + e0) = ncrf;
+        *reinterpret_cast<i32x4*>(d.tau + base + e0) = ntau;
+      }
+    } else if (e0 < n) {                     // the unit's last, partial group: entry by entry
+      for (int e = 0; e < 4 && e0 + e < n; ++e) {
+        if ((stored >> e) & 1u) {
+          d.crf[base + e0 + e] = ncrf[e];
+          d.tau[base + e0 + e] = t;
         }
       }
     }
