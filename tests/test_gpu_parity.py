@@ -90,6 +90,41 @@ def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     g.close()
 
 
+@pytest.mark.parametrize("path,n_big", [(3, 4500), (3, 8300), (4, 2500), (4, 4400)])
+def test_fused_kernel_large_units(path, n_big):
+    """Units beyond 16 entries per thread: 17..32 per thread keep the weights in registers with the per-entry
+    state loaded in chunks, more than 32 per thread go through the LDS-resident generic path.  (Path 3 has 256
+    threads per unit, path 4 has 128.)  A small unit shares the call."""
+    cfg = _small("qwen7b", n_layers=1, batch=1, n_q_heads=4, n_kv_heads=2, prompt=n_big - 10, decode_steps=4,
+                 budget=n_big // 2, budget_min=200, budget_max=n_big + 60, seed=23)
+    budgets = np.array([[[n_big, 300]]], dtype=np.int32)
+    cap = (n_big + 64 + 31) // 32 * 32
+    st, o, g = _pair(cfg, cap=cap, budgets=budgets, path=path)
+    waves, _ = g.path_info()
+    assert waves == (4 if path == 3 else 2)
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=2)
+    assert stats.resynced <= 1, stats.notes
+    assert np.array_equal(g.lengths(), o.lengths())
+    g.close()
+
+
+def test_path_selection_api():
+    """Mode 0 picks the fused kernel only for enough units; 1 forces the separate kernels; 2-4 the fused
+    variants; other values are refused."""
+    _, ckv, _ = _mods()
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, seed=2)
+    st, o, g = _pair(cfg, cap=96)
+    assert g.path_info()[0] == 0                       # 4 units: separate kernels by default
+    for mode, waves in ((1, 0), (2, 4), (3, 4), (4, 2)):
+        g.set_path(mode)
+        assert g.path_info()[0] == waves
+    for bad in (-1, 5):
+        with pytest.raises(ckv.CkvError) as e:
+            g.set_path(bad)
+        assert e.value.code == ckv.EINVAL
+    g.close()
+
+
 def test_per_layer_calls():
     """The shape a real model imposes: one call per layer, t advancing after the last layer."""
     cfg = _small("llama8b", n_layers=3, n_q_heads=8, n_kv_heads=2, seed=11)
