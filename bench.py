@@ -28,7 +28,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-RING = 8                      # distinct synthetic step inputs, replayed cyclically
+RING = 32                     # distinct synthetic step inputs, replayed cyclically.  Not fewer: entries with
+                              # identical keys tie in the top-p and eviction orders, and a cache that fills up
+                              # with copies of a few keys drifts into the (slow, unrealistic) tie-breaking paths
 
 
 def build_workload(cfg, device):
@@ -194,7 +196,7 @@ def main():
 
     # ---- roofline pass: eager, HIP events around every scan launch
     g.profile_enable(True)
-    eager_steps(RING * 2)
+    eager_steps(RING)
     scan_ms, launches = g.profile_read()
     g.profile_enable(False)
     scan_bytes, step_bytes, entries, fused_bytes = algorithmic_bytes(cfg, g.budgets())
@@ -248,7 +250,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, "
                                f"batch {cfg.batch}, mean budget {cfg.budget} "
                                f"({cfg.budget_min}..{cfg.budget_max}), evict every step, steady state at t={cfg.prompt + cfg.decode_steps // 2}",
-                   "units": int(cfg.n_units), "entries_per_step": entries, "launch": "all layers per call, HIP graph of 8 steps"
+                   "units": int(cfg.n_units), "entries_per_step": entries, "launch": f"all layers per call, HIP graph of {RING} steps"
                    if graph is not None else "all layers per call, eager"},
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

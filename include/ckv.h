@@ -201,10 +201,11 @@ int ckv_import_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int3
                     const int32_t* pos, int32_t t_unit);
 
 /* Timing hook for benchmarks: while enabled, every ckv_decode_step brackets
- * its scan kernel with HIP events on the launch stream (do not enable while
- * the stream is being captured into a graph).  ckv_profile_read waits for the
- * device and returns the summed scan-kernel time and launch count since
- * enabling. */
+ * its dominant kernel (the fused per-unit kernel, or the scan kernel when the
+ * separate kernels are used) with HIP events on the launch stream (do not
+ * enable while the stream is being captured into a graph).  ckv_profile_read
+ * waits for the device and returns that kernel's summed time and launch count
+ * since enabling. */
 int ckv_profile_enable(ckv_ctx* ctx, int32_t on);
 int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
 
@@ -226,7 +227,7 @@ int ckv_path_info(ckv_ctx* ctx, int32_t* fused_waves, int32_t* lds_main_bytes);
  * 16 KiB is read completely; at least 1 MiB) from dev `src` with plain 16-byte
  * non-temporal loads (dst == NULL; `sink` is a dev uint32 that is never
  * actually written) or copies them to dev `dst`.  Gives the on-box bandwidth
- * ceiling next to which the scan kernel is reported, and kernels of known size
+ * ceiling next to which the streaming kernels are reported, and kernels of known size
  * for calibrating profiler byte counters.  Pointers 16-byte aligned. */
 int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, void* stream);
 
