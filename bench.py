@@ -56,6 +56,29 @@ def build_workload(cfg, device):
     return g, budgets, ring
 
 
+def build_fullkv(cfg, device, tokens, total_steps):
+    """The FullKV baseline of Table 1 on the same geometry: every unit holds all `tokens` positions and
+    nothing is ever evicted (room for `total_steps` appended entries)."""
+    import numpy as np
+    import torch
+    from paper_2601_16986_amd import ckv, workloads as wl
+
+    budgets = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), tokens, dtype=np.int32)
+    cap = (tokens + total_steps + 1 + 31) // 32 * 32
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
+                      lam=cfg.lam, top_p=cfg.top_p, t0=tokens, budget_min=1, budget_max=cap - 1, device=device)
+    m = wl.torch_mean_query(cfg, device)
+    gen = wl.torch_generator(cfg, 9, device)
+    r_now = math.sqrt(wl.DRIFT_VAR) * torch.randn(m.shape, generator=gen, device=device)
+    for layer in range(cfg.n_layers):
+        k, v, n, crf, tau, pos = wl.torch_steady_layer(cfg, layer, budgets[layer], tokens, m[layer], r_now[layer], device)
+        g.load_cache(layer, k, v, n, crf, tau, pos)
+        torch.cuda.synchronize()
+        del k, v, n, crf, tau, pos
+    ring = wl.torch_step_ring(cfg, RING, m, r_now, device)
+    return g, budgets, ring
+
+
 def algorithmic_bytes(cfg, budgets):
     """Per decode step.  Scan kernel: K and V rows of every cached entry once
     (512 B) plus the query group; whole step: 524 B per entry (K, V, CRF and
@@ -133,6 +156,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
     ap.add_argument("--path", type=int, default=0,
                     help="kernels of the all-layers step: 0 default, 1 separate scan/finish, 3 / 4 fused with 4 / 2 wavefronts per unit")
+    ap.add_argument("--fullkv", type=int, default=0, metavar="TOKENS",
+                    help="FullKV baseline instead: every unit holds TOKENS positions, attention-only steps, no eviction")
     ap.add_argument("--probe-only", action="store_true",
                     help="only run the plain streaming-read and copy kernels (4 GiB each): counter calibration")
     args = ap.parse_args()
@@ -154,17 +179,21 @@ def main():
     if args.probe_only:
         print(json.dumps({"stream_read_gbps": read_gbps, "copy_gbps": copy_gbps, "bytes": 4 << 30}))
         return
-    g, budgets, (rq, rk, rv) = build_workload(cfg, device)
+    steps = max(RING, args.steps // RING * RING)
+    warm = max(RING, (args.warmup + RING - 1) // RING * RING)
+    fullkv = args.fullkv > 0
+    if fullkv:
+        g, budgets, (rq, rk, rv) = build_fullkv(cfg, device, args.fullkv, warm + steps + 2 * RING)
+    else:
+        g, budgets, (rq, rk, rv) = build_workload(cfg, device)
     if args.path:
         g.set_path(args.path)
     out = torch.empty(rq.shape[1:], dtype=torch.float32, device=device)
-    steps = max(RING, args.steps // RING * RING)
-    warm = max(RING, (args.warmup + RING - 1) // RING * RING)
-    R = cfg.rebudget_interval
+    R = 0 if fullkv else cfg.rebudget_interval
 
     def eager_steps(k):
         for i in range(k):
-            g.decode_step(rq[i % RING], rk[i % RING], rv[i % RING], out=out)
+            g.decode_step(rq[i % RING], rk[i % RING], rv[i % RING], out=out, evict=not fullkv, attention_only=fullkv)
 
     eager_steps(warm)
     torch.cuda.synchronize()
@@ -199,18 +228,20 @@ def main():
     eager_steps(RING)
     scan_ms, launches = g.profile_read()
     g.profile_enable(False)
-    scan_bytes, step_bytes, entries, fused_bytes = algorithmic_bytes(cfg, g.budgets())
+    scan_bytes, step_bytes, entries, fused_bytes = algorithmic_bytes(cfg, g.lengths() - 1 if fullkv else g.budgets())
+    if fullkv:                                           # attention only: K, V, q, out
+        fused_bytes = step_bytes = scan_bytes + int(cfg.n_units) * cfg.group * 512
     fused_waves, _ = g.path_info()
     # dominant kernel of an all-layers step: the fused per-unit kernel if the context uses it, else the scan kernel
     kernel_name = f"unit_kernel<{fused_waves}>" if fused_waves else "scan_kernel"
     kernel_bytes = fused_bytes if fused_waves else scan_bytes
     scan_avg_ms = scan_ms / max(launches, 1)
     achieved = kernel_bytes / (scan_avg_ms * 1e-3) / 1e9
-    traffic = measured_traffic(kernel_name, cfg.name)
+    traffic = None if fullkv else measured_traffic(kernel_name, cfg.name)
 
     # ---- secondary: the shape a real model imposes, one call per layer
     per_layer = None
-    if not args.no_per_layer and not args.no_graph:
+    if not args.no_per_layer and not args.no_graph and not fullkv:
         outl = out[0]
 
         def layer_steps(k):
@@ -232,10 +263,12 @@ def main():
         per_layer = (time.perf_counter() - t1) * 1e3 / (reps * RING)
 
     lengths = g.lengths()
-    assert np.array_equal(lengths, g.budgets()), "caches are not at their budgets after the run"
+    if not fullkv:
+        assert np.array_equal(lengths, g.budgets()), "caches are not at their budgets after the run"
 
     res = {
-        "metric": "decode steps/s (attention + LRFU + evict, all layers per step)",
+        "metric": "decode steps/s (attention + LRFU + evict, all layers per step)" if not fullkv
+                  else "decode steps/s (FullKV baseline: attention only, nothing evicted)",
         "value": 1e3 / ms_per_step,
         "unit": "steps/s",
         "n_gpus": 1,
@@ -247,9 +280,12 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, "
-                               f"batch {cfg.batch}, mean budget {cfg.budget} "
-                               f"({cfg.budget_min}..{cfg.budget_max}), evict every step, steady state at t={cfg.prompt + cfg.decode_steps // 2}",
+        "config": {"workload": (f"{cfg.name}: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, "
+                                f"batch {cfg.batch}, mean budget {cfg.budget} "
+                                f"({cfg.budget_min}..{cfg.budget_max}), evict every step, steady state at t={cfg.prompt + cfg.decode_steps // 2}")
+                   if not fullkv else
+                   (f"{cfg.name} FullKV: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, batch {cfg.batch}, "
+                    f"every cache holds all {args.fullkv} positions and grows by one per step"),
                    "units": int(cfg.n_units), "entries_per_step": entries, "launch": f"all layers per call, HIP graph of {RING} steps"
                    if graph is not None else "all layers per call, eager"},
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,

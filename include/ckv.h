@@ -59,6 +59,8 @@ enum { CKV_FLAG_HIT = 1,                             /* per-slot flag as exporte
 enum { CKV_CLASS_SLIP = 0, CKV_CLASS_POTENTIAL = 1, CKV_CLASS_CRYSTAL = 2 };
 
 #define CKV_FUSE_EVICT 1u   /* ckv_decode_step: run Alg. 1 Step 4 in the same pass */
+#define CKV_ATTENTION_ONLY 2u /* ckv_decode_step: append and attend only (the FullKV baseline of Table 1): no hit
+                               * mask, no score update, no eviction; excludes CKV_FUSE_EVICT */
 
 /* Geometry.  head_dim must be 128; n_q_heads = G * n_kv_heads with G <= 8;
  * `cap` = slots per unit, a multiple of 32, at most 32768. */
@@ -154,7 +156,9 @@ int ckv_load_cache(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, in
  * aggregated CRF for Alg. 2, and with CKV_FUSE_EVICT evicts down to the budget
  * (as ckv_evict).  Layers must be stepped in order 0..n_layers-1; t advances
  * after the last one.  A unit that is already full (n == cap) is not
- * appended to: the step still runs and ckv_status() reports CKV_ECAPACITY. */
+ * appended to: the step still runs and ckv_status() reports CKV_ECAPACITY.
+ * With CKV_ATTENTION_ONLY the stored scores, taus and the Alg. 2 window are left
+ * alone (the new entry is still appended with CRF 0, tau t). */
 int ckv_decode_step(ckv_ctx* ctx, int32_t layer, const void* q, const void* k_new,
                     const void* v_new, void* out, uint32_t flags, void* stream);
 

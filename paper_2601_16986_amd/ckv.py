@@ -19,6 +19,7 @@ BF16, F32 = 1, 2
 REWARD_TOPP_HIT, REWARD_ATTN_WEIGHTED = 0, 1
 FLAG_HIT, FLAG_SLIP = 1, 2
 FUSE_EVICT = 1
+ATTENTION_ONLY = 2
 
 EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_load_cache", "ckv_decode_step", "ckv_evict",
@@ -204,7 +205,7 @@ class CrystalKV:
         self._check(self.lib.ckv_load_cache(self.ctx, layer, k.data_ptr(), v.data_ptr(), P, lengths.data_ptr(),
                                             crf0.data_ptr(), tau0.data_ptr(), pos0.data_ptr(), self._stream()))
 
-    def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None):
+    def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None, attention_only=False):
         """q [L][Bz][Hq][d], k_new / v_new [L][Bz][Hkv][d] (no leading [L] for a single layer).
         Returns the device tensor `out` of the same shape as q."""
         t = self.torch
@@ -215,7 +216,9 @@ class CrystalKV:
         if out is None:
             out = t.empty(q.shape, dtype=t.float32 if self.out_dtype == F32 else t.bfloat16, device=self.device)
         self._check(self.lib.ckv_decode_step(self.ctx, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
-                                             out.data_ptr(), FUSE_EVICT if evict else 0, self._stream()))
+                                             out.data_ptr(),
+                                             ATTENTION_ONLY if attention_only else (FUSE_EVICT if evict else 0),
+                                             self._stream()))
         return out
 
     def evict(self, layer=-1):

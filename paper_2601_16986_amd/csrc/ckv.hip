@@ -375,7 +375,9 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
                     uint32_t flags, void* stream) {
   if (!c) return CKV_EINVAL;
   if (!q || !k_new || !v_new || !out) return fail(c, CKV_EINVAL, "q, k_new, v_new or out is NULL");
-  if (flags & ~CKV_FUSE_EVICT) return fail(c, CKV_EINVAL, "unknown flag bits");
+  if (flags & ~(CKV_FUSE_EVICT | CKV_ATTENTION_ONLY)) return fail(c, CKV_EINVAL, "unknown flag bits");
+  if ((flags & CKV_ATTENTION_ONLY) && (flags & CKV_FUSE_EVICT))
+    return fail(c, CKV_EINVAL, "CKV_ATTENTION_ONLY excludes CKV_FUSE_EVICT");
   int begin, count;
   if (int rc = layer_range(c, layer, &begin, &count)) return rc;
   if (layer == -1) {
@@ -412,10 +414,10 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (fused) {
     if (fv->waves == 4)
       hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, c->dev, (const uint16_t*)q, out,
-                         flags & CKV_FUSE_EVICT, advance, fv->lds_main);
+                         flags, advance, fv->lds_main);
     else
       hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, c->dev, (const uint16_t*)q, out,
-                         flags & CKV_FUSE_EVICT, advance, fv->lds_main);
+                         flags, advance, fv->lds_main);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
     return CKV_OK;
@@ -428,7 +430,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
 
   hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out,
-                     flags & CKV_FUSE_EVICT, advance);
+                     flags, advance);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
 }

@@ -442,6 +442,7 @@ __device__ __forceinline__ void scan_qk(const KFrag& f, const bf16x8 (&qv)[4], f
   // logits: row j of the LDS buffer (a wave-private staging tile, or the block's
   // place in a resident logits tile); with lg_dst the tile is forwarded to memory
   // as one contiguous 128 G-byte store
+  if (lds_lg == nullptr) return;            // attention only: nobody looks at the logits afterwards
   if (j < G) {
     *reinterpret_cast<f32x4*>(lds_lg + j * lds_row + 4 * kg) = f32x4{sv[0], sv[1], sv[2], sv[3]};
     *reinterpret_cast<f32x4*>(lds_lg + j * lds_row + 16 + 4 * kg) = f32x4{sv[4], sv[5], sv[6], sv[7]};
@@ -1306,7 +1307,9 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
     const int nch = (n + kChunk - 1) / kChunk;
     merge_partials(d, u, urel, nch, d.sc[SC_SEQ], sM, sInv, sW, out, tid);
     const bool evict = (call_flags & 1u) != 0;
-    if (n <= 8 * kThreads) {
+    if (call_flags & 2u) {
+      // attention only: the outputs are written, nothing else changes
+    } else if (n <= 8 * kThreads) {
       float a[8];
       mean_weights_regs(d, u, n, sM, sInv, a, tid);
       f32x4 crf[2];

@@ -179,7 +179,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(slane, 8 * G - 1);
     auto qk = [&](int blk, float (&sv)[8]) {
       const bool resident = blk < res_blk;
-      float* lds_dst = resident ? lg + (size_t)blk * (G * kBlk) : s_buf + wave * (kMaxGroup * kLgRow);
+      float* lds_dst = (call_flags & 2u) ? nullptr : resident ? lg + (size_t)blk * (G * kBlk) : s_buf + wave * (kMaxGroup * kLgRow);
       scan_qk(ka, qv, sv, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
               resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
     };
@@ -338,7 +338,10 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       lrfu_regs<R, CH, CH, ValFused, NT>(d, u, n, B, t, a, crf, tau, ps, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4,
                                          s_tab, s_tab_n, rb, phase, sh, ftid, publish);
     };
-    if (n <= 8 * NT) {
+    if (call_flags & 2u) {               // attention only: no bookkeeping, just keep the stream and the queue going
+      request_next();
+      if (ftid == 0) s_claim = 3 * grid + claimed;
+    } else if (n <= 8 * NT) {
       regs_path(std::integral_constant<int, 8>{});
     } else if (n <= 16 * NT) {
       regs_path(std::integral_constant<int, 16>{});

@@ -108,6 +108,36 @@ def test_fused_kernel_large_units(path, n_big):
     g.close()
 
 
+@pytest.mark.parametrize("path", PATHS)
+def test_attention_only_steps(path):
+    """CKV_ATTENTION_ONLY (the FullKV baseline): outputs as the oracle's attention over the growing cache;
+    scores and taus of the old entries stay as loaded, the new entries arrive with CRF 0 and tau = pos = t,
+    nothing is evicted; combining it with eviction is refused."""
+    _, ckv, _ = _mods()
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, prompt=70, decode_steps=12, budget=60, seed=31)
+    st, o, g = _pair(cfg, cap=128, path=path)
+    before = {key: g.export_unit(*key, with_kv=False) for key in o.units}
+    for s in range(cfg.decode_steps):
+        ref, _ = o.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+        out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s], attention_only=True).cpu().numpy()
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+    assert g.status() == 0 and g.time() == cfg.prompt + cfg.decode_steps
+    for key, b in before.items():
+        e = g.export_unit(*key, with_kv=False)
+        n0 = b["n"]
+        assert e["n"] == n0 + cfg.decode_steps
+        assert np.array_equal(e["crf"][:n0], b["crf"]) and np.array_equal(e["tau"][:n0], b["tau"])
+        assert np.array_equal(e["pos"][:n0], b["pos"])
+        new_t = np.arange(cfg.prompt, cfg.prompt + cfg.decode_steps)
+        assert np.array_equal(e["pos"][n0:], new_t) and np.array_equal(e["tau"][n0:], new_t)
+        assert np.all(e["crf"][n0:] == 0)
+    with pytest.raises(ckv.CkvError) as err:
+        # both flags at once: refused during argument validation, before any pointer is looked at
+        g._check(g.lib.ckv_decode_step(g.ctx, -1, 1, 1, 1, 1, ckv.FUSE_EVICT | ckv.ATTENTION_ONLY, None))
+    assert err.value.code == ckv.EINVAL
+    g.close()
+
+
 def test_path_selection_api():
     """Mode 0 picks the fused kernel only for enough units; 1 forces the separate kernels; 2-4 the fused
     variants; other values are refused."""
