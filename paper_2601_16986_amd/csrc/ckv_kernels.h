@@ -672,19 +672,39 @@ __device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, i
 // row, the V row and the per-slot state are handled by different wavefronts;
 // the state comes from sh[1..4] = {CRF bits, tau, position} of the last slot's
 // entry and the victim's position, so no per-slot array is read.
+// The K and V rows of the slot that will move are read ahead of time (load_row, by the wavefronts that
+// will store them), so that the eviction itself only stores.
+struct EntryRow {
+  u32x4 k;             // lanes 0..15 of wavefront 0: 8 dims of the K row each
+  uint16_t v0, v1;     // wavefront 1 (0 if there is only one): dims lane and lane + 64 of the V row
+};
+
 template <int NT = kThreads>
-__device__ __forceinline__ void evict_one(const Dev& d, size_t base, int src, int dst, const int* sh, int tid) {
+__device__ __forceinline__ EntryRow load_row(const Dev& d, size_t base, int src, int tid) {
+  const int wave = tid >> 6, lane = tid & 63;
+  constexpr int W = NT / 64;
+  const uint16_t* K = d.K + base * kDim;
+  const uint16_t* V = d.V + base * kDim;
+  EntryRow r{{0u, 0u, 0u, 0u}, 0, 0};
+  if (wave == 0 && lane < 16) r.k = *reinterpret_cast<const u32x4*>(K + k_offset(src, lane * 8));
+  if (wave == (W > 1 ? 1 : 0)) {
+    r.v0 = V[v_offset(src, lane)];
+    r.v1 = V[v_offset(src, lane + 64)];
+  }
+  return r;
+}
+
+template <int NT = kThreads>
+__device__ __forceinline__ void evict_one(const Dev& d, size_t base, int src, int dst, const int* sh, int tid, const EntryRow& row) {
   const int wave = tid >> 6, lane = tid & 63;
   constexpr int W = NT / 64;
   uint16_t* K = d.K + base * kDim;
   uint16_t* V = d.V + base * kDim;
   if (dst != src) {
-    if (wave == 0 && lane < 16)
-      *reinterpret_cast<u32x4*>(K + k_offset(dst, lane * 8)) = *reinterpret_cast<const u32x4*>(K + k_offset(src, lane * 8));
+    if (wave == 0 && lane < 16) *reinterpret_cast<u32x4*>(K + k_offset(dst, lane * 8)) = row.k;
     if (wave == (W > 1 ? 1 : 0)) {
-      const uint16_t v0 = V[v_offset(src, lane)], v1 = V[v_offset(src, lane + 64)];
-      V[v_offset(dst, lane)] = v0;
-      V[v_offset(dst, lane + 64)] = v1;
+      V[v_offset(dst, lane)] = row.v0;
+      V[v_offset(dst, lane + 64)] = row.v1;
     }
   }
   if (wave == (W > 2 ? 2 : 0) && lane == 32) {
@@ -905,11 +925,26 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
 // close to 1) in global memory.  Written as two loads in two address spaces on purpose: a conditional
 // expression over the two pointers becomes one flat load, which waits for every vector-memory
 // operation in flight.
+__device__ __forceinline__ float decay_far(const Dev& d, int delta) {
+  float far = d.tab[delta];
+  asm volatile("" : "+v"(far));          // the wait for this load stays inside the caller's branch: placed after
+  return far;                            // the branch it would be a wait for every vector-memory operation
+}                                        // in flight, executed for every entry
 __device__ __forceinline__ float decay_of(const Dev& d, int delta, const float* s_tab, int s_tab_n) {
   float dec = s_tab[min(delta, s_tab_n - 1)];
   asm volatile("" : "+v"(dec));          // pins the LDS load: otherwise the two loads are merged again
-  if (delta >= s_tab_n) dec = d.tab[delta];
+  if (delta >= s_tab_n) dec = decay_far(d, delta);
   return dec;
+}
+// Four lookups at once: the LDS reads are issued together and waited for once.
+__device__ __forceinline__ void decay4_of(const Dev& d, const int (&delta)[4], const float* s_tab, int s_tab_n, float (&dec)[4]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) dec[e] = s_tab[min(delta[e], s_tab_n - 1)];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(dec[e]));
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (delta[e] >= s_tab_n) dec[e] = decay_far(d, delta[e]);
 }
 
 // Mean attention weight of every entry of unit u into val[0..n).
@@ -1127,6 +1162,12 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   const size_t base = (size_t)u * d.cap;
 #pragma unroll
   for (int c = CP; c < CH; ++c) load_meta<NT>(d, base, n, t, c, tid, crf[c], tau[c], ps[c]);
+  // what the end of the step would otherwise wait for: the unit's running sum, and the last slot's rows
+  // (the entry that moves if exactly one entry is evicted)
+  const u64 window0 = d.window[u];
+  const bool evict_single = evict && n - B == 1;
+  EntryRow last_row{{0u, 0u, 0u, 0u}, 0, 0};
+  if (evict_single) last_row = load_row<NT>(d, base, n - 1, tid);
   // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
   uint32_t theta = 0;
   bool ties_all = true;
@@ -1135,7 +1176,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     // largest pattern theta with sum{a >= theta} > p, two bits per round (one barrier each): the three
     // candidates' sums are nested, so the largest candidate that passes is what bit-by-bit bisection
     // would reach.  Bit 30 is never set: the weights are <= 1.
-    for (int bit = 29; bit >= 1; bit -= 2) {
+    auto round = [&](int bit) {
       const uint32_t c1 = theta | (1u << (bit - 1)), c2 = theta | (1u << bit), c3 = c1 | c2;
       float p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
@@ -1147,6 +1188,68 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       }
       block_sum3_f32<NT>(p1, p2, p3, rb, phase, tid);
       theta = p3 > d.top_p ? c3 : p2 > d.top_p ? c2 : p1 > d.top_p ? c1 : theta;
+    };
+    constexpr int kListBit = 17;        // the rounds for the bits above this one run over all entries
+    int bit = 29;
+    for (; bit > kListBit; bit -= 2) round(bit);
+    // With the top 12 bits fixed, the weights that can still decide a candidate, those in
+    // [theta, theta + 2^18), are usually a handful.  If at most 64, they are collected in LDS (in a fixed
+    // order: by wavefront, register index, lane) and one wavefront finishes the bisection on them alone:
+    // nine rounds without barriers over one register instead of R.
+    {
+      const uint32_t lo = theta > 1u ? theta : 1u, hi = theta + (2u << kListBit);
+      const int lane = tid & 63, wave = tid >> 6;
+      float ab = 0.f;
+      int mine = 0;
+#pragma unroll
+      for (int k = 0; k < R; ++k) {
+        const uint32_t b = __float_as_uint(a[k]);
+        ab += (b >= hi) ? a[k] : 0.f;
+        mine += (b >= lo && b < hi) ? 1 : 0;
+      }
+      ab = wave_sum_f32(ab);
+      mine = wave_sum_i32(mine);
+      if (lane == 0) *reinterpret_cast<f32x4*>(rb.t[phase][wave]) = f32x4{ab, __int_as_float(mine), 0.f, 0.f};
+      __syncthreads();
+      float above_bucket = 0.f;
+      int m = 0, off = 0;
+#pragma unroll
+      for (int w = 0; w < NT / 64; ++w) {
+        const f32x4 q = *reinterpret_cast<const f32x4*>(rb.t[phase][w]);
+        above_bucket += q[0];
+        const int cw = __float_as_int(q[1]);
+        off += w < wave ? cw : 0;
+        m += cw;
+      }
+      phase ^= 1;
+      if (m <= 64 && lst_cap >= 64) {
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+          const uint32_t b = __float_as_uint(a[k]);
+          const bool in = b >= lo && b < hi;
+          const unsigned long long mask = __ballot(in);
+          const int r = off + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+          if (in) lst[r] = (int)b;
+          off += __popcll(mask);
+        }
+        __syncthreads();
+        if (wave == 0) {
+          const uint32_t bj = lane < m ? (uint32_t)lst[lane] : 0u;
+          const float aj = __uint_as_float(bj);
+          for (; bit >= 1; bit -= 2) {
+            const uint32_t c1 = theta | (1u << (bit - 1)), c2 = theta | (1u << bit), c3 = c1 | c2;
+            const float p1 = above_bucket + wave_sum_f32(bj >= c1 ? aj : 0.f);
+            const float p2 = above_bucket + wave_sum_f32(bj >= c2 ? aj : 0.f);
+            const float p3 = above_bucket + wave_sum_f32(bj >= c3 ? aj : 0.f);
+            theta = p3 > d.top_p ? c3 : p2 > d.top_p ? c2 : p1 > d.top_p ? c1 : theta;
+          }
+          if (lane == 0) sh[7] = (int)theta;
+        }
+        __syncthreads();
+        theta = (uint32_t)sh[7];
+      } else {
+        for (; bit >= 1; bit -= 2) round(bit);
+      }
     }
     if (theta != 0) {
       float above = 0.f;
@@ -1206,14 +1309,18 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     i32x4 ntau = tau[c];
     uint32_t stored = 0;                    // bit e: entry e0 + e gets a new (CRF, tau)
     const bool topp = d.reward_mode == 0;
+    int delta4[4];
+    float dec4[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) delta4[e] = min(max(t - tau[c][e], 0), d.tab_last);
+    decay4_of(d, delta4, s_tab, s_tab_n, dec4);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int i = e0 + e;
       const bool ok = i < n;
       const int pe = ps[c][e];
       const float w = a[4 * cc + e];
-      const int delta = min(max(t - tau[c][e], 0), d.tab_last);
-      const float dec = decay_of(d, delta, s_tab, s_tab_n);
+      const float dec = dec4[e];
       const uint32_t b = __float_as_uint(w);
       const bool hit = topp & ((b > theta) | ((b == theta) & (ties_all | (pe <= pos_cut))) |
                                ((i == n - 1) & (pe == t)));          // the entry appended this step is always hit
@@ -1255,7 +1362,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   }
   sfix = block_sum_u64<NT>(sfix, rb, phase, tid);
   if (tid == 0) {
-    d.window[u] += sfix;
+    d.window[u] = window0 + sfix;
     d.t_unit[u] = t;
   }
   // ---- Step 4
@@ -1263,14 +1370,14 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     if (tid == 0) d.nev[u] = 0;
     return;
   }
-  if (n - B == 1) {
+  if (evict_single) {
     const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
     if (best == gbest && best_i >= 0) {     // keys are unique: one writer
       sh[0] = best_i;
       sh[4] = ~(int)(uint32_t)best;         // the victim's position
     }
     __syncthreads();
-    evict_one<NT>(d, base, n - 1, sh[0], sh, tid);
+    evict_one<NT>(d, base, n - 1, sh[0], sh, tid, last_row);
     if (tid == 0) {
       d.n[u] = B;
       d.nev[u] = 1;

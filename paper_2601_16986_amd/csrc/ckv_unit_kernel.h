@@ -91,7 +91,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   __shared__ float s_buf[kStageFloats > kOutFloats ? kStageFloats : kOutFloats];
   float* s_out = s_buf;
   __shared__ float s_ml[W][kMaxGroup][2];
-  __shared__ float sM[kMaxGroup], sInv[kMaxGroup];
+  __shared__ __align__(16) float sM[kMaxGroup];
+  __shared__ __align__(16) float sInv[kMaxGroup];
   __shared__ float s_tab[kTabLds];
   __shared__ RedBuf rb;
   __shared__ int sh[8];
@@ -291,7 +292,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     const bool evict = (call_flags & 1u) != 0;
     const float invG = 1.0f / (float)G;
     const float* lgg = d.logits + (size_t)u * d.cap * G;
-    // mean weights of the four consecutive entries e0 .. e0 + 3 (one 16-byte read per head)
+    // mean weights of the four consecutive entries e0 .. e0 + 3 (one 16-byte read per head; the heads'
+    // maxima and reciprocal denominators are read as four 16-byte vectors per group, not once per use)
     auto weights4 = [&](int e0, float* a4) {
       f32x4 x[kMaxGroup];
       const int off = (e0 >> 5) * (G * kBlk) + (e0 & 31);
@@ -304,14 +306,18 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         for (int g = 0; g < kMaxGroup; ++g)
           x[g] = (g < G && e0 < n) ? *reinterpret_cast<const f32x4*>(lgg + off + g * kBlk) : ninf;
       }
+      const f32x4 hM[2] = {*reinterpret_cast<const f32x4*>(sM), *reinterpret_cast<const f32x4*>(sM + 4)};
+      const f32x4 hInv[2] = {*reinterpret_cast<const f32x4*>(sInv), *reinterpret_cast<const f32x4*>(sInv + 4)};
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float a = 0.f;
+      for (int g = 0; g < kMaxGroup; ++g) {
+        if (g < G) {                      // uniform; heads in ascending order, as everywhere
 #pragma unroll
-        for (int g = 0; g < kMaxGroup; ++g)
-          if (g < G) a += fast_exp2(x[g][e] - sM[g]) * sInv[g];
-        a4[e] = (e0 + e < n) ? a * invG : 0.f;
+          for (int e = 0; e < 4; ++e) acc[e] += fast_exp2(x[g][e] - hM[g >> 2][g & 3]) * hInv[g >> 2][g & 3];
+        }
       }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a4[e] = (e0 + e < n) ? acc[e] * invG : 0.f;
     };
     // R entries per thread.  The groups' state that was not requested at the unit's start is requested
     // after the weights have been computed (fewer live registers) and arrives during the bisection.
