@@ -29,6 +29,10 @@ What follows which passage of the paper (arxiv 2601.16986):
                            top 30 % = CrystalKV, bottom 30 % = SlipKV.
 * `CrystalKVOracle`      - the per-step control flow of Sec. 4 / Alg. 1 over all
                            (layer, sequence, KV head) units.
+* `CrystalKVOracle.seed_prompt`
+                         - Alg. 1 Steps 1-3 replayed over the prompt's last
+                           queries (the paper leaves the prompt's scores open;
+                           reading stated below).
 
 Readings where the paper is silent (each is a named parameter or stated here):
 
@@ -57,6 +61,14 @@ Readings where the paper is silent (each is a named parameter or stated here):
   (floor(CRF_temp * 2^20) as an integer), averaged over the steps since the
   last re-allocation.
 * integer budgets: see `apportion` and `rebudget`.
+* prompt scores (`seed_prompt`): the paper starts Alg. 1 at decode time and
+  says nothing about the scores the prompt's entries start with.  Reading: the
+  last W prompt positions P-W .. P-1 are treated as W decode steps that have
+  already happened, without eviction: the query of position t sees the entries
+  of positions <= t (causal), Steps 1-3 run at time t, and position t's own
+  entry, arriving at that step, is in its hit set (the insertion rule above).
+  Entries before the window count as referenced once, on arrival (CRF = 1,
+  tau = position).  Nothing of this enters the aggregated-CRF window of Alg. 2.
 * reward_mode 1 ("attention weighted", a labelled variant, not the paper's
   Alg. 1): the reward is the entry's mean attention weight instead of 0/1, and
   every entry stores its score and tau each step.
@@ -478,6 +490,41 @@ class CrystalKVOracle:
                 u.tau = (np.full(P, P - 1, np.int64) if tau0 is None
                          else np.asarray(tau0[b, h], np.int64).copy())
                 u.hit = np.zeros(P, dtype=bool)
+
+    def seed_prompt(self, layer, q_obs):
+        """Scores of a freshly loaded prompt from its last W queries (reading
+        in the header).  q_obs: [W][Bz][Hq][d], the queries of positions
+        P-W .. P-1 in order.  Replaces the CRF and tau the prompt was loaded
+        with.  Returns {unit key: [HitDecision of position P-W, ..., P-1]}."""
+        q_obs = np.asarray(q_obs, dtype=np.float64)
+        W = q_obs.shape[0]
+        decisions = {}
+        for b in range(self.Bz):
+            for h in range(self.Hkv):
+                u = self.units[(layer, b, h)]
+                P = u.n
+                assert 1 <= W <= P and np.array_equal(u.pos, np.arange(P)), "needs a freshly loaded prompt"
+                u.crf = np.where(u.pos < P - W, np.float32(1.0), np.float32(0.0)).astype(np.float32)
+                u.tau = u.pos.astype(np.int64).copy()
+                decs = []
+                for j in range(W):
+                    t = P - W + j                       # time of this query = its position
+                    nv = t + 1                          # entries of positions 0 .. t are visible
+                    q = q_obs[j, b, h * self.G:(h + 1) * self.G]
+                    _, a = attention(q, u.K[:nv], u.V[:nv], self.scale)
+                    abar = a.sum(axis=0) / float(self.G)
+                    if self.reward_mode == REWARD_TOPP_HIT:
+                        dec = hit_mask(abar, u.pos[:nv], self.top_p, new_index=nv - 1)
+                        reward, store = dec.hit.astype(np.float32), dec.hit
+                    else:
+                        dec = HitDecision(np.ones(nv, bool), nv, np.arange(nv), math.inf, math.inf)
+                        reward, store = abar.astype(np.float32), np.ones(nv, dtype=bool)
+                    _, u.crf[:nv], u.tau[:nv] = crf_update(u.crf[:nv], u.tau[:nv], t, reward, store, self.tab)
+                    decs.append(dec)
+                u.hit = np.zeros(P, dtype=bool)
+                u.hit[:len(decs[-1].hit)] = decs[-1].hit
+                decisions[(layer, b, h)] = decs
+        return decisions
 
     def set_unit(self, key, K, V, pos, crf, tau):
         u = self.units[key]

@@ -370,3 +370,84 @@ def test_tiny_workload_invariants_and_heavy_survival(golden_dir):
     fx = json.load(open(os.path.join(golden_dir, "table1_hbm_saving.json")))
     for row in fx["rows"]:
         assert round(100.0 * (1.0 - row["budget"] / row["gen_len"]), 2) == pytest.approx(row["saving_percent"], abs=0.006)
+
+
+# ------------------------------------------------------------------ prompt scores
+def _seed_case(seed, P=37, W=9, lam=0.6, top_p=0.9, hq=8, hkv=2):
+    cfg = wl.scaled(wl.CONFIGS["tiny"], n_layers=1, batch=2, n_q_heads=hq, n_kv_heads=hkv, prompt=P, decode_steps=W,
+                    budget=1000, budget_min=1, budget_max=1000, seed=seed)
+    st = wl.make_stream(cfg)
+    q_obs = st.q[:W, 0]                                   # any W queries: [W][Bz][Hq][d]
+    return cfg, st, q_obs
+
+
+@pytest.mark.parametrize("seed,lam", [(3, 0.6), (4, 0.0), (5, 1.0), (6, 0.93)])
+def test_seed_prompt_equals_decoding_the_window_without_eviction(seed, lam):
+    """The reading behind `seed_prompt`: the prompt's last W positions are W decode steps that already
+    happened.  Loading only the first P - W tokens (each referenced once, on arrival) and decoding the
+    other W tokens with the same queries, nothing evicted, must leave the same scores.  The two routes
+    share `attention`, `hit_mask` and `crf_update` but not the bookkeeping around them (append and time
+    there, prefix views here)."""
+    P, W = 37, 9
+    cfg, st, q_obs = _seed_case(seed, P, W, lam)
+    big = np.full((1, 2, 2), 1000)
+    a = ok.CrystalKVOracle(1, 2, 8, 2, 128, big, lam=lam, top_p=0.9, t0=P)
+    a.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    a.seed_prompt(0, q_obs)
+    b = ok.CrystalKVOracle(1, 2, 8, 2, 128, big, lam=lam, top_p=0.9, t0=P - W)
+    head = np.arange(P - W)
+    b.load_prompt(0, st.prompt_k[0][:, :, :P - W], st.prompt_v[0][:, :, :P - W],
+                  crf0=np.ones((2, 2, P - W), np.float32), tau0=np.broadcast_to(head, (2, 2, P - W)))
+    for j in range(W):
+        k_new = st.prompt_k[:, :, :, P - W + j]           # [L][Bz][Hkv][d]
+        v_new = st.prompt_v[:, :, :, P - W + j]
+        b.decode_step(q_obs[j][None], k_new, v_new, evict=False)
+    assert b.t == P
+    for key in a.units:
+        ua, ub = a.units[key], b.units[key]
+        assert np.array_equal(ua.pos, ub.pos)
+        assert np.array_equal(ua.crf.view(np.uint32), ub.crf.view(np.uint32)) and np.array_equal(ua.tau, ub.tau)
+        assert ua.crf_window == 0                          # nothing of the replay reaches Alg. 2's window
+
+
+def test_seed_prompt_scores_are_the_closed_form_over_the_hit_times():
+    """Sec. 5.2: CRF = sum_j lambda^(t - t_j) over the entry's reference times, here its arrival (entries
+    of the window and before alike) plus every window query that hit it, evaluated at the last of them."""
+    P, W, lam = 41, 12, 0.7
+    cfg, st, q_obs = _seed_case(11, P, W, lam)
+    o = ok.CrystalKVOracle(1, 2, 8, 2, 128, np.full((1, 2, 2), 1000), lam=lam, top_p=0.9, t0=P)
+    o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    decs = o.seed_prompt(0, q_obs)
+    for key, u in o.units.items():
+        for i in range(P):
+            times = [i] + [P - W + j for j, dcs in enumerate(decs[key])
+                           if i < len(dcs.hit) and dcs.hit[i] and P - W + j != i]
+            assert u.tau[i] == max(times)
+            want = sum(lam ** (max(times) - tj) for tj in times)
+            assert abs(float(u.crf[i]) - want) <= 1e-5 * want
+
+
+def test_seed_prompt_limits_lru_lfu_and_single_query():
+    """lambda = 0: only the last reference counts (CRF = 1, tau = last hit); lambda = 1: CRF = number of
+    references; W = 1: the last query's nucleus and the last token itself are the only entries touched."""
+    P, W = 33, 8
+    cfg, st, q_obs = _seed_case(21, P, W)
+    for lam in (0.0, 1.0):
+        o = ok.CrystalKVOracle(1, 2, 8, 2, 128, np.full((1, 2, 2), 1000), lam=lam, top_p=0.9, t0=P)
+        o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+        decs = o.seed_prompt(0, q_obs)
+        for key, u in o.units.items():
+            nhits = np.ones(P, np.int64)
+            for j, dcs in enumerate(decs[key]):
+                h = np.zeros(P, bool)
+                h[:len(dcs.hit)] = dcs.hit
+                h[P - W + j] = False                       # the arrival is already counted
+                nhits += h
+            assert np.array_equal(u.crf, np.ones(P, np.float32) if lam == 0.0 else nhits.astype(np.float32))
+    o = ok.CrystalKVOracle(1, 2, 8, 2, 128, np.full((1, 2, 2), 1000), lam=0.5, top_p=0.9, t0=P)
+    o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    decs = o.seed_prompt(0, q_obs[-1:])
+    for key, u in o.units.items():
+        hit = decs[key][0].hit
+        assert hit[P - 1] and np.array_equal(u.tau, np.where(hit, P - 1, np.arange(P)))
+        assert np.array_equal(u.crf, np.where(hit & (np.arange(P) < P - 1), np.float32(1.0) + np.float32(0.5) ** (P - 1 - np.arange(P)).astype(np.float32), np.float32(1.0)).astype(np.float32))
