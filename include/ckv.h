@@ -132,6 +132,21 @@ void ckv_destroy(ckv_ctx* ctx);
 int ckv_load_prompt(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, int32_t P,
                     const float* crf0, const int32_t* tau0, void* stream);
 
+/* Scores of a loaded prompt from its last W queries (the step before the decode
+ * path: Alg. 1 Steps 1-3, Sec. 5.2, replayed; the paper does not say what scores
+ * the prompt's entries start with).  q_obs: dev bf16 [W][batch][n_q_heads][128],
+ * the queries of positions P-W .. P-1 in order.  Replaces the CRF and tau the
+ * layer's prompt was loaded with: every entry starts as referenced once, on
+ * arrival (CRF 1, tau = position), then for t = P-W .. P-1 the query of position
+ * t attends to the entries of positions <= t and their scores are updated at
+ * time t exactly as in a decode step that evicts nothing, position t's own
+ * entry being in its hit set.  Nothing is appended, evicted or written to an
+ * output, the time stays t0, and the replay leaves no trace in the aggregated
+ * CRF that ckv_rebudget consumes.  Requires a layer filled by ckv_load_prompt
+ * and not touched since (CKV_ESTATE otherwise) and 1 <= W <= P.  3 W + 2 kernel
+ * launches on `stream`; asynchronous. */
+int ckv_seed_prompt(ckv_ctx* ctx, int32_t layer, const void* q_obs, int32_t W, void* stream);
+
 /* Fill the empty caches of one layer with entries from the middle of a
  * sequence (restoring a checkpoint, or building a steady-state cache for
  * measurements).  k, v as in ckv_load_prompt with row stride P; unit (b, h)

@@ -22,7 +22,8 @@ FUSE_EVICT = 1
 ATTENTION_ONLY = 2
 
 EXPORTS = [
-    "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_load_cache", "ckv_decode_step", "ckv_evict",
+    "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_seed_prompt", "ckv_load_cache", "ckv_decode_step",
+    "ckv_evict",
     "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
     "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
@@ -67,6 +68,7 @@ def load():
     lib.ckv_destroy.argtypes = [vp]
     lib.ckv_load_prompt.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp]
     lib.ckv_load_cache.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.ckv_seed_prompt.argtypes = [vp, i32, vp, i32, vp]
     lib.ckv_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, u32, vp]
     lib.ckv_evict.argtypes = [vp, i32, vp]
     lib.ckv_rebudget.argtypes = [vp, vp]
@@ -193,6 +195,14 @@ class CrystalKV:
                                              c0.data_ptr() if c0 is not None else None,
                                              t0.data_ptr() if t0 is not None else None, self._stream()))
         self._keep = (k, v, c0, t0)
+
+    def seed_prompt(self, layer, q_obs):
+        """q_obs: [W][Bz][Hq][d], the queries of the prompt's last W positions (numpy on the bf16 grid or a
+        device bf16 tensor): replaces the loaded prompt's scores by those the W queries give them."""
+        W = q_obs.shape[0]
+        q = self._dev_bf16(q_obs, (W, self.Bz, self.Hq, self.d))
+        self._check(self.lib.ckv_seed_prompt(self.ctx, layer, q.data_ptr(), W, self._stream()))
+        self._keep_q = q
 
     def load_cache(self, layer, k, v, lengths, crf0, tau0, pos0):
         """Device tensors: k, v bf16 [Bz][Hkv][P][d]; lengths int32 [Bz][Hkv]; crf0 f32, tau0 / pos0 int32 [Bz][Hkv][P]."""

@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -36,6 +38,7 @@ struct ckv_ctx {
     size_t lds = 0;             // dynamic LDS per workgroup
   } fused[2];                   // [0]: 4 wavefronts, 2 workgroups per CU; [1]: 2 wavefronts, 4 workgroups per CU
   std::vector<uint8_t> prompt_loaded;
+  std::vector<int32_t> prompt_len;   // per layer: length of a prompt loaded whole and untouched since, else -1
   std::string err;
   // scan timing
   bool profile = false;
@@ -230,6 +233,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   c->units_per_layer = layout->batch * layout->n_kv_heads;
   c->units = layout->n_layers * c->units_per_layer;
   c->prompt_loaded.assign(layout->n_layers, 0);
+  c->prompt_len.assign(layout->n_layers, -1);
   hipStream_t s = (hipStream_t)stream;
 
   int devid = 0;
@@ -356,6 +360,7 @@ int ckv_load_cache(ckv_ctx* c, int32_t layer, const void* k, const void* v, int3
   if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
   if (c->prompt_loaded[layer]) return fail(c, CKV_ESTATE, "layer already holds entries");
   c->prompt_loaded[layer] = 1;
+  c->prompt_len[layer] = (!lengths && !pos0) ? P : -1;
   dim3 grid((unsigned)((P + kBlk - 1) / kBlk), (unsigned)c->units_per_layer);
   hipLaunchKernelGGL(load_cache_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, c->dev,
                      layer * c->units_per_layer, (const uint16_t*)k, (const uint16_t*)v, (int)P, lengths, crf0, tau0,
@@ -387,14 +392,17 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   }
   const int advance = (layer == -1 || layer == c->lay.n_layers - 1) ? 1 : 0;
   c->next_layer = advance ? 0 : layer + 1;
-  for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_loaded[l] = 1;
+  for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) {
+    c->prompt_loaded[l] = 1;
+    c->prompt_len[l] = -1;
+  }
   hipStream_t s = (hipStream_t)stream;
 
   const ckv_ctx::Fused* fv = layer == -1 ? fused_variant(c) : nullptr;
   if (fv && c->path_mode == 0 && count < 4 * fv->grid) fv = nullptr;
   const bool fused = fv != nullptr;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1);
+                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX);
   CKV_HIP(c, hipGetLastError());
 
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -430,7 +438,41 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
 
   hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out,
-                     flags, advance);
+                     flags, advance, INT_MAX, -1);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (layer < 0 || layer >= c->lay.n_layers) return fail(c, CKV_EINVAL, "layer out of range");
+  if (!q_obs) return fail(c, CKV_EINVAL, "q_obs is NULL");
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  const int P = c->prompt_len[layer];
+  if (P < 0) return fail(c, CKV_ESTATE, "needs a prompt loaded whole (ckv_load_prompt) and not touched since");
+  if (W < 1 || W > P) return fail(c, CKV_EINVAL, "need 1 <= W <= P");
+  hipStream_t s = (hipStream_t)stream;
+  const int begin = layer * c->units_per_layer, count = c->units_per_layer;
+  const dim3 sgrid((unsigned)std::min((P + kThreads - 1) / kThreads, 64), (unsigned)count);
+  hipLaunchKernelGGL(seed_state_kernel, sgrid, dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 0, 0);
+  CKV_HIP(c, hipGetLastError());
+  const size_t q_stride = (size_t)c->lay.batch * c->lay.n_q_heads * kDim;
+  for (int j = 0; j < W; ++j) {
+    const int t_j = P - W + j;                  // the query's position = its time; it sees positions 0 .. t_j
+    hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin,
+                       count, (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, t_j + 1);
+    CKV_HIP(c, hipGetLastError());
+    const long long max_items = (long long)count * c->dev.max_chunks;
+    long long blocks = 2ll * c->n_cu;
+    if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
+    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin,
+                       (const uint16_t*)q_obs + (size_t)j * q_stride);
+    CKV_HIP(c, hipGetLastError());
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, (void*)nullptr,
+                       0u, 0, t_j + 1, t_j);
+    CKV_HIP(c, hipGetLastError());
+  }
+  hipLaunchKernelGGL(seed_state_kernel, dim3(1, (unsigned)count), dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 1, c->par.t0 - 1);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
 }
@@ -439,6 +481,7 @@ int ckv_evict(ckv_ctx* c, int32_t layer, void* stream) {
   if (!c) return CKV_EINVAL;
   int begin, count;
   if (int rc = layer_range(c, layer, &begin, &count)) return rc;
+  for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_len[l] = -1;
   hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
@@ -460,7 +503,7 @@ int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, 
   const int begin = layer * c->units_per_layer, count = c->units_per_layer;
   hipStream_t s = (hipStream_t)stream;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0);
+                     (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, INT_MAX);
   CKV_HIP(c, hipGetLastError());
   const long long max_items = (long long)count * c->dev.max_chunks;
   long long blocks = 2ll * c->n_cu;
@@ -600,6 +643,7 @@ int ckv_import_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
   CKV_HIP(c, hipMemcpy(c->dev.nev + u, &zero, 4, hipMemcpyHostToDevice));
   CKV_HIP(c, hipMemcpy(c->dev.t_unit + u, &t_unit, 4, hipMemcpyHostToDevice));
   c->prompt_loaded[layer] = 1;
+  c->prompt_len[layer] = -1;
   return CKV_OK;
 }
 

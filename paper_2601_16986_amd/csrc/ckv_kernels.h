@@ -315,6 +315,26 @@ __global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_be
   }
 }
 
+// Before the replay of a prompt's last W queries (done = 0): every entry of the layer's units starts as
+// referenced once, on arrival (CRF 1, tau = position), the W entries of the window as not yet arrived
+// (CRF 0; their own query's step is their arrival).  After it (done = 1): the replay leaves no trace in
+// the units' aggregated-CRF window, and their last-step time is the one a fresh context has.
+__global__ __launch_bounds__(kThreads) void seed_state_kernel(Dev d, int unit_begin, int P, int W, int done, int t_unit) {
+  const int u = unit_begin + blockIdx.y;
+  if (done) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      d.window[u] = 0;
+      d.t_unit[u] = t_unit;
+    }
+    return;
+  }
+  const size_t base = (size_t)u * d.cap;
+  for (int i = blockIdx.x * kThreads + threadIdx.x; i < P; i += gridDim.x * kThreads) {
+    d.crf[base + i] = i < P - W ? 1.0f : 0.0f;
+    d.tau[base + i] = i;
+  }
+}
+
 // ------------------------------------------------------------------ prep
 // 32 threads per unit, 32 units per workgroup: append the new entry (unless
 // bit 0 of `append` is clear) and, unless bit 1 is set, publish the unit's scan work items {unit, chunk, entries
@@ -326,7 +346,7 @@ constexpr int kPrepThreads = 1024;
 constexpr int kPrepUnits = 32;
 
 __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begin, int unit_count, const uint16_t* k_new,
-                                                            const uint16_t* v_new, int append) {
+                                                            const uint16_t* v_new, int append, int n_limit) {
   __shared__ int s_nch[kPrepUnits], s_nblk[kPrepUnits];
   __shared__ u64 s_base;
   const int tid = threadIdx.x, sub = tid & 31, slot = tid >> 5;
@@ -335,7 +355,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
   const int u = unit_begin + w;
   int n = 0;
   if (active) {
-    n = d.n[u];
+    n = min(d.n[u], n_limit);            // n_limit < n: only the unit's first n_limit entries take part (prompt replay)
     if (append & 1) {
       const int t = d.sc[SC_T];
       if (n >= d.cap) {
@@ -1393,8 +1413,10 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   }
 }
 
+// n_limit / t_fixed: the replay of a prompt's last queries runs the step over the unit's first n_limit
+// entries at time t_fixed (otherwise INT_MAX and -1: all entries, the context's time).
 __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin, void* out, uint32_t call_flags,
-                                                          int advance) {
+                                                          int advance, int n_limit, int t_fixed) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
@@ -1404,8 +1426,8 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   __shared__ float s_tab[kTabLds];
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
-  const int n = d.n[u];
-  const int t = d.sc[SC_T];
+  const int n = min(d.n[u], n_limit);
+  const int t = t_fixed >= 0 ? t_fixed : d.sc[SC_T];
   const int B = d.budget[u];
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
   if (tid < s_tab_n) s_tab[tid] = d.tab[tid];

@@ -155,6 +155,61 @@ def test_path_selection_api():
     g.close()
 
 
+@pytest.mark.parametrize("hq,hkv,P,W,lam", [(8, 2, 45, 9, 0.5), (10, 2, 70, 32, 0.7), (2, 2, 33, 1, 0.5), (14, 2, 300, 17, 0.97),
+                                             (16, 2, 64, 64, 0.0), (8, 2, 610, 40, 1.0)])
+def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam):
+    """Scores of a loaded prompt from its last W queries (all of it for W = P, one query for W = 1; prompts
+    shorter and longer than a 256-entry chunk, not multiples of the 32-entry block): CRF bits and tau of
+    every entry equal the oracle's; the time and the Alg. 2 window are untouched (the decode steps and
+    the re-allocation that follow match the oracle as after any load)."""
+    cfg = _small("tiny", n_layers=2, n_q_heads=hq, n_kv_heads=hkv, prompt=P, decode_steps=max(W, 10), lam=lam,
+                 budget=P + 5, budget_min=8, budget_max=P + 30, seed=300 + W)
+    st, o, g = _pair(cfg, cap=(P + 64) // 32 * 32)
+    total0 = o.budgets().sum(axis=(0, 2))
+    resync = 0
+    for l in range(cfg.n_layers):
+        q_obs = st.q[:W, l]
+        decs = o.seed_prompt(l, q_obs)
+        g.seed_prompt(l, q_obs)
+        for key, dl in decs.items():
+            u, e = o.units[key], g.export_unit(*key)
+            assert e["n"] == P and np.array_equal(e["pos"], u.pos)
+            if np.array_equal(e["crf"].view(np.uint32), u.crf.view(np.uint32)) and np.array_equal(e["tau"], u.tau):
+                continue
+            assert min(min(d.sum_margin, d.edge_gap) for d in dl) < parity.MARGIN_TOL, (key, e["crf"][:8], u.crf[:8])
+            parity.sync_unit_to_gpu(g, o, key)
+            resync += 1
+    assert resync <= 1
+    assert g.time() == P and g.status() == 0
+    stats = parity.lockstep(g, o, st, 10, check_kv_every=5)
+    assert stats.resynced <= 1, stats.notes
+    if resync == 0 and stats.resynced == 0:
+        nb = o.rebudget()
+        g.rebudget()
+        assert np.array_equal(g.budgets(), nb) and np.array_equal(nb.sum(axis=(0, 2)), total0)
+    g.close()
+
+
+def test_seed_prompt_argument_and_state_errors():
+    _, ckv, _ = _mods()
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, seed=5)
+    st, o, g = _pair(cfg, cap=96)
+    P = cfg.prompt
+    with pytest.raises(ckv.CkvError) as e:
+        g.seed_prompt(0, st.q[:P + 1, 0].repeat(2, axis=0)[:P + 1])       # W > P
+    assert e.value.code == ckv.EINVAL
+    with pytest.raises(ckv.CkvError) as e:
+        g.seed_prompt(7, st.q[:4, 0])
+    assert e.value.code == ckv.EINVAL
+    g.seed_prompt(0, st.q[:4, 0])                                          # twice is allowed: same result
+    g.seed_prompt(0, st.q[:4, 0])
+    g.decode_step(st.q[0], st.k_new[0], st.v_new[0])
+    with pytest.raises(ckv.CkvError) as e:
+        g.seed_prompt(0, st.q[:4, 0])                                      # the layer has been stepped
+    assert e.value.code == ckv.ESTATE
+    g.close()
+
+
 def test_per_layer_calls():
     """The shape a real model imposes: one call per layer, t advancing after the last layer."""
     cfg = _small("llama8b", n_layers=3, n_q_heads=8, n_kv_heads=2, seed=11)
