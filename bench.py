@@ -79,6 +79,52 @@ def build_fullkv(cfg, device, tokens, total_steps):
     return g, budgets, ring
 
 
+def seed_prompt_bench(cfg, device, P, W):
+    """Prompt-side seeding on the workload's geometry: every layer holds a P-token prompt; ckv_seed_prompt
+    replays its last W queries (W scans over a growing prefix plus W score updates per layer).  Timed with
+    events over all layers after one untimed layer; bytes = K and V of the visible prefixes."""
+    import numpy as np
+    import torch
+    from paper_2601_16986_amd import ckv, workloads as wl
+
+    budgets = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), P, dtype=np.int32)
+    cap = (P + 64) // 32 * 32
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
+                      lam=cfg.lam, top_p=cfg.top_p, t0=P, budget_min=1, budget_max=cap - 1, device=device)
+    m = wl.torch_mean_query(cfg, device)
+    gen = wl.torch_generator(cfg, 9, device)
+    r_now = math.sqrt(wl.DRIFT_VAR) * torch.randn(m.shape, generator=gen, device=device)
+    for layer in range(cfg.n_layers):
+        k, v, *_ = wl.torch_steady_layer(cfg, layer, budgets[layer], P, m[layer], r_now[layer], device)
+        g.load_prompt(layer, k, v)
+        torch.cuda.synchronize()
+        del k, v
+    q_obs = (torch.randn((W, cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=gen, device=device)
+             + m.repeat_interleave(cfg.group, dim=2)[None]).to(torch.bfloat16)
+    g.seed_prompt(0, q_obs[:, 0].contiguous())
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    qs = [q_obs[:, l].contiguous() for l in range(cfg.n_layers)]
+    e0.record()
+    for l in range(cfg.n_layers):
+        g.seed_prompt(l, qs[l])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    upl = cfg.batch * cfg.n_kv_heads
+    entries = sum(P - W + j + 1 for j in range(W)) * upl             # per layer
+    bytes_layer = entries * 512
+    assert g.status() == 0
+    g.close()
+    return {"metric": "prompt seeding (ckv_seed_prompt), layers/s", "value": cfg.n_layers / (ms * 1e-3), "unit": "layers/s",
+            "n_gpus": 1, "ms_per_layer": ms / cfg.n_layers, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"{cfg.name} geometry: {cfg.n_layers} layers, batch {cfg.batch}, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, "
+                                   f"prompt of {P} tokens, window of {W} queries", "units_per_layer": upl,
+                       "entries_scanned_per_layer": entries},
+            "kv_gbps": bytes_layer / (ms / cfg.n_layers * 1e-3) / 1e9,
+            "hbm_frac": bytes_layer / (ms / cfg.n_layers * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
 def algorithmic_bytes(cfg, budgets):
     """Per decode step.  Scan kernel: K and V rows of every cached entry once
     (512 B) plus the query group; whole step: 524 B per entry (K, V, CRF and
@@ -158,6 +204,8 @@ def main():
                     help="kernels of the all-layers step: 0 default, 1 separate scan/finish, 3 / 4 fused with 4 / 2 wavefronts per unit")
     ap.add_argument("--fullkv", type=int, default=0, metavar="TOKENS",
                     help="FullKV baseline instead: every unit holds TOKENS positions, attention-only steps, no eviction")
+    ap.add_argument("--seed-prompt", default="", metavar="P,W",
+                    help="instead: time ckv_seed_prompt (scores of a P-token prompt from its last W queries) over all layers")
     ap.add_argument("--probe-only", action="store_true",
                     help="only run the plain streaming-read and copy kernels (4 GiB each): counter calibration")
     args = ap.parse_args()
@@ -178,6 +226,9 @@ def main():
     copy_gbps = ckv.bandwidth_probe(4 << 30, copy=True)
     if args.probe_only:
         print(json.dumps({"stream_read_gbps": read_gbps, "copy_gbps": copy_gbps, "bytes": 4 << 30}))
+        return
+    if args.seed_prompt:
+        print(json.dumps(seed_prompt_bench(cfg, device, *[int(x) for x in args.seed_prompt.split(",")])))
         return
     steps = max(RING, args.steps // RING * RING)
     warm = max(RING, (args.warmup + RING - 1) // RING * RING)
