@@ -210,6 +210,21 @@ def test_seed_prompt_argument_and_state_errors():
     g.close()
 
 
+def test_lambda_top_p_sweep_script_runs(capsys, monkeypatch):
+    """The hyper-parameter sweep (a user-facing script on top of the binding) at a toy size: recalls are
+    fractions, and the recommended setting keeps more of the heavy positions than a sliding window."""
+    import json
+    import sys
+    from paper_2601_16986_amd import sweep
+    monkeypatch.setattr(sys, "argv", ["sweep", "--tokens", "224", "--prompt", "32", "--budget", "40"])
+    sweep.main()
+    res = json.loads(capsys.readouterr().out.strip().splitlines()[-1])["results"]
+    assert len(res) == 25 and all(0.0 <= r["heavy_recall"] <= 1.0 and 0.0 <= r["crystal_recall"] <= 1.0 for r in res)
+    rec = next(r for r in res if r["name"] == "recent")
+    best = next(r for r in res if r["name"] is None and r["lambda"] == 0.5 and r["top_p"] == 0.9)
+    assert best["heavy_recall"] >= rec["heavy_recall"] and best["crystal_recall"] >= rec["crystal_recall"]
+
+
 def test_per_layer_calls():
     """The shape a real model imposes: one call per layer, t advancing after the last layer."""
     cfg = _small("llama8b", n_layers=3, n_q_heads=8, n_kv_heads=2, seed=11)
