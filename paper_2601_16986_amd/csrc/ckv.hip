@@ -399,7 +399,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   hipStream_t s = (hipStream_t)stream;
 
   const ckv_ctx::Fused* fv = layer == -1 ? fused_variant(c) : nullptr;
-  if (fv && c->path_mode == 0 && count < 4 * fv->grid) fv = nullptr;
+  if (fv && c->path_mode == 0 && count < fv->grid) fv = nullptr;      // fewer units than workgroups: split the units instead
   const bool fused = fv != nullptr;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX);
@@ -700,7 +700,7 @@ int ckv_set_path(ckv_ctx* c, int32_t mode) {
 int ckv_path_info(ckv_ctx* c, int32_t* fused_waves, int32_t* lds_main_bytes) {
   if (!c) return CKV_EINVAL;
   const ckv_ctx::Fused* f = fused_variant(c);
-  if (f && c->path_mode == 0 && c->units < 4 * f->grid) f = nullptr;
+  if (f && c->path_mode == 0 && c->units < f->grid) f = nullptr;
   if (fused_waves) *fused_waves = f ? f->waves : 0;
   if (lds_main_bytes) *lds_main_bytes = f ? f->lds_main : 0;
   return CKV_OK;

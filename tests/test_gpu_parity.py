@@ -219,7 +219,7 @@ def test_lambda_top_p_sweep_script_runs(capsys, monkeypatch):
     monkeypatch.setattr(sys, "argv", ["sweep", "--tokens", "224", "--prompt", "32", "--budget", "40"])
     sweep.main()
     res = json.loads(capsys.readouterr().out.strip().splitlines()[-1])["results"]
-    assert len(res) == 25 and all(0.0 <= r["heavy_recall"] <= 1.0 and 0.0 <= r["crystal_recall"] <= 1.0 for r in res)
+    assert len(res) == 26 and all(0.0 <= r["heavy_recall"] <= 1.0 and 0.0 <= r["crystal_recall"] <= 1.0 for r in res)
     rec = next(r for r in res if r["name"] == "recent")
     best = next(r for r in res if r["name"] is None and r["lambda"] == 0.5 and r["top_p"] == 0.9)
     assert best["heavy_recall"] >= rec["heavy_recall"] and best["crystal_recall"] >= rec["crystal_recall"]
