@@ -232,9 +232,12 @@ int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
  * (default), 1 = separate scan and finish kernels (always used for single-layer
  * calls), 2 = the fused per-unit kernel, which keeps the logits in LDS, in the
  * widest variant that fits; 3 / 4 = the fused kernel with 4 / 2 wavefronts per
- * unit (2 / 4 workgroups per compute unit).  A variant needs 4 * cap bytes of
- * LDS in its workgroup's share (CKV_EINVAL otherwise).  Results do not depend
- * on the choice beyond floating-point summation order.
+ * unit (2 / 4 workgroups per compute unit); 5 = the fused kernel with four
+ * streaming wavefronts and a fifth that does the bookkeeping of the previous
+ * unit meanwhile (two logits tiles per workgroup).  A variant needs 4 * cap
+ * bytes of LDS in its workgroup's share, mode 5 in each of its two tiles
+ * (CKV_EINVAL otherwise).  Results do not depend on the choice beyond
+ * floating-point summation order.
  * ckv_path_info reports what all-layer steps use under the current mode:
  * *fused_waves = wavefronts per unit of the fused variant (0: separate
  * kernels), *lds_main_bytes = bytes of its LDS tile for logits and per-entry

@@ -29,14 +29,16 @@ struct ckv_ctx {
   int n_cu = 256;
   size_t finish_lds = 0;
   // fused path (unit_kernel)
-  int path_mode = 0;            // 0 auto, 1 separate kernels, 2 fused kernel, 3 / 4 fused with 4 / 2 wavefronts per unit
+  int path_mode = 0;            // 0 auto, 1 separate kernels, 2 fused kernel, 3 / 4 fused with 4 / 2 wavefronts per unit,
+                                // 5 fused with four book-keeping wavefronts beside four streaming ones
   struct Fused {                // one variant of the fused kernel
     bool ok = false;
     int waves = 0;              // wavefronts per workgroup (= per unit)
     int grid = 0;
     int lds_main = 0;           // bytes of the logits / values tile
     size_t lds = 0;             // dynamic LDS per workgroup
-  } fused[2];                   // [0]: 4 wavefronts, 2 workgroups per CU; [1]: 2 wavefronts, 4 workgroups per CU
+  } fused[3];                   // [0]: 4 wavefronts, 2 workgroups per CU; [1]: 2 wavefronts, 4 workgroups per CU;
+                                // [2]: unit_kernel_split, 4 + 4 wavefronts, 1 workgroup per CU, lds_main = bytes of ONE of its two tiles
   std::vector<uint8_t> prompt_loaded;
   std::vector<int32_t> prompt_len;   // per layer: length of a prompt loaded whole and untouched since, else -1
   std::string err;
@@ -154,6 +156,7 @@ int check_budgets(ckv_ctx* c, const ckv_layout* l, const ckv_lrfu_params* p, con
 // The variant of the fused kernel the current path mode selects (nullptr: none fits or separate kernels).
 const ckv_ctx::Fused* fused_variant(const ckv_ctx* c) {
   if (c->path_mode == 1) return nullptr;
+  if (c->path_mode == 5) return c->fused[2].ok ? &c->fused[2] : nullptr;
   const ckv_ctx::Fused* f = c->path_mode == 3 ? &c->fused[0] : c->path_mode == 4 ? &c->fused[1]
                             : c->fused[0].ok ? &c->fused[0] : &c->fused[1];
   return f->ok ? f : nullptr;
@@ -278,6 +281,21 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     const void* fn = v == 0 ? reinterpret_cast<const void*>(unit_kernel<4>) : reinterpret_cast<const void*>(unit_kernel<2>);
     if (f.ok && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)f.lds) != hipSuccess) f.ok = false;
   }
+  {                                                               // unit_kernel_split: two tiles per workgroup
+    ckv_ctx::Fused& f = c->fused[2];
+    f.waves = 4;
+    const int evm_bytes = ((layout->cap + 31) / 32) * 4;
+    const int share = 160 * 1024;                                 // one workgroup of eight wavefronts per CU
+    const int per_wg = max_lds < share ? max_lds : share;
+    const int tile = ((per_wg - 11 * 1024 - evm_bytes) / 2) & ~127;
+    f.grid = c->n_cu;
+    f.ok = tile >= 4 * layout->cap;
+    f.lds_main = tile;
+    f.lds = 2 * (size_t)tile + evm_bytes;
+    if (f.ok && hipFuncSetAttribute(reinterpret_cast<const void*>(unit_kernel_split), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)f.lds) != hipSuccess)
+      f.ok = false;
+  }
 
   Dev& d = c->dev;
   d.L = layout->n_layers;
@@ -400,6 +418,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
 
   const ckv_ctx::Fused* fv = layer == -1 ? fused_variant(c) : nullptr;
   if (fv && c->path_mode == 0 && count < fv->grid) fv = nullptr;      // fewer units than workgroups: split the units instead
+  if (fv == &c->fused[2] && (flags & CKV_ATTENTION_ONLY)) fv = &c->fused[0];   // no bookkeeping to move aside
   const bool fused = fv != nullptr;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX);
@@ -420,7 +439,10 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     CKV_HIP(c, hipEventRecord(e0, s));
   }
   if (fused) {
-    if (fv->waves == 4)
+    if (fv == &c->fused[2])
+      hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, c->dev, (const uint16_t*)q, out, flags,
+                         advance, fv->lds_main);
+    else if (fv->waves == 4)
       hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, c->dev, (const uint16_t*)q, out,
                          flags, advance, fv->lds_main);
     else
@@ -562,6 +584,7 @@ int ckv_status(ckv_ctx* c) {
   CKV_HIP(c, hipMemcpy(&st, c->dev.sc + SC_STATUS, 4, hipMemcpyDeviceToHost));
   if (st) {
     CKV_HIP(c, hipMemcpy(c->dev.sc + SC_STATUS, &zero, 4, hipMemcpyHostToDevice));
+    if (st & 2) return fail(c, CKV_EHIP, "a wait between wavefronts of the fused kernel did not end: the last steps' results are invalid");
     return fail(c, CKV_ECAPACITY, "an append found its unit full");
   }
   return CKV_OK;
@@ -689,9 +712,9 @@ int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, vo
 }
 
 int ckv_set_path(ckv_ctx* c, int32_t mode) {
-  if (!c || mode < 0 || mode > 4) return CKV_EINVAL;
+  if (!c || mode < 0 || mode > 5) return CKV_EINVAL;
   const bool any = c->fused[0].ok || c->fused[1].ok;
-  if ((mode == 2 && !any) || (mode == 3 && !c->fused[0].ok) || (mode == 4 && !c->fused[1].ok))
+  if ((mode == 2 && !any) || (mode == 3 && !c->fused[0].ok) || (mode == 4 && !c->fused[1].ok) || (mode == 5 && !c->fused[2].ok))
     return fail(c, CKV_EINVAL, "cap too large for the fused kernel's LDS");
   c->path_mode = mode;
   return CKV_OK;

@@ -142,19 +142,60 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
   return min_u64(min_u64(readlane_u64(v, 0), readlane_u64(v, 16)), min_u64(readlane_u64(v, 32), readlane_u64(v, 48)));
 }
 
-// Block-wide reductions over NT threads with a fixed combination order
-// (deterministic).  `rb` is a [2][NT/64] LDS array used alternately, so one
-// barrier per call suffices.
+// Barrier among the NT threads that work on one unit.  NT = 64: a single wavefront, which may be one of
+// several in its workgroup and must not touch the workgroup barrier: its LDS and memory operations
+// already execute in program order, only the compiler has to keep them so.
+//
+// SB = 1: the NT threads are some of the wavefronts of a workgroup whose other wavefronts do something
+// else meanwhile (unit_kernel_split's book-keepers), so the workgroup barrier is not theirs to use.  They
+// meet at a counter in LDS instead: every wavefront adds one on arrival and leaves when the count reaches
+// the next multiple of NT / 64.  All of them are resident and none waits for anything else, so the wait
+// ends; it is bounded all the same (kSoftLimit polls, then `soft_fail` is raised and the kernel reports
+// it through the context's status word instead of hanging).
 struct alignas(16) RedBuf {
   u64 v[2][4];
   float t[2][4][4];
+  int soft;         // arrivals at the counter barrier since the kernel began
+  int soft_fail;    // a counter barrier gave up waiting
 };
+constexpr int kSoftLimit = 1 << 20;
 
-template <int NT = kThreads>
+template <int NT, int SB = 0>
+__device__ __forceinline__ void block_sync(RedBuf& rb) {
+  if constexpr (NT == 64) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  } else if constexpr (SB == 1) {
+    constexpr int kWaves = NT / 64;
+    static_assert((kWaves & (kWaves - 1)) == 0, "power of two");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    int old = 0;
+    if ((threadIdx.x & 63) == 0) old = __hip_atomic_fetch_add(&rb.soft, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const int target = (__builtin_amdgcn_readfirstlane(old) & ~(kWaves - 1)) + kWaves;
+    int polls = 0;
+    while (__hip_atomic_load(&rb.soft, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target) {
+      __builtin_amdgcn_s_sleep(1);
+      // give up after kSoftLimit polls, and at once if a barrier has given up before (then nothing is in step any more)
+      if (++polls > kSoftLimit || __hip_atomic_load(&rb.soft_fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0) {
+        __hip_atomic_store(&rb.soft_fail, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        break;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  } else {
+    __syncthreads();
+  }
+}
+
+// Block-wide reductions over NT threads with a fixed combination order
+// (deterministic).  `rb` is a [2][NT/64] LDS array used alternately, so one
+// barrier per call suffices.  NT = 64: the wavefront's own reduction, nothing else.
+template <int NT = kThreads, int SB = 0>
 __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_u64(v);
+  if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
-  __syncthreads();
+  block_sync<NT, SB>(rb);
   u64 r = rb.v[phase][0];
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r += rb.v[phase][w];
@@ -162,11 +203,12 @@ __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int 
   return r;
 }
 
-template <int NT = kThreads>
+template <int NT = kThreads, int SB = 0>
 __device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_i32(v);
+  if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)(uint32_t)v;
-  __syncthreads();
+  block_sync<NT, SB>(rb);
   int r = (int)(uint32_t)rb.v[phase][0];
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r += (int)(uint32_t)rb.v[phase][w];
@@ -174,11 +216,12 @@ __device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int 
   return r;
 }
 
-template <int NT = kThreads>
+template <int NT = kThreads, int SB = 0>
 __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_f32(v);
+  if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)__float_as_uint(v);
-  __syncthreads();
+  block_sync<NT, SB>(rb);
   float r = __uint_as_float((uint32_t)rb.v[phase][0]);
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r += __uint_as_float((uint32_t)rb.v[phase][w]);
@@ -187,13 +230,14 @@ __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, 
 }
 
 // Three sums at once (one barrier).
-template <int NT = kThreads>
+template <int NT = kThreads, int SB = 0>
 __device__ __forceinline__ void block_sum3_f32(float& x, float& y, float& z, RedBuf& rb, int& phase, int tid) {
   x = wave_sum_f32(x);
   y = wave_sum_f32(y);
   z = wave_sum_f32(z);
+  if constexpr (NT == 64) return;
   if ((tid & 63) == 0) *reinterpret_cast<f32x4*>(rb.t[phase][tid >> 6]) = f32x4{x, y, z, 0.f};
-  __syncthreads();
+  block_sync<NT, SB>(rb);
   f32x4 r = *reinterpret_cast<const f32x4*>(rb.t[phase][0]);
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) {
@@ -208,11 +252,12 @@ __device__ __forceinline__ void block_sum3_f32(float& x, float& y, float& z, Red
   phase ^= 1;
 }
 
-template <int NT = kThreads>
+template <int NT = kThreads, int SB = 0>
 __device__ __forceinline__ u64 block_min_u64(u64 v, RedBuf& rb, int& phase, int tid) {
   v = wave_min_u64(v);
+  if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
-  __syncthreads();
+  block_sync<NT, SB>(rb);
   u64 r = rb.v[phase][0];
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r = rb.v[phase][w] < r ? rb.v[phase][w] : r;
@@ -749,7 +794,7 @@ struct ValLinear {
 // Alg. 1 Step 4 for one unit with n > B.  val(i) = CRF_temp of slot i (LDS),
 // evm = LDS bit mask of n bits, lst = LDS scratch of lst_cap >= n ints that may
 // overlap the storage behind `val` (the scores are dead by the time it is used).
-template <class Val, int NT = kThreads>
+template <class Val, int NT = kThreads, int SB = 0>
 __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
                             int& phase, int* sh, int tid) {
   const size_t base = (size_t)u * d.cap;
@@ -777,9 +822,9 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
         }
       }
     }
-    const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
+    const u64 gbest = block_min_u64<NT, SB>(best, rb, phase, tid);
     if (best == gbest && best_i >= 0) sh[0] = best_i;     // keys are unique: one writer
-    __syncthreads();
+    block_sync<NT, SB>(rb);
     const int e = sh[0];
     if (wave == 0) {
       if (e != n - 1) {
@@ -795,15 +840,15 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
       const u64 trial = X | (1ull << bit);
       int cnt = 0;
       for (int i = tid; i < n; i += NT) cnt += evict_key(val(i), d.pos[base + i]) < trial ? 1 : 0;
-      cnt = block_sum_int<NT>(cnt, rb, phase, tid);
+      cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
       if (cnt < k) X = trial;
     }
     const int words = (n + 31) >> 5;
     for (int w = tid; w < words; w += NT) evm[w] = 0u;
-    __syncthreads();
+    block_sync<NT, SB>(rb);
     for (int i = tid; i < n; i += NT)
       if (evict_key(val(i), d.pos[base + i]) <= X) atomicOr(&evm[i >> 5], 1u << (i & 31));
-    __syncthreads();
+    block_sync<NT, SB>(rb);
     // holes = evicted slots below B, movers = surviving slots at or above B (equal counts)
     const int wpt = (words + NT - 1) / NT;
     const int w0 = min(words, tid * wpt), w1 = min(words, w0 + wpt);
@@ -824,7 +869,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
       if (lane >= o) incl += y;
     }
     if (lane == 63) sh[4 + wave] = (int)incl;
-    __syncthreads();
+    block_sync<NT, SB>(rb);
     uint32_t prefix = 0, total = 0;
 #pragma unroll
     for (int w = 0; w < NT / 64; ++w) {
@@ -849,7 +894,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
         mm &= mm - 1;
       }
     }
-    __syncthreads();
+    block_sync<NT, SB>(rb);
     // evicted entries that already sit at or above B just get their flag
     for (int i = B + tid; i < n; i += NT)
       if ((evm[i >> 5] >> (i & 31)) & 1u) d.flags[base + i] = FLAG_SLIP;
@@ -999,7 +1044,7 @@ __device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const f
 // score update, flags.  Leaves CRF_temp in val(i) and returns the unit's
 // aggregated CRF (2^-20 fixed point), summed over the block.  s_tab: the first
 // s_tab_n entries of the decay table in LDS.
-template <class Val, int NT = kThreads>
+template <class Val, int NT = kThreads, int SB = 0>
 __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
                            int& phase, int tid) {
   const size_t base = (size_t)u * d.cap;
@@ -1015,7 +1060,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
         const float a = val(i);
         part += (__float_as_uint(a) >= cand) ? a : 0.f;
       }
-      const float tot = block_sum_f32<NT>(part, rb, phase, tid);
+      const float tot = block_sum_f32<NT, SB>(part, rb, phase, tid);
       if (tot > d.top_p) theta = cand;
     }
     if (theta != 0) {
@@ -1028,8 +1073,8 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
         above += (b > theta) ? a : 0.f;
         ties += (b == theta) ? 1 : 0;
       }
-      above = block_sum_f32<NT>(above, rb, phase, tid);
-      ties = block_sum_int<NT>(ties, rb, phase, tid);
+      above = block_sum_f32<NT, SB>(above, rb, phase, tid);
+      ties = block_sum_int<NT, SB>(ties, rb, phase, tid);
       if (ties > 1) {
         const float th = __uint_as_float(theta);
         float c = above;
@@ -1046,7 +1091,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
             int cnt = 0;
             for (int i = tid; i < n; i += NT)
               cnt += (__float_as_uint(val(i)) == theta && d.pos[base + i] < trial) ? 1 : 0;
-            cnt = block_sum_int<NT>(cnt, rb, phase, tid);
+            cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
           }
           pos_cut = X;
@@ -1104,7 +1149,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
       }
     }
   }
-  return block_sum_u64<NT>(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
+  return block_sum_u64<NT, SB>(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
 }
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -1172,7 +1217,7 @@ struct NoHook {
 
 // `after_step1` runs once between Step 1 and the score update (the fused kernel
 // picks up its queue claim there).
-template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook>
+template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook, int SB = 0>
 __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
                                           i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
                                           int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
@@ -1206,7 +1251,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
         p2 += (b >= c2) ? a[k] : 0.f;
         p3 += (b >= c3) ? a[k] : 0.f;
       }
-      block_sum3_f32<NT>(p1, p2, p3, rb, phase, tid);
+      block_sum3_f32<NT, SB>(p1, p2, p3, rb, phase, tid);
       theta = p3 > d.top_p ? c3 : p2 > d.top_p ? c2 : p1 > d.top_p ? c1 : theta;
     };
     constexpr int kListBit = 17;        // the rounds for the bits above this one run over all entries
@@ -1230,7 +1275,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       ab = wave_sum_f32(ab);
       mine = wave_sum_i32(mine);
       if (lane == 0) *reinterpret_cast<f32x4*>(rb.t[phase][wave]) = f32x4{ab, __int_as_float(mine), 0.f, 0.f};
-      __syncthreads();
+      block_sync<NT, SB>(rb);
       float above_bucket = 0.f;
       int m = 0, off = 0;
 #pragma unroll
@@ -1252,7 +1297,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
           if (in) lst[r] = (int)b;
           off += __popcll(mask);
         }
-        __syncthreads();
+        block_sync<NT, SB>(rb);
         if (wave == 0) {
           const uint32_t bj = lane < m ? (uint32_t)lst[lane] : 0u;
           const float aj = __uint_as_float(bj);
@@ -1265,7 +1310,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
           }
           if (lane == 0) sh[7] = (int)theta;
         }
-        __syncthreads();
+        block_sync<NT, SB>(rb);
         theta = (uint32_t)sh[7];
       } else {
         for (; bit >= 1; bit -= 2) round(bit);
@@ -1280,8 +1325,8 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
         above += (b > theta) ? a[k] : 0.f;
         ties += (b == theta) ? 1 : 0;
       }
-      above = block_sum_f32<NT>(above, rb, phase, tid);
-      ties = block_sum_int<NT>(ties, rb, phase, tid);
+      above = block_sum_f32<NT, SB>(above, rb, phase, tid);
+      ties = block_sum_int<NT, SB>(ties, rb, phase, tid);
       if (ties > 1) {
         const float th = __uint_as_float(theta);
         float c = above;
@@ -1300,7 +1345,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
               const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
               if (__float_as_uint(a[k]) == theta && i < n && d.pos[base + i] < trial) ++cnt;
             }
-            cnt = block_sum_int<NT>(cnt, rb, phase, tid);
+            cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
           }
           pos_cut = X;
@@ -1318,6 +1363,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   for (int cc = 0; cc < C; ++cc) {
     const int c = cc % CH;                  // register slot of group cc
     if (cc >= CH && c == 0) {               // next chunk of groups: its state is requested only now
+      __builtin_amdgcn_sched_barrier(0);    // (and not earlier: hoisted, the chunks' registers would all be live at once)
 #pragma unroll
       for (int k = 0; k < CH; ++k) load_meta<NT>(d, base, n, t, cc + k, tid, crf[k], tau[k], ps[k]);
     }
@@ -1380,7 +1426,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       }
     }
   }
-  sfix = block_sum_u64<NT>(sfix, rb, phase, tid);
+  sfix = block_sum_u64<NT, SB>(sfix, rb, phase, tid);
   if (tid == 0) {
     d.window[u] = window0 + sfix;
     d.t_unit[u] = t;
@@ -1391,12 +1437,12 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     return;
   }
   if (evict_single) {
-    const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
+    const u64 gbest = block_min_u64<NT, SB>(best, rb, phase, tid);
     if (best == gbest && best_i >= 0) {     // keys are unique: one writer
       sh[0] = best_i;
       sh[4] = ~(int)(uint32_t)best;         // the victim's position
     }
-    __syncthreads();
+    block_sync<NT, SB>(rb);
     evict_one<NT>(d, base, n - 1, sh[0], sh, tid, last_row);
     if (tid == 0) {
       d.n[u] = B;
@@ -1408,8 +1454,8 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
       if (i < n) val(i) = a[k];
     }
-    __syncthreads();
-    evict_phase<Val, NT>(d, u, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
+    block_sync<NT, SB>(rb);
+    evict_phase<Val, NT, SB>(d, u, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
   }
 }
 

@@ -42,7 +42,7 @@ def _small(name, **kw):
     return wl.scaled(wl.CONFIGS[name], **base)
 
 
-PATHS = [1, 3, 4]     # separate kernels; fused kernel with 4 and with 2 wavefronts per unit
+PATHS = [1, 3, 4, 5]  # separate kernels; fused kernel with 4 and with 2 wavefronts per unit; fused with a book-keeping wavefront
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -73,7 +73,7 @@ def test_units_longer_than_a_chunk_and_ragged_tails(path):
     g.close()
 
 
-@pytest.mark.parametrize("path", [3, 4])
+@pytest.mark.parametrize("path", [3, 4, 5])
 def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     """A unit of ~3000 entries with 8 query heads per KV head needs 96 KB of logits: more than the fused
     kernel's LDS tile, so the logits of its last blocks take the global-memory route; a second, small
@@ -90,7 +90,7 @@ def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     g.close()
 
 
-@pytest.mark.parametrize("path,n_big", [(3, 4500), (3, 8300), (4, 2500), (4, 4400)])
+@pytest.mark.parametrize("path,n_big", [(3, 4500), (3, 8300), (4, 2500), (4, 4400), (5, 1900), (5, 8300)])
 def test_fused_kernel_large_units(path, n_big):
     """Units beyond 16 entries per thread: 17..32 per thread keep the weights in registers with the per-entry
     state loaded in chunks, more than 32 per thread go through the LDS-resident generic path.  (Path 3 has 256
@@ -101,7 +101,7 @@ def test_fused_kernel_large_units(path, n_big):
     cap = (n_big + 64 + 31) // 32 * 32
     st, o, g = _pair(cfg, cap=cap, budgets=budgets, path=path)
     waves, _ = g.path_info()
-    assert waves == (4 if path == 3 else 2)
+    assert waves == (2 if path == 4 else 4)
     stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=2)
     assert stats.resynced <= 1, stats.notes
     assert np.array_equal(g.lengths(), o.lengths())
@@ -145,10 +145,10 @@ def test_path_selection_api():
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, seed=2)
     st, o, g = _pair(cfg, cap=96)
     assert g.path_info()[0] == 0                       # 4 units: separate kernels by default
-    for mode, waves in ((1, 0), (2, 4), (3, 4), (4, 2)):
+    for mode, waves in ((1, 0), (2, 4), (3, 4), (4, 2), (5, 4)):
         g.set_path(mode)
         assert g.path_info()[0] == waves
-    for bad in (-1, 5):
+    for bad in (-1, 6):
         with pytest.raises(ckv.CkvError) as e:
             g.set_path(bad)
         assert e.value.code == ckv.EINVAL
