@@ -524,6 +524,13 @@ __device__ __forceinline__ void scan_qk(const KFrag& f, const bf16x8 (&qv)[4], f
 
 // Second half: online softmax update and probabilities (split into two bf16
 // terms) times V on the matrix cores.  The V fragment is dead afterwards.
+//
+// PACK: the caller has duplicated the query heads 0..7 into the MFMA's columns 8..15 (at most 8 heads are
+// real), so lane (j + 8, kg) holds the same logits and probabilities as lane (j, kg).  The product's
+// operand then carries the high terms in rows 0..7 and the low terms in rows 8..15: one MFMA per 16
+// dims instead of two, the result rows g (high) and g + 8 (low) of head g are added by the caller at the
+// end of the unit (acc of lane + 32).
+template <bool PACK = false>
 __device__ __forceinline__ void scan_pv(const float (&sv)[8], const VFrag& fv, f32x4 (&acc)[8], float& m_run, float& l_run,
                                         int lane) {
   float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
@@ -555,10 +562,19 @@ __device__ __forceinline__ void scan_pv(const float (&sv)[8], const VFrag& fv, f
     pl[i] = (__bf16)(p - (float)h);
   }
   l_run += ps;
+  if constexpr (PACK) {
+    const bool low = (lane & 8) != 0;
+    const u32x4 h4 = __builtin_bit_cast(u32x4, ph), l4 = __builtin_bit_cast(u32x4, pl);
+    const u32x4 a4 = {low ? l4[0] : h4[0], low ? l4[1] : h4[1], low ? l4[2] : h4[2], low ? l4[3] : h4[3]};
+    const bf16x8 pa = as_bf16x8(a4);
 #pragma unroll
-  for (int dt = 0; dt < 8; ++dt) {
-    acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ph, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
-    acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
+    for (int dt = 0; dt < 8; ++dt) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ph, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
+      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl, as_bf16x8(fv.v[dt]), acc[dt], 0, 0, 0);
+    }
   }
 }
 

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     return (size_t)uu * unit_elems + (size_t)min(wave, max(nb - 1, 0)) * kBlkElems + slane * 8;
   };
   auto load_q = [&](int uu) {
-    const int jh = slane & 15;
+    const int jh = slane & 7;       // columns 8..15 repeat the heads 0..7 (scan_pv<true>)
     const uint16_t* qrow = q + ((size_t)uu * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       float sv[8];
       qk(blk, sv);
       load_k(ka, kcur + (size_t)(blk + W) * kBlkElems);
-      scan_pv(sv, va, acc, m_run, l_run, slane);
+      scan_pv<true>(sv, va, acc, m_run, l_run, slane);
       load_v(va, vcur + (size_t)(blk + W) * kBlkElems);
     }
     // without a next unit the prefetch reads this unit's first block again and is ignored
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     if (my_cnt > 0) {
       float sv[8];
       qk(wave + W * (my_cnt - 1), sv);
-      scan_pv(sv, va, acc, m_run, l_run, slane);
+      scan_pv<true>(sv, va, acc, m_run, l_run, slane);
     }
     // The next unit's first block, its queries and the claim of the slot three units ahead are requested
     // once this unit's weights sit in registers (the block's 64 registers are free until then, which is
@@ -216,6 +216,13 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     int ftid = tid;
     asm volatile("" : "+v"(ftid));
 
+    // rows g + 8 of the accumulators hold the products of the probabilities' low terms (scan_pv<true>): they
+    // sit 32 lanes up and join the rows g of the high terms here, once per unit
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[dt][v] += __shfl_down(acc[dt][v], 32);
+    }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     asm volatile("" : "+v"(slane));
@@ -453,7 +460,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
     return (size_t)uu * unit_elems + (size_t)min(wave, max(nb - 1, 0)) * kBlkElems + slane * 8;
   };
   auto load_q = [&](int uu) {
-    const int jh = slane & 15;
+    const int jh = slane & 7;       // columns 8..15 repeat the heads 0..7 (scan_pv<true>)
     const uint16_t* qrow = q + ((size_t)uu * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
 #pragma unroll
     for (int s = 0; s < 4; ++s) qv[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * s));
@@ -513,13 +520,13 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
           float sv[8];
           qk(blk, sv);
           load_k(ka, kcur + (size_t)(blk + W) * kBlkElems);
-          scan_pv(sv, va, acc, m_run, l_run, slane);
+          scan_pv<true>(sv, va, acc, m_run, l_run, slane);
           load_v(va, vcur + (size_t)(blk + W) * kBlkElems);
         }
         if (my_cnt > 0) {
           float sv[8];
           qk(wave + W * (my_cnt - 1), sv);
-          scan_pv(sv, va, acc, m_run, l_run, slane);
+          scan_pv<true>(sv, va, acc, m_run, l_run, slane);
         }
         // the stream goes on with the next unit's first block (this unit's again if there is none)
         const bool have_next = u1 >= 0;
@@ -529,6 +536,12 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
         load_v(va, d.V + o_next);
         load_q(u_next);
         if (tid == 0) claimed = atomicAdd(&d.sc[SC_QUEUE], 1);
+        // the low terms' rows (g + 8, 32 lanes up) join the high terms' rows g (scan_pv<true>)
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[dt][v] += __shfl_down(acc[dt][v], 32);
+        }
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
         asm volatile("" : "+v"(slane));
