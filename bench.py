@@ -291,27 +291,33 @@ def main():
     traffic = None if fullkv else measured_traffic(kernel_name, cfg.name)
 
     # ---- secondary: the shape a real model imposes, one call per layer
-    per_layer = None
+    per_layer = per_layer_deferred = None
     if not args.no_per_layer and not args.no_graph and not fullkv:
         outl = out[0]
 
-        def layer_steps(k):
+        def layer_steps(k, defer):
             for i in range(k):
                 for l in range(cfg.n_layers):
-                    g.decode_step(rq[i % RING, l], rk[i % RING, l], rv[i % RING, l], layer=l, out=outl)
+                    g.decode_step(rq[i % RING, l], rk[i % RING, l], rv[i % RING, l], layer=l, out=outl, defer=defer)
 
-        layer_steps(1)
-        torch.cuda.synchronize()
-        gl = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gl):
-            layer_steps(RING)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        reps = max(1, steps // RING // 2)
-        for _ in range(reps):
-            gl.replay()
-        torch.cuda.synchronize()
-        per_layer = (time.perf_counter() - t1) * 1e3 / (reps * RING)
+        res_pl = []
+        for defer in (False, True):          # plain, then with the layers' bookkeeping on the context's own stream
+            layer_steps(1, defer)
+            g.join()
+            torch.cuda.synchronize()
+            gl = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gl):
+                layer_steps(RING, defer)
+                g.join()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            reps = max(1, steps // RING // 2)
+            for _ in range(reps):
+                gl.replay()
+            torch.cuda.synchronize()
+            res_pl.append((time.perf_counter() - t1) * 1e3 / (reps * RING))
+            del gl
+        per_layer, per_layer_deferred = res_pl
 
     lengths = g.lengths()
     if not fullkv:
@@ -342,6 +348,7 @@ def main():
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "per_layer_graph_ms_per_step": per_layer,
+        "per_layer_deferred_graph_ms_per_step": per_layer_deferred,   # same, CKV_DEFER_BOOKKEEPING on every call
         "stream_read_gbps": read_gbps,          # plain non-temporal streaming read measured on this machine
         "copy_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

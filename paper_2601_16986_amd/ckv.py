@@ -20,13 +20,14 @@ REWARD_TOPP_HIT, REWARD_ATTN_WEIGHTED = 0, 1
 FLAG_HIT, FLAG_SLIP = 1, 2
 FUSE_EVICT = 1
 ATTENTION_ONLY = 2
+DEFER_BOOKKEEPING = 4
 
 EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_seed_prompt", "ckv_load_cache", "ckv_decode_step",
     "ckv_evict",
     "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
-    "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
+    "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_join", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
 ]
 
 
@@ -86,6 +87,7 @@ def load():
     lib.ckv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     lib.ckv_set_path.argtypes = [vp, i32]
     lib.ckv_path_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+    lib.ckv_join.argtypes = [vp, vp]
     lib.ckv_bandwidth_probe.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.ckv_strerror.restype = C.c_char_p
     lib.ckv_strerror.argtypes = [C.c_int]
@@ -215,9 +217,10 @@ class CrystalKV:
         self._check(self.lib.ckv_load_cache(self.ctx, layer, k.data_ptr(), v.data_ptr(), P, lengths.data_ptr(),
                                             crf0.data_ptr(), tau0.data_ptr(), pos0.data_ptr(), self._stream()))
 
-    def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None, attention_only=False):
+    def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None, attention_only=False, defer=False):
         """q [L][Bz][Hq][d], k_new / v_new [L][Bz][Hkv][d] (no leading [L] for a single layer).
-        Returns the device tensor `out` of the same shape as q."""
+        Returns the device tensor `out` of the same shape as q.  defer (single layers only): the layer's
+        bookkeeping runs on the context's own stream, see `join`."""
         t = self.torch
         lead = (self.L,) if layer == -1 else ()
         q = self._dev_bf16(q, lead + (self.Bz, self.Hq, self.d))
@@ -227,9 +230,13 @@ class CrystalKV:
             out = t.empty(q.shape, dtype=t.float32 if self.out_dtype == F32 else t.bfloat16, device=self.device)
         self._check(self.lib.ckv_decode_step(self.ctx, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
                                              out.data_ptr(),
-                                             ATTENTION_ONLY if attention_only else (FUSE_EVICT if evict else 0),
-                                             self._stream()))
+                                             (ATTENTION_ONLY if attention_only else (FUSE_EVICT if evict else 0))
+                                             | (DEFER_BOOKKEEPING if defer else 0), self._stream()))
         return out
+
+    def join(self):
+        """Order the current stream after the bookkeeping that deferred steps left in flight."""
+        self._check(self.lib.ckv_join(self.ctx, self._stream()))
 
     def evict(self, layer=-1):
         self._check(self.lib.ckv_evict(self.ctx, layer, self._stream()))

@@ -41,6 +41,14 @@ struct ckv_ctx {
                                 // [2]: unit_kernel_split, 4 + 4 wavefronts, 1 workgroup per CU, lds_main = bytes of ONE of its two tiles
   std::vector<uint8_t> prompt_loaded;
   std::vector<int32_t> prompt_len;   // per layer: length of a prompt loaded whole and untouched since, else -1
+  // Deferred bookkeeping of single-layer steps (CKV_DEFER_BOOKKEEPING): the second part of finish_kernel runs on
+  // `side`, ordered by events against the caller's stream.  pending[l]: layer l's bookkeeping has been queued on
+  // `side` and nothing on the caller's side has waited for it yet.
+  hipStream_t side = nullptr;
+  hipEvent_t ev_out = nullptr;
+  std::vector<hipEvent_t> ev_book;
+  std::vector<uint8_t> pending;
+  bool any_pending = false;
   std::string err;
   // scan timing
   bool profile = false;
@@ -114,7 +122,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -140,6 +148,7 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.order = take(U * 4);
   c.rank = take(U * 4);
   c.sched = take(U * 16);
+  c.layer_ts = take((size_t)l->n_layers * 8);
   c.total = off;
   return c;
 }
@@ -160,6 +169,23 @@ const ckv_ctx::Fused* fused_variant(const ckv_ctx* c) {
   const ckv_ctx::Fused* f = c->path_mode == 3 ? &c->fused[0] : c->path_mode == 4 ? &c->fused[1]
                             : c->fused[0].ok ? &c->fused[0] : &c->fused[1];
   return f->ok ? f : nullptr;
+}
+
+// Order `s` after the deferred bookkeeping still in flight on the side stream (all layers, or one).
+int join_side(ckv_ctx* c, hipStream_t s, int layer = -1) {
+  if (!c->any_pending) return CKV_OK;
+  bool left = false;
+  for (int l = 0; l < c->lay.n_layers; ++l) {
+    if (!c->pending[l]) continue;
+    if (layer >= 0 && l != layer) {
+      left = true;
+      continue;
+    }
+    CKV_HIP(c, hipStreamWaitEvent(s, c->ev_book[l], 0));
+    c->pending[l] = 0;
+  }
+  c->any_pending = left;
+  return CKV_OK;
 }
 
 // (Re)build the fused kernel's schedule (units by descending budget) from the budgets in device memory.
@@ -337,11 +363,20 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.order = (int32_t*)(ws + cv.order);
   d.rank = (int32_t*)(ws + cv.rank);
   d.sched = (int4*)(ws + cv.sched);
+  d.layer_ts = (int32_t*)(ws + cv.layer_ts);
 
   auto bail = [&](int rc) {
-    delete c;
+    ckv_destroy(c);
     return rc;
   };
+  c->pending.assign(layout->n_layers, 0);
+  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) return bail(CKV_EHIP);
+  if (hipEventCreateWithFlags(&c->ev_out, hipEventDisableTiming) != hipSuccess) return bail(CKV_EHIP);
+  for (int l = 0; l < layout->n_layers; ++l) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return bail(CKV_EHIP);
+    c->ev_book.push_back(e);
+  }
   const size_t S = (size_t)c->units * layout->cap;
   int rc;
   if ((rc = fill32(c, d.K, 0u, S * kDim / 2, s))) return bail(rc);
@@ -365,6 +400,12 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
 
 void ckv_destroy(ckv_ctx* c) {
   if (!c) return;
+  if (c->side) {
+    (void)hipStreamSynchronize(c->side);
+    (void)hipStreamDestroy(c->side);
+  }
+  if (c->ev_out) (void)hipEventDestroy(c->ev_out);
+  for (hipEvent_t e : c->ev_book) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   delete c;
 }
@@ -379,6 +420,7 @@ int ckv_load_cache(ckv_ctx* c, int32_t layer, const void* k, const void* v, int3
   if (c->prompt_loaded[layer]) return fail(c, CKV_ESTATE, "layer already holds entries");
   c->prompt_loaded[layer] = 1;
   c->prompt_len[layer] = (!lengths && !pos0) ? P : -1;
+  if (int rc = join_side(c, (hipStream_t)stream)) return rc;
   dim3 grid((unsigned)((P + kBlk - 1) / kBlk), (unsigned)c->units_per_layer);
   hipLaunchKernelGGL(load_cache_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, c->dev,
                      layer * c->units_per_layer, (const uint16_t*)k, (const uint16_t*)v, (int)P, lengths, crf0, tau0,
@@ -398,7 +440,9 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
                     uint32_t flags, void* stream) {
   if (!c) return CKV_EINVAL;
   if (!q || !k_new || !v_new || !out) return fail(c, CKV_EINVAL, "q, k_new, v_new or out is NULL");
-  if (flags & ~(CKV_FUSE_EVICT | CKV_ATTENTION_ONLY)) return fail(c, CKV_EINVAL, "unknown flag bits");
+  if (flags & ~(CKV_FUSE_EVICT | CKV_ATTENTION_ONLY | CKV_DEFER_BOOKKEEPING)) return fail(c, CKV_EINVAL, "unknown flag bits");
+  if ((flags & CKV_DEFER_BOOKKEEPING) && (layer == -1 || (flags & CKV_ATTENTION_ONLY)))
+    return fail(c, CKV_EINVAL, "CKV_DEFER_BOOKKEEPING is for single-layer steps with bookkeeping");
   if ((flags & CKV_ATTENTION_ONLY) && (flags & CKV_FUSE_EVICT))
     return fail(c, CKV_EINVAL, "CKV_ATTENTION_ONLY excludes CKV_FUSE_EVICT");
   int begin, count;
@@ -420,6 +464,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (fv && c->path_mode == 0 && count < fv->grid) fv = nullptr;      // fewer units than workgroups: split the units instead
   if (fv == &c->fused[2] && (flags & CKV_ATTENTION_ONLY)) fv = &c->fused[0];   // no bookkeeping to move aside
   const bool fused = fv != nullptr;
+  if (int rc = join_side(c, s, layer)) return rc;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX);
   CKV_HIP(c, hipGetLastError());
@@ -459,8 +504,24 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   CKV_HIP(c, hipGetLastError());
   if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
 
+  const uint32_t kflags = flags & (CKV_FUSE_EVICT | CKV_ATTENTION_ONLY);
+  if (flags & CKV_DEFER_BOOKKEEPING) {
+    // what the caller waits for on its own stream; the scores and the eviction follow on the side stream
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out, kflags,
+                       advance, INT_MAX, -1, 1, (int)layer);
+    CKV_HIP(c, hipGetLastError());
+    CKV_HIP(c, hipEventRecord(c->ev_out, s));
+    CKV_HIP(c, hipStreamWaitEvent(c->side, c->ev_out, 0));
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, c->side, c->dev, begin,
+                       (void*)nullptr, kflags, 0, INT_MAX, -1, 2, (int)layer);
+    CKV_HIP(c, hipGetLastError());
+    CKV_HIP(c, hipEventRecord(c->ev_book[layer], c->side));
+    c->pending[layer] = 1;
+    c->any_pending = true;
+    return CKV_OK;
+  }
   hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out,
-                     flags, advance, INT_MAX, -1);
+                     kflags, advance, INT_MAX, -1, 0, 0);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
 }
@@ -474,6 +535,7 @@ int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, voi
   if (P < 0) return fail(c, CKV_ESTATE, "needs a prompt loaded whole (ckv_load_prompt) and not touched since");
   if (W < 1 || W > P) return fail(c, CKV_EINVAL, "need 1 <= W <= P");
   hipStream_t s = (hipStream_t)stream;
+  if (int rc = join_side(c, s)) return rc;
   const int begin = layer * c->units_per_layer, count = c->units_per_layer;
   const dim3 sgrid((unsigned)std::min((P + kThreads - 1) / kThreads, 64), (unsigned)count);
   hipLaunchKernelGGL(seed_state_kernel, sgrid, dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 0, 0);
@@ -491,7 +553,7 @@ int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, voi
                        (const uint16_t*)q_obs + (size_t)j * q_stride);
     CKV_HIP(c, hipGetLastError());
     hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, (void*)nullptr,
-                       0u, 0, t_j + 1, t_j);
+                       0u, 0, t_j + 1, t_j, 0, 0);
     CKV_HIP(c, hipGetLastError());
   }
   hipLaunchKernelGGL(seed_state_kernel, dim3(1, (unsigned)count), dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 1, c->par.t0 - 1);
@@ -504,6 +566,7 @@ int ckv_evict(ckv_ctx* c, int32_t layer, void* stream) {
   int begin, count;
   if (int rc = layer_range(c, layer, &begin, &count)) return rc;
   for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_len[l] = -1;
+  if (int rc = join_side(c, (hipStream_t)stream)) return rc;
   hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
@@ -512,6 +575,7 @@ int ckv_evict(ckv_ctx* c, int32_t layer, void* stream) {
 int ckv_rebudget(ckv_ctx* c, void* stream) {
   if (!c) return CKV_EINVAL;
   if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  if (int rc = join_side(c, (hipStream_t)stream)) return rc;
   hipLaunchKernelGGL(rebudget_kernel, dim3((unsigned)c->lay.batch), dim3(kThreads), 0, (hipStream_t)stream, c->dev);
   CKV_HIP(c, hipGetLastError());
   return launch_schedule(c, (hipStream_t)stream);
@@ -524,6 +588,7 @@ int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, 
   if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
   const int begin = layer * c->units_per_layer, count = c->units_per_layer;
   hipStream_t s = (hipStream_t)stream;
+  if (int rc = join_side(c, s)) return rc;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                      (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, INT_MAX);
   CKV_HIP(c, hipGetLastError());
@@ -727,6 +792,11 @@ int ckv_path_info(ckv_ctx* c, int32_t* fused_waves, int32_t* lds_main_bytes) {
   if (fused_waves) *fused_waves = f ? f->waves : 0;
   if (lds_main_bytes) *lds_main_bytes = f ? f->lds_main : 0;
   return CKV_OK;
+}
+
+int ckv_join(ckv_ctx* c, void* stream) {
+  if (!c) return CKV_EINVAL;
+  return join_side(c, (hipStream_t)stream);
 }
 
 const char* ckv_strerror(int code) {

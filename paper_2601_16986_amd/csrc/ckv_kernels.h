@@ -64,6 +64,7 @@ struct Dev {
   int32_t* order;        // [units] unit indices by descending budget (schedule of the fused kernel)
   int32_t* rank;         // [units] inverse of `order`
   int4* sched;           // [units] schedule entry i: {unit order[i], its entry count after this step's append, its budget, 0}
+  int32_t* layer_ts;     // [layers][2] time and launch sequence number of a layer's last deferred step (finish_kernel part 1 -> 2)
 };
 
 
@@ -1477,8 +1478,11 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
 
 // n_limit / t_fixed: the replay of a prompt's last queries runs the step over the unit's first n_limit
 // entries at time t_fixed (otherwise INT_MAX and -1: all entries, the context's time).
+// part: 0 = the whole step; 1 = only what the caller waits for (merge -> out, the step scalars), leaving
+// the time and the launch sequence number in d.layer_ts[layer]; 2 = the rest (mean weights, Alg. 1 Steps
+// 1-4) later, on another stream, from the partials and logits of the same launch.
 __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin, void* out, uint32_t call_flags,
-                                                          int advance, int n_limit, int t_fixed) {
+                                                          int advance, int n_limit, int t_fixed, int part, int layer) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
@@ -1489,17 +1493,22 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
   const int n = min(d.n[u], n_limit);
-  const int t = t_fixed >= 0 ? t_fixed : d.sc[SC_T];
+  const int t = part == 2 ? d.layer_ts[2 * layer] : t_fixed >= 0 ? t_fixed : d.sc[SC_T];
+  const int seq = part == 2 ? d.layer_ts[2 * layer + 1] : d.sc[SC_SEQ];
+  if (part == 1 && blockIdx.x == 0 && tid == 0) {
+    d.layer_ts[2 * layer] = t;
+    d.layer_ts[2 * layer + 1] = seq;
+  }
   const int B = d.budget[u];
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
   if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
   int phase = 0;
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
-    merge_partials(d, u, urel, nch, d.sc[SC_SEQ], sM, sInv, sW, out, tid);
+    merge_partials(d, u, urel, nch, seq, sM, sInv, sW, part == 2 ? nullptr : out, tid);
     const bool evict = (call_flags & 1u) != 0;
-    if (call_flags & 2u) {
-      // attention only: the outputs are written, nothing else changes
+    if ((call_flags & 2u) || part == 1) {
+      // attention only, or the bookkeeping comes later: the outputs are written, nothing else changes
     } else if (n <= 8 * kThreads) {
       float a[8];
       mean_weights_regs(d, u, n, sM, sInv, a, tid);
@@ -1537,7 +1546,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
         d.nev[u] = 0;
     }
   }
-  step_epilogue(d, t, advance, tid);
+  if (part != 2) step_epilogue(d, t, advance, tid);
 }
 
 // Alg. 1 Step 4 on its own: scores decayed to the unit's last step, no update.

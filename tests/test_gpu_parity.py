@@ -251,6 +251,81 @@ def test_per_layer_calls():
     g.close()
 
 
+@pytest.mark.parametrize("hq,hkv,cap", [(8, 2, 96), (10, 2, 416)])
+def test_per_layer_calls_with_deferred_bookkeeping(hq, hkv, cap):
+    """Single-layer steps whose scores and evictions run on the context's own stream (CKV_DEFER_BOOKKEEPING):
+    the attention output is on the caller's stream at once, the state equals the oracle's after every step,
+    through evictions, a re-allocation of the budgets (which has to order itself after the bookkeeping in
+    flight) and all-layers steps mixed in."""
+    big = cap > 96
+    cfg = _small("llama8b", n_layers=4, n_q_heads=hq, n_kv_heads=hkv, seed=13, **(dict(prompt=330, budget=340, budget_min=64,
+                                                                                budget_max=400) if big else {}))
+    st, o, g = _pair(cfg, cap=cap)
+    stats = parity.LockstepStats()
+    import torch
+    for s in range(24):
+        ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        if s % 8 == 5:                               # an all-layers step in between: it waits for what is in flight
+            out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).cpu().numpy()
+        else:
+            outs = [g.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l, defer=True) for l in range(cfg.n_layers)]
+            out = torch.stack(outs).cpu().numpy()
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+        assert g.time() == cfg.prompt + s + 1
+        for key, rec in recs.items():
+            parity.compare_unit(g, o, key, rec, stats)
+        if s == 11 and stats.resynced == 0:
+            nb = o.rebudget()
+            g.rebudget()
+            assert np.array_equal(g.budgets(), nb)
+    assert stats.resynced <= 2, stats.notes
+    _, ckv, _ = _mods()
+    for bad in dict(layer=-1, defer=True), dict(layer=0, defer=True, attention_only=True, evict=False):
+        with pytest.raises(ckv.CkvError) as e:
+            g.decode_step(st.q[24] if bad["layer"] == -1 else st.q[24, 0], st.k_new[24] if bad["layer"] == -1 else st.k_new[24, 0],
+                          st.v_new[24] if bad["layer"] == -1 else st.v_new[24, 0], **bad)
+        assert e.value.code == ckv.EINVAL
+    g.close()
+
+
+def test_hip_graph_of_deferred_per_layer_steps_matches_eager():
+    """Two decode steps of three single-layer calls each, with deferred bookkeeping, captured into one HIP graph
+    (the context's stream takes part in the capture and rejoins it through join()) and replayed three times
+    with eager work in between: outputs and final state equal an eager context's."""
+    import torch
+    cfg = _small("tiny", n_layers=3, n_q_heads=8, n_kv_heads=2, decode_steps=8, seed=72)
+    st, o, g = _pair(cfg, cap=96)
+    _, _, g2 = _pair(cfg, cap=96)
+    dev = g.device
+    as_dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(torch.bfloat16)
+    q, k, v = as_dev(st.q), as_dev(st.k_new), as_dev(st.v_new)
+    eager = [torch.stack([g2.decode_step(q[s, l], k[s, l], v[s, l], layer=l) for l in range(3)]).clone() for s in range(6)]
+    torch.cuda.synchronize()
+    sq, sk, sv = q[:2].clone(), k[:2].clone(), v[:2].clone()
+    outs = [[torch.empty_like(eager[0][0]) for _ in range(3)] for _ in range(2)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(2):
+            for l in range(3):
+                g.decode_step(sq[i, l], sk[i, l], sv[i, l], layer=l, out=outs[i][l], defer=True)
+        g.join()
+    for rep in range(3):
+        sq.copy_(q[2 * rep:2 * rep + 2]); sk.copy_(k[2 * rep:2 * rep + 2]); sv.copy_(v[2 * rep:2 * rep + 2])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite((torch.randn(1 << 16, device=dev) * 2).sum().item())
+        for i in range(2):
+            for l in range(3):
+                assert torch.equal(outs[i][l], eager[2 * rep + i][l]), (rep, i, l)
+    assert g.time() == cfg.prompt + 6
+    for key in o.units:
+        a, b = g.export_unit(*key), g2.export_unit(*key)
+        for f in ("pos", "crf", "tau", "flags"):
+            assert np.array_equal(a[f], b[f])
+    g.close(); g2.close()
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_eviction_on_its_own_and_after_a_budget_cut(path):
     """Steps without eviction let caches grow past their budgets; ckv_evict then removes many entries
