@@ -277,7 +277,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     return CKV_EHIP;
   }
   c->finish_lds = (size_t)layout->cap * 4 + (size_t)((layout->cap + 31) / 32) * 4;
-  if (c->finish_lds + 8192 > (size_t)max_lds) {   // static LDS of the kernels stays below 8 KB
+  if (c->finish_lds + 12288 > (size_t)max_lds) {   // static LDS of the kernels stays below 12 KB
     delete c;
     return CKV_EINVAL;
   }

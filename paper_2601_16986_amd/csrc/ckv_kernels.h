@@ -954,12 +954,16 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
   const int G = d.G;
   const size_t slot0 = (size_t)u * d.slots;
   const int ns = nch + 1;
-  // weights: sW[s * 8 + g] = exp2(m_s - M) for live slots, 0 for the others
+  float* sL = sW + (kMaxChunks + 1) * kMaxGroup;      // second half of the caller's array: the slots' sums
+  // running maxima and sums of the live slots (m = -inf, l = 0 for the others), one 8-byte read each
   for (int i = tid; i < ns * kMaxGroup; i += kThreads) {
     const int sidx = i >> 3, g = i & 7;
-    float m = -INFINITY;
-    if (g < G && d.stamp[slot0 + sidx] == seq) m = d.ml[((slot0 + sidx) * G + g) * 2];
-    sW[i] = m;
+    // both reads are issued at once (the slot's record exists whether or not this launch wrote it)
+    const int stamp = d.stamp[slot0 + sidx];
+    const float2 ml = *reinterpret_cast<const float2*>(d.ml + ((slot0 + sidx) * G + min(g, G - 1)) * 2);
+    const bool live = g < G && stamp == seq;
+    sW[i] = live ? ml.x : -INFINITY;
+    sL[i] = live ? ml.y : 0.f;
   }
   __syncthreads();
   if (tid < G) {
@@ -969,6 +973,7 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
     sM[g] = M;
   }
   __syncthreads();
+  // weights: sW[s * 8 + g] = exp2(m_s - M) for live slots, 0 for the others
   for (int i = tid; i < ns * kMaxGroup; i += kThreads) {
     const int g = i & 7;
     const float m = sW[i];
@@ -980,7 +985,7 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
     float Lsum = 0.f;
     for (int sidx = 0; sidx < ns; ++sidx) {
       const float w = sW[sidx * kMaxGroup + g];
-      if (w != 0.f) Lsum += d.ml[((slot0 + sidx) * G + g) * 2 + 1] * w;
+      if (w != 0.f) Lsum += sL[sidx * kMaxGroup + g] * w;
     }
     sInv[g] = 1.0f / Lsum;
   }
@@ -989,9 +994,16 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
     for (int idx = tid; idx < G * kDim; idx += kThreads) {
       const int g = idx >> 7, dim = idx & 127;
       float o = 0.f;
-      for (int sidx = 0; sidx < ns; ++sidx) {
-        const float w = sW[sidx * kMaxGroup + g];
-        if (w != 0.f) o += d.partial[((slot0 + sidx) * G + g) * kDim + dim] * w;   // dead slots hold stale data
+      // eight slots' partials are requested at once (dead slots hold stale data: read, never used)
+      for (int s0 = 0; s0 < ns; s0 += 8) {
+        float x[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x[k] = d.partial[((slot0 + min(s0 + k, ns - 1)) * G + g) * kDim + dim];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const float w = s0 + k < ns ? sW[(s0 + k) * kMaxGroup + g] : 0.f;
+          if (w != 0.f) o += x[k] * w;
+        }
       }
       o *= sInv[g];
       const size_t oi = ((size_t)urel * G + g) * kDim + dim;
@@ -1002,6 +1014,7 @@ __device__ __forceinline__ void merge_partials(const Dev& d, int u, int urel, in
     }
   }
 }
+
 
 // lambda^delta from the decay table: its first s_tab_n entries sit in LDS, the rest (long tables: lambda
 // close to 1) in global memory.  Written as two loads in two address spaces on purpose: a conditional
@@ -1486,7 +1499,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
-  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[(kMaxChunks + 1) * kMaxGroup];
+  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[2 * (kMaxChunks + 1) * kMaxGroup];
   __shared__ RedBuf rb;
   __shared__ int sh[8];
   __shared__ float s_tab[kTabLds];
@@ -1582,7 +1595,7 @@ __global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin) 
 __global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, uint8_t* classes) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
-  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[(kMaxChunks + 1) * kMaxGroup];
+  __shared__ float sM[kMaxGroup], sInv[kMaxGroup], sW[2 * (kMaxChunks + 1) * kMaxGroup];
   __shared__ RedBuf rb;
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
