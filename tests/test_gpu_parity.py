@@ -190,6 +190,24 @@ def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam):
     g.close()
 
 
+def test_seed_prompt_with_the_attention_weighted_reward():
+    """The labelled reward variant through the prompt replay: every entry's score accumulates its mean
+    weights (within 1e-5 relative of the oracle's, as for decode steps), tau = P - 1 for every entry."""
+    ok, _, _ = _mods()
+    P, W = 77, 12
+    cfg = _small("tiny", n_layers=1, n_q_heads=10, n_kv_heads=2, prompt=P, decode_steps=W, budget=P + 5, budget_min=8,
+                 budget_max=P + 30, seed=91)
+    st, o, g = _pair(cfg, cap=128, reward_mode=ok.REWARD_ATTN_WEIGHTED)
+    o.seed_prompt(0, st.q[:W, 0])
+    g.seed_prompt(0, st.q[:W, 0])
+    for key, u in o.units.items():
+        e = g.export_unit(*key, with_kv=False)
+        assert np.array_equal(e["pos"], u.pos) and np.array_equal(e["tau"], u.tau)
+        assert np.allclose(e["crf"], u.crf, rtol=1e-5, atol=1e-30)
+        assert np.all(u.tau == P - 1)
+    g.close()
+
+
 def test_seed_prompt_argument_and_state_errors():
     _, ckv, _ = _mods()
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, seed=5)
