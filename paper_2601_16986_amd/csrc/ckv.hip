@@ -18,6 +18,8 @@
 
 using namespace ckv;
 
+constexpr int kSide = 2;   // streams of the context's own for deferred bookkeeping
+
 struct ckv_ctx {
   ckv_layout lay;
   ckv_lrfu_params par;
@@ -41,10 +43,11 @@ struct ckv_ctx {
                                 // [2]: unit_kernel_split, 4 + 4 wavefronts, 1 workgroup per CU, lds_main = bytes of ONE of its two tiles
   std::vector<uint8_t> prompt_loaded;
   std::vector<int32_t> prompt_len;   // per layer: length of a prompt loaded whole and untouched since, else -1
-  // Deferred bookkeeping of single-layer steps (CKV_DEFER_BOOKKEEPING): the second part of finish_kernel runs on
-  // `side`, ordered by events against the caller's stream.  pending[l]: layer l's bookkeeping has been queued on
-  // `side` and nothing on the caller's side has waited for it yet.
-  hipStream_t side = nullptr;
+  // Deferred bookkeeping of single-layer steps (CKV_DEFER_BOOKKEEPING): finish_kernel (late = 1) runs on
+  // one of the `side` streams (layer l on side[l % kSide], so that the bookkeeping of consecutive layers, which
+  // share nothing, can overlap), ordered by events against the caller's stream.  pending[l]: layer l's
+  // bookkeeping has been queued there and nothing on the caller's side has waited for it yet.
+  hipStream_t side[kSide] = {};
   hipEvent_t ev_out = nullptr;
   std::vector<hipEvent_t> ev_book;
   std::vector<uint8_t> pending;
@@ -122,7 +125,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -136,6 +139,7 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.budget = take(U * 4);
   c.t_unit = take(U * 4);
   c.nev = take(U * 4);
+  c.arrive = take(U * 4);
   c.window = take(U * 8);
   c.sc = take(SC_COUNT * 4);
   c.stamp = take(U * (mc + 1) * 4);
@@ -171,7 +175,7 @@ const ckv_ctx::Fused* fused_variant(const ckv_ctx* c) {
   return f->ok ? f : nullptr;
 }
 
-// Order `s` after the deferred bookkeeping still in flight on the side stream (all layers, or one).
+// Order `s` after the deferred bookkeeping still in flight on the side streams (all layers, or one).
 int join_side(ckv_ctx* c, hipStream_t s, int layer = -1) {
   if (!c->any_pending) return CKV_OK;
   bool left = false;
@@ -364,13 +368,15 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.rank = (int32_t*)(ws + cv.rank);
   d.sched = (int4*)(ws + cv.sched);
   d.layer_ts = (int32_t*)(ws + cv.layer_ts);
+  d.arrive = (int32_t*)(ws + cv.arrive);
 
   auto bail = [&](int rc) {
     ckv_destroy(c);
     return rc;
   };
   c->pending.assign(layout->n_layers, 0);
-  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) return bail(CKV_EHIP);
+  for (int i = 0; i < kSide; ++i)
+    if (hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) != hipSuccess) return bail(CKV_EHIP);
   if (hipEventCreateWithFlags(&c->ev_out, hipEventDisableTiming) != hipSuccess) return bail(CKV_EHIP);
   for (int l = 0; l < layout->n_layers; ++l) {
     hipEvent_t e;
@@ -400,10 +406,11 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
 
 void ckv_destroy(ckv_ctx* c) {
   if (!c) return;
-  if (c->side) {
-    (void)hipStreamSynchronize(c->side);
-    (void)hipStreamDestroy(c->side);
-  }
+  for (int i = 0; i < kSide; ++i)
+    if (c->side[i]) {
+      (void)hipStreamSynchronize(c->side[i]);
+      (void)hipStreamDestroy(c->side[i]);
+    }
   if (c->ev_out) (void)hipEventDestroy(c->ev_out);
   for (hipEvent_t e : c->ev_book) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -500,22 +507,28 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   const long long max_items = (long long)count * c->dev.max_chunks;
   long long blocks = 2ll * c->n_cu;
   if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
-  hipLaunchKernelGGL(scan_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q);
+  const uint32_t kflags = flags & CKV_FUSE_EVICT;
+  // when nothing but the output is due on the caller's stream, the scan merges its own partials and ends the step
+  const bool scan_merges = (flags & (CKV_DEFER_BOOKKEEPING | CKV_ATTENTION_ONLY)) != 0;
+  if (scan_merges)
+    hipLaunchKernelGGL(scan_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q, out,
+                       advance, (flags & CKV_DEFER_BOOKKEEPING) ? (int)layer : -1);
+  else
+    hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q,
+                       (void*)nullptr, 0, -1);
   CKV_HIP(c, hipGetLastError());
   if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
+  if (flags & CKV_ATTENTION_ONLY) return CKV_OK;
 
-  const uint32_t kflags = flags & (CKV_FUSE_EVICT | CKV_ATTENTION_ONLY);
   if (flags & CKV_DEFER_BOOKKEEPING) {
-    // what the caller waits for on its own stream; the scores and the eviction follow on the side stream
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out, kflags,
-                       advance, INT_MAX, -1, 1, (int)layer);
-    CKV_HIP(c, hipGetLastError());
+    // the caller waits for the scan alone; the scores and the eviction follow on a side stream
     CKV_HIP(c, hipEventRecord(c->ev_out, s));
-    CKV_HIP(c, hipStreamWaitEvent(c->side, c->ev_out, 0));
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, c->side, c->dev, begin,
-                       (void*)nullptr, kflags, 0, INT_MAX, -1, 2, (int)layer);
+    hipStream_t side = c->side[layer % kSide];
+    CKV_HIP(c, hipStreamWaitEvent(side, c->ev_out, 0));
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, side, c->dev, begin,
+                       (void*)nullptr, kflags, 0, INT_MAX, -1, 1, (int)layer);
     CKV_HIP(c, hipGetLastError());
-    CKV_HIP(c, hipEventRecord(c->ev_book[layer], c->side));
+    CKV_HIP(c, hipEventRecord(c->ev_book[layer], side));
     c->pending[layer] = 1;
     c->any_pending = true;
     return CKV_OK;
@@ -549,8 +562,8 @@ int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, voi
     const long long max_items = (long long)count * c->dev.max_chunks;
     long long blocks = 2ll * c->n_cu;
     if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
-    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin,
-                       (const uint16_t*)q_obs + (size_t)j * q_stride);
+    hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin,
+                       (const uint16_t*)q_obs + (size_t)j * q_stride, (void*)nullptr, 0, -1);
     CKV_HIP(c, hipGetLastError());
     hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, (void*)nullptr,
                        0u, 0, t_j + 1, t_j, 0, 0);
@@ -595,7 +608,8 @@ int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, 
   const long long max_items = (long long)count * c->dev.max_chunks;
   long long blocks = 2ll * c->n_cu;
   if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
-  hipLaunchKernelGGL(scan_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q_probe);
+  hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q_probe,
+                     (void*)nullptr, 0, -1);
   CKV_HIP(c, hipGetLastError());
   hipLaunchKernelGGL(probe_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, classes);
   CKV_HIP(c, hipGetLastError());

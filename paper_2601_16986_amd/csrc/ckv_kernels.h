@@ -5,7 +5,8 @@
 //                  of scan work items (unit, chunk of 256 entries)
 //   scan_kernel    the HBM-bound pass: stream K and V once, QK^T and PV on the
 //                  matrix cores, online softmax per work item; leaves the
-//                  scaled logits and one partial (max, sum, acc) per item
+//                  scaled logits and one partial (max, sum, acc) per item;
+//                  on request also merges the partials -> out and ends the step
 //   finish_kernel  one workgroup per unit: merge partials -> out, mean
 //                  attention weight per entry, top-p hit mask, CRF update,
 //                  aggregated CRF, and (optionally) eviction + compaction
@@ -64,7 +65,8 @@ struct Dev {
   int32_t* order;        // [units] unit indices by descending budget (schedule of the fused kernel)
   int32_t* rank;         // [units] inverse of `order`
   int4* sched;           // [units] schedule entry i: {unit order[i], its entry count after this step's append, its budget, 0}
-  int32_t* layer_ts;     // [layers][2] time and launch sequence number of a layer's last deferred step (finish_kernel part 1 -> 2)
+  int32_t* layer_ts;     // [layers][2] time and launch sequence number of a layer's last deferred step (scan_kernel<true> -> finish_kernel with late = 1)
+  int32_t* arrive;       // [units] runs of the unit published so far by a scan that also merges (zero between launches)
 };
 
 
@@ -609,6 +611,135 @@ __device__ __forceinline__ int find_item(const Dev& d, int n_items, int b, int l
   return __builtin_amdgcn_readfirstlane(lo);
 }
 
+// What step_epilogue leaves behind, written by the one thread that knows the launch is complete (the end of
+// the kernel makes it visible).
+__device__ __forceinline__ void scan_epilogue(const Dev& d, int seq, int advance, int layer) {
+  const int t = d.sc[SC_T];
+  if (layer >= 0) {
+    d.layer_ts[2 * layer] = t;
+    d.layer_ts[2 * layer + 1] = seq;
+  }
+  d.sc[SC_DONE] = 0;
+  d.sc[SC_CLAIM] = 0;
+  d.sc[SC_CLAIM + 1] = 0;
+  d.sc[SC_SEQ] = seq + 1;
+  if (advance) {
+    d.sc[SC_T] = t + 1;
+    d.sc[SC_WINDOW_STEPS] = d.sc[SC_WINDOW_STEPS] + 1;
+  }
+}
+
+// Stores and loads that are coherent across the chip's L2 caches one by one (no cache-wide write-back or
+// invalidation, which a fence at that scope would cost every wavefront): how a scan that merges hands its
+// partials from the wavefronts that wrote them to the one that combines them.
+template <bool COHERENT, class T>
+__device__ __forceinline__ void put(T* p, T v) {
+  if constexpr (COHERENT)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
+template <class T>
+__device__ __forceinline__ T get_coherent(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// LDS floats one wavefront needs for merge_unit_wave: maximum/weight and sum of every run and head
+constexpr int kMergeLds = 2 * (kMaxChunks + 1) * kMaxGroup;
+
+// merge_partials for one wavefront of a scan that merges: the same values combined in the same order (slot
+// after slot), so the output has the same bits; only the distribution over lanes differs.  The reads are
+// coherent ones, since the partials come from other wavefronts of the same launch, and no stamp is read:
+// the unit's blocks start at global block u0 and shares are `per` blocks long, so run r > 0 begins at the
+// r-th share boundary inside the unit, which names its slot.  `sw` holds kMergeLds floats.
+__device__ __forceinline__ void merge_unit_wave(const Dev& d, int u, int urel, int u0, int per, int runs, float* sw, void* out,
+                                                int lane) {
+  const int G = d.G;
+  const size_t slot0 = (size_t)u * d.slots;
+  float* sl = sw + (kMaxChunks + 1) * kMaxGroup;
+  const int first = u0 / per;
+  auto slot_of = [&](int r) { return r == 0 ? 0 : 1 + ((first + r) * per - u0) / kChunkBlocks; };
+  const int g_lane = lane & 7;                         // i & 7 for every i this lane visits
+  // four runs' partials (all heads, two dims per lane) are requested at once, the first four before anything else
+  float2 x[4][kMaxGroup];
+  auto request = [&](int r0) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const size_t slot = slot0 + slot_of(min(r0 + k, runs - 1));
+#pragma unroll
+      for (int g = 0; g < kMaxGroup; ++g) {
+        const float* pp = d.partial + (slot * G + min(g, G - 1)) * kDim + 2 * lane;
+        x[k][g] = make_float2(get_coherent(pp), get_coherent(pp + 1));
+      }
+    }
+  };
+  if (out) request(0);
+  for (int i = lane; i < runs * kMaxGroup; i += 64) {
+    const float* mlp = d.ml + ((slot0 + slot_of(i >> 3)) * G + min(g_lane, G - 1)) * 2;
+    const float m = get_coherent(mlp), l = get_coherent(mlp + 1);
+    sw[i] = g_lane < G ? m : -INFINITY;
+    sl[i] = g_lane < G ? l : 0.f;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  float M = -INFINITY;
+  if (lane < G)
+    for (int r = 0; r < runs; ++r) M = fmaxf(M, sw[r * kMaxGroup + lane]);
+  const float Mg = __shfl(M, g_lane);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  for (int i = lane; i < runs * kMaxGroup; i += 64) {
+    const float m = sw[i];
+    sw[i] = (g_lane < G && m > -INFINITY) ? fast_exp2(m - Mg) : 0.f;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  float inv = 0.f;
+  if (lane < G) {
+    float Lsum = 0.f;
+    for (int r = 0; r < runs; ++r) {
+      const float w = sw[r * kMaxGroup + lane];
+      if (w != 0.f) Lsum += sl[r * kMaxGroup + lane] * w;
+    }
+    inv = 1.0f / Lsum;
+  }
+  if (!out) return;
+  float2 o[kMaxGroup];
+#pragma unroll
+  for (int g = 0; g < kMaxGroup; ++g) o[g] = make_float2(0.f, 0.f);
+  for (int r0 = 0; r0 < runs; r0 += 4) {
+    if (r0 > 0) request(r0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (r0 + k < runs) {
+#pragma unroll
+        for (int g = 0; g < kMaxGroup; ++g) {
+          const float w = sw[(r0 + k) * kMaxGroup + g];
+          if (w != 0.f) {
+            o[g].x += x[k][g].x * w;
+            o[g].y += x[k][g].y * w;
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < kMaxGroup; ++g) {
+    const float inv_g = __shfl(inv, g);
+    if (g < G) {
+      const size_t oi = ((size_t)urel * G + g) * kDim + 2 * lane;
+      const float ox = o[g].x * inv_g, oy = o[g].y * inv_g;
+      if (d.out_bf16) {
+        __bf16* dst = reinterpret_cast<__bf16*>(out) + oi;
+        dst[0] = (__bf16)ox;
+        dst[1] = (__bf16)oy;
+      } else {
+        *reinterpret_cast<float2*>(reinterpret_cast<float*>(out) + oi) = make_float2(ox, oy);
+      }
+    }
+  }
+}
+
 // Persistent grid.  The blocks (32 entries) of all work items form one
 // sequence, sorted unit-major; every wavefront takes an equal contiguous share
 // of it.  Its share is a few long RUNS: consecutive blocks of one unit,
@@ -622,8 +753,19 @@ __device__ __forceinline__ int find_item(const Dev& d, int n_items, int b, int l
 // first block (shares are at least one chunk long, so no two runs collide).
 // `q` holds the query rows of the units [unit_begin, ...) of this call:
 // row (u - unit_begin) * G + g.
-__global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q) {
+//
+// MERGE: the kernel also finishes the attention.  Every run is counted on its
+// unit; the wavefront that publishes a unit's last run merges the unit's
+// partials and writes its output rows, so no second kernel stands between the
+// scan and the caller.  The wavefront that accounts for the launch's last block
+// leaves the step scalars as step_epilogue would and, for a single-layer step
+// whose bookkeeping follows later, notes the step's time and sequence number
+// under `layer`.
+template <bool MERGE>
+__global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q, void* out,
+                                                           int advance, int layer) {
   __shared__ float s_lg[kThreads / 64][kMaxGroup * kLgRow];
+  __shared__ float s_mw[MERGE ? kThreads / 64 : 1][MERGE ? kMergeLds : 1];
   const int lane = threadIdx.x & 63;
   const int nw = gridDim.x * (kThreads / 64);
   const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6));
@@ -633,7 +775,11 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
   const int per = max(kChunkBlocks, (n_blocks + nw - 1) / nw);
   int b_cur = gw * per;                                  // global block index
   const int b_end = min(n_blocks, b_cur + per);
-  if (b_cur >= b_end) return;
+  const int b_mine = b_end - b_cur;
+  if (b_cur >= b_end) {
+    if (MERGE && n_blocks == 0 && gw == 0 && lane == 0) scan_epilogue(d, seq, advance, layer);   // nothing to scan at all
+    return;
+  }
   float* lds_lg = s_lg[threadIdx.x >> 6];
   const int j = lane & 15, kg = lane >> 4;
   const int G = d.G;
@@ -703,23 +849,41 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
     l_run += __shfl_xor(l_run, 32);
     const size_t slot = (size_t)cur.u * d.slots + (fb == 0 ? 0 : 1 + fb / kChunkBlocks);
     if (head_lane && kg == 0) {
-      d.ml[(slot * G + j) * 2] = m_run;
-      d.ml[(slot * G + j) * 2 + 1] = l_run;
+      put<MERGE>(&d.ml[(slot * G + j) * 2], m_run);
+      put<MERGE>(&d.ml[(slot * G + j) * 2 + 1], l_run);
     }
-    if (lane == 0) d.stamp[slot] = seq;
+    if (lane == 0) put<MERGE>(&d.stamp[slot], seq);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int head = 4 * kg + v;
       if (head < G) {
         float* dst = d.partial + (slot * G + head) * kDim + j;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) dst[16 * dt] = acc[dt][v];
+        for (int dt = 0; dt < 8; ++dt) put<MERGE>(&dst[16 * dt], acc[dt][v]);
       }
+    }
+    if (MERGE) {
+      // the partial before the count: its stores are coherent across the chip, so it is enough that they have completed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // runs of this unit = shares that its blocks [u0, u0 + unb) touch
+      const int u0 = cur.blk_off - cur.c * kChunkBlocks;
+      const int unb = (cur.n_valid + cur.c * kChunk + kBlk - 1) / kBlk;
+      const int runs = (u0 + unb - 1) / per - u0 / per + 1;
+      int last = 0;
+      if (lane == 0) {
+        last = atomicAdd(&d.arrive[cur.u], 1) == runs - 1;
+        if (last) d.arrive[cur.u] = 0;
+      }
+      if (__builtin_amdgcn_readfirstlane(last))          // the other runs' partials are read with coherent loads
+        merge_unit_wave(d, cur.u, cur.u - unit_begin, u0, per, runs, s_mw[threadIdx.x >> 6], out, lane);
     }
     if (!have_next) break;
     b_cur = b_next;
     it = it_next;
     cur = nxt;
+  }
+  if (MERGE && lane == 0) {
+    if (atomicAdd(&d.sc[SC_DONE], b_mine) + b_mine == n_blocks) scan_epilogue(d, seq, advance, layer);
   }
 }
 
@@ -1491,11 +1655,12 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
 
 // n_limit / t_fixed: the replay of a prompt's last queries runs the step over the unit's first n_limit
 // entries at time t_fixed (otherwise INT_MAX and -1: all entries, the context's time).
-// part: 0 = the whole step; 1 = only what the caller waits for (merge -> out, the step scalars), leaving
-// the time and the launch sequence number in d.layer_ts[layer]; 2 = the rest (mean weights, Alg. 1 Steps
-// 1-4) later, on another stream, from the partials and logits of the same launch.
+// late: 0 = the whole step.  1 = the bookkeeping alone (mean weights, Alg. 1 Steps 1-4) of a single-layer
+// step whose scan has already merged the partials, written the output and ended the step: it runs later,
+// on another stream, from the partials and logits of that launch, whose time and sequence number the scan
+// left in d.layer_ts[layer], and touches no step scalar.
 __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin, void* out, uint32_t call_flags,
-                                                          int advance, int n_limit, int t_fixed, int part, int layer) {
+                                                          int advance, int n_limit, int t_fixed, int late, int layer) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
@@ -1506,23 +1671,17 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
   const int n = min(d.n[u], n_limit);
-  const int t = part == 2 ? d.layer_ts[2 * layer] : t_fixed >= 0 ? t_fixed : d.sc[SC_T];
-  const int seq = part == 2 ? d.layer_ts[2 * layer + 1] : d.sc[SC_SEQ];
-  if (part == 1 && blockIdx.x == 0 && tid == 0) {
-    d.layer_ts[2 * layer] = t;
-    d.layer_ts[2 * layer + 1] = seq;
-  }
+  const int t = late ? d.layer_ts[2 * layer] : t_fixed >= 0 ? t_fixed : d.sc[SC_T];
+  const int seq = late ? d.layer_ts[2 * layer + 1] : d.sc[SC_SEQ];
   const int B = d.budget[u];
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
   if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
   int phase = 0;
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
-    merge_partials(d, u, urel, nch, seq, sM, sInv, sW, part == 2 ? nullptr : out, tid);
+    merge_partials(d, u, urel, nch, seq, sM, sInv, sW, late ? nullptr : out, tid);
     const bool evict = (call_flags & 1u) != 0;
-    if ((call_flags & 2u) || part == 1) {
-      // attention only, or the bookkeeping comes later: the outputs are written, nothing else changes
-    } else if (n <= 8 * kThreads) {
+    if (n <= 8 * kThreads) {
       float a[8];
       mean_weights_regs(d, u, n, sM, sInv, a, tid);
       f32x4 crf[2];
@@ -1559,7 +1718,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
         d.nev[u] = 0;
     }
   }
-  if (part != 2) step_epilogue(d, t, advance, tid);
+  if (!late) step_epilogue(d, t, advance, tid);
 }
 
 // Alg. 1 Step 4 on its own: scores decayed to the unit's last step, no update.

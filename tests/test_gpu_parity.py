@@ -269,6 +269,45 @@ def test_per_layer_calls():
     g.close()
 
 
+@pytest.mark.parametrize("prompt", [8, 333, 2100])
+def test_scan_that_merges_its_own_partials_gives_the_bits_of_the_finish_kernel(prompt):
+    """Attention-only steps and steps with deferred bookkeeping get their output from the scan itself (the
+    wavefront that publishes a unit's last run merges the unit); plain steps get it from the finish kernel.
+    Same cache, same queries: the same bits, and the oracle's values, for units of one block (several units
+    per wavefront), of two or three runs, and of more runs than one batch of the merge holds."""
+    import torch
+    cfg = _small("qwen14b", n_layers=2, batch=2, n_q_heads=10, n_kv_heads=2, prompt=prompt, decode_steps=10,
+                 budget=prompt + 20, budget_min=1, budget_max=prompt + 20, seed=17)
+    cap = (prompt + 21 + 31) // 32 * 32
+    st, o, g_plain = _pair(cfg, cap=cap, path=1)
+    _, _, g_attn = _pair(cfg, cap=cap, stream=st, path=1)
+    _, _, g_defer = _pair(cfg, cap=cap, stream=st, path=1)
+    _, _, g_all = _pair(cfg, cap=cap, stream=st, path=1)
+    for s in range(cfg.decode_steps):
+        ref, _ = o.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+        layers = range(cfg.n_layers)
+        a = torch.stack([g_plain.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l, evict=False) for l in layers])
+        b = torch.stack([g_attn.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l, attention_only=True)
+                         for l in layers])
+        c = torch.stack([g_defer.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l, evict=False, defer=True)
+                         for l in layers])
+        d = g_all.decode_step(st.q[s], st.k_new[s], st.v_new[s], attention_only=True)
+        assert parity.out_error(a.cpu().numpy(), ref) <= parity.OUT_TOL
+        assert parity.out_error(d.cpu().numpy(), ref) <= parity.OUT_TOL      # other shares, other rounding
+        for name, other in (("attention only", b), ("deferred", c)):
+            assert torch.equal(a, other), (name, s, float((a - other).abs().max()))
+        for g in (g_plain, g_attn, g_defer, g_all):
+            assert g.time() == cfg.prompt + s + 1
+    g_defer.join()
+    # the deferred bookkeeping saw the same partials as the plain step's: the same scores, bit for bit
+    for key in o.units:
+        e1, e2 = g_plain.export_unit(*key, with_kv=False), g_defer.export_unit(*key, with_kv=False)
+        assert np.array_equal(e1["crf"], e2["crf"]) and np.array_equal(e1["tau"], e2["tau"])
+    for g in (g_plain, g_attn, g_defer, g_all):
+        assert g.status() == 0
+        g.close()
+
+
 @pytest.mark.parametrize("hq,hkv,cap", [(8, 2, 96), (10, 2, 416)])
 def test_per_layer_calls_with_deferred_bookkeeping(hq, hkv, cap):
     """Single-layer steps whose scores and evictions run on the context's own stream (CKV_DEFER_BOOKKEEPING):
