@@ -197,6 +197,15 @@ int ckv_decode_step(ckv_ctx* ctx, int32_t layer, const void* q, const void* k_ne
  * slots [B, n_old) then hold the evicted positions with CKV_FLAG_SLIP. */
 int ckv_evict(ckv_ctx* ctx, int32_t layer, void* stream);
 
+/* A comparison policy on the same caches, not part of the method (Sec. 2.3: the
+ * baseline that assumes attention goes to the initial and the most recent
+ * tokens).  For every unit of `layer` (-1: all) holding more entries than its
+ * budget B: keep the entries whose position is below n_sink (the lowest of them
+ * if even they exceed B) and fill the budget with the highest positions; scores
+ * play no part and stay as they are on the survivors.  Slots, flags and the
+ * eviction record as after ckv_evict.  n_sink < 0: CKV_EINVAL. */
+int ckv_evict_window(ckv_ctx* ctx, int32_t layer, int32_t n_sink, void* stream);
+
 /* Alg. 2: new integer budgets for every (layer, head) of every sequence from
  * the aggregated CRF averaged over the decode steps since the last call (or
  * since init), keeping each sequence's total; restarts the averaging window.

@@ -27,6 +27,10 @@ What follows which passage of the paper (arxiv 2601.16986):
                            silent on this; reading stated below).
 * `probe_classes`        - Sec. 3: rank entries by the answer query's attention,
                            top 30 % = CrystalKV, bottom 30 % = SlipKV.
+* `window_select`        - Sec. 2.3, the baseline that assumes attention goes to
+                           the initial and the most recent tokens: keep the
+                           sink positions and the newest entries (a comparison
+                           policy on the same caches, not part of the method).
 * `CrystalKVOracle`      - the per-step control flow of Sec. 4 / Alg. 1 over all
                            (layer, sequence, KV head) units.
 * `CrystalKVOracle.seed_prompt`
@@ -218,6 +222,25 @@ def evict_select(tmp, pos, budget):
     order = np.lexsort((pos, -tmp.astype(np.float64)))
     retain = np.sort(order[:budget])
     evicted = np.sort(order[budget:])
+    return retain, evicted
+
+
+def window_select(pos, budget, n_sink):
+    """Sink-plus-recent-window retention (Sec. 2.3: the baseline that keeps the
+    initial and the most recent tokens).  Sinks are the entries whose position
+    is below `n_sink`; they are kept first (lowest position first if even they
+    exceed the budget), the rest of the budget goes to the highest positions.
+    Returns (retain, evicted) as ascending index arrays."""
+    pos = np.asarray(pos)
+    n = pos.shape[0]
+    if n <= budget:
+        return np.arange(n), np.zeros(0, dtype=np.int64)
+    idx = np.arange(n)
+    sinks = sorted(idx[pos < n_sink], key=lambda i: pos[i])
+    others = sorted(idx[pos >= n_sink], key=lambda i: -pos[i])
+    keep = (sinks + others)[:budget]
+    retain = np.sort(np.asarray(keep, dtype=np.int64))
+    evicted = np.setdiff1d(idx, retain)
     return retain, evicted
 
 
@@ -567,11 +590,14 @@ class CrystalKVOracle:
             evicted_pos, gap = self._evict_unit(u, tmp)
         return StepRecord(y, abar, dec, tmp, s_fixed, evicted_pos, gap)
 
-    def _evict_unit(self, u, tmp):
+    def _evict_unit(self, u, tmp, n_sink=None):
         if u.n <= u.budget:
             u.last_evicted = np.zeros(0, np.int64)
             return u.last_evicted, math.inf
-        retain, evicted = evict_select(tmp, u.pos, u.budget)
+        if n_sink is None:
+            retain, evicted = evict_select(tmp, u.pos, u.budget)
+        else:
+            retain, evicted = window_select(u.pos, u.budget, n_sink)
         kept_min = float(tmp[retain].min())
         ev_max = float(tmp[evicted].max())
         gap = (kept_min - ev_max) / kept_min if kept_min > 0 else 0.0
@@ -608,6 +634,15 @@ class CrystalKVOracle:
         for key in (self.units if keys is None else keys):
             u = self.units[key]
             res[key] = self._evict_unit(u, self.current_tmp(u))[0]
+        return res
+
+    def evict_window(self, n_sink, keys=None):
+        """The sink-plus-recent-window baseline's eviction (`window_select`) on the same caches:
+        scores play no part and stay as they are on the survivors."""
+        res = {}
+        for key in (self.units if keys is None else keys):
+            u = self.units[key]
+            res[key] = self._evict_unit(u, self.current_tmp(u), n_sink)[0]
         return res
 
     # -- Alg. 2 ----------------------------------------------------------------

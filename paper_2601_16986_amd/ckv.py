@@ -25,6 +25,7 @@ DEFER_BOOKKEEPING = 4
 EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_seed_prompt", "ckv_load_cache", "ckv_decode_step",
     "ckv_evict",
+    "ckv_evict_window",
     "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
     "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_join", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
@@ -72,6 +73,7 @@ def load():
     lib.ckv_seed_prompt.argtypes = [vp, i32, vp, i32, vp]
     lib.ckv_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, u32, vp]
     lib.ckv_evict.argtypes = [vp, i32, vp]
+    lib.ckv_evict_window.argtypes = [vp, i32, i32, vp]
     lib.ckv_rebudget.argtypes = [vp, vp]
     lib.ckv_probe.argtypes = [vp, i32, vp, vp, vp]
     lib.ckv_get_budgets.argtypes = [vp, vp]
@@ -240,6 +242,10 @@ class CrystalKV:
 
     def evict(self, layer=-1):
         self._check(self.lib.ckv_evict(self.ctx, layer, self._stream()))
+
+    def evict_window(self, n_sink, layer=-1):
+        """The sink-plus-recent-window comparison policy: keep positions below n_sink and the newest entries."""
+        self._check(self.lib.ckv_evict_window(self.ctx, layer, n_sink, self._stream()))
 
     def rebudget(self):
         self._check(self.lib.ckv_rebudget(self.ctx, self._stream()))

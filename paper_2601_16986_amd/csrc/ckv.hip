@@ -580,7 +580,20 @@ int ckv_evict(ckv_ctx* c, int32_t layer, void* stream) {
   if (int rc = layer_range(c, layer, &begin, &count)) return rc;
   for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_len[l] = -1;
   if (int rc = join_side(c, (hipStream_t)stream)) return rc;
-  hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin);
+  hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin, -1);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_evict_window(ckv_ctx* c, int32_t layer, int32_t n_sink, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (n_sink < 0) return fail(c, CKV_EINVAL, "n_sink is negative");
+  int begin, count;
+  if (int rc = layer_range(c, layer, &begin, &count)) return rc;
+  for (int l = (layer == -1 ? 0 : layer); l < (layer == -1 ? c->lay.n_layers : layer + 1); ++l) c->prompt_len[l] = -1;
+  if (int rc = join_side(c, (hipStream_t)stream)) return rc;
+  hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin,
+                     (int)n_sink);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
 }

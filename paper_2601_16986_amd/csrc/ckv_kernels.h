@@ -1722,7 +1722,10 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
 }
 
 // Alg. 1 Step 4 on its own: scores decayed to the unit's last step, no update.
-__global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin) {
+// n_sink < 0: Alg. 1 Step 4 (retain the highest CRF_temp).  n_sink >= 0: the comparison policy of Sec. 2.3
+// that keeps the initial and the most recent tokens; the retention key is then the position itself, carried
+// as a bit pattern (the eviction only ever compares the bits), and the largest pattern for positions below n_sink.
+__global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin, int n_sink) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
@@ -1738,12 +1741,19 @@ __global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin) 
     return;
   }
   const int t = d.t_unit[u];
-  for (int i = tid; i < n; i += kThreads) {
-    int delta = t - d.tau[base + i];
-    delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
-    float tmp = __fmul_rn(d.tab[delta], d.crf[base + i]);
-    if (tmp < FLT_MIN) tmp = 0.0f;
-    val[i] = tmp;
+  if (n_sink >= 0) {
+    for (int i = tid; i < n; i += kThreads) {
+      const int p = d.pos[base + i];
+      val[i] = __uint_as_float(p < n_sink ? 0x7FFFFFFFu : (uint32_t)p);
+    }
+  } else {
+    for (int i = tid; i < n; i += kThreads) {
+      int delta = t - d.tau[base + i];
+      delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+      float tmp = __fmul_rn(d.tab[delta], d.crf[base + i]);
+      if (tmp < FLT_MIN) tmp = 0.0f;
+      val[i] = tmp;
+    }
   }
   __syncthreads();
   evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);

@@ -14,11 +14,12 @@ the whole sequence is decoded with eviction every step, then two recalls are tak
   whose budget holds the whole sequence (nothing evicted) and `ckv_probe`; the answer query is the held-out
   query of the step after the last one.  Normalised by min(|Crystal|, budget).
 
-Two reference rows on the same skeleton: "recent" keeps the newest B entries (lambda = 0 with p so small
-that only the arriving entry is hit: a sliding window), "accumulated attention" scores every entry by the
-plain sum of its attention weights (the attention-weighted reward with lambda = 1: the accumulation policy
-of heavy-hitter eviction schemes).  Policies only: no accuracy claim.  Prints one markdown table and one
-JSON line.
+Three reference rows on the same skeleton (the policies Sec. 2.3 names): "recent" keeps the newest B entries
+(lambda = 0 with p so small that only the arriving entry is hit: a sliding window), "sink + recent" keeps
+the first 4 positions and the newest B - 4 (`ckv_evict_window` after every step), "accumulated attention"
+scores every entry by the plain sum of its attention weights (the attention-weighted reward with
+lambda = 1: the accumulation policy of heavy-hitter eviction schemes).  Policies only: no accuracy claim.
+Prints one markdown table and one JSON line.
 """
 import argparse
 import json
@@ -26,7 +27,7 @@ import json
 import numpy as np
 
 
-def run(cfg, st, lam, top_p, budget, torch, ckv, device, answer_q, reward_mode=0):
+def run(cfg, st, lam, top_p, budget, torch, ckv, device, answer_q, reward_mode=0, n_sink=None):
     T = cfg.decode_steps
     N = cfg.prompt + T
     budgets = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), budget, dtype=np.int32)
@@ -35,11 +36,14 @@ def run(cfg, st, lam, top_p, budget, torch, ckv, device, answer_q, reward_mode=0
                       top_p=top_p, reward_mode=reward_mode, t0=cfg.prompt, budget_min=1, budget_max=cap - 1, device=device)
     for l in range(cfg.n_layers):
         g.load_prompt(l, st["pk"][l], st["pv"][l])
+    evict = g.evict if n_sink is None else (lambda: g.evict_window(n_sink))
     if budget < cfg.prompt:
-        g.evict()
+        evict()
     out = torch.empty((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device=device)
     for s in range(T):
-        g.decode_step(st["q"][s], st["k"][s], st["v"][s], out=out)
+        g.decode_step(st["q"][s], st["k"][s], st["v"][s], out=out, evict=n_sink is None)
+        if n_sink is not None:
+            evict()
     assert g.status() == 0
     kept = {}
     for l in range(cfg.n_layers):
@@ -86,10 +90,12 @@ def main():
     lams = [0.0, 0.3, 0.5, 0.7, 0.9, 1.0]
     ps = [0.5, 0.7, 0.9, 0.95]
     rows, results = [], []
-    settings = [("recent", 0.0, 1e-30), ("accumulated", 1.0, 0.9)] + [(None, lam, p) for p in ps for lam in lams]
+    settings = ([("recent", 0.0, 1e-30), ("accumulated", 1.0, 0.9), ("sink + recent", 0.5, 0.9)]
+                + [(None, lam, p) for p in ps for lam in lams])
     for name, lam, p in settings:
         kept, _ = run(cfg, st, lam, p, args.budget, torch, ckv, device, answer_q,
-                      reward_mode=ckv.REWARD_ATTN_WEIGHTED if name == "accumulated" else ckv.REWARD_TOPP_HIT)
+                      reward_mode=ckv.REWARD_ATTN_WEIGHTED if name == "accumulated" else ckv.REWARD_TOPP_HIT,
+                      n_sink=4 if name == "sink + recent" else None)
         hr, cr = [], []
         for key, pos in kept.items():
             have = set(pos.tolist())
@@ -106,8 +112,9 @@ def main():
     for p in ps:
         cells = [r for r in results if r["name"] is None and r["top_p"] == p]
         print(f"| {p:g} | " + " | ".join(f"{r['heavy_recall']:.2f} / {r['crystal_recall']:.2f}" for r in cells) + " |")
-    r0, r1 = results[0], results[1]
+    r0, r1, r2 = results[0], results[1], results[2]
     print(f"| newest {args.budget} only | {r0['heavy_recall']:.2f} / {r0['crystal_recall']:.2f} |" + " |" * (len(lams) - 1))
+    print(f"| 4 sinks + newest {args.budget - 4} | {r2['heavy_recall']:.2f} / {r2['crystal_recall']:.2f} |" + " |" * (len(lams) - 1))
     print(f"| accumulated attention | {r1['heavy_recall']:.2f} / {r1['crystal_recall']:.2f} |" + " |" * (len(lams) - 1))
     print(json.dumps({"tokens": args.tokens, "prompt": args.prompt, "budget": args.budget, "cells": "heavy recall / Crystal recall",
                       "results": results}))

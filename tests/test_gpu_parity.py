@@ -237,10 +237,12 @@ def test_lambda_top_p_sweep_script_runs(capsys, monkeypatch):
     monkeypatch.setattr(sys, "argv", ["sweep", "--tokens", "224", "--prompt", "32", "--budget", "40"])
     sweep.main()
     res = json.loads(capsys.readouterr().out.strip().splitlines()[-1])["results"]
-    assert len(res) == 26 and all(0.0 <= r["heavy_recall"] <= 1.0 and 0.0 <= r["crystal_recall"] <= 1.0 for r in res)
+    assert len(res) == 27 and all(0.0 <= r["heavy_recall"] <= 1.0 and 0.0 <= r["crystal_recall"] <= 1.0 for r in res)
     rec = next(r for r in res if r["name"] == "recent")
     best = next(r for r in res if r["name"] is None and r["lambda"] == 0.5 and r["top_p"] == 0.9)
     assert best["heavy_recall"] >= rec["heavy_recall"] and best["crystal_recall"] >= rec["crystal_recall"]
+    sink = next(r for r in res if r["name"] == "sink + recent")
+    assert best["heavy_recall"] >= sink["heavy_recall"]
 
 
 def test_per_layer_calls():
@@ -419,6 +421,53 @@ def test_eviction_on_its_own_and_after_a_budget_cut(path):
             assert np.array_equal(e["K"][og], u.K[oo].astype(np.float32))
             assert np.array_equal(e["V"][og], u.V[oo].astype(np.float32))
     assert stats.resynced <= 2
+    g.close()
+
+
+@pytest.mark.parametrize("every,n_sink", [(1, 4), (7, 4), (5, 0), (9, 30)])
+def test_sink_plus_recent_window_policy_matches_oracle(every, n_sink):
+    """The comparison policy of Sec. 2.3 (initial + most recent tokens) on the same caches: steps without
+    eviction, then ckv_evict_window every few steps.  Evicted positions, survivors with their scores, taus,
+    keys and values as the oracle's; with n_sink above the budget of one unit the lowest sinks stay."""
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, prompt=40, decode_steps=36, budget=26, seed=23)
+    budgets = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), 26, dtype=np.int32)
+    budgets[1, 0, 1] = 9
+    st, o, g = _pair(cfg, cap=96, budgets=budgets)
+    stats = parity.LockstepStats()
+
+    def evict_and_compare():
+        ev = o.evict_window(n_sink)
+        g.evict_window(n_sink)
+        for key in o.units:
+            e = g.export_unit(*key)
+            u = o.units[key]
+            assert e["n"] == u.n == u.budget
+            assert np.array_equal(e["evicted_pos"], ev[key])
+            assert np.all(e["evicted_flags"] == 2)
+            og, oo = np.argsort(e["pos"]), np.argsort(u.pos)
+            assert np.array_equal(e["pos"][og], u.pos[oo])
+            assert np.array_equal(e["crf"][og], u.crf[oo]) and np.array_equal(e["tau"][og], u.tau[oo])
+            assert np.array_equal(e["K"][og], u.K[oo].astype(np.float32))
+            assert np.array_equal(e["V"][og], u.V[oo].astype(np.float32))
+
+    evict_and_compare()                                # the prompt (40 entries) down to the budgets
+    for s in range(cfg.decode_steps):
+        ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+        out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False).cpu().numpy()
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+        for key, rec in recs.items():
+            parity.compare_unit(g, o, key, rec, stats)
+        if (s + 1) % every == 0:
+            evict_and_compare()
+    assert stats.resynced <= 2, stats.notes
+    if every == 1 and n_sink == 4:                     # the sliding window itself
+        t = cfg.prompt + cfg.decode_steps - 1
+        e = g.export_unit(0, 0, 0, with_kv=False)
+        assert sorted(e["pos"].tolist()) == list(range(4)) + list(range(t - 21, t + 1))
+    _, ckv, _ = _mods()
+    with pytest.raises(ckv.CkvError) as err:
+        g.evict_window(-1)
+    assert err.value.code == ckv.EINVAL
     g.close()
 
 

@@ -451,3 +451,64 @@ def test_seed_prompt_limits_lru_lfu_and_single_query():
         hit = decs[key][0].hit
         assert hit[P - 1] and np.array_equal(u.tau, np.where(hit, P - 1, np.arange(P)))
         assert np.array_equal(u.crf, np.where(hit & (np.arange(P) < P - 1), np.float32(1.0) + np.float32(0.5) ** (P - 1 - np.arange(P)).astype(np.float32), np.float32(1.0)).astype(np.float32))
+
+
+# ------------------------------------------------------------------ sink + recent window (comparison policy)
+def test_window_select_closed_form_and_brute_force():
+    """Sec. 2.3's initial-plus-recent baseline.  With positions 0..n-1 the survivors are the first
+    n_sink and the last B - n_sink positions; in any order of the entries the same set of positions
+    survives; and on tiny inputs the survivors are the best subset under "sinks first, then the newer
+    the better", found by brute force over all subsets."""
+    rng = np.random.default_rng(5)
+    for n, B, s in [(40, 12, 4), (40, 12, 0), (9, 8, 3), (17, 5, 5), (10, 10, 2), (6, 9, 1)]:
+        pos = rng.permutation(n)
+        retain, evicted = ok.window_select(pos, B, s)
+        want = set(range(n)) if n <= B else set(range(s)) | set(range(n - (B - s), n))
+        assert set(pos[retain].tolist()) == want
+        assert sorted(retain.tolist() + evicted.tolist()) == list(range(n))
+        assert np.all(np.diff(retain) > 0)
+    # more sinks than budget: the lowest positions stay
+    retain, _ = ok.window_select(np.array([7, 0, 3, 1, 2, 9]), 2, 4)
+    assert retain.tolist() == [1, 3]
+    # brute force with gaps in the positions (some already evicted)
+    for trial in range(20):
+        n, B, s = 7, int(rng.integers(1, 7)), int(rng.integers(0, 5))
+        pos = np.sort(rng.choice(30, size=n, replace=False))
+        rng.shuffle(pos)
+        def goodness(sub):
+            p = sorted(pos[list(sub)].tolist())
+            sinks = [x for x in p if x < s]
+            # every kept sink outranks any number of recent entries; among sinks the lower the better
+            return (len(sinks), [-x for x in sinks], sorted([x for x in p if x >= s], reverse=True))
+        best = max(itertools.combinations(range(n), B), key=goodness)
+        retain, _ = ok.window_select(pos, B, s)
+        assert retain.tolist() == sorted(best)
+
+
+def test_window_policy_keeps_a_sliding_window_through_decoding():
+    """Decoding with the window policy after every step: each cache holds exactly the sink positions and
+    the latest budget - n_sink positions at every time, the attention output is plain softmax attention
+    over those entries, and the stored scores of survivors are untouched by the policy."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], prompt=30, decode_steps=25, budget=16, budget_min=1, budget_max=64)
+    st = wl.make_stream(cfg, tiny_heavy=False)
+    B, s = 16, 4
+    o = ok.CrystalKVOracle(1, 1, 8, 2, 128, np.full((1, 1, 2), B), lam=0.5, top_p=0.9, t0=30)
+    o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    o.evict_window(s)
+    for step in range(25):
+        out, recs = o.decode_step(st.q[step], st.k_new[step], st.v_new[step], evict=False)
+        for key, u in o.units.items():
+            # attention over [sinks, window, new]: compare with softmax attention written out here
+            h = key[2]
+            K, V = u.K, u.V
+            for g in range(4):
+                lg = (K @ st.q[step, 0, 0, 4 * h + g].astype(np.float64)) * o.scale
+                w = np.exp(lg - lg.max())
+                assert np.allclose(out[0, 0, 4 * h + g], (w / w.sum()) @ V, rtol=1e-11, atol=1e-13)
+        crf_after_step = {k: dict(zip(u.pos.tolist(), u.crf.tolist())) for k, u in o.units.items()}
+        ev = o.evict_window(s)
+        t = 30 + step
+        for key, u in o.units.items():
+            assert sorted(u.pos.tolist()) == list(range(s)) + list(range(t - (B - s) + 1, t + 1))
+            assert ev[key].tolist() == [t - (B - s)]
+            assert all(crf_after_step[key][p] == c for p, c in zip(u.pos.tolist(), u.crf.tolist()))
