@@ -15,9 +15,9 @@ the whole sequence is decoded with eviction every step, then two recalls are tak
   query of the step after the last one.  Normalised by min(|Crystal|, budget).
 
 Three reference rows on the same skeleton (the policies Sec. 2.3 names): "recent" keeps the newest B entries
-(lambda = 0 with p so small that only the arriving entry is hit: a sliding window), "sink + recent" keeps
-the first 4 positions and the newest B - 4 (`ckv_evict_window` after every step), "accumulated attention"
-scores every entry by the plain sum of its attention weights (the attention-weighted reward with
+(a sliding window: `ckv_evict_window` with no sinks after every step), "sink + recent" keeps the first 4
+positions and the newest B - 4 (the same call with 4 sinks), "accumulated attention" scores every entry by
+the plain sum of its attention weights (the attention-weighted reward with
 lambda = 1: the accumulation policy of heavy-hitter eviction schemes).  Policies only: no accuracy claim.
 Prints one markdown table and one JSON line.
 """
@@ -90,12 +90,12 @@ def main():
     lams = [0.0, 0.3, 0.5, 0.7, 0.9, 1.0]
     ps = [0.5, 0.7, 0.9, 0.95]
     rows, results = [], []
-    settings = ([("recent", 0.0, 1e-30), ("accumulated", 1.0, 0.9), ("sink + recent", 0.5, 0.9)]
+    settings = ([("recent", 0.5, 0.9), ("accumulated", 1.0, 0.9), ("sink + recent", 0.5, 0.9)]
                 + [(None, lam, p) for p in ps for lam in lams])
     for name, lam, p in settings:
         kept, _ = run(cfg, st, lam, p, args.budget, torch, ckv, device, answer_q,
                       reward_mode=ckv.REWARD_ATTN_WEIGHTED if name == "accumulated" else ckv.REWARD_TOPP_HIT,
-                      n_sink=4 if name == "sink + recent" else None)
+                      n_sink={"recent": 0, "sink + recent": 4}.get(name))
         hr, cr = [], []
         for key, pos in kept.items():
             have = set(pos.tolist())
