@@ -284,7 +284,7 @@ def main():
         fused_bytes = step_bytes = scan_bytes + int(cfg.n_units) * cfg.group * 512
     fused_waves, _ = g.path_info()
     # dominant kernel of an all-layers step: the fused per-unit kernel if the context uses it, else the scan kernel
-    kernel_name = f"unit_kernel<{fused_waves}>" if fused_waves else "scan_kernel"
+    kernel_name = f"unit_kernel<{fused_waves}>" if fused_waves else "scan_kernel<false>"
     kernel_bytes = fused_bytes if fused_waves else scan_bytes
     scan_avg_ms = scan_ms / max(launches, 1)
     achieved = kernel_bytes / (scan_avg_ms * 1e-3) / 1e9
