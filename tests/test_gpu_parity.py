@@ -108,6 +108,29 @@ def test_fused_kernel_large_units(path, n_big):
     g.close()
 
 
+@pytest.mark.parametrize("defer", [False, True])
+def test_units_at_the_maximum_capacity(defer):
+    """cap = 32768 slots, the most the layout admits: one unit stays full (one entry evicted per step once
+    its budget is reached), the other is cut from 32700 entries to a budget of 16000 in its first step (the
+    general select and compaction at full size) and then scanned as 63 chunks.  Single-layer calls, plain
+    and with deferred bookkeeping (the scan then merges up to 129 runs per unit)."""
+    cfg = _small("qwen7b", n_layers=1, batch=1, n_q_heads=4, n_kv_heads=2, prompt=32700, decode_steps=8,
+                 budget=32704, budget_min=200, budget_max=32767, seed=29)
+    budgets = np.array([[[32704, 16000]]], dtype=np.int32)
+    st, o, g = _pair(cfg, cap=32768, budgets=budgets)
+    stats = parity.LockstepStats()
+    for s in range(cfg.decode_steps):
+        ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        out = g.decode_step(st.q[s, 0], st.k_new[s, 0], st.v_new[s, 0], layer=0, defer=defer).cpu().numpy()[None]
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+        for key, rec in recs.items():
+            parity.compare_unit(g, o, key, rec, stats, check_kv=(s in (0, 7)))
+    assert stats.resynced <= 1, stats.notes
+    assert g.status() == 0 and np.array_equal(g.lengths(), o.lengths())
+    assert g.lengths().tolist() == [[[32704, 16000]]]
+    g.close()
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_attention_only_steps(path):
     """CKV_ATTENTION_ONLY (the FullKV baseline): outputs as the oracle's attention over the growing cache;
