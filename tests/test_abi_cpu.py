@@ -65,6 +65,10 @@ def test_init_rejects_bad_arguments_without_touching_the_gpu():
     assert ctx.value is None
     assert lib.ckv_init(None, C.byref(lay), None, C.byref(par), C.byref(bufs), None) == ckv.EINVAL
     assert lib.ckv_decode_step(None, 0, None, None, None, None, 0, None) == ckv.EINVAL
+    # every call that takes a context refuses a NULL one before anything else
+    assert lib.ckv_evict(None, 0, None) == ckv.EINVAL and lib.ckv_evict_window(None, 0, 4, None) == ckv.EINVAL
+    assert lib.ckv_seed_prompt(None, 0, None, 1, None) == ckv.EINVAL and lib.ckv_rebudget(None, None) == ckv.EINVAL
+    assert lib.ckv_join(None, None) == ckv.EINVAL and lib.ckv_set_path(None, 0) == ckv.EINVAL
     assert lib.ckv_strerror(ckv.ECAPACITY).decode() == "unit full at append"
     assert lib.ckv_strerror(0).decode() == "ok"
 
