@@ -301,7 +301,7 @@ def main():
                     g.decode_step(rq[i % RING, l], rk[i % RING, l], rv[i % RING, l], layer=l, out=outl, defer=defer)
 
         res_pl = []
-        for defer in (False, True):          # plain, then with the layers' bookkeeping on the context's own stream
+        for defer in (False, True):          # plain, then with the layers' bookkeeping on the context's own streams
             layer_steps(1, defer)
             g.join()
             torch.cuda.synchronize()

@@ -62,7 +62,7 @@ enum { CKV_CLASS_SLIP = 0, CKV_CLASS_POTENTIAL = 1, CKV_CLASS_CRYSTAL = 2 };
 #define CKV_ATTENTION_ONLY 2u /* ckv_decode_step: append and attend only (the FullKV baseline of Table 1): no hit
                                * mask, no score update, no eviction; excludes CKV_FUSE_EVICT */
 #define CKV_DEFER_BOOKKEEPING 4u /* ckv_decode_step of a single layer: only the attention output is ordered on the
-                                  * caller's stream; scores and eviction follow on a stream of the context (see there) */
+                                  * caller's stream; scores and eviction follow on streams of the context (see there) */
 
 /* Geometry.  head_dim must be 128; n_q_heads = G * n_kv_heads with G <= 8;
  * `cap` = slots per unit, a multiple of 32, at most 32768. */
@@ -179,14 +179,14 @@ int ckv_load_cache(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, in
  * With CKV_DEFER_BOOKKEEPING (single-layer calls only) the call puts on `stream`
  * only what the next operation of a model needs, the append and the attention
  * output; the hit set, the scores and the eviction of that layer run afterwards
- * on a stream the context owns, beside whatever `stream` does next (the next
- * layer's step, the model's other work).  Results are the same.  Every later
+ * on one of two streams the context owns, beside whatever `stream` does next (the
+ * next layer's step, the model's other work).  Results are the same.  Every later
  * ckv_* call that takes a stream orders itself after the bookkeeping it depends
  * on (the next step of the same layer after that layer's, everything else after
  * all of it); the host-side getters wait for the whole device.  ckv_join orders
  * a stream after all of it explicitly: call it before reading the caller-owned
  * state arrays directly, and before ending a stream capture that contains such
- * steps (the context's stream takes part in the capture and must rejoin it). */
+ * steps (the context's streams take part in the capture and must rejoin it). */
 int ckv_decode_step(ckv_ctx* ctx, int32_t layer, const void* q, const void* k_new,
                     const void* v_new, void* out, uint32_t flags, void* stream);
 
@@ -268,7 +268,7 @@ int ckv_set_path(ckv_ctx* ctx, int32_t mode);
 int ckv_path_info(ckv_ctx* ctx, int32_t* fused_waves, int32_t* lds_main_bytes);
 
 /* Orders `stream` after the bookkeeping that steps with CKV_DEFER_BOOKKEEPING have
- * left in flight on the context's own stream (no-op if there is none). */
+ * left in flight on the context's own streams (no-op if there is none). */
 int ckv_join(ckv_ctx* ctx, void* stream);
 
 /* Measurement aid, independent of any context: streams `bytes` (a multiple of

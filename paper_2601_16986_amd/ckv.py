@@ -222,7 +222,7 @@ class CrystalKV:
     def decode_step(self, q, k_new, v_new, layer=-1, evict=True, out=None, attention_only=False, defer=False):
         """q [L][Bz][Hq][d], k_new / v_new [L][Bz][Hkv][d] (no leading [L] for a single layer).
         Returns the device tensor `out` of the same shape as q.  defer (single layers only): the layer's
-        bookkeeping runs on the context's own stream, see `join`."""
+        bookkeeping runs on one of the context's own streams, see `join`."""
         t = self.torch
         lead = (self.L,) if layer == -1 else ()
         q = self._dev_bf16(q, lead + (self.Bz, self.Hq, self.d))
