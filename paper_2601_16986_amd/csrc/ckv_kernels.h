@@ -775,9 +775,24 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
   const int per = max(kChunkBlocks, (n_blocks + nw - 1) / nw);
   int b_cur = gw * per;                                  // global block index
   const int b_end = min(n_blocks, b_cur + per);
-  const int b_mine = b_end - b_cur;
+  // MERGE: the launch is complete when every block is accounted for; a workgroup reports its blocks once, through
+  // its last wavefront to finish (one atomic per workgroup on the shared counter instead of one per wavefront)
+  __shared__ int s_waves_done;
+  if (MERGE) {
+    if (threadIdx.x == 0) s_waves_done = 0;
+    __syncthreads();
+  }
+  auto wave_done = [&]() {
+    if (lane != 0 || atomicAdd(&s_waves_done, 1) != kThreads / 64 - 1) return;
+    const int w0 = blockIdx.x * (kThreads / 64);
+    const int wg_blocks = min(n_blocks, (w0 + kThreads / 64) * per) - min(n_blocks, w0 * per);
+    if (wg_blocks > 0 && atomicAdd(&d.sc[SC_DONE], wg_blocks) + wg_blocks == n_blocks) scan_epilogue(d, seq, advance, layer);
+  };
   if (b_cur >= b_end) {
-    if (MERGE && n_blocks == 0 && gw == 0 && lane == 0) scan_epilogue(d, seq, advance, layer);   // nothing to scan at all
+    if (MERGE) {
+      if (n_blocks == 0 && gw == 0 && lane == 0) scan_epilogue(d, seq, advance, layer);   // nothing to scan at all
+      wave_done();
+    }
     return;
   }
   float* lds_lg = s_lg[threadIdx.x >> 6];
@@ -882,9 +897,7 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
     it = it_next;
     cur = nxt;
   }
-  if (MERGE && lane == 0) {
-    if (atomicAdd(&d.sc[SC_DONE], b_mine) + b_mine == n_blocks) scan_epilogue(d, seq, advance, layer);
-  }
+  if (MERGE) wave_done();
 }
 
 // ------------------------------------------------------------------ eviction
