@@ -1102,11 +1102,14 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
 
 // ------------------------------------------------------------------ finish
 // Ends a kernel that must leave the step scalars consistent: the last block
-// to arrive resets the work list and, if asked, advances time.
+// to arrive resets the work list and, if asked, advances time.  No fence: the
+// last block reads nothing the others wrote (the scalars it updates are read-only
+// during the launch, and every claim on the queue has returned before its
+// workgroup gets here); the end of the kernel publishes what it writes.  A
+// device-scope fence here would write back a whole L2 once per workgroup.
 __device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, int tid, int queue_reset = -1) {
   __syncthreads();
   if (tid == 0) {
-    __threadfence();
     const int prev = atomicAdd(&d.sc[SC_DONE], 1);
     if (prev == (int)gridDim.x - 1) {
       d.sc[SC_DONE] = 0;
@@ -1118,7 +1121,6 @@ __device__ __forceinline__ void step_epilogue(const Dev& d, int t, int advance, 
         d.sc[SC_T] = t + 1;
         d.sc[SC_WINDOW_STEPS] = d.sc[SC_WINDOW_STEPS] + 1;
       }
-      __threadfence();
     }
   }
 }
