@@ -293,8 +293,8 @@ def test_per_layer_calls():
     g.close()
 
 
-@pytest.mark.parametrize("prompt", [8, 333, 2100])
-def test_scan_that_merges_its_own_partials_gives_the_bits_of_the_finish_kernel(prompt):
+@pytest.mark.parametrize("prompt,bf16", [(8, False), (333, False), (2100, False), (333, True)])
+def test_scan_that_merges_its_own_partials_gives_the_bits_of_the_finish_kernel(prompt, bf16):
     """Attention-only steps and steps with deferred bookkeeping get their output from the scan itself (the
     wavefront that publishes a unit's last run merges the unit); plain steps get it from the finish kernel.
     Same cache, same queries: the same bits, and the oracle's values, for units of one block (several units
@@ -303,10 +303,12 @@ def test_scan_that_merges_its_own_partials_gives_the_bits_of_the_finish_kernel(p
     cfg = _small("qwen14b", n_layers=2, batch=2, n_q_heads=10, n_kv_heads=2, prompt=prompt, decode_steps=10,
                  budget=prompt + 20, budget_min=1, budget_max=prompt + 20, seed=17)
     cap = (prompt + 21 + 31) // 32 * 32
-    st, o, g_plain = _pair(cfg, cap=cap, path=1)
-    _, _, g_attn = _pair(cfg, cap=cap, stream=st, path=1)
-    _, _, g_defer = _pair(cfg, cap=cap, stream=st, path=1)
-    _, _, g_all = _pair(cfg, cap=cap, stream=st, path=1)
+    _, ckv, wl = _mods()
+    kw = dict(out_dtype=ckv.BF16) if bf16 else {}
+    st, o, g_plain = _pair(cfg, cap=cap, path=1, **kw)
+    _, _, g_attn = _pair(cfg, cap=cap, stream=st, path=1, **kw)
+    _, _, g_defer = _pair(cfg, cap=cap, stream=st, path=1, **kw)
+    _, _, g_all = _pair(cfg, cap=cap, stream=st, path=1, **kw)
     for s in range(cfg.decode_steps):
         ref, _ = o.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
         layers = range(cfg.n_layers)
@@ -316,10 +318,16 @@ def test_scan_that_merges_its_own_partials_gives_the_bits_of_the_finish_kernel(p
         c = torch.stack([g_defer.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l, evict=False, defer=True)
                          for l in layers])
         d = g_all.decode_step(st.q[s], st.k_new[s], st.v_new[s], attention_only=True)
-        assert parity.out_error(a.cpu().numpy(), ref) <= parity.OUT_TOL
-        assert parity.out_error(d.cpu().numpy(), ref) <= parity.OUT_TOL      # other shares, other rounding
+        if bf16:                                                             # within one bf16 ulp of the rounded reference
+            ref16 = wl.bf16_round(ref.astype(np.float32))
+            ulp = np.maximum(np.abs(ref16), 2.0 ** -126) * 2.0 ** -7
+            for x in (a, d):
+                assert np.all(np.abs(x.float().cpu().numpy() - ref16) <= ulp + parity.OUT_TOL * 1e-2 * np.abs(ref).max())
+        else:
+            assert parity.out_error(a.cpu().numpy(), ref) <= parity.OUT_TOL
+            assert parity.out_error(d.cpu().numpy(), ref) <= parity.OUT_TOL  # other shares, other rounding
         for name, other in (("attention only", b), ("deferred", c)):
-            assert torch.equal(a, other), (name, s, float((a - other).abs().max()))
+            assert torch.equal(a, other), (name, s, float((a.float() - other.float()).abs().max()))
         for g in (g_plain, g_attn, g_defer, g_all):
             assert g.time() == cfg.prompt + s + 1
     g_defer.join()
