@@ -125,7 +125,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -153,6 +153,7 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.rank = take(U * 4);
   c.sched = take(U * 16);
   c.layer_ts = take((size_t)l->n_layers * 8);
+  c.snew = take(U * kMaxGroup * 4);
   c.total = off;
   return c;
 }
@@ -369,6 +370,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.sched = (int4*)(ws + cv.sched);
   d.layer_ts = (int32_t*)(ws + cv.layer_ts);
   d.arrive = (int32_t*)(ws + cv.arrive);
+  d.snew = (float*)(ws + cv.snew);
 
   auto bail = [&](int rc) {
     ckv_destroy(c);
@@ -473,7 +475,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   const bool fused = fv != nullptr;
   if (int rc = join_side(c, s, layer)) return rc;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX);
+                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX, (const uint16_t*)q);
   CKV_HIP(c, hipGetLastError());
 
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -496,10 +498,10 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
                          advance, fv->lds_main);
     else if (fv->waves == 4)
       hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, c->dev, (const uint16_t*)q, out,
-                         flags, advance, fv->lds_main);
+                         flags, advance, fv->lds_main, (const uint16_t*)v_new);
     else
       hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, c->dev, (const uint16_t*)q, out,
-                         flags, advance, fv->lds_main);
+                         flags, advance, fv->lds_main, (const uint16_t*)v_new);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
     return CKV_OK;
@@ -557,7 +559,7 @@ int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, voi
   for (int j = 0; j < W; ++j) {
     const int t_j = P - W + j;                  // the query's position = its time; it sees positions 0 .. t_j
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin,
-                       count, (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, t_j + 1);
+                       count, (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, t_j + 1, (const uint16_t*)nullptr);
     CKV_HIP(c, hipGetLastError());
     const long long max_items = (long long)count * c->dev.max_chunks;
     long long blocks = 2ll * c->n_cu;
@@ -616,7 +618,7 @@ int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, 
   hipStream_t s = (hipStream_t)stream;
   if (int rc = join_side(c, s)) return rc;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, INT_MAX);
+                     (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, INT_MAX, (const uint16_t*)nullptr);
   CKV_HIP(c, hipGetLastError());
   const long long max_items = (long long)count * c->dev.max_chunks;
   long long blocks = 2ll * c->n_cu;

@@ -67,6 +67,7 @@ struct Dev {
   int4* sched;           // [units] schedule entry i: {unit order[i], its entry count after this step's append, its budget, 0}
   int32_t* layer_ts;     // [layers][2] time and launch sequence number of a layer's last deferred step (scan_kernel<true> -> finish_kernel with late = 1)
   int32_t* arrive;       // [units] runs of the unit published so far by a scan that also merges (zero between launches)
+  float* snew;           // [units][8] scaled logits (base-2 domain) of the entry appended in this step, per query head
 };
 
 
@@ -394,16 +395,18 @@ constexpr int kPrepThreads = 1024;
 constexpr int kPrepUnits = 32;
 
 __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begin, int unit_count, const uint16_t* k_new,
-                                                            const uint16_t* v_new, int append, int n_limit) {
+                                                            const uint16_t* v_new, int append, int n_limit,
+                                                            const uint16_t* __restrict__ q) {
   __shared__ int s_nch[kPrepUnits], s_nblk[kPrepUnits];
   __shared__ u64 s_base;
   const int tid = threadIdx.x, sub = tid & 31, slot = tid >> 5;
   const int w = blockIdx.x * kPrepUnits + slot;
   const bool active = w < unit_count;
   const int u = unit_begin + w;
-  int n = 0;
+  int n = 0, n_before = 0;
   if (active) {
     n = min(d.n[u], n_limit);            // n_limit < n: only the unit's first n_limit entries take part (prompt replay)
+    n_before = n;
     if (append & 1) {
       const int t = d.sc[SC_T];
       if (n >= d.cap) {
@@ -429,7 +432,25 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
     }
   }
   if (append & 2) {                       // the fused kernel schedules whole units: one schedule entry per unit, no work list
-    if (active && sub == 0) d.sched[d.rank[u]] = make_int4(u, n, d.budget[u], 0);
+    // It also gets the new entry's logits ready-made (fp32 dot products of the bf16 inputs): a new entry that
+    // opens a block of its own then needs no pass over that block.  Entry .w says whether one was appended.
+    const bool appended = active && n > n_before;
+    if (appended) {
+      const uint16_t* kr = k_new + (size_t)w * kDim + 4 * sub;
+      float kf[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) kf[e] = __uint_as_float((uint32_t)kr[e] << 16);
+      for (int g = 0; g < d.G; ++g) {
+        const uint16_t* qr = q + ((size_t)w * d.G + g) * kDim + 4 * sub;
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc += __uint_as_float((uint32_t)qr[e] << 16) * kf[e];
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 32);
+        if (sub == 0) d.snew[(size_t)u * kMaxGroup + g] = acc * d.scale_log2e;
+      }
+    }
+    if (active && sub == 0) d.sched[d.rank[u]] = make_int4(u, n, d.budget[u], appended ? 1 : 0);
     return;
   }
   const int nch = active ? (n + kChunk - 1) / kChunk : 0;

@@ -80,7 +80,8 @@ __global__ __launch_bounds__(1024) void schedule_kernel(Dev d) {
 // W wavefronts per workgroup (and per unit), 8 / W workgroups per CU.
 template <int W>
 __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* __restrict__ q, void* out,
-                                                             uint32_t call_flags, int advance, int lds_main) {
+                                                             uint32_t call_flags, int advance, int lds_main,
+                                                             const uint16_t* __restrict__ v_new) {
   constexpr int NT = 64 * W;
   constexpr int kSlices = W / 2;             // LDS slices the accumulators are merged through, two waves each
   extern __shared__ unsigned char smem[];
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   constexpr int kStageFloats = W * kMaxGroup * kLgRow, kOutFloats = kSlices * kMaxGroup * kDim;
   __shared__ float s_buf[kStageFloats > kOutFloats ? kStageFloats : kOutFloats];
   float* s_out = s_buf;
-  __shared__ float s_ml[W][kMaxGroup][2];
+  __shared__ float s_ml[W + 1][kMaxGroup][2];   // row W: the step's new entry when it is merged as a state of its own
   __shared__ __align__(16) float sM[kMaxGroup];
   __shared__ __align__(16) float sInv[kMaxGroup];
   __shared__ float s_tab[kTabLds];
@@ -115,15 +116,19 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   // result of the vector memory pipeline is a wait for all results requested before it).
   __shared__ int s_claim;
   const int grid = (int)gridDim.x, wg = (int)blockIdx.x;
-  auto fetch = [&](int slot, int& uu, int& nn, int& bb) {      // uniform slot: scalar loads
+  // `lone`: the entry appended in this step opens a block of its own (a fixed budget that is a multiple of 32
+  // makes that the steady state).  Its logits come ready-made from prep_kernel and its value row from the step's
+  // input, so it joins the merge as one more online-softmax state and the block is never streamed.
+  auto fetch = [&](int slot, int& uu, int& nn, int& bb, int& ll) {      // uniform slot: scalar loads
     const int4 e = d.sched[min(slot, n_units - 1)];
     uu = slot < n_units ? e.x : -1;
     nn = e.y;
     bb = e.z;
+    ll = (e.w != 0 && ((e.y - 1) & (kBlk - 1)) == 0) ? 1 : 0;
   };
-  int u, n, B, u1, n1, B1;
-  fetch(wg, u, n, B);
-  fetch(grid + wg, u1, n1, B1);
+  int u, n, B, lone, u1, n1, B1, lone1;
+  fetch(wg, u, n, B, lone);
+  fetch(grid + wg, u1, n1, B1, lone1);
   int slot2 = 2 * grid + wg;                                   // slot of the unit after next
   // Per-lane values are re-derived, from a copy of the lane index the compiler cannot see through, at
   // the start of every phase that needs them: otherwise they are computed once, kept alive across the
@@ -149,14 +154,15 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     }
   };
   if (u >= 0) {
-    const size_t o = first_off(u, n);
+    const size_t o = first_off(u, n - lone);
     load_k(ka, d.K + o);
     load_v(va, d.V + o);
     load_q(u);
   }
 
   while (u >= 0) {
-    const int nblk = (n + kBlk - 1) / kBlk;
+    const int ns = n - lone;                       // entries that are streamed
+    const int nblk = (ns + kBlk - 1) / kBlk;
     const int n_res = resident_entries(n, G, lds_main);
     const int res_blk = n_res / kBlk;
     const int my_cnt = wave < nblk ? (nblk - wave + W - 1) / W : 0;
@@ -164,8 +170,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     asm volatile("" : "+v"(slane));
     // ---- schedule entry of the unit after next: scalar loads, waited for with the first LDS access
     // below, a unit before they are needed
-    int u2, n2, B2;
-    fetch(slot2, u2, n2, B2);
+    int u2, n2, B2, lone2;
+    fetch(slot2, u2, n2, B2, lone2);
 
     // ---- stream this wave's blocks (wave + W i, i < my_cnt): while block i is computed, block i + 1 is
     // in flight; the last block's successor is the wave's first block of the next unit, so the loads
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     auto qk = [&](int blk, float (&sv)[8]) {
       const bool resident = blk < res_blk;
       float* lds_dst = (call_flags & 2u) ? nullptr : resident ? lg + (size_t)blk * (G * kBlk) : s_buf + wave * (kMaxGroup * kLgRow);
-      scan_qk(ka, qv, sv, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
+      scan_qk(ka, qv, sv, d.scale_log2e, 0, ns - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
               resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
     };
     for (int i = 0; i + 1 < my_cnt; ++i) {
@@ -195,8 +201,11 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     // without a next unit the prefetch reads this unit's first block again and is ignored
     const bool have_next = u1 >= 0;
     const int u_next = have_next ? u1 : u;
-    const int n_next = have_next ? n1 : n;
+    const int n_next = have_next ? n1 - lone1 : ns;
     const size_t o_next = first_off(u_next, n_next);
+    // the new entry's logit (threads below G) and value element, requested a block before they are used
+    const float snew = d.snew[(size_t)u * kMaxGroup + (slane & (kMaxGroup - 1))];
+    const uint16_t vnew = v_new[(size_t)u * kDim + (slane & 63) + 64 * (wave & 1)];
     if (my_cnt > 0) {
       float sv[8];
       qk(wave + W * (my_cnt - 1), sv);
@@ -231,6 +240,17 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       s_ml[wave][j][0] = m_run;
       s_ml[wave][j][1] = l_run;
     }
+    if (ftid < G) {
+      s_ml[W][ftid][0] = lone ? snew : -INFINITY;
+      s_ml[W][ftid][1] = lone ? 1.f : 0.f;
+      if (lone && !(call_flags & 2u)) {             // its logit where the bookkeeping looks for it: column 0 of its block
+        const int bn = (n - 1) / kBlk;
+        if (bn < res_blk)
+          lg[(size_t)bn * (G * kBlk) + ftid * kBlk] = snew;
+        else
+          d.logits[(size_t)u * d.cap * G + (size_t)bn * (G * kBlk) + ftid * kBlk] = snew;
+      }
+    }
     __syncthreads();
 
     // ---- merge the four online-softmax states -> out.  Every thread derives the global max and
@@ -239,9 +259,9 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     asm volatile("" : "+v"(ftid));
     if (ftid < G) {
       float M = -INFINITY;
-      for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][ftid][0]);
+      for (int w = 0; w < W + 1; ++w) M = fmaxf(M, s_ml[w][ftid][0]);
       float L = 0.f;
-      for (int w = 0; w < W; ++w) {
+      for (int w = 0; w < W + 1; ++w) {
         const float m = s_ml[w][ftid][0];
         L += m > -INFINITY ? s_ml[w][ftid][1] * fast_exp2(m - M) : 0.f;
       }
@@ -255,7 +275,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         const int head = min(4 * kg + v, kMaxGroup - 1);
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][head][0]);
+        for (int w = 0; w < W + 1; ++w) M = fmaxf(M, s_ml[w][head][0]);
         const float m = s_ml[wave][head][0];
         sc[v] = m > -INFINITY ? fast_exp2(m - M) : 0.f;
       }
@@ -282,6 +302,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       const int g = o >> 7;
       float y = s_out[o];
       if (kSlices == 2) y += s_out[kMaxGroup * kDim + o];
+      if (lone) y += fast_exp2(s_ml[W][g][0] - sM[g]) * __uint_as_float((uint32_t)vnew << 16);
       y *= sInv[g];
       const size_t oi = (size_t)u * G * kDim + o;
       if (d.out_bf16)
@@ -390,6 +411,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     u1 = u2;
     n1 = n2;
     B1 = B2;
+    lone = lone1;
+    lone1 = lone2;
     slot2 = __builtin_amdgcn_readfirstlane(s_claim);
   }
   step_epilogue(d, t, advance, tid, 0);

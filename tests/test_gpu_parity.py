@@ -90,6 +90,38 @@ def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     g.close()
 
 
+@pytest.mark.parametrize("path", [3, 4, 5])
+@pytest.mark.parametrize("hq", [2, 10, 16])
+def test_new_entry_alone_in_its_block(path, hq):
+    """Budgets that are multiples of 32: in the steady state every unit holds B + 1 entries while it attends, the
+    new one alone in the last block.  The fused kernel then does not stream that block: the entry joins the
+    merge as a state of its own (logits from prep_kernel, value row from the step's input).  From an empty
+    cache (the first entry is alone too) through growth over block boundaries into the steady state."""
+    cfg = _small("qwen14b", n_layers=2, batch=2, n_q_heads=hq, n_kv_heads=2, prompt=0, decode_steps=150,
+                 budget=64, budget_min=1, budget_max=128, seed=37)
+    budgets = np.array([[[64, 96], [32, 128]], [[64, 64], [96, 32]]], dtype=np.int32)
+    st, o, g = _pair(cfg, cap=160, budgets=budgets, path=path, load=False)
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=25)
+    assert stats.resynced <= 2, stats.notes
+    assert np.array_equal(g.lengths(), budgets) and g.status() == 0
+    g.close()
+
+
+@pytest.mark.parametrize("path", [3, 4])
+def test_new_entry_alone_in_a_block_whose_logits_live_in_global_memory(path):
+    """As above for a unit too long for the LDS tile: the lone entry's logits take the global-memory route."""
+    cfg = _small("qwen7b", n_layers=1, batch=1, n_q_heads=16, n_kv_heads=2, prompt=2890, decode_steps=6,
+                 budget=1800, budget_min=600, budget_max=3071, seed=15)
+    budgets = np.array([[[2880, 704]]], dtype=np.int32)
+    st, o, g = _pair(cfg, cap=3072, budgets=budgets, path=path)
+    _, lds_main = g.path_info()
+    assert 2881 * 8 * 4 > lds_main
+    stats = parity.lockstep(g, o, st, cfg.decode_steps, check_kv_every=3)
+    assert stats.resynced <= 1, stats.notes
+    assert g.lengths().tolist() == [[[2880, 704]]]
+    g.close()
+
+
 @pytest.mark.parametrize("path,n_big", [(3, 4500), (3, 8300), (4, 2500), (4, 4400), (5, 1900), (5, 8300)])
 def test_fused_kernel_large_units(path, n_big):
     """Units beyond 16 entries per thread: 17..32 per thread keep the weights in registers with the per-entry
