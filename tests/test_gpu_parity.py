@@ -169,7 +169,8 @@ def test_attention_only_steps(path):
     scores and taus of the old entries stay as loaded, the new entries arrive with CRF 0 and tau = pos = t,
     nothing is evicted; combining it with eviction is refused."""
     _, ckv, _ = _mods()
-    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, prompt=70, decode_steps=12, budget=60, seed=31)
+    # prompt 60: the caches grow across a block boundary (64), where the new entry is alone in its block
+    cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, prompt=60, decode_steps=12, budget=60, seed=31)
     st, o, g = _pair(cfg, cap=128, path=path)
     before = {key: g.export_unit(*key, with_kv=False) for key in o.units}
     for s in range(cfg.decode_steps):
