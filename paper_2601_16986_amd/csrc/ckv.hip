@@ -495,7 +495,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (fused) {
     if (fv == &c->fused[2])
       hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, c->dev, (const uint16_t*)q, out, flags,
-                         advance, fv->lds_main);
+                         advance, fv->lds_main, (const uint16_t*)v_new);
     else if (fv->waves == 4)
       hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, c->dev, (const uint16_t*)q, out,
                          flags, advance, fv->lds_main, (const uint16_t*)v_new);

@@ -430,14 +430,15 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
 // unit_kernel, one stage deeper: a slot is claimed four units ahead, so that the claim's result is never
 // waited for.
 __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_t* __restrict__ q, void* out,
-                                                            uint32_t call_flags, int advance, int lds_tile) {
+                                                            uint32_t call_flags, int advance, int lds_tile,
+                                                            const uint16_t* __restrict__ v_new) {
   constexpr int W = 4, NT = 256, kSlices = 2;
   extern __shared__ unsigned char smem[];
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + 2 * (size_t)lds_tile);
   constexpr int kStageFloats = W * kMaxGroup * kLgRow, kOutFloats = kSlices * kMaxGroup * kDim;
   __shared__ float s_buf[kStageFloats > kOutFloats ? kStageFloats : kOutFloats];
   float* s_out = s_buf;
-  __shared__ float s_ml[W][kMaxGroup][2];
+  __shared__ float s_ml[W + 1][kMaxGroup][2];   // row W: a new entry alone in its block (as in unit_kernel)
   __shared__ __align__(16) float sM[2][kMaxGroup];
   __shared__ __align__(16) float sInv[2][kMaxGroup];
   __shared__ float s_tab[kTabLds];
@@ -461,16 +462,17 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
   __syncthreads();
 
   const int grid = (int)gridDim.x, wg = (int)blockIdx.x;
-  auto fetch = [&](int slot, int& uu, int& nn, int& bb) {      // uniform slot: scalar loads
+  auto fetch = [&](int slot, int& uu, int& nn, int& bb, int& ll) {      // uniform slot: scalar loads
     const int4 e = d.sched[min(slot, n_units - 1)];
     uu = slot < n_units ? e.x : -1;
     nn = e.y;
     bb = e.z;
+    ll = (e.w != 0 && ((e.y - 1) & (kBlk - 1)) == 0) ? 1 : 0;  // the new entry opens a block of its own
   };
-  int u, n, B, u1, n1, B1;
+  int u, n, B, lone, u1, n1, B1, lone1;
   int up = -1, np_ = 0, Bp = 0;                                // the book-keeper's unit: the streamers' previous one
-  fetch(wg, u, n, B);
-  fetch(grid + wg, u1, n1, B1);
+  fetch(wg, u, n, B, lone);
+  fetch(grid + wg, u1, n1, B1, lone1);
   int slot2 = 2 * grid + wg;
   int par = 0, iter = 0;
   int slane = lane;
@@ -489,7 +491,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
     for (int s = 0; s < 4; ++s) qv[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * s));
   };
   if (streamer && u >= 0) {
-    const size_t o = first_off(u, n);
+    const size_t o = first_off(u, n - lone);
     load_k(ka, d.K + o);
     load_v(va, d.V + o);
     load_q(u);
@@ -497,16 +499,18 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
 
   // The two roles run their own copy of the unit loop (same trip count, four barriers per iteration
   // each): what one role keeps in registers across iterations must not count against the other.
-  auto rotate = [&](int u2, int n2, int B2) {
+  auto rotate = [&](int u2, int n2, int B2, int lone2) {
     up = u;
     np_ = n;
     Bp = B;
     u = u1;
     n = n1;
     B = B1;
+    lone = lone1;
     u1 = u2;
     n1 = n2;
     B1 = B2;
+    lone1 = lone2;
     slot2 = __builtin_amdgcn_readfirstlane(s_claim);
     par ^= 1;
     ++iter;
@@ -514,15 +518,17 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
   if (streamer) {
     int claimed_prev = -1;                                     // thread 0: the claim made one unit ago (-1: none)
     while (u >= 0 || up >= 0) {
-      int u2, n2, B2;
-      fetch(slot2, u2, n2, B2);
+      int u2, n2, B2, lone2;
+      fetch(slot2, u2, n2, B2, lone2);
       float* lg = reinterpret_cast<float*>(smem + (size_t)par * lds_tile);
       f32x4 acc[8];
+      uint16_t vnew = 0;
       int claimed = -1;
       const bool merge = u >= 0;
       if (merge) {
         // ---- stream unit u (as in unit_kernel)
-        const int nblk = (n + kBlk - 1) / kBlk;
+        const int ns = n - lone;                               // entries that are streamed
+        const int nblk = (ns + kBlk - 1) / kBlk;
         const int res_blk = resident_entries(n, G, lds_tile) / kBlk;
         const int my_cnt = wave < nblk ? (nblk - wave + W - 1) / W : 0;
         asm volatile("" : "+v"(slane));
@@ -535,7 +541,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
         auto qk = [&](int blk, float (&sv)[8]) {
           const bool resident = blk < res_blk;
           float* lds_dst = resident ? lg + (size_t)blk * (G * kBlk) : s_buf + wave * (kMaxGroup * kLgRow);
-          scan_qk(ka, qv, sv, d.scale_log2e, 0, n - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
+          scan_qk(ka, qv, sv, d.scale_log2e, 0, ns - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
                   resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
         };
         for (int i = 0; i + 1 < my_cnt; ++i) {
@@ -546,6 +552,9 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
           scan_pv<true>(sv, va, acc, m_run, l_run, slane);
           load_v(va, vcur + (size_t)(blk + W) * kBlkElems);
         }
+        // the new entry's logit (threads below G) and value element, requested a block before they are used
+        const float snew = d.snew[(size_t)u * kMaxGroup + (slane & (kMaxGroup - 1))];
+        vnew = v_new[(size_t)u * kDim + (slane & 63) + 64 * (wave & 1)];
         if (my_cnt > 0) {
           float sv[8];
           qk(wave + W * (my_cnt - 1), sv);
@@ -554,7 +563,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
         // the stream goes on with the next unit's first block (this unit's again if there is none)
         const bool have_next = u1 >= 0;
         const int u_next = have_next ? u1 : u;
-        const size_t o_next = first_off(u_next, have_next ? n1 : n);
+        const size_t o_next = first_off(u_next, have_next ? n1 - lone1 : ns);
         load_k(ka, d.K + o_next);
         load_v(va, d.V + o_next);
         load_q(u_next);
@@ -573,6 +582,19 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
           s_ml[wave][j0][0] = m_run;
           s_ml[wave][j0][1] = l_run;
         }
+        int t0 = tid;
+        asm volatile("" : "+v"(t0));
+        if (t0 < G) {
+          s_ml[W][t0][0] = lone ? snew : -INFINITY;
+          s_ml[W][t0][1] = lone ? 1.f : 0.f;
+          if (lone) {                                          // its logit where the book-keepers look for it
+            const int bn = (n - 1) / kBlk;
+            if (bn < res_blk)
+              lg[(size_t)bn * (G * kBlk) + t0 * kBlk] = snew;
+            else
+              d.logits[(size_t)u * d.cap * G + (size_t)bn * (G * kBlk) + t0 * kBlk] = snew;
+          }
+        }
       }
       __syncthreads();                                         // (1) s_ml of unit u complete
 
@@ -585,9 +607,9 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
       if (merge) {
         if (ftid < G) {
           float M = -INFINITY;
-          for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][ftid][0]);
+          for (int w = 0; w < W + 1; ++w) M = fmaxf(M, s_ml[w][ftid][0]);
           float L = 0.f;
-          for (int w = 0; w < W; ++w) {
+          for (int w = 0; w < W + 1; ++w) {
             const float m = s_ml[w][ftid][0];
             L += m > -INFINITY ? s_ml[w][ftid][1] * fast_exp2(m - M) : 0.f;
           }
@@ -599,7 +621,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
           const int head = min(4 * kg + v, kMaxGroup - 1);
           float M = -INFINITY;
 #pragma unroll
-          for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][head][0]);
+          for (int w = 0; w < W + 1; ++w) M = fmaxf(M, s_ml[w][head][0]);
           const float m = s_ml[wave][head][0];
           sc[v] = m > -INFINITY ? fast_exp2(m - M) : 0.f;
         }
@@ -625,7 +647,9 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
       if (merge) {
         for (int o = ftid; o < G * kDim; o += NT) {
           const int g = o >> 7;
-          const float y = (s_out[o] + s_out[kMaxGroup * kDim + o]) * sInv[par][g];
+          float y = s_out[o] + s_out[kMaxGroup * kDim + o];
+          if (lone) y += fast_exp2(s_ml[W][g][0] - sM[par][g]) * __uint_as_float((uint32_t)vnew << 16);
+          y *= sInv[par][g];
           const size_t oi = (size_t)u * G * kDim + o;
           if (d.out_bf16)
             reinterpret_cast<__bf16*>(out)[oi] = (__bf16)y;
@@ -637,12 +661,12 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
       if (tid == 0) s_claim = iter == 0 ? 3 * grid + wg : claimed_prev >= 0 ? 4 * grid + claimed_prev : n_units;
       claimed_prev = claimed;
       __syncthreads();                                         // (4) s_out and the staging tiles are free; s_claim is set
-      rotate(u2, n2, B2);
+      rotate(u2, n2, B2, lone2);
     }
   } else {
     while (u >= 0 || up >= 0) {
-      int u2, n2, B2;
-      fetch(slot2, u2, n2, B2);
+      int u2, n2, B2, lone2;
+      fetch(slot2, u2, n2, B2, lone2);
       if (up >= 0) {
         // ---- Alg. 1 Steps 1-4 of the previous unit, from the other tile (the code of unit_kernel's
         // bookkeeping phase, 256 threads, with the book-keepers' own barrier)
@@ -725,7 +749,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
       __syncthreads();                                         // (2)
       __syncthreads();                                         // (3)
       __syncthreads();                                         // (4)
-      rotate(u2, n2, B2);
+      rotate(u2, n2, B2, lone2);
     }
   }
   __syncthreads();
