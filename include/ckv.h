@@ -250,13 +250,15 @@ int ckv_import_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int3
 int ckv_profile_enable(ckv_ctx* ctx, int32_t on);
 int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
 
-/* Which kernels ckv_decode_step(layer = -1) uses: 0 = choose by unit count
- * (default), 1 = separate scan and finish kernels (always used for single-layer
- * calls), 2 = the fused per-unit kernel, which keeps the logits in LDS, in the
- * widest variant that fits; 3 / 4 = the fused kernel with 4 / 2 wavefronts per
- * unit (2 / 4 workgroups per compute unit); 5 = the fused kernel with four
- * streaming wavefronts and a fifth that does the bookkeeping of the previous
- * unit meanwhile (two logits tiles per workgroup).  A variant needs 4 * cap
+/* Which kernels ckv_decode_step uses: 0 = choose by unit count (default),
+ * 1 = separate scan and finish kernels, 2 = the fused per-unit kernel, which
+ * keeps the logits in LDS, in the widest variant that fits; 3 / 4 = the fused
+ * kernel with 4 / 2 wavefronts per unit (2 / 4 workgroups per compute unit);
+ * 5 = the fused kernel with four streaming wavefronts and four that do the
+ * bookkeeping of the previous unit meanwhile (two logits tiles per workgroup).
+ * Whatever the mode, a single-layer call takes the separate kernels if the
+ * layer has fewer units than the fused kernel has workgroups or if its
+ * bookkeeping is deferred.  A variant needs 4 * cap
  * bytes of LDS in its workgroup's share, mode 5 in each of its two tiles
  * (CKV_EINVAL otherwise).  Results do not depend on the choice beyond
  * floating-point summation order.

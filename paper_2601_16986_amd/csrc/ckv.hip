@@ -469,13 +469,15 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   }
   hipStream_t s = (hipStream_t)stream;
 
-  const ckv_ctx::Fused* fv = layer == -1 ? fused_variant(c) : nullptr;
-  if (fv && c->path_mode == 0 && count < fv->grid) fv = nullptr;      // fewer units than workgroups: split the units instead
+  // The fused kernel takes whole units: all layers at once, or one layer that has at least a unit per
+  // workgroup (a step with deferred bookkeeping always takes the separate kernels).
+  const ckv_ctx::Fused* fv = (flags & CKV_DEFER_BOOKKEEPING) ? nullptr : fused_variant(c);
+  if (fv && (c->path_mode == 0 || layer >= 0) && count < fv->grid) fv = nullptr;   // fewer units than workgroups: split the units instead
   if (fv == &c->fused[2] && (flags & CKV_ATTENTION_ONLY)) fv = &c->fused[0];   // no bookkeeping to move aside
   const bool fused = fv != nullptr;
   if (int rc = join_side(c, s, layer)) return rc;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? 3 : 1, INT_MAX, (const uint16_t*)q);
+                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? (layer >= 0 ? 7 : 3) : 1, INT_MAX, (const uint16_t*)q);
   CKV_HIP(c, hipGetLastError());
 
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -493,15 +495,22 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     CKV_HIP(c, hipEventRecord(e0, s));
   }
   if (fused) {
+    // The kernel indexes its inputs, its output and the schedule by unit: for a single layer it gets the
+    // layer's part of the schedule (which prep_kernel has just filled in unit order) as if it were all there
+    // is, and pointers moved back by the layer's first unit, so that unit u finds row u - begin.
+    Dev dv = c->dev;
+    dv.sched = c->dev.sched + (layer >= 0 ? begin : 0);
+    dv.units = count;
+    const size_t rows = (size_t)(layer >= 0 ? begin : 0);
+    const uint16_t* qb = (const uint16_t*)q - rows * dv.G * kDim;
+    const uint16_t* vb = (const uint16_t*)v_new - rows * kDim;
+    void* ob = (char*)out - rows * dv.G * kDim * (dv.out_bf16 ? 2 : 4);
     if (fv == &c->fused[2])
-      hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, c->dev, (const uint16_t*)q, out, flags,
-                         advance, fv->lds_main, (const uint16_t*)v_new);
+      hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
     else if (fv->waves == 4)
-      hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, c->dev, (const uint16_t*)q, out,
-                         flags, advance, fv->lds_main, (const uint16_t*)v_new);
+      hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
     else
-      hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, c->dev, (const uint16_t*)q, out,
-                         flags, advance, fv->lds_main, (const uint16_t*)v_new);
+      hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
     return CKV_OK;

@@ -450,7 +450,8 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
         if (sub == 0) d.snew[(size_t)u * kMaxGroup + g] = acc * d.scale_log2e;
       }
     }
-    if (active && sub == 0) d.sched[d.rank[u]] = make_int4(u, n, d.budget[u], appended ? 1 : 0);
+    // all layers: the slot the budget order gives the unit; one layer (append & 4): the units in their own order
+    if (active && sub == 0) d.sched[(append & 4) ? u : d.rank[u]] = make_int4(u, n, d.budget[u], appended ? 1 : 0);
     return;
   }
   const int nch = active ? (n + kChunk - 1) / kChunk : 0;

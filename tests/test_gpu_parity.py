@@ -326,6 +326,34 @@ def test_per_layer_calls():
     g.close()
 
 
+@pytest.mark.parametrize("path", [0, 5])
+def test_per_layer_calls_of_layers_with_a_unit_per_workgroup_take_the_fused_kernel(path):
+    """A layer of 512 units (batch 64 x 8 KV heads) fills the fused kernel's grid, so single-layer steps run
+    it on the layer's part of the schedule, with inputs and output addressed relative to the layer; all-layers
+    steps in between use the budget-ordered schedule again.  Lock-step with the oracle throughout."""
+    import torch
+    cfg = _small("llama8b", n_layers=2, batch=64, n_q_heads=16, n_kv_heads=8, prompt=20, decode_steps=14,
+                 budget=24, budget_min=1, budget_max=63, seed=43)
+    st, o, g = _pair(cfg, cap=64, path=path)
+    waves, _ = g.path_info()
+    assert waves == 4
+    stats = parity.LockstepStats()
+    for s in range(cfg.decode_steps):
+        ref, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        if s % 5 == 3:
+            out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s]).cpu().numpy()
+        else:
+            out = torch.stack([g.decode_step(st.q[s, l], st.k_new[s, l], st.v_new[s, l], layer=l)
+                               for l in range(cfg.n_layers)]).cpu().numpy()
+        assert parity.out_error(out, ref) <= parity.OUT_TOL
+        assert g.time() == cfg.prompt + s + 1
+        for key, rec in recs.items():
+            parity.compare_unit(g, o, key, rec, stats)
+    assert stats.resynced <= 3, stats.notes
+    assert g.status() == 0 and np.array_equal(g.lengths(), o.lengths())
+    g.close()
+
+
 @pytest.mark.parametrize("prompt,bf16", [(8, False), (333, False), (2100, False), (333, True)])
 def test_scan_that_merges_its_own_partials_gives_the_bits_of_the_finish_kernel(prompt, bf16):
     """Attention-only steps and steps with deferred bookkeeping get their output from the scan itself (the
