@@ -125,6 +125,7 @@ class HitDecision:
     order: np.ndarray          # entry indices, by (weight desc, position asc)
     sum_margin: float          # min(c_m* - p, p - c_(m*-1)): distance of the cut to p
     edge_gap: float            # relative weight gap between last-in and first-out
+    abar: np.ndarray = None    # the weights the decision was taken on (record keeping)
 
 
 def hit_mask(abar, pos, p, new_index=None):
@@ -152,7 +153,7 @@ def hit_mask(abar, pos, p, new_index=None):
         edge = (a_in - a_out) / a_in if a_in > 0 else 0.0
     else:
         edge = math.inf
-    return HitDecision(hit, m_star, order, float(min(upper, lower)), float(edge))
+    return HitDecision(hit, m_star, order, float(min(upper, lower)), float(edge), abar)
 
 
 # ----------------------------------------------------------------------------
@@ -459,6 +460,13 @@ class StepRecord:
     crf_sum: int               # fixed-point aggregated CRF
     evicted_pos: np.ndarray    # positions evicted in this step (sorted)
     evict_gap: float           # relative gap between the last kept and first evicted score
+    # the unit as it stood after the append and before Alg. 1 ran (record keeping for parity checks that
+    # replay Steps 2-4 under another admissible hit decision; no arithmetic)
+    t: int = 0
+    budget: int = 0
+    pre_pos: np.ndarray = None
+    pre_crf: np.ndarray = None
+    pre_tau: np.ndarray = None
 
 
 class CrystalKVOracle:
@@ -571,6 +579,7 @@ class CrystalKVOracle:
         u.crf = np.append(u.crf, np.float32(0.0))
         u.tau = np.append(u.tau, np.int64(t))
         n = u.n
+        pre = (u.pos.copy(), u.crf.copy(), u.tau.copy())
         y, a = attention(q, u.K, u.V, self.scale)
         abar = a.sum(axis=0) / float(self.G)
         if self.reward_mode == REWARD_TOPP_HIT:
@@ -588,7 +597,7 @@ class CrystalKVOracle:
         evicted_pos, gap = np.zeros(0, np.int64), math.inf
         if evict:
             evicted_pos, gap = self._evict_unit(u, tmp)
-        return StepRecord(y, abar, dec, tmp, s_fixed, evicted_pos, gap)
+        return StepRecord(y, abar, dec, tmp, s_fixed, evicted_pos, gap, t, u.budget, *pre)
 
     def _evict_unit(self, u, tmp, n_sink=None):
         if u.n <= u.budget:

@@ -1,10 +1,13 @@
 """Lock-step comparison of the HIP path with the CPU oracle (test helper).
 
 Both sides consume the same seeded inputs.  Information flows from the oracle
-to the GPU only: when a hit decision lies within rounding distance of its
-threshold (the oracle's own margins say so) and the GPU decided the other way,
-the GPU unit is re-imported from the oracle's state and the event is counted;
-any other difference fails the test.
+to the GPU only.  When a hit decision lies within rounding distance of its
+threshold (the oracle's own margins say so, and they are pinned by the CPU
+tests) the GPU may have decided the other way for the entries at the edge of
+the nucleus, and for those alone: the oracle replays Alg. 1 Steps 2-4 of that
+unit under every admissible alternative decision, the GPU's whole state must
+equal one of the outcomes bit for bit, the event is counted and the GPU unit is
+re-imported from the oracle's own state.  Any other difference fails the test.
 """
 from __future__ import annotations
 
@@ -40,7 +43,48 @@ def sync_unit_to_gpu(g, o, key):
     g.import_unit(*key, u.K.astype(np.float32), u.V.astype(np.float32), u.crf, u.tau, u.pos, o.t - 1)
 
 
-def compare_unit(g, o, key, rec, stats, *, check_kv=False, allow_resync=True):
+def edge_entries(rec, tol=MARGIN_TOL):
+    """Indices (into the step's pre-update arrays) of the entries a sub-margin decision may flip: the last
+    entry inside the nucleus and the first outside when the cut's sum lies within `tol` of p, and every
+    entry whose weight lies within `tol` (relative) of the weight at the cut.  `rec`: a StepRecord, or a
+    HitDecision whose last entry is the one that arrived in its step."""
+    d = getattr(rec, "decision", rec)
+    abar = d.abar
+    n = len(abar)
+    edge = set()
+    if d.m_star >= 1:
+        a_cut = abar[d.order[d.m_star - 1]]
+        if d.sum_margin < tol:
+            edge.add(int(d.order[d.m_star - 1]))
+            if d.m_star < n:
+                edge.add(int(d.order[d.m_star]))
+        if d.edge_gap < tol:
+            edge.update(int(i) for i in np.nonzero(np.abs(abar - a_cut) <= tol * a_cut)[0])
+    edge.discard(n - 1)                     # the entry appended this step is a hit whatever its weight
+    return sorted(edge)
+
+
+def admissible_outcomes(o, rec, max_edge=6):
+    """States the unit may be in after the step if the hit bits of the edge entries fall either way:
+    Steps 2-4 of Alg. 1 replayed by the oracle's own functions from the recorded pre-update state.
+    Yields dicts of pos, crf, tau, hit (position-sorted) and evicted_pos."""
+    from itertools import product
+    from oracle import crystal_kv as ok
+    edge = edge_entries(rec)
+    assert 0 < len(edge) <= max_edge, f"{len(edge)} entries at the edge of the nucleus"
+    base = rec.decision.hit
+    for bits in product((False, True), repeat=len(edge)):
+        hit = base.copy()
+        hit[edge] = bits
+        if np.array_equal(hit, base):
+            continue
+        tmp, crf, tau = ok.crf_update(rec.pre_crf, rec.pre_tau, rec.t, hit.astype(np.float32), hit, o.tab)
+        retain, evicted = ok.evict_select(tmp, rec.pre_pos, rec.budget)
+        srt = retain[np.argsort(rec.pre_pos[retain])]
+        yield dict(pos=rec.pre_pos[srt], crf=crf[srt], tau=tau[srt], hit=hit[srt], evicted_pos=np.sort(rec.pre_pos[evicted]))
+
+
+def compare_unit(g, o, key, rec, stats, *, check_kv=False, allow_resync=True, evicting=True):
     """Compare one unit after a step.  Returns True if the unit was re-imported."""
     u = o.units[key]
     e = g.export_unit(*key, with_kv=check_kv)
@@ -75,11 +119,28 @@ def compare_unit(g, o, key, rec, stats, *, check_kv=False, allow_resync=True):
             badh = np.nonzero((e["flags"][order_g] & 1).astype(bool) != u.hit[order_o])[0][:10]
             msg.append(f"hit differs at pos {gp[order_g][badh].tolist()}")
         raise AssertionError("\n".join(msg))
-    # sub-margin: only the entries at the edge of the nucleus may differ
+    # sub-margin: the GPU's state must be what Alg. 1 gives when only edge entries' hit bits differ
+    gs = dict(pos=gp[order_g], crf=e["crf"][order_g].view(np.uint32), tau=e["tau"][order_g],
+              hit=(e["flags"][order_g] & 1).astype(bool), evicted_pos=e["evicted_pos"])
+    if not evicting:
+        rec = _without_eviction(rec)
+    matched = any(len(c["pos"]) == len(gs["pos"]) and np.array_equal(c["pos"], gs["pos"])
+                  and np.array_equal(c["crf"].view(np.uint32), gs["crf"]) and np.array_equal(c["tau"], gs["tau"])
+                  and np.array_equal(c["hit"], gs["hit"]) and np.array_equal(c["evicted_pos"], gs["evicted_pos"])
+                  for c in admissible_outcomes(o, rec))
+    assert matched, (f"unit {key} at t={o.t - 1}: the decision is sub-margin (sum_margin {d.sum_margin:.3e}, edge_gap "
+                     f"{d.edge_gap:.3e}) but the GPU's state is none of the outcomes that flipping the edge entries "
+                     f"{rec.pre_pos[edge_entries(rec)].tolist()} allows")
     stats.resynced += 1
     stats.notes.append((o.t - 1, key, d.sum_margin, d.edge_gap))
     sync_unit_to_gpu(g, o, key)
     return True
+
+
+def _without_eviction(rec):
+    """The record of a step that ran without Step 4: the replay must not evict either."""
+    from dataclasses import replace
+    return replace(rec, budget=len(rec.pre_pos))
 
 
 def lockstep(g, o, stream, n_steps, *, evict=True, check_kv_every=0, on_step=None):
@@ -92,7 +153,7 @@ def lockstep(g, o, stream, n_steps, *, evict=True, check_kv_every=0, on_step=Non
         assert stats.max_out_err <= OUT_TOL, f"step {s}: attention output off by {stats.max_out_err}"
         ck = bool(check_kv_every) and (s % check_kv_every == check_kv_every - 1)
         for key, rec in recs.items():
-            compare_unit(g, o, key, rec, stats, check_kv=ck)
+            compare_unit(g, o, key, rec, stats, check_kv=ck, evicting=evict)
             stats.unit_steps += 1
         stats.steps += 1
         if on_step is not None:

@@ -232,7 +232,11 @@ def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam):
             assert e["n"] == P and np.array_equal(e["pos"], u.pos)
             if np.array_equal(e["crf"].view(np.uint32), u.crf.view(np.uint32)) and np.array_equal(e["tau"], u.tau):
                 continue
-            assert min(min(d.sum_margin, d.edge_gap) for d in dl) < parity.MARGIN_TOL, (key, e["crf"][:8], u.crf[:8])
+            # only entries at the edge of a sub-margin decision of the window may carry other scores
+            sub = [d for d in dl if min(d.sum_margin, d.edge_gap) < parity.MARGIN_TOL]
+            may = set(i for d in sub for i in parity.edge_entries(d))
+            differ = set(np.nonzero((e["crf"].view(np.uint32) != u.crf.view(np.uint32)) | (e["tau"] != u.tau))[0].tolist())
+            assert sub and differ <= may, (key, sorted(differ), sorted(may))
             parity.sync_unit_to_gpu(g, o, key)
             resync += 1
     assert resync <= 1
@@ -490,7 +494,7 @@ def test_eviction_on_its_own_and_after_a_budget_cut(path):
             out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False).cpu().numpy()
             assert parity.out_error(out, ref) <= parity.OUT_TOL
             for key, rec in recs.items():
-                parity.compare_unit(g, o, key, rec, stats)
+                parity.compare_unit(g, o, key, rec, stats, evicting=False)
             s += 1
         if rnd == 1:                      # cut budgets: k becomes large
             newb = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), 23, dtype=np.int32)
@@ -547,7 +551,7 @@ def test_sink_plus_recent_window_policy_matches_oracle(every, n_sink):
         out = g.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False).cpu().numpy()
         assert parity.out_error(out, ref) <= parity.OUT_TOL
         for key, rec in recs.items():
-            parity.compare_unit(g, o, key, rec, stats)
+            parity.compare_unit(g, o, key, rec, stats, evicting=False)
         if (s + 1) % every == 0:
             evict_and_compare()
     assert stats.resynced <= 2, stats.notes

@@ -512,3 +512,239 @@ def test_window_policy_keeps_a_sliding_window_through_decoding():
             assert sorted(u.pos.tolist()) == list(range(s)) + list(range(t - (B - s) + 1, t + 1))
             assert ev[key].tolist() == [t - (B - s)]
             assert all(crf_after_step[key][p] == c for p, c in zip(u.pos.tolist(), u.crf.tolist()))
+
+
+# ------------------------------------------------------------------ margins of the decisions
+def _frac(x):
+    return math.inf if x is None else x[0] / x[1]
+
+
+def test_hit_decision_margins_of_the_hand_worked_trace(golden_dir):
+    """`sum_margin` and `edge_gap` decide which GPU/oracle differences the parity tests may accept, so they
+    are pinned like any other output: the fixture lists, per step, the nucleus size, the distance of the cut
+    to p and the relative weight gap at the edge, all computed by hand."""
+    fx = json.load(open(os.path.join(golden_dir, "alg1_trace_8tok.json")))
+    for st in fx["steps"]:
+        d = ok.hit_mask(np.array(st["abar"]), np.array(st["live"]), fx["top_p"], new_index=len(st["live"]) - 1)
+        assert d.m_star == st["m_star"]
+        assert d.sum_margin == pytest.approx(st["sum_margin"], rel=1e-12, abs=1e-15)
+        want = _frac(st["edge_gap_fraction"])
+        assert d.edge_gap == (want if math.isinf(want) else pytest.approx(want, rel=1e-12, abs=1e-15))
+        # the order the margins refer to: weight descending, position ascending
+        ranked = sorted(range(len(st["live"])), key=lambda i: (-st["abar"][i], st["live"][i]))
+        assert d.order.tolist() == ranked
+
+
+def test_hit_decision_margins_on_constructed_edge_cases():
+    pos = np.arange(4)
+    # the cut lands 1e-7 above p: the margin is that distance, not the (large) distance below
+    d = ok.hit_mask(np.array([0.5, 0.3 + 1e-7, 0.1, 0.1 - 1e-7]), pos, 0.8)
+    assert d.m_star == 2 and d.sum_margin == pytest.approx(1e-7, rel=1e-6)
+    assert d.edge_gap == pytest.approx((0.3 + 1e-7 - 0.1) / (0.3 + 1e-7), rel=1e-12)
+    # the sum before the cut lies 2e-8 below p: that side is the margin
+    d = ok.hit_mask(np.array([0.8 - 2e-8, 0.1, 0.05 + 2e-8, 0.05]), pos, 0.8)
+    assert d.m_star == 2 and d.sum_margin == pytest.approx(2e-8, rel=1e-6)
+    # two weights 3e-7 apart (relative) at the edge
+    a_in = 0.2
+    a_out = a_in * (1 - 3e-7)
+    d = ok.hit_mask(np.array([0.5, a_in, a_out, 1 - 0.5 - a_in - a_out]), pos, 0.6)
+    assert d.m_star == 2 and d.edge_gap == pytest.approx(3e-7, rel=1e-6) and d.sum_margin == pytest.approx(0.1, rel=1e-9)
+    # exact tie at the edge: gap 0 (the position decides); no entry outside: gap infinite
+    assert ok.hit_mask(np.array([0.4, 0.3, 0.3]), np.array([5, 9, 2]), 0.6).edge_gap == 0.0
+    d = ok.hit_mask(np.array([0.5, 0.3, 0.2]), np.arange(3), 1.0)
+    assert d.m_star == 3 and math.isinf(d.edge_gap) and d.sum_margin == pytest.approx(1.0 - 0.8, rel=1e-12)
+    # a margin must never be negative and never exceed p or the last included weight
+    g = np.random.default_rng(17)
+    for _ in range(200):
+        n = int(g.integers(1, 30))
+        a = g.random(n) ** 3
+        a /= a.sum()
+        p = float(g.choice([0.3, 0.6, 0.9]))
+        d = ok.hit_mask(a, g.permutation(100)[:n], p)
+        assert 0.0 <= d.sum_margin <= max(p, 1 - p) + 1e-12 and d.edge_gap >= 0.0
+        srt = np.sort(a)[::-1]
+        c = np.cumsum(srt)
+        assert d.sum_margin <= srt[d.m_star - 1] + 1e-15       # both sides of the cut are within one weight of p
+        if d.m_star < n:
+            assert d.edge_gap == pytest.approx((srt[d.m_star - 1] - srt[d.m_star]) / srt[d.m_star - 1], abs=1e-12)
+
+
+def test_evict_gap_and_step_record_of_the_hand_worked_trace(golden_dir):
+    """The class's record of a step: evict_gap as computed by hand, and the pre-update state it keeps for
+    parity checks is the state the step started from (after the append)."""
+    fx = json.load(open(os.path.join(golden_dir, "alg1_trace_8tok.json")))
+    o = ok.CrystalKVOracle(1, 1, 1, 1, 8, np.full((1, 1, 1), fx["budget"]), lam=fx["lambda"],
+                           top_p=fx["top_p"], softmax_scale=1.0, t0=0)
+    prev = {}
+    for st in fx["steps"]:
+        t = st["t"]
+        k_new = np.zeros(8)
+        k_new[t] = 1.0
+        q = np.full(8, -1e4)
+        for ppos, w in zip(st["live"], st["abar"]):
+            q[ppos] = math.log(w)
+        rec = o.step_unit((0, 0, 0), q[None, :], k_new, np.zeros(8))
+        want = _frac(st["evict_gap_fraction"])
+        assert rec.evict_gap == (want if math.isinf(want) else pytest.approx(want, rel=1e-12))
+        assert rec.t == t and rec.budget == fx["budget"] and rec.pre_pos.tolist() == st["live"]
+        for p_, c_, tt in zip(rec.pre_pos.tolist(), rec.pre_crf.tolist(), rec.pre_tau.tolist()):
+            assert (c_, tt) == prev.get(p_, (0.0, t))           # stored state of the previous step; new entry: (0, t)
+        u = o.units[(0, 0, 0)]
+        prev = {p_: (c_, tt) for p_, c_, tt in zip(u.pos.tolist(), u.crf.tolist(), u.tau.tolist())}
+        o.t += 1
+
+
+# ------------------------------------------------------------------ aggregated CRF (Alg. 2 input)
+def test_crf_sum_fixed_hand_case_and_bound():
+    """Aggregated CRF of a head in 2^-20 fixed point.  Dyadic scores make floor(x 2^20) exact by hand:
+    1.5 -> 1572864, 0.25 -> 262144, 3 * 2^-22 -> 0 (floor, where rounding would give 1), 0.75 + 2^-20 + 2^-21
+    -> 786433, 2^-20 -> 1; total 2621442.  In general the fixed-point sum lies at most n * 2^-20 below the
+    plain float64 sum and never above it."""
+    tmp = np.array([1.5, 0.25, 3 * 2.0 ** -22, 0.75 + 2.0 ** -20 + 2.0 ** -21, 2.0 ** -20], np.float32)
+    assert ok.crf_sum_fixed(tmp) == 1572864 + 262144 + 0 + 786433 + 1 == 2621442
+    assert ok.crf_sum_fixed(np.zeros(0, np.float32)) == 0
+    assert ok.FIXED_POINT_ONE == 2 ** 20
+    g = np.random.default_rng(23)
+    for n in (1, 7, 300, 5000):
+        tmp = (g.random(n) * g.choice([1e-7, 1e-3, 1.0, 2.0], size=n)).astype(np.float32)
+        plain = float(np.sum(tmp.astype(np.float64)))
+        fixed = ok.crf_sum_fixed(tmp) / 2.0 ** 20
+        assert plain - n * 2.0 ** -20 <= fixed <= plain + 1e-12 * plain
+        assert isinstance(ok.crf_sum_fixed(tmp), int)
+
+
+def _dictated_step(o, key, t, live, weights, d=16):
+    """One decode step of unit `key` whose attention weights are dictated: one-hot keys (position i answers
+    on coordinate i) and a query whose logits are the logs of the wanted weights."""
+    k_new = np.zeros(d)
+    k_new[t] = 1.0
+    q = np.full(d, -1e4)
+    for p_, w in zip(live, weights):
+        q[p_] = math.log(w)
+    return o.step_unit(key, q[None, :], k_new, np.zeros(d))
+
+
+def test_rebudget_window_mean_equals_alg2_on_the_plain_mean_hand_case():
+    """Sec. 5.3 / Alg. 2 through the class: two layers x two heads start empty with budget 60 each and take
+    two decode steps with dictated weights.  Step t = 0: the lone new entry scores 1.  Step t = 1 (lambda
+    = 0.5, p = 0.6): in units A the old entry gets weight 0.9 (hit: 0.5 * 1 + 1 = 1.5, plus the new entry's 1
+    -> 2.5), in unit B the new entry gets 0.9 (old entry missed: 0.5, plus 1 -> 1.5).  Window means of the
+    aggregated CRF: A = (1 + 2.5) / 2 = 1.75, B = (1 + 1.5) / 2 = 1.25.  Layer 0 = (A, B), layer 1 = (A, A).
+    Alg. 2 by hand: eta_0 = 3 / 120, eta_1 = 3.5 / 120; B'_0 = 240 * 3 / 6.5 = 110.77, B'_1 = 129.23 ->
+    integers 111, 129 (floor, the unit left over to the larger fraction); heads of layer 0: 111 * 1.75 / 3 =
+    64.75 and 46.25 -> 65, 46; heads of layer 1: 64.5 each -> 65, 64 (tie: lower index).  The scores are
+    dyadic, so the 2^-20 fixed-point accumulator is exact and the class must agree with Alg. 2 applied to
+    the plain float64 means."""
+    o = ok.CrystalKVOracle(2, 1, 2, 2, 16, np.full((2, 1, 2), 60), lam=0.5, top_p=0.6, softmax_scale=1.0, t0=0,
+                           budget_min=10, budget_max=100)
+    unit_b = (0, 0, 1)
+    sums = {key: [] for key in o.units}
+    for t in range(2):
+        for key in o.units:
+            if t == 0:
+                rec = _dictated_step(o, key, 0, [0], [1.0])
+            elif key == unit_b:
+                rec = _dictated_step(o, key, 1, [0, 1], [0.1, 0.9])
+            else:
+                rec = _dictated_step(o, key, 1, [0, 1], [0.9, 0.1])
+            sums[key].append(float(np.sum(rec.tmp.astype(np.float64))))     # plain sum of this step's CRF_temp
+            assert rec.crf_sum == int(round(sums[key][-1] * 2 ** 20))       # dyadic: the fixed point is exact
+        o.t += 1
+        o.window_steps += 1
+    assert sums[unit_b] == [1.0, 1.5] and sums[(0, 0, 0)] == [1.0, 2.5]
+    C_plain = np.array([[np.mean(sums[(l, 0, h)]) for h in range(2)] for l in range(2)])
+    assert C_plain.tolist() == [[1.75, 1.25], [1.75, 1.75]]
+    want = ok.rebudget(C_plain, np.full((2, 2), 60), 240, 10, 100)
+    got = o.rebudget()
+    assert got[:, 0, :].tolist() == want.tolist() == [[65, 46], [65, 64]]
+    # the real-valued shares of Alg. 2 Steps 1-4 that these integers round
+    Bl, Bh = ok.budget_shares(C_plain, np.full((2, 2), 60), 240)
+    assert np.allclose(Bl, [240 * 3 / 6.5, 240 * 3.5 / 6.5], rtol=1e-14)
+    assert np.allclose(Bh, [[Bl[0] * 1.75 / 3, Bl[0] * 1.25 / 3], [Bl[1] / 2, Bl[1] / 2]], rtol=1e-14)
+    # the window restarts: a second call without steps in between changes nothing
+    assert o.window_steps == 0 and all(u.crf_window == 0 for u in o.units.values())
+    assert np.array_equal(o.rebudget(), got)
+
+
+def test_rebudget_window_mean_is_a_mean_over_steps_not_a_sum_or_last_value():
+    """Units whose per-step aggregated CRF differ between steps: the class's budgets must equal Alg. 2 on the
+    mean over the window's steps of the plain float64 sums (to within the fixed point's 2^-20 per entry, which
+    cannot move these budgets: the test checks that), for windows of 1, 3 and 5 steps, random geometry."""
+    g = np.random.default_rng(31)
+    for n_steps in (1, 3, 5):
+        L, H = 3, 2
+        budgets = g.integers(20, 60, size=(L, 1, H))
+        cfg = wl.scaled(wl.CONFIGS["tiny"], n_layers=L, batch=1, n_q_heads=2 * H, n_kv_heads=H, prompt=12, decode_steps=n_steps,
+                        budget=40, budget_min=5, budget_max=100, seed=400 + n_steps)
+        st = wl.make_stream(cfg, tiny_heavy=False)
+        o = ok.CrystalKVOracle(L, 1, 2 * H, H, 128, budgets, lam=0.7, top_p=0.9, t0=12, budget_min=5, budget_max=100)
+        for l in range(L):
+            o.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+        acc = np.zeros((L, H))
+        for s in range(n_steps):
+            _, recs = o.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+            for (l, b, h), r in recs.items():
+                acc[l, h] += float(np.sum(r.tmp.astype(np.float64)))
+        C_plain = acc / n_steps
+        n_max = 12 + n_steps
+        want = ok.rebudget(C_plain, budgets[:, 0, :], int(budgets.sum()), 5, 100)
+        # the fixed point lowers every mean by at most n 2^-20: budgets computed from the lowered means
+        lowered = ok.rebudget(C_plain - n_max * 2.0 ** -20, budgets[:, 0, :], int(budgets.sum()), 5, 100)
+        got = o.rebudget()[:, 0, :]
+        assert np.array_equal(want, lowered), "pick another seed: this case sits on a rounding edge"
+        assert np.array_equal(got, want)
+        if n_steps > 1:
+            # the case has the power to tell the window mean from the last step's value alone (Alg. 2 is scale
+            # invariant, so a sum and a mean over the same steps are the same input by construction)
+            last = np.array([[float(np.sum(recs[(l, 0, h)].tmp.astype(np.float64))) for h in range(H)] for l in range(L)])
+            assert not np.array_equal(ok.rebudget(last, budgets[:, 0, :], int(budgets.sum()), 5, 100), want)
+
+
+# ------------------------------------------------------------------ Alg. 1 Step 4 on its own
+def test_standalone_evict_uses_scores_decayed_to_the_last_step():
+    """`current_tmp` / `evict()`: Step 4 called between steps ranks entries by CRF_temp at the time of the
+    last completed step.  Pins: (i) the closed form of Sec. 5.2 for an entry not accessed since tau,
+    lambda^(t_last - tau) CRF(tau), and the full closed form sum_j lambda^(t_last - t_j) over the logged hit
+    times; (ii) a step without eviction followed by evict() leaves what the same step with eviction
+    leaves; (iii) brute force: the evicted entries are the lowest under (closed-form score, higher
+    position first)."""
+    lam = 0.5
+    cfg = wl.scaled(wl.CONFIGS["tiny"], prompt=20, decode_steps=30, budget=24, budget_min=1, budget_max=64, seed=77)
+    st = wl.make_stream(cfg)
+    mk = lambda: ok.CrystalKVOracle(1, 1, 8, 2, 128, np.full((1, 1, 2), 24), lam=lam, top_p=0.9, t0=20)
+    a, b = mk(), mk()
+    for o in (a, b):
+        o.load_prompt(0, st.prompt_k[0], st.prompt_v[0])
+    hits = {key: {p_: [19] for p_ in range(20)} for key in a.units}       # prompt entries: referenced at P - 1
+    for s in range(30):
+        lazy = s % 4 != 3                                       # `a` evicts only every fourth step, on its own
+        _, recs = a.decode_step(st.q[s], st.k_new[s], st.v_new[s], evict=False)
+        t_last = a.t - 1
+        for key, r in recs.items():
+            u = a.units[key]
+            hits[key][t_last] = []
+            for p_, h in zip(u.pos.tolist(), r.decision.hit.tolist()):
+                if h:
+                    hits[key][p_].append(t_last)
+            tmp = a.current_tmp(u)
+            for i, p_ in enumerate(u.pos.tolist()):
+                closed = sum(lam ** (t_last - tj) for tj in hits[key][p_])
+                assert float(tmp[i]) == pytest.approx(closed, rel=1e-6)
+                assert float(tmp[i]) == pytest.approx(float(u.crf[i]) * lam ** (t_last - int(u.tau[i])), rel=1e-6)
+            assert np.array_equal(tmp, r.tmp)                   # the step's own CRF_temp, recomputed from the stored state
+        if lazy:
+            continue
+        # catch `b` up with fused evictions only on the same steps: both must agree after a.evict()
+        before = {key: (u.pos.copy(), a.current_tmp(u)) for key, u in a.units.items()}
+        ev = a.evict()
+        for key, (pos0, tmp0) in before.items():
+            ranked = sorted(range(len(pos0)), key=lambda i: (float(tmp0[i]), -int(pos0[i])))
+            k = len(pos0) - 24
+            assert sorted(pos0[ranked[:k]].tolist()) == ev[key].tolist() and len(ev[key]) == k == (0 if s == 3 else 4)
+            for p_ in ev[key].tolist():
+                del hits[key][p_]
+        for s2 in range(s - 3, s + 1):
+            b.decode_step(st.q[s2], st.k_new[s2], st.v_new[s2], evict=(s2 == s))
+        for key in a.units:
+            ua, ub = a.units[key], b.units[key]
+            assert np.array_equal(ua.pos, ub.pos) and np.array_equal(ua.crf, ub.crf) and np.array_equal(ua.tau, ub.tau)
