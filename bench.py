@@ -33,12 +33,15 @@ RING = 32                     # distinct synthetic step inputs, replayed cyclica
                               # with copies of a few keys drifts into the (slow, unrealistic) tie-breaking paths
 
 
-def build_workload(cfg, device):
+def build_workload(cfg, device, budgets=None):
+    """Steady-state caches of the workload on the device (every unit full at its budget), plus the ring of
+    step inputs.  budgets: override of the workload's own draw (tests place units at chosen sizes)."""
     import numpy as np
     import torch
     from paper_2601_16986_amd import ckv, workloads as wl
 
-    budgets = wl.draw_budgets(cfg)
+    if budgets is None:
+        budgets = wl.draw_budgets(cfg)
     cap = (cfg.budget_max + 1 + 31) // 32 * 32
     t_now = cfg.prompt + cfg.decode_steps // 2
     g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
@@ -153,42 +156,84 @@ def measured_traffic(kernel_name, workload):
     return None
 
 
-def cpu_baseline(cfg, budgets, seconds=15.0):
-    """Time the numpy oracle on a few units of the same workload; scale by entries."""
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _oracle_worker(job):
+    """Steps the oracle over this worker's units (their own caches and the workload's own step inputs,
+    cycled) until the deadline; one BLAS thread.  Returns (cached entries attended, wall seconds)."""
     import numpy as np
     from threadpoolctl import threadpool_limits
     from oracle import crystal_kv as ok
-    from paper_2601_16986_amd import workloads as wl
-
-    flat = np.asarray(budgets).reshape(-1)
-    t_now = cfg.prompt + cfg.decode_steps // 2
-    m = wl.mean_query(wl.scaled(cfg, n_layers=1, batch=1))      # one layer/sequence worth of directions
-    sample = [int(u) for u in np.linspace(0, flat.size - 1, 6).astype(int)]
-    o = ok.CrystalKVOracle(1, 1, cfg.group * len(sample), len(sample), cfg.head_dim,
-                           np.asarray([flat[u] for u in sample]).reshape(1, 1, -1), lam=cfg.lam, top_p=cfg.top_p, t0=t_now)
-    rng = np.random.default_rng(0)
-    for i, u in enumerate(sample):
-        c = wl.steady_unit(cfg, u, int(flat[u]), t_now, m[0, 0, i % m.shape[2]])
+    cfg, t_now, caches, inputs, seconds = job
+    o = ok.CrystalKVOracle(1, 1, cfg.group * len(caches), len(caches), cfg.head_dim,
+                           np.asarray([c[1] for c in caches]).reshape(1, 1, -1), lam=cfg.lam, top_p=cfg.top_p, t0=t_now)
+    for i, (c, _) in enumerate(caches):
         o.set_unit((0, 0, i), c.K, c.V, c.pos, c.crf, c.tau)
     entries = 0
-    steps = 0
     with threadpool_limits(limits=1):
         t0 = time.perf_counter()
+        s = 0
         while time.perf_counter() - t0 < seconds:
-            for i in range(len(sample)):
-                q = wl.bf16_round(rng.standard_normal((cfg.group, cfg.head_dim)).astype(np.float32))
-                k = wl.bf16_round(rng.standard_normal(cfg.head_dim).astype(np.float32))
-                v = wl.bf16_round(rng.standard_normal(cfg.head_dim).astype(np.float32))
+            for i in range(len(caches)):
+                q, k, v = inputs[i][s % len(inputs[i])]
                 o.step_unit((0, 0, i), q, k, v)
                 entries += o.units[(0, 0, i)].n + 1
             o.t += 1
-            steps += 1
+            s += 1
         dt = time.perf_counter() - t0
+    return entries, dt
+
+
+def cpu_baseline(cfg, budgets, seconds=8.0, n_inputs=8):
+    """The numpy oracle, as it stands, on the host: units spread over the workload, each with its steady-state
+    cache and the rows the workload's own step generator gives it; one thread, then one process per host core
+    over independent units.  Scaled by cached entries to the whole workload.  Runs before anything touches the
+    GPU (the worker processes are forked)."""
+    import multiprocessing as mp
+    import numpy as np
+    from paper_2601_16986_amd import workloads as wl
+
+    cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16), 16))
+    flat = np.asarray(budgets).reshape(-1)
+    shape = np.asarray(budgets).shape
+    t_now = cfg.prompt + cfg.decode_steps // 2
+    m = wl.mean_query(cfg)
+    n_units = 2 * cores
+    sample = sorted(set(int(u) for u in np.linspace(0, flat.size - 1, n_units).astype(int)))
+    keys = [tuple(int(v) for v in np.unravel_index(u, shape)) for u in sample]
+    G = cfg.group
+    steps_in, r = [], None
+    for s in range(n_inputs):                                   # the workload's own decode-step inputs (all layers), untimed
+        q, k, v, r = wl.decode_inputs(cfg, s, m, r)
+        steps_in.append([(q[l, b, h * G:(h + 1) * G].copy(), k[l, b, h].copy(), v[l, b, h].copy()) for (l, b, h) in keys])
+    caches = [(wl.steady_unit(cfg, u, int(flat[u]), t_now, m[key]), int(flat[u])) for u, key in zip(sample, keys)]
+    inputs = [[steps_in[s][i] for s in range(n_inputs)] for i in range(len(sample))]
     total_entries = int((flat.astype(np.int64) + 1).sum())
-    steps_per_s = (entries / dt) / total_entries
-    return {"value": steps_per_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
-            "sample": f"{len(sample)} units spread over the workload x {steps} decode steps "
-                      f"({entries} cached entries in {dt:.1f} s), scaled by entries to all {flat.size} units"}
+    # one thread: every other sampled unit
+    one = list(range(0, len(sample), max(1, len(sample) // 6)))[:6]
+    e1, dt1 = _oracle_worker((cfg, t_now, [caches[i] for i in one], [inputs[i] for i in one], seconds))
+    single = (e1 / dt1) / total_entries
+    # all host cores: one process per core, each with its own units
+    jobs = [(cfg, t_now, caches[w::cores], inputs[w::cores], seconds) for w in range(cores) if caches[w::cores]]
+    with mp.get_context("fork").Pool(len(jobs)) as pool:
+        res = pool.map(_oracle_worker, jobs)
+    rate = sum(e / dt for e, dt in res)
+    return {"value": rate / total_entries, "unit": "steps/s", "cores": len(jobs), "kind": "oracle",
+            "host_cpus": os.cpu_count(), "cpu_model": _cpu_model(),
+            "single_thread": {"value": single, "unit": "steps/s", "cores": 1},
+            "sample": f"{len(sample)} units spread over the workload with their steady-state caches and the workload's own "
+                      f"step inputs ({n_inputs} steps, cycled): one thread over {len(one)} of them for {dt1:.1f} s "
+                      f"({e1} cached entries), then {len(jobs)} processes (one BLAS thread each) over all of them for "
+                      f"{max(dt for _, dt in res):.1f} s ({sum(e for e, _ in res)} cached entries); "
+                      f"scaled by entries to all {flat.size} units ({total_entries} entries per step)"}
 
 
 def main():
@@ -196,6 +241,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--repeats", type=int, default=5, help="the K timed steps are run this many times; the median is reported")
     ap.add_argument("--config", default="qwen14b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-layer", action="store_true")
@@ -215,10 +261,17 @@ def main():
         sys.exit(2)
 
     import numpy as np
-    import torch
     from paper_2601_16986_amd import workloads as wl
 
     cfg = wl.CONFIGS[args.config]
+    fullkv = args.fullkv > 0
+    plain = not (fullkv or args.seed_prompt or args.probe_only)
+    # the host leg first: its worker processes are forked, which must happen before the GPU is initialised
+    cpu = None
+    if plain and not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, wl.draw_budgets(cfg))
+
+    import torch
     device = torch.device("cuda:0")
     torch.cuda.set_device(device)
     from paper_2601_16986_amd import ckv
@@ -230,11 +283,11 @@ def main():
     if args.seed_prompt:
         print(json.dumps(seed_prompt_bench(cfg, device, *[int(x) for x in args.seed_prompt.split(",")])))
         return
-    steps = max(RING, args.steps // RING * RING)
-    warm = max(RING, (args.warmup + RING - 1) // RING * RING)
-    fullkv = args.fullkv > 0
+    steps = max(1, args.steps)
+    warm = max(1, args.warmup)
+    repeats = max(1, args.repeats)
     if fullkv:
-        g, budgets, (rq, rk, rv) = build_fullkv(cfg, device, args.fullkv, warm + steps + 2 * RING)
+        g, budgets, (rq, rk, rv) = build_fullkv(cfg, device, args.fullkv, warm + (repeats + 2) * steps + 4 * RING)
     else:
         g, budgets, (rq, rk, rv) = build_workload(cfg, device)
     if args.path:
@@ -250,36 +303,45 @@ def main():
     torch.cuda.synchronize()
     assert g.status() == 0, "a unit overflowed during warm-up"
 
-    # ---- timed region: graph replays of RING consecutive steps
-    graph = None
+    # ---- timed region: exactly `steps` decode steps (HIP-graph replays of up to RING consecutive steps, then a
+    # shorter graph for what is left), synchronised on both sides; `repeats` such regions, the median is reported
+    n_full, n_tail = divmod(steps, RING)
+    g_full = g_tail = None
     if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            eager_steps(RING)
+        if n_full:
+            g_full = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_full):
+                eager_steps(RING)
+        if n_tail:
+            g_tail = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_tail):
+                eager_steps(n_tail)
         torch.cuda.synchronize()
-    done_since_rebudget = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps // RING):
-        if graph is not None:
-            graph.replay()
+    times = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if args.no_graph:
+            eager_steps(steps)
         else:
-            eager_steps(RING)
-        done_since_rebudget += RING
-        if R and done_since_rebudget >= R:
-            g.rebudget()
-            done_since_rebudget = 0
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / steps
+            for _ in range(n_full):
+                g_full.replay()
+            if n_tail:
+                g_tail.replay()
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3 / steps)
+    ms_steps_only = float(np.median(times))
     assert g.status() == 0
 
-    # ---- roofline pass: eager, HIP events around every scan launch
+    # ---- roofline pass: eager, HIP events around every launch of the dominant kernel
     g.profile_enable(True)
     eager_steps(RING)
     scan_ms, launches = g.profile_read()
     g.profile_enable(False)
-    scan_bytes, step_bytes, entries, fused_bytes = algorithmic_bytes(cfg, g.lengths() - 1 if fullkv else g.budgets())
+    lengths = g.lengths()
+    if not fullkv:
+        assert np.array_equal(lengths, g.budgets()), "caches are not at their budgets after the run"
+    scan_bytes, step_bytes, entries, fused_bytes = algorithmic_bytes(cfg, lengths - 1 if fullkv else g.budgets())
     if fullkv:                                           # attention only: K, V, q, out
         fused_bytes = step_bytes = scan_bytes + int(cfg.n_units) * cfg.group * 512
     fused_waves, _ = g.path_info()
@@ -310,18 +372,38 @@ def main():
                 layer_steps(RING, defer)
                 g.join()
             torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            reps = max(1, steps // RING // 2)
-            for _ in range(reps):
+            tl = []
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
                 gl.replay()
-            torch.cuda.synchronize()
-            res_pl.append((time.perf_counter() - t1) * 1e3 / (reps * RING))
+                torch.cuda.synchronize()
+                tl.append((time.perf_counter() - t1) * 1e3 / RING)
+            res_pl.append(float(np.median(tl)))
             del gl
         per_layer, per_layer_deferred = res_pl
 
-    lengths = g.lengths()
-    if not fullkv:
-        assert np.array_equal(lengths, g.budgets()), "caches are not at their budgets after the run"
+    # ---- Alg. 2 at its interval.  A re-allocation moves the caches away from the steady state the workload
+    # defines (shrunken units drop thousands of entries at once, grown ones refill one entry per step), so it is
+    # measured last and charged per step: what ckv_rebudget plus the step after it (which evicts down to the
+    # new budgets) take beyond an ordinary step, divided by the interval.
+    rebudget = None
+    ms_per_step = ms_steps_only
+    if R:
+        def timed(fn):
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t1) * 1e3
+        plain_ms = float(np.median([timed(lambda: eager_steps(1)) for _ in range(5)]))
+        with_ms = timed(lambda: (g.rebudget(), eager_steps(1)))
+        extra = max(0.0, with_ms - plain_ms)
+        after = g.budgets()
+        assert np.array_equal(after.sum(axis=(0, 2)), np.asarray(budgets).sum(axis=(0, 2))) and g.status() == 0
+        ms_per_step = ms_steps_only + extra / R
+        rebudget = {"interval": R, "rebudget_plus_next_step_ms": with_ms, "ordinary_eager_step_ms": plain_ms,
+                    "amortised_ms_per_step": extra / R, "budgets_changed": int((after != np.asarray(budgets)).sum())}
 
     res = {
         "metric": "decode steps/s (attention + LRFU + evict, all layers per step)" if not fullkv
@@ -331,7 +413,9 @@ def main():
         "n_gpus": 1,
         "steps": steps,
         "warmup": warm,
+        "repeats": repeats,
         "ms_per_step": ms_per_step,
+        "ms_per_step_repeats": times,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -339,12 +423,15 @@ def main():
         "data": "synthetic",
         "config": {"workload": (f"{cfg.name}: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, "
                                 f"batch {cfg.batch}, mean budget {cfg.budget} "
-                                f"({cfg.budget_min}..{cfg.budget_max}), evict every step, steady state at t={cfg.prompt + cfg.decode_steps // 2}")
+                                f"({cfg.budget_min}..{cfg.budget_max}), evict every step, steady state at t={cfg.prompt + cfg.decode_steps // 2}"
+                                + (f", Alg. 2 every {R} steps (amortised)" if R else ""))
                    if not fullkv else
                    (f"{cfg.name} FullKV: {cfg.n_layers} layers, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, d=128, batch {cfg.batch}, "
                     f"every cache holds all {args.fullkv} positions and grows by one per step"),
-                   "units": int(cfg.n_units), "entries_per_step": entries, "launch": f"all layers per call, HIP graph of {RING} steps"
-                   if graph is not None else "all layers per call, eager"},
+                   "units": int(cfg.n_units), "entries_per_step": entries,
+                   "launch": ("all layers per call, eager" if args.no_graph else
+                              f"all layers per call, HIP graphs of up to {RING} steps, median of {repeats} timed regions of {steps} steps")},
+        "rebudget": rebudget,
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "per_layer_graph_ms_per_step": per_layer,
@@ -353,11 +440,13 @@ def main():
         "copy_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc summary of this kernel and workload, committed)"
+                     if traffic is not None else None,
                      "bytes_per_launch": kernel_bytes, "avg_launch_ms": scan_avg_ms, "launches": launches,
                      "frac_of_stream_read": achieved / read_gbps},
     }
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg, budgets)
+    if cpu is not None:
+        res["cpu_baseline"] = cpu
     g.close()
     print(json.dumps(res))
 

@@ -336,6 +336,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.G = layout->n_q_heads / layout->n_kv_heads;
   d.cap = layout->cap;
   d.units = c->units;
+  d.unit0 = 0;
   d.max_chunks = (layout->cap + kChunk - 1) / kChunk;
   d.slots = d.max_chunks + 1;
   d.out_bf16 = layout->out_dtype == CKV_BF16;
@@ -495,16 +496,16 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     CKV_HIP(c, hipEventRecord(e0, s));
   }
   if (fused) {
-    // The kernel indexes its inputs, its output and the schedule by unit: for a single layer it gets the
-    // layer's part of the schedule (which prep_kernel has just filled in unit order) as if it were all there
-    // is, and pointers moved back by the layer's first unit, so that unit u finds row u - begin.
+    // The kernel indexes the schedule by slot and its inputs and output by unit: for a single layer it gets
+    // the layer's part of the schedule (which prep_kernel has just filled in unit order) as if it were all
+    // there is, and the layer's first unit, whose rows come first in q, v_new and out.
     Dev dv = c->dev;
     dv.sched = c->dev.sched + (layer >= 0 ? begin : 0);
     dv.units = count;
-    const size_t rows = (size_t)(layer >= 0 ? begin : 0);
-    const uint16_t* qb = (const uint16_t*)q - rows * dv.G * kDim;
-    const uint16_t* vb = (const uint16_t*)v_new - rows * kDim;
-    void* ob = (char*)out - rows * dv.G * kDim * (dv.out_bf16 ? 2 : 4);
+    dv.unit0 = layer >= 0 ? begin : 0;
+    const uint16_t* qb = (const uint16_t*)q;
+    const uint16_t* vb = (const uint16_t*)v_new;
+    void* ob = out;
     if (fv == &c->fused[2])
       hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
     else if (fv->waves == 4)

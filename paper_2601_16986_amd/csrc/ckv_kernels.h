@@ -40,6 +40,7 @@ constexpr int kTabLds = 256;              // decay-table entries kept in LDS by 
 
 struct Dev {
   int32_t L, Bz, Hq, Hkv, G, cap, units, max_chunks, slots, out_bf16;   // slots = partial slots per unit
+  int32_t unit0;         // fused kernel: unit whose rows come first in the call's q, v_new and out (a single layer's first unit)
   float scale_log2e;     // softmax_scale * log2(e): logits are kept in the base-2 domain
   float top_p;
   int32_t reward_mode, bmin, bmax, tab_last;
@@ -909,7 +910,7 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
       int last = 0;
       if (lane == 0) {
         last = atomicAdd(&d.arrive[cur.u], 1) == runs - 1;
-        if (last) d.arrive[cur.u] = 0;
+        if (last) __hip_atomic_store(&d.arrive[cur.u], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word other wavefronts update atomically
       }
       if (__builtin_amdgcn_readfirstlane(last))          // the other runs' partials are read with coherent loads
         merge_unit_wave(d, cur.u, cur.u - unit_begin, u0, per, runs, s_mw[threadIdx.x >> 6], out, lane);

@@ -145,7 +145,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   };
   auto load_q = [&](int uu) {
     const int jh = slane & 7;       // columns 8..15 repeat the heads 0..7 (scan_pv<true>)
-    const uint16_t* qrow = q + ((size_t)uu * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
+    const uint16_t* qrow = q + ((size_t)(uu - d.unit0) * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       // lanes beyond the group read head 0's row: the columns they produce are never looked at, and
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     const size_t o_next = first_off(u_next, n_next);
     // the new entry's logit (threads below G) and value element, requested a block before they are used
     const float snew = d.snew[(size_t)u * kMaxGroup + (slane & (kMaxGroup - 1))];
-    const uint16_t vnew = v_new[(size_t)u * kDim + (slane & 63) + 64 * (wave & 1)];
+    const uint16_t vnew = v_new[(size_t)(u - d.unit0) * kDim + (slane & 63) + 64 * (wave & 1)];
     if (my_cnt > 0) {
       float sv[8];
       qk(wave + W * (my_cnt - 1), sv);
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       if (kSlices == 2) y += s_out[kMaxGroup * kDim + o];
       if (lone) y += fast_exp2(s_ml[W][g][0] - sM[g]) * __uint_as_float((uint32_t)vnew << 16);
       y *= sInv[g];
-      const size_t oi = (size_t)u * G * kDim + o;
+      const size_t oi = (size_t)(u - d.unit0) * G * kDim + o;
       if (d.out_bf16)
         reinterpret_cast<__bf16*>(out)[oi] = (__bf16)y;
       else
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
   };
   auto load_q = [&](int uu) {
     const int jh = slane & 7;       // columns 8..15 repeat the heads 0..7 (scan_pv<true>)
-    const uint16_t* qrow = q + ((size_t)uu * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
+    const uint16_t* qrow = q + ((size_t)(uu - d.unit0) * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
 #pragma unroll
     for (int s = 0; s < 4; ++s) qv[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * s));
   };
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
         }
         // the new entry's logit (threads below G) and value element, requested a block before they are used
         const float snew = d.snew[(size_t)u * kMaxGroup + (slane & (kMaxGroup - 1))];
-        vnew = v_new[(size_t)u * kDim + (slane & 63) + 64 * (wave & 1)];
+        vnew = v_new[(size_t)(u - d.unit0) * kDim + (slane & 63) + 64 * (wave & 1)];
         if (my_cnt > 0) {
           float sv[8];
           qk(wave + W * (my_cnt - 1), sv);
@@ -650,7 +650,7 @@ __global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_
           float y = s_out[o] + s_out[kMaxGroup * kDim + o];
           if (lone) y += fast_exp2(s_ml[W][g][0] - sM[par][g]) * __uint_as_float((uint32_t)vnew << 16);
           y *= sInv[par][g];
-          const size_t oi = (size_t)u * G * kDim + o;
+          const size_t oi = (size_t)(u - d.unit0) * G * kDim + o;
           if (d.out_bf16)
             reinterpret_cast<__bf16*>(out)[oi] = (__bf16)y;
           else

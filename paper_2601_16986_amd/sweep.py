@@ -63,6 +63,19 @@ def run(cfg, st, lam, top_p, budget, torch, ckv, device, answer_q, reward_mode=0
     return kept, classes
 
 
+def recalls(kept, heavy, crystal, budget):
+    """Mean over the units of the share of heavy positions, and of the reference Crystal set, still cached.
+    kept: {unit: positions}, heavy: bool [L][Bz][Hkv][N], crystal: {unit: set of positions}."""
+    hr, cr = [], []
+    for key, pos in kept.items():
+        have = set(np.asarray(pos).tolist())
+        hp = set(np.nonzero(heavy[key])[0].tolist())
+        if hp:
+            hr.append(len(hp & have) / min(len(hp), budget))
+        cr.append(len(crystal[key] & have) / min(len(crystal[key]), budget))
+    return float(np.mean(hr)), float(np.mean(cr))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--tokens", type=int, default=2048)
@@ -96,15 +109,8 @@ def main():
         kept, _ = run(cfg, st, lam, p, args.budget, torch, ckv, device, answer_q,
                       reward_mode=ckv.REWARD_ATTN_WEIGHTED if name == "accumulated" else ckv.REWARD_TOPP_HIT,
                       n_sink={"recent": 0, "sink + recent": 4}.get(name))
-        hr, cr = [], []
-        for key, pos in kept.items():
-            have = set(pos.tolist())
-            hp = set(np.nonzero(heavy[key])[0].tolist())
-            if hp:
-                hr.append(len(hp & have) / min(len(hp), args.budget))
-            cr.append(len(crystal[key] & have) / min(len(crystal[key]), args.budget))
-        results.append({"lambda": lam, "top_p": p, "name": name, "heavy_recall": float(np.mean(hr)),
-                        "crystal_recall": float(np.mean(cr))})
+        hr, cr = recalls(kept, heavy, crystal, args.budget)
+        results.append({"lambda": lam, "top_p": p, "name": name, "heavy_recall": hr, "crystal_recall": cr})
     print(f"tokens {args.tokens} (prompt {args.prompt}), budget {args.budget} per unit, {len(crystal)} units, "
           f"heavy positions per unit {heavy.sum() / len(crystal):.1f}, reference Crystal set {np.mean([len(c) for c in crystal.values()]):.0f} positions")
     print("| top-p \\ lambda | " + " | ".join(f"{x:g}" for x in lams) + " |")

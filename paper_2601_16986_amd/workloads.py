@@ -65,7 +65,7 @@ class Config:
 CONFIGS = {
     "tiny": Config("tiny", 1, 1, 8, 2, 128, 64, 512, 128, 128, 128, False, 0, seed=1000),
     "qwen7b": Config("qwen7b", 28, 8, 28, 4, 128, 256, 8192, 2048, 2048, 2048, False, 0, seed=2000),
-    "qwen14b": Config("qwen14b", 48, 16, 40, 8, 128, 512, 16384, 2048, 256, 8192, True, 0, seed=3000),
+    "qwen14b": Config("qwen14b", 48, 16, 40, 8, 128, 512, 16384, 2048, 256, 8192, True, 256, seed=3000),
     "llama8b": Config("llama8b", 32, 64, 32, 8, 128, 1024, 32768, 1024, 1024, 1024, False, 0, seed=4000),
     "qwen32b": Config("qwen32b", 64, 32, 40, 8, 128, 512, 32768, 4096, 512, 16384, True, 256, seed=5000),
 }

@@ -1,11 +1,14 @@
 """Parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times
 (all layers per call, steady-state caches built as in bench.py).
 
-The oracle cannot step thousands of units in test time, so a sample of units spread over the
-workload is filled from the host-side generator (the oracle and the GPU get the same arrays) and
-compared entry by entry for a few decode steps; all other units are checked through properties
-that hold at any size: caches sit at their budgets after eviction, outputs are finite, no
-capacity overflow, time advanced, and (adaptive workloads) Alg. 2 conserves every sequence's total."""
+The oracle cannot step thousands of units in test time, so a sample of units is filled from the
+host-side generator (the oracle and the GPU get the same arrays) and compared entry by entry for
+eight decode steps: 64 units spread over the workload, the units with the smallest and the largest
+budget, and (adaptive workloads) units re-sized to sit exactly at and one entry beyond each size
+at which the fused kernel changes its code path.  All other units are checked through properties
+that hold at any size: caches sit at their budgets after eviction, outputs are finite, no capacity
+overflow, time advanced, and Alg. 2 conserves every sequence's total.  Alg. 2 itself is compared
+with the oracle at the real number of (layer, head) pairs per sequence on small caches."""
 import numpy as np
 import pytest
 
@@ -13,11 +16,44 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 
-N_SAMPLE = 10
-N_STEPS = 3
+N_SAMPLE = 64
+N_STEPS = 8
 
 
-def _run(name, n_sample=N_SAMPLE, n_steps=N_STEPS, rebudget_after=None):
+def _lds_resident_limit(cap, G):
+    """Largest entry count whose logits all stay in the fused kernel's LDS tile (4 wavefronts per unit, two
+    workgroups per compute unit: 80 KB each less 11 KB of static arrays and the eviction bit mask).  The test
+    asserts below that the context reports the tile size assumed here."""
+    lds_main = (80 * 1024 - 11 * 1024 - (cap + 31) // 32 * 4) & ~127
+    n = 32
+    while (n + 32) * G * 4 <= lds_main:
+        n += 32
+    return n, lds_main
+
+
+def _sample(cfg, budgets, n_sample, boundaries):
+    """Unit indices to compare entry by entry: the smallest and the largest budget, `n_sample` units spread
+    over the index range, and units re-sized to sit just under and just over the kernel's internal size
+    limits (their budgets are overwritten in `budgets`; a limit n means n entries while attending)."""
+    flat = budgets.reshape(-1)
+    spread = [int(x) for x in np.linspace(0, flat.size - 1, n_sample).astype(int)]
+    taken = set(spread)
+    placed = []
+    u = 1
+    for n_att in boundaries:
+        for b in (n_att - 1, n_att):               # budget n - 1 attends over n entries: at the limit, and one over it
+            if not (cfg.budget_min <= b <= cfg.budget_max):
+                continue
+            while u in taken:
+                u += 7
+            flat[u] = b
+            taken.add(u)
+            placed.append(u)
+    idx = sorted(taken | {int(np.argmin(flat)), int(np.argmax(flat))})
+    return idx, placed
+
+
+def _run(name, n_sample=N_SAMPLE, n_steps=N_STEPS, rebudget_after=None, boundaries=()):
     import torch
     import bench
     from oracle import crystal_kv as ok
@@ -25,13 +61,19 @@ def _run(name, n_sample=N_SAMPLE, n_steps=N_STEPS, rebudget_after=None):
 
     cfg = wl.CONFIGS[name]
     dev = torch.device("cuda:0")
-    g, budgets, (rq, rk, rv) = bench.build_workload(cfg, dev)
+    budgets = wl.draw_budgets(cfg).copy()
+    cap = (cfg.budget_max + 1 + 31) // 32 * 32
+    n_lds, lds_main = _lds_resident_limit(cap, cfg.group)
+    limits = [b for b in boundaries] + ([n_lds] if boundaries else [])
+    idx, placed = _sample(cfg, budgets, n_sample, limits)
+    g, budgets, (rq, rk, rv) = bench.build_workload(cfg, dev, budgets=budgets)
+    waves, lds_ctx = g.path_info()
+    assert waves == 4 and lds_ctx == lds_main, (waves, lds_ctx, lds_main)
     t_now = cfg.prompt + cfg.decode_steps // 2
     flat = budgets.reshape(-1)
-    # sample: smallest and largest budget plus units spread over the index range
-    idx = sorted(set([int(np.argmin(flat)), int(np.argmax(flat))] +
-                     [int(x) for x in np.linspace(0, flat.size - 1, n_sample).astype(int)]))
     keys = [tuple(int(v) for v in np.unravel_index(u, budgets.shape)) for u in idx]
+    print(f"{name}: {len(keys)} sampled units, budgets {int(flat[idx].min())}..{int(flat[idx].max())}, "
+          f"units at size limits {sorted(int(flat[u]) for u in placed)}", flush=True)
     o = ok.CrystalKVOracle(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, budgets,
                            lam=cfg.lam, top_p=cfg.top_p, t0=t_now, budget_min=cfg.budget_min, budget_max=cfg.budget_max)
     m = wl.mean_query(wl.scaled(cfg, n_layers=1, batch=1))
@@ -55,13 +97,15 @@ def _run(name, n_sample=N_SAMPLE, n_steps=N_STEPS, rebudget_after=None):
         o.t += 1
         for key in keys:
             parity.compare_unit(g, o, key, recs[key], stats, check_kv=(s == n_steps - 1))
+            stats.unit_steps += 1
         # properties over every unit
         assert np.isfinite(outh).all()
         assert np.array_equal(g.lengths(), g.budgets())
         assert g.status() == 0 and g.time() == t_now + s + 1
+        print(f"  step {s}: {len(keys)} units equal the oracle, max out err so far {stats.max_out_err:.2e}", flush=True)
     print(f"{name}: {len(keys)} sampled units x {n_steps} steps, max out err {stats.max_out_err:.2e}, "
-          f"resynced {stats.resynced}")
-    assert stats.resynced <= 2, stats.notes
+          f"resynced {stats.resynced} {stats.notes}")
+    assert stats.resynced <= max(2, stats.unit_steps // 200), stats.notes
     if rebudget_after:
         # Alg. 2 at full size: totals conserved, bounds kept, next step evicts down to the new budgets
         before = g.budgets()
@@ -76,12 +120,17 @@ def _run(name, n_sample=N_SAMPLE, n_steps=N_STEPS, rebudget_after=None):
     g.close()
 
 
+# entries per unit at which the fused kernel changes its code path: 8, 16 and 32 entries per thread of a
+# 256-thread workgroup (the LDS tile's limit is added by _run)
+THREAD_LIMITS = (2048, 4096, 8192)
+
+
 def test_qwen7b_full_size():
     _run("qwen7b")
 
 
 def test_qwen14b_full_size_bench_configuration():
-    _run("qwen14b", rebudget_after=True)
+    _run("qwen14b", rebudget_after=True, boundaries=THREAD_LIMITS)
 
 
 def test_llama8b_full_size():
@@ -89,7 +138,56 @@ def test_llama8b_full_size():
 
 
 def test_qwen32b_full_size():
-    _run("qwen32b", n_sample=6, n_steps=2, rebudget_after=True)
+    _run("qwen32b", rebudget_after=True, boundaries=THREAD_LIMITS)
+
+
+@pytest.mark.parametrize("n_layers", [48, 64])
+def test_rebudget_at_the_real_head_count_matches_oracle_with_active_bounds(n_layers):
+    """Alg. 2 at the problem size of the 14B and 32B shapes, L x H = 384 and 512 (layer, head) pairs per
+    sequence (the kernel's per-layer threads and its serial layer-level apportionment at their real
+    trip counts), on caches small enough for the oracle to step every unit: budgets bit-equal to the
+    oracle's after lock-step decoding, totals conserved, and both a lower and an upper bound active
+    in the result (the budget range is narrow, so the utilisations' spread reaches both)."""
+    from oracle import crystal_kv as ok
+    from paper_2601_16986_amd import ckv, workloads as wl
+    cfg = wl.scaled(wl.CONFIGS["qwen14b"], n_layers=n_layers, batch=2, prompt=30, decode_steps=16, budget=24,
+                    budget_min=21, budget_max=27, adaptive=True, seed=880 + n_layers)
+    st = wl.make_stream(cfg)
+    budgets = wl.draw_budgets(cfg)
+    assert budgets.min() == 21 and budgets.max() == 27
+    o = ok.CrystalKVOracle(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, budgets, lam=cfg.lam,
+                           top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min, budget_max=cfg.budget_max)
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 64, budgets, lam=cfg.lam,
+                      top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min, budget_max=cfg.budget_max)
+    for l in range(cfg.n_layers):
+        o.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+        g.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+    total0 = budgets.sum(axis=(0, 2))
+    step = 0
+    for rnd in range(2):
+        stats = parity.lockstep(g, o, st_slice(st, step, 8), 8)
+        step += 8
+        assert stats.resynced == 0, "window sums are only comparable without re-synchronised units"
+        nb = o.rebudget()
+        g.rebudget()
+        gb = g.budgets()
+        assert np.array_equal(gb, nb), np.argwhere(gb != nb)[:10]
+        assert np.array_equal(gb.sum(axis=(0, 2)), total0)
+        for b in range(cfg.batch):
+            assert gb[:, b].min() == cfg.budget_min and gb[:, b].max() == cfg.budget_max, (gb[:, b].min(), gb[:, b].max())
+        # and the layer level: some layer of every sequence sits at H b_min or H b_max only if its heads all do;
+        # what must hold is that layer totals stay inside [H b_min, H b_max]
+        lt = gb.sum(axis=2)
+        assert lt.min() >= cfg.n_kv_heads * cfg.budget_min and lt.max() <= cfg.n_kv_heads * cfg.budget_max
+        print(f"L x H = {n_layers * cfg.n_kv_heads}: round {rnd}, budgets equal the oracle's, "
+              f"{int((gb == cfg.budget_min).sum())} at the lower and {int((gb == cfg.budget_max).sum())} at the upper bound", flush=True)
+    g.close()
+
+
+def st_slice(st, first, count):
+    """The decode steps [first, first + count) of a stream, as a stream of its own."""
+    from dataclasses import replace
+    return replace(st, q=st.q[first:first + count], k_new=st.k_new[first:first + count], v_new=st.v_new[first:first + count])
 
 
 def test_qwen14b_full_size_one_call_per_layer_with_deferred_bookkeeping():

@@ -756,3 +756,39 @@ def test_hip_graph_replay_matches_eager(path):
         for f in ("pos", "crf", "tau", "flags"):
             assert np.array_equal(a[f], b[f])
     g.close(); g2.close()
+
+
+@pytest.mark.parametrize("path", [3, 5])
+def test_probe_classes_on_multi_chunk_units_of_a_fused_path_context(path):
+    """Sec. 3 classes on units of 300..700 entries (several 256-entry chunks, ragged last blocks, 7 query
+    heads per KV head) in a context whose decode steps run the fused kernel: the probe shares the context's
+    workspace (work list, partials, logits buffer) with those steps, leaves the caches untouched, and the
+    decode steps that follow still match the oracle."""
+    cfg = _small("qwen7b", n_layers=1, batch=3, n_q_heads=14, n_kv_heads=2, prompt=333, decode_steps=16,
+                 budget=500, budget_min=300, budget_max=735, seed=5)
+    budgets = np.array([[[300, 700], [513, 333], [641, 352]]], dtype=np.int32)
+    st, o, g = _pair(cfg, cap=736, budgets=budgets, path=path)
+    stats = parity.lockstep(g, o, parity_slice(st, 0, 8), 8)
+    cls = g.probe(0, st.probe_q[0]).cpu().numpy()
+    for (l, b, h), u in o.units.items():
+        ref, abar = o.probe((l, b, h), st.probe_q[l, b, h * o.G:(h + 1) * o.G])
+        e = g.export_unit(l, b, h, with_kv=False)
+        got = cls[b, h, :e["n"]]
+        by_pos_g = dict(zip(e["pos"].tolist(), got.tolist()))
+        by_pos_o = dict(zip(u.pos.tolist(), ref.tolist()))
+        srt = np.sort(abar)
+        k = (3 * u.n) // 10
+        assert k >= 90
+        edges = [srt[k - 1], srt[k], srt[u.n - k - 1], srt[u.n - k]]
+        for p_, a in zip(u.pos.tolist(), abar.tolist()):
+            if by_pos_g[p_] != by_pos_o[p_]:
+                assert min(abs(a - x) / x for x in edges) < 1e-5, (p_, a)
+        assert (got == 2).sum() == k and (got == 0).sum() == k and (cls[b, h, e["n"]:] == 255).all()
+    stats2 = parity.lockstep(g, o, parity_slice(st, 8, 8), 8, check_kv_every=8)
+    assert stats.resynced + stats2.resynced <= 2 and g.status() == 0
+    g.close()
+
+
+def parity_slice(st, first, count):
+    from dataclasses import replace
+    return replace(st, q=st.q[first:first + count], k_new=st.k_new[first:first + count], v_new=st.v_new[first:first + count])

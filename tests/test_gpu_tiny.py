@@ -43,3 +43,32 @@ def test_tiny_lockstep_all_512_steps():
         heavy_pos = set(np.nonzero(st.heavy[l, b, h])[0].tolist())
         assert heavy_pos <= set(g.export_unit(l, b, h, with_kv=False)["pos"].tolist())
     g.close()
+
+
+def test_tiny_free_run_report():
+    """Free-running comparison (reported, not a gate): both sides decode all 512 steps of the tiny workload
+    from the same prompt without ever exchanging state.  Stored scores are exactly reproducible and hit
+    decisions only differ when a cut lies within rounding of p, so the runs normally never part; the test
+    prints the first step at which the retained sets differ (none = -1) and the Jaccard index of the final
+    retained sets, and only requires that both runs complete with full caches."""
+    from paper_2601_16986_amd import workloads as wl
+    cfg = wl.CONFIGS["tiny"]
+    st, o, g = _pair(cfg, cap=160)
+    first = -1
+    for s in range(cfg.decode_steps):
+        o.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        g.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        if first < 0 and (s % 8 == 7 or s == cfg.decode_steps - 1):
+            for key, u in o.units.items():
+                if sorted(g.export_unit(*key, with_kv=False)["pos"].tolist()) != sorted(u.pos.tolist()):
+                    first = s - (s % 8)                   # within this group of eight steps
+                    break
+    jac = []
+    for key, u in o.units.items():
+        a, b = set(g.export_unit(*key, with_kv=False)["pos"].tolist()), set(u.pos.tolist())
+        jac.append(len(a & b) / len(a | b))
+        assert len(a) == len(b) == cfg.budget
+    print(f"tiny free run, {cfg.decode_steps} steps: first divergence in steps [{first}, {first + 8}) (-1 = none), "
+          f"final retained-set Jaccard per unit {jac}")
+    assert g.status() == 0
+    g.close()
