@@ -220,6 +220,19 @@ int ckv_rebudget(ckv_ctx* ctx, void* stream);
  * last floor(0.3 n) Slip, the rest Potential. */
 int ckv_probe(ckv_ctx* ctx, int32_t layer, const void* q_probe, uint8_t* classes, void* stream);
 
+/* ckv_probe for callers that cannot allocate or bring a workspace of their own for it: code under HIP graph
+ * capture, tight serving loops that probe beside decode steps, harnesses that forbid hipMalloc.  Same
+ * arguments, same result (the classes are identical, byte for byte), but the scan's scratch - work list,
+ * partial results, logits, launch counters - lives in a static device array of 128 MiB that the library
+ * owns on every GPU it is loaded on (held until the process ends), not in the context's workspace; so the
+ * call leaves the context's workspace alone.  It calls no hipMalloc, hipFree or
+ * other allocating routine.  A layer whose scratch (about batch * n_kv_heads * cap * 6 * G bytes, G = n_q_heads / n_kv_heads) does
+ * not fit is refused with CKV_EWORKSPACE; a context created on another device than the current one, or a
+ * per-layer step in progress, with CKV_ESTATE.  All calls on one GPU share the array, whose contents
+ * persist from call to call: calls that overlap on one GPU (two streams, two contexts, two threads) race;
+ * calls ordered on one stream, or by events, do not.  Asynchronous on `stream`. */
+int ckv_probe_noalloc(ckv_ctx* ctx, int32_t layer, const void* q_probe, uint8_t* classes, void* stream);
+
 /* Synchronous readers (wait for the device). Host arrays [n_layers][batch][n_kv_heads]. */
 int ckv_get_budgets(ckv_ctx* ctx, int32_t* budgets);
 int ckv_get_lengths(ckv_ctx* ctx, int32_t* lengths);

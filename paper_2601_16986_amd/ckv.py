@@ -26,7 +26,7 @@ EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_seed_prompt", "ckv_load_cache", "ckv_decode_step",
     "ckv_evict",
     "ckv_evict_window",
-    "ckv_rebudget", "ckv_probe", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
+    "ckv_rebudget", "ckv_probe", "ckv_probe_noalloc", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
     "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_join", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
 ]
@@ -76,6 +76,7 @@ def load():
     lib.ckv_evict_window.argtypes = [vp, i32, i32, vp]
     lib.ckv_rebudget.argtypes = [vp, vp]
     lib.ckv_probe.argtypes = [vp, i32, vp, vp, vp]
+    lib.ckv_probe_noalloc.argtypes = [vp, i32, vp, vp, vp]
     lib.ckv_get_budgets.argtypes = [vp, vp]
     lib.ckv_get_lengths.argtypes = [vp, vp]
     lib.ckv_set_budgets.argtypes = [vp, vp]
@@ -257,6 +258,15 @@ class CrystalKV:
         cls = t.full((self.Bz, self.Hkv, self.cap), 255, dtype=t.uint8, device=self.device)
         self._check(self.lib.ckv_probe(self.ctx, layer, q.data_ptr(), cls.data_ptr(), self._stream()))
         return cls
+
+    def probe_noalloc(self, layer, q_probe, classes):
+        """ckv_probe with the library's static scratch; q_probe a device bf16 tensor [Bz][Hq][d], `classes` a
+        caller-allocated uint8 device tensor [Bz][Hkv][cap] (nothing is allocated here either)."""
+        t = self.torch
+        assert q_probe.dtype == t.bfloat16 and q_probe.is_contiguous() and tuple(q_probe.shape) == (self.Bz, self.Hq, self.d)
+        assert classes.dtype == t.uint8 and classes.is_contiguous() and tuple(classes.shape) == (self.Bz, self.Hkv, self.cap)
+        self._check(self.lib.ckv_probe_noalloc(self.ctx, layer, q_probe.data_ptr(), classes.data_ptr(), self._stream()))
+        return classes
 
     def budgets(self):
         b = np.zeros((self.L, self.Bz, self.Hkv), dtype=np.int32)

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -20,6 +21,14 @@ using namespace ckv;
 
 constexpr int kSide = 2;   // streams of the context's own for deferred bookkeeping
 
+// Scratch of ckv_probe_noalloc: device memory the library owns from the moment it is loaded, so that the
+// call never needs a caller's workspace or an allocation.  In host code `scratch` is only a handle: the
+// array's address on a device comes from hipGetSymbolAddress, once per device (scratch_setup), and that
+// pointer is what kernels and fills get.  One array per GPU, shared by every context on it.
+constexpr size_t kScratchBytes = (size_t)128 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+
 struct ckv_ctx {
   ckv_layout lay;
   ckv_lrfu_params par;
@@ -29,6 +38,7 @@ struct ckv_ctx {
   int units_per_layer = 0;
   int next_layer = 0;
   int n_cu = 256;
+  int device = 0;               // the HIP device the context was created on
   size_t finish_lds = 0;
   // fused path (unit_kernel)
   int path_mode = 0;            // 0 auto, 1 separate kernels, 2 fused kernel, 3 / 4 fused with 4 / 2 wavefronts per unit,
@@ -222,6 +232,24 @@ int fill32(ckv_ctx* c, void* p, uint32_t v, size_t count, hipStream_t s) {
   return CKV_OK;
 }
 
+// Address of the library's static scratch on each device, and whether its launch sequence number has been
+// started (at 1: the array is zero when the library is loaded, and a stamp of 0 must never look current).
+// The number is never restarted: partials that earlier calls left in the array carry earlier numbers.
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_setup(int devid, hipStream_t s) {
+  if (devid < 0 || devid >= kMaxDevices) return CKV_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[devid]) return CKV_OK;
+  unsigned char* p = nullptr;
+  if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CKV_EHIP;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(p) + SC_SEQ, 1u, (size_t)1);
+  if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return CKV_EHIP;
+  g_scratch_ptr[devid] = p;
+  return CKV_OK;
+}
+
 int layer_range(ckv_ctx* c, int32_t layer, int* begin, int* count) {
   if (layer == -1) {
     *begin = 0;
@@ -280,6 +308,11 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   if (e != hipSuccess || c->n_cu <= 0) {
     delete c;
     return CKV_EHIP;
+  }
+  c->device = devid;
+  if (int rc = scratch_setup(devid, s)) {        // the static scratch of ckv_probe_noalloc: its address on this device
+    delete c;
+    return rc;
   }
   c->finish_lds = (size_t)layout->cap * 4 + (size_t)((layout->cap + 31) / 32) * 4;
   if (c->finish_lds + 12288 > (size_t)max_lds) {   // static LDS of the kernels stays below 12 KB
@@ -637,6 +670,69 @@ int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, 
                      (void*)nullptr, 0, -1);
   CKV_HIP(c, hipGetLastError());
   hipLaunchKernelGGL(probe_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, classes);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+int ckv_probe_noalloc(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (!q_probe || !classes) return fail(c, CKV_EINVAL, "q_probe or classes is NULL");
+  if (layer < 0 || layer >= c->lay.n_layers) return fail(c, CKV_EINVAL, "layer out of range");
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  int devid = -1;
+  if (hipGetDevice(&devid) != hipSuccess) return fail(c, CKV_EHIP, "hipGetDevice failed");
+  if (devid != c->device) return fail(c, CKV_ESTATE, "the context's device is not the current one");
+  unsigned char* base = g_scratch_ptr[devid];     // set by ckv_init on this device
+  if (!base) return fail(c, CKV_ESTATE, "the library's scratch was not set up on this device");
+  const int begin = layer * c->units_per_layer, count = c->units_per_layer;
+  // the layer's scan scratch, carved from the static array instead of the context's workspace
+  const size_t U = (size_t)count, G = (size_t)c->dev.G, mc = (size_t)c->dev.max_chunks, slots = mc + 1;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  const size_t o_sc = take(SC_COUNT * 4), o_items = take(U * mc * 16), o_stamp = take(U * slots * 4),
+               o_ml = take(U * slots * G * 2 * 4), o_partial = take(U * slots * G * kDim * 4),
+               o_logits = take(U * G * (size_t)c->dev.cap * 4);
+  if (off > kScratchBytes)
+    return fail(c, CKV_EWORKSPACE, "one layer's scan scratch (" + std::to_string(off >> 20) + " MiB) exceeds the library's static scratch of " +
+                                       std::to_string(kScratchBytes >> 20) + " MiB: use ckv_probe");
+  // the layer's units as units 0 .. count-1 of a context of their own: caches and lengths from the real context,
+  // work list, partials, logits and step counters from the scratch
+  Dev ds = c->dev;
+  const size_t slot0 = (size_t)begin * c->dev.cap;
+  ds.units = count;
+  ds.K += slot0 * kDim;
+  ds.V += slot0 * kDim;
+  ds.crf += slot0;
+  ds.tau += slot0;
+  ds.pos += slot0;
+  ds.flags += slot0;
+  ds.n += begin;
+  ds.budget += begin;
+  ds.t_unit += begin;
+  ds.nev += begin;
+  ds.window += begin;
+  ds.sc = reinterpret_cast<int32_t*>(base + o_sc);
+  ds.items = reinterpret_cast<int4*>(base + o_items);
+  ds.stamp = reinterpret_cast<int32_t*>(base + o_stamp);
+  ds.ml = reinterpret_cast<float*>(base + o_ml);
+  ds.partial = reinterpret_cast<float*>(base + o_partial);
+  ds.logits = reinterpret_cast<float*>(base + o_logits);
+  hipStream_t s = (hipStream_t)stream;
+  if (int rc = join_side(c, s)) return rc;
+  // counters that must start at zero (a fill kernel, not a memset: the call may be captured in a graph); the
+  // launch sequence number before them keeps counting
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ds.sc) + SC_DONE, 0u, (size_t)(SC_CLAIM + 2 - SC_DONE));
+  CKV_HIP(c, hipGetLastError());
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, ds, 0, count,
+                     (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, INT_MAX, (const uint16_t*)nullptr);
+  CKV_HIP(c, hipGetLastError());
+  const long long max_items = (long long)count * ds.max_chunks;
+  long long blocks = 2ll * c->n_cu;
+  if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
+  hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, ds, 0, (const uint16_t*)q_probe,
+                     (void*)nullptr, 0, -1);
+  CKV_HIP(c, hipGetLastError());
+  hipLaunchKernelGGL(probe_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, ds, 0, classes);
   CKV_HIP(c, hipGetLastError());
   return CKV_OK;
 }
