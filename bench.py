@@ -115,17 +115,28 @@ def seed_prompt_bench(cfg, device, P, W):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1)
     upl = cfg.batch * cfg.n_kv_heads
-    entries = sum(P - W + j + 1 for j in range(W)) * upl             # per layer
+    entries = sum(P - W + j + 1 for j in range(W)) * upl             # per layer, query by query
     bytes_layer = entries * 512
+    # what the replay needs at the least: every key row once (weights only, so no values), the queries, and the
+    # scores read and written once per query
+    Q = max(1, 16 // cfg.group)
+    passes = (W + Q - 1) // Q
+    min_bytes = upl * (P * 256 + W * cfg.group * 256 + W * P * 16)
+    pass_bytes = upl * (passes * P * 256 + W * cfg.group * 256 + W * P * (16 + 2 * 4 * cfg.group))   # as built: keys once per pass, logits written and read back
+    sec = ms / cfg.n_layers * 1e-3
     assert g.status() == 0
     g.close()
     return {"metric": "prompt seeding (ckv_seed_prompt), layers/s", "value": cfg.n_layers / (ms * 1e-3), "unit": "layers/s",
             "n_gpus": 1, "ms_per_layer": ms / cfg.n_layers, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": f"{cfg.name} geometry: {cfg.n_layers} layers, batch {cfg.batch}, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, "
                                    f"prompt of {P} tokens, window of {W} queries", "units_per_layer": upl,
-                       "entries_scanned_per_layer": entries},
-            "kv_gbps": bytes_layer / (ms / cfg.n_layers * 1e-3) / 1e9,
-            "hbm_frac": bytes_layer / (ms / cfg.n_layers * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+                       "entries_scanned_per_layer": entries, "queries_per_pass": Q, "passes_over_the_keys": passes},
+            # K and V of the W visible prefixes, the bytes a query-by-query replay of decode steps moves (the figure of
+            # the first version, kept for comparison; the replay as built reads far less, so this can exceed 1)
+            "kv_gbps": bytes_layer / sec / 1e9,
+            "hbm_frac": bytes_layer / sec / 1e9 / HBM_PEAK_GBPS,
+            "bytes_as_built": pass_bytes, "hbm_frac_as_built": pass_bytes / sec / 1e9 / HBM_PEAK_GBPS,
+            "bytes_minimum": min_bytes, "hbm_frac_of_minimum": min_bytes / sec / 1e9 / HBM_PEAK_GBPS}
 
 
 def algorithmic_bytes(cfg, budgets):

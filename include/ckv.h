@@ -145,7 +145,9 @@ int ckv_load_prompt(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, i
  * entry being in its hit set.  Nothing is appended, evicted or written to an
  * output, the time stays t0, and the replay leaves no trace in the aggregated
  * CRF that ckv_rebudget consumes.  Requires a layer filled by ckv_load_prompt
- * and not touched since (CKV_ESTATE otherwise) and 1 <= W <= P.  3 W + 2 kernel
+ * and not touched since (CKV_ESTATE otherwise) and 1 <= W <= P.  The keys are read
+ * once per group of floor(16 / G) queries (G = n_q_heads / n_kv_heads), the values
+ * not at all (only weights are needed): 2 ceil(W / floor(16 / G)) + 2 kernel
  * launches on `stream`; asynchronous. */
 int ckv_seed_prompt(ckv_ctx* ctx, int32_t layer, const void* q_obs, int32_t W, void* stream);
 

@@ -38,6 +38,8 @@ struct ckv_ctx {
   int units_per_layer = 0;
   int next_layer = 0;
   int n_cu = 256;
+  float* seedlg = nullptr;      // workspace of the prompt replay
+  float* seedml = nullptr;
   int device = 0;               // the HIP device the context was created on
   size_t finish_lds = 0;
   // fused path (unit_kernel)
@@ -135,7 +137,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, seedlg, seedml, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -164,6 +166,10 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.sched = take(U * 16);
   c.layer_ts = take((size_t)l->n_layers * 8);
   c.snew = take(U * kMaxGroup * 4);
+  // prompt replay (ckv_seed_prompt), one layer at a time: logits of 16 query columns per entry, softmax partials per chunk
+  const size_t UL = (size_t)l->batch * l->n_kv_heads;
+  c.seedlg = take(UL * (size_t)l->cap * kSeedCols * 4);
+  c.seedml = take(UL * mc * kSeedCols * 2 * 4);
   c.total = off;
   return c;
 }
@@ -319,8 +325,8 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     delete c;
     return CKV_EINVAL;
   }
-  const void* lds_kernels[3] = {reinterpret_cast<const void*>(finish_kernel), reinterpret_cast<const void*>(evict_kernel),
-                                reinterpret_cast<const void*>(probe_kernel)};
+  const void* lds_kernels[4] = {reinterpret_cast<const void*>(finish_kernel), reinterpret_cast<const void*>(evict_kernel),
+                                reinterpret_cast<const void*>(probe_kernel), reinterpret_cast<const void*>(seed_finish_kernel)};
   for (const void* fn : lds_kernels) {
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->finish_lds) != hipSuccess) {
       delete c;
@@ -405,6 +411,8 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.layer_ts = (int32_t*)(ws + cv.layer_ts);
   d.arrive = (int32_t*)(ws + cv.arrive);
   d.snew = (float*)(ws + cv.snew);
+  c->seedlg = (float*)(ws + cv.seedlg);
+  c->seedml = (float*)(ws + cv.seedml);
 
   auto bail = [&](int rc) {
     ckv_destroy(c);
@@ -598,20 +606,17 @@ int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, voi
   const dim3 sgrid((unsigned)std::min((P + kThreads - 1) / kThreads, 64), (unsigned)count);
   hipLaunchKernelGGL(seed_state_kernel, sgrid, dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 0, 0);
   CKV_HIP(c, hipGetLastError());
-  const size_t q_stride = (size_t)c->lay.batch * c->lay.n_q_heads * kDim;
-  for (int j = 0; j < W; ++j) {
-    const int t_j = P - W + j;                  // the query's position = its time; it sees positions 0 .. t_j
-    hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin,
-                       count, (const uint16_t*)nullptr, (const uint16_t*)nullptr, 0, t_j + 1, (const uint16_t*)nullptr);
+  // Q queries per pass over the keys: the 16 query columns of the matrix-core tile hold G heads each of Q queries
+  const int Q = kSeedCols / c->dev.G;
+  for (int j0 = 0; j0 < W; j0 += Q) {
+    const int q_now = std::min(Q, (int)W - j0);
+    const int n_max = P - W + j0 + q_now;                  // entries the pass's last query sees
+    const int chunks = (n_max + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(seed_scan_kernel, dim3((unsigned)((chunks + kThreads / 64 - 1) / (kThreads / 64)), (unsigned)count), dim3(kThreads), 0, s,
+                       c->dev, begin, (const uint16_t*)q_obs, j0, q_now, P, (int)W, c->seedlg, c->seedml);
     CKV_HIP(c, hipGetLastError());
-    const long long max_items = (long long)count * c->dev.max_chunks;
-    long long blocks = 2ll * c->n_cu;
-    if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
-    hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin,
-                       (const uint16_t*)q_obs + (size_t)j * q_stride, (void*)nullptr, 0, -1);
-    CKV_HIP(c, hipGetLastError());
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, (void*)nullptr,
-                       0u, 0, t_j + 1, t_j, 0, 0);
+    hipLaunchKernelGGL(seed_finish_kernel, dim3((unsigned)count), dim3(kSeedThreads), c->finish_lds, s, c->dev, begin, j0, q_now, P, (int)W,
+                       (const float*)c->seedlg, (const float*)c->seedml);
     CKV_HIP(c, hipGetLastError());
   }
   hipLaunchKernelGGL(seed_state_kernel, dim3(1, (unsigned)count), dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 1, c->par.t0 - 1);

@@ -158,8 +158,8 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
 // ends; it is bounded all the same (kSoftLimit polls, then `soft_fail` is raised and the kernel reports
 // it through the context's status word instead of hanging).
 struct alignas(16) RedBuf {
-  u64 v[2][4];
-  float t[2][4][4];
+  u64 v[2][8];          // one slot per wavefront: up to 512 threads
+  float t[2][8][4];
   int soft;         // arrivals at the counter barrier since the kernel began
   int soft_fail;    // a counter barrier gave up waiting
 };
@@ -1244,24 +1244,36 @@ __device__ __forceinline__ void decay4_of(const Dev& d, const int (&delta)[4], c
     if (delta[e] >= s_tab_n) dec[e] = decay_far(d, delta[e]);
 }
 
-// Mean attention weight of every entry of unit u into val[0..n).
-__device__ __forceinline__ void mean_weights(const Dev& d, int u, int n, const float* sM, const float* sInv, float* val,
+// Where a unit's scaled logits lie in memory: per block of 32 entries a group of rows [row][32], of which
+// the G rows from `p` on are the unit's heads (the scan kernel leaves exactly G rows per block; the prompt
+// replay leaves 16, G of them per query).
+struct LgView {
+  const float* p;      // head 0, entry 0
+  int blk_stride;      // floats from one block to the next
+};
+__device__ __forceinline__ LgView unit_logits(const Dev& d, int u) {
+  return LgView{d.logits + (size_t)u * d.G * d.cap, d.G * kBlk};
+}
+
+// Mean attention weight of every entry of a unit into val[0..n).
+template <int NT = kThreads>
+__device__ __forceinline__ void mean_weights(const Dev& d, LgView lv, int n, const float* sM, const float* sInv, float* val,
                                              int tid) {
   const int G = d.G;
   const float invG = 1.0f / (float)G;
-  const float* lg = d.logits + (size_t)u * G * d.cap;      // per block of 32 entries: [head][32]
-  for (int i0 = tid; i0 < n; i0 += 4 * kThreads) {
+  const float* lg = lv.p;
+  for (int i0 = tid; i0 < n; i0 += 4 * NT) {
     float x[4][kMaxGroup];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int i = i0 + r * kThreads;
-      const float* row = lg + (size_t)(i >> 5) * (G * kBlk) + (i & 31);
+      const int i = i0 + r * NT;
+      const float* row = lg + (size_t)(i >> 5) * lv.blk_stride + (i & 31);
 #pragma unroll
       for (int g = 0; g < kMaxGroup; ++g) x[r][g] = (i < n && g < G) ? row[g * kBlk] : -INFINITY;
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int i = i0 + r * kThreads;
+      const int i = i0 + r * NT;
       float a = 0.f;
 #pragma unroll
       for (int g = 0; g < kMaxGroup; ++g)
@@ -1396,16 +1408,16 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 // Mean attention weights of this thread's groups from logits in global memory
 // (per block of 32 entries: [head][32]); 0 beyond n.
 template <int R, int NT = kThreads>
-__device__ __forceinline__ void mean_weights_regs(const Dev& d, int u, int n, const float* sM, const float* sInv,
+__device__ __forceinline__ void mean_weights_regs(const Dev& d, LgView lv, int n, const float* sM, const float* sInv,
                                                   float (&a)[R], int tid) {
   const int G = d.G;
   const float invG = 1.0f / (float)G;
-  const float* lg = d.logits + (size_t)u * G * d.cap;
+  const float* lg = lv.p;
 #pragma unroll
   for (int c = 0; c < R / 4; ++c) {
     const int e0 = 4 * (tid + c * NT);
     f32x4 x[kMaxGroup];
-    const float* row = lg + (size_t)(e0 >> 5) * (G * kBlk) + (e0 & 31);
+    const float* row = lg + (size_t)(e0 >> 5) * lv.blk_stride + (e0 & 31);
 #pragma unroll
     for (int g = 0; g < kMaxGroup; ++g)
       x[g] = (e0 < n && g < G) ? *reinterpret_cast<const f32x4*>(row + g * kBlk) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
@@ -1691,6 +1703,49 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   }
 }
 
+// Mean weights of the unit's first n entries from its logits (softmax maxima sM and reciprocal denominators
+// sInv per head in LDS), then Alg. 1 Steps 1-3 at time t and, if asked, Step 4.  One workgroup of kThreads.
+// val: n floats of LDS, evm: the eviction bit mask behind them.
+// sh: 4 + NT / 64 ints.
+template <int NT = kThreads>
+__device__ __forceinline__ void unit_bookkeeping(const Dev& d, int u, int n, int B, int t, LgView lv, const float* sM,
+                                                 const float* sInv, bool evict, float* val, uint32_t* evm, const float* s_tab,
+                                                 int s_tab_n, RedBuf& rb, int& phase, int* sh, int tid) {
+  if (n <= 8 * NT) {
+    float a[8];
+    mean_weights_regs<8, NT>(d, lv, n, sM, sInv, a, tid);
+    f32x4 crf[2];
+    i32x4 tau[2], ps[2];
+    lrfu_regs<8, 2, 0, ValLinear, NT>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+                                      s_tab, s_tab_n, rb, phase, sh, tid);
+  } else if (n <= 16 * NT) {
+    float a[16];
+    mean_weights_regs<16, NT>(d, lv, n, sM, sInv, a, tid);
+    f32x4 crf[4];
+    i32x4 tau[4], ps[4];
+    lrfu_regs<16, 4, 0, ValLinear, NT>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+                                       s_tab, s_tab_n, rb, phase, sh, tid);
+  } else if (n <= 32 * NT) {
+    float a[32];
+    mean_weights_regs<32, NT>(d, lv, n, sM, sInv, a, tid);
+    f32x4 crf[8];
+    i32x4 tau[8], ps[8];
+    lrfu_regs<32, 8, 0, ValLinear, NT>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+                                       s_tab, s_tab_n, rb, phase, sh, tid);
+  } else {
+    mean_weights<NT>(d, lv, n, sM, sInv, val, tid);
+    const u64 sfix = lrfu_update<ValLinear, NT>(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
+    if (tid == 0) {
+      d.window[u] += sfix;
+      d.t_unit[u] = t;
+    }
+    if (evict && n > B)
+      evict_phase<ValLinear, NT>(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
+    else if (tid == 0)
+      d.nev[u] = 0;
+  }
+}
+
 // n_limit / t_fixed: the replay of a prompt's last queries runs the step over the unit's first n_limit
 // entries at time t_fixed (otherwise INT_MAX and -1: all entries, the context's time).
 // late: 0 = the whole step.  1 = the bookkeeping alone (mean weights, Alg. 1 Steps 1-4) of a single-layer
@@ -1718,45 +1773,138 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
     merge_partials(d, u, urel, nch, seq, sM, sInv, sW, late ? nullptr : out, tid);
-    const bool evict = (call_flags & 1u) != 0;
-    if (n <= 8 * kThreads) {
-      float a[8];
-      mean_weights_regs(d, u, n, sM, sInv, a, tid);
-      f32x4 crf[2];
-      i32x4 tau[2], ps[2];
-      lrfu_regs<8, 2, 0, ValLinear>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
-                  s_tab, s_tab_n, rb,
-                   phase, sh, tid);
-    } else if (n <= 16 * kThreads) {
-      float a[16];
-      mean_weights_regs(d, u, n, sM, sInv, a, tid);
-      f32x4 crf[4];
-      i32x4 tau[4], ps[4];
-      lrfu_regs<16, 4, 0, ValLinear>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
-                   s_tab, s_tab_n, rb,
-                    phase, sh, tid);
-    } else if (n <= 32 * kThreads) {
-      float a[32];
-      mean_weights_regs(d, u, n, sM, sInv, a, tid);
-      f32x4 crf[8];
-      i32x4 tau[8], ps[8];
-      lrfu_regs<32, 8, 0, ValLinear>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
-                   s_tab, s_tab_n, rb,
-                    phase, sh, tid);
-    } else {
-      mean_weights(d, u, n, sM, sInv, val, tid);
-      const u64 sfix = lrfu_update(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
-      if (tid == 0) {
-        d.window[u] += sfix;
-        d.t_unit[u] = t;
-      }
-      if (evict && n > B)
-        evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
-      else if (tid == 0)
-        d.nev[u] = 0;
-    }
+    unit_bookkeeping(d, u, n, B, t, unit_logits(d, u), sM, sInv, (call_flags & 1u) != 0, val, evm, s_tab, s_tab_n, rb, phase, sh, tid);
   }
   if (!late) step_epilogue(d, t, advance, tid);
+}
+
+// ------------------------------------------------------------------ prompt replay (scores of a loaded prompt)
+// The prompt's last W queries, Q = 16 / G of them per pass over the keys: the matrix-core tile has 16 query
+// columns, of which a decode step fills G.  Column c of a pass holds head c % G of query j0 + c / G.  Only the
+// weights are wanted (no output), so V is never read.
+//
+// seed_scan_kernel: one wavefront per 256-entry chunk of a unit.  Per block of 32 entries the scaled logits of
+// all 16 columns go to `slg` ([unit][block][column][32]); query j sees the entries of positions <= its own,
+// i.e. indices < P - W + j + 1 (the prompt's entries sit in position order), the rest is masked.  Per chunk and
+// column the running maximum and sum of the softmax go to `sml`.
+// grid: (ceil(chunks / 4), units of the layer), kThreads threads.
+constexpr int kSeedCols = 16;
+
+__global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q_obs, int j0,
+                                                             int Q, int P, int W, float* __restrict__ slg,
+                                                             float* __restrict__ sml) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int urel = blockIdx.y, u = unit_begin + urel;
+  const int chunk = blockIdx.x * (kThreads / 64) + wave;
+  const int G = d.G;
+  const int j = lane & 15, kg = lane >> 4;
+  const int qi = min(j / G, Q - 1);                       // the column's query within the pass (columns beyond Q G: unused)
+  const bool col_ok = j < Q * G;
+  const int n_first = P - W + j0 + 1;                     // entries the pass's first query sees
+  const int lim = col_ok ? n_first + qi : 0;              // entries this column's query sees
+  const int n_max = n_first + Q - 1;                      // ... and the pass's last query
+  const int e_chunk = chunk * kChunk;
+  const int mc = d.max_chunks;
+  if (e_chunk >= n_max) return;
+  // queries: B operand, lane (j, kg) holds dims 32 s + 8 kg .. + 7 of its column's head
+  bf16x8 qv[4];
+  {
+    const int b = urel / d.Hkv, h = urel % d.Hkv;
+    const uint16_t* qrow = q_obs + ((((size_t)(j0 + qi) * d.Bz + b) * d.Hq) + (size_t)h * G + (j % G)) * kDim + 8 * kg;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      u32x4 x = *reinterpret_cast<const u32x4*>(qrow + 32 * s4);
+      if (!col_ok) x = u32x4{0u, 0u, 0u, 0u};
+      qv[s4] = as_bf16x8(x);
+    }
+  }
+  const int nblk = min(kChunkBlocks, (n_max - e_chunk + kBlk - 1) / kBlk);
+  const uint16_t* kb = d.K + (size_t)u * d.cap * kDim + (size_t)chunk * kChunkBlocks * kBlkElems + lane * 8;
+  float* lgp = slg + ((size_t)urel * (d.cap / kBlk) + (size_t)chunk * kChunkBlocks) * (kSeedCols * kBlk) + j * kBlk + 4 * kg;
+  float m_run = -INFINITY, l_run = 0.f;                   // this lane's entries only; the four lanes of a column meet at the end
+  KFrag ka, kn;
+  load_k(ka, kb);
+  for (int blk = 0; blk < nblk; ++blk) {
+    if (blk + 1 < nblk) load_k(kn, kb + (size_t)(blk + 1) * kBlkElems);
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[s4]), qv[s4], s0, 0, 0, 0);
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[4 + s4]), qv[s4], s1, 0, 0, 0);
+    const int e0 = e_chunk + blk * kBlk + 4 * kg;
+    float sv[8];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      sv[v] = (e0 + v < lim) ? s0[v] * d.scale_log2e : -INFINITY;
+      sv[4 + v] = (e0 + 16 + v < lim) ? s1[v] * d.scale_log2e : -INFINITY;
+    }
+    *reinterpret_cast<f32x4*>(lgp + (size_t)blk * (kSeedCols * kBlk)) = f32x4{sv[0], sv[1], sv[2], sv[3]};
+    *reinterpret_cast<f32x4*>(lgp + (size_t)blk * (kSeedCols * kBlk) + 16) = f32x4{sv[4], sv[5], sv[6], sv[7]};
+    float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    if (bm > m_run) {
+      l_run *= fast_exp2(m_run - bm);                     // exp2(-inf) = 0 the first time
+      m_run = bm;
+    }
+    if (m_run > -INFINITY) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) l_run += fast_exp2(sv[i] - m_run);
+    }
+    if (blk + 1 < nblk) ka = kn;
+  }
+  // the column's four lanes (kg = 0..3): maximum, then the sums rescaled to it, in a fixed order
+  float M = fmaxf(m_run, __shfl_xor(m_run, 16));
+  M = fmaxf(M, __shfl_xor(M, 32));
+  const float mine = m_run > -INFINITY ? l_run * fast_exp2(m_run - M) : 0.f;
+  const float l0 = __shfl(mine, j), l1 = __shfl(mine, j + 16), l2 = __shfl(mine, j + 32), l3 = __shfl(mine, j + 48);
+  if (kg == 0) {
+    float* dst = sml + (((size_t)urel * mc + chunk) * kSeedCols + j) * 2;
+    dst[0] = M;
+    dst[1] = (l0 + l1) + (l2 + l3);
+  }
+}
+
+// seed_finish_kernel: one workgroup per unit; the pass's queries in order, each one a decode step's
+// bookkeeping without eviction at its own time over the entries it sees (Alg. 1 Steps 1-3): softmax maxima
+// and denominators of its G columns from the chunks' partials, mean weights from the logits, hit set, scores.
+constexpr int kSeedThreads = 512;      // twice a decode step's workgroup: prompts are long, and a layer has few units
+
+__global__ __launch_bounds__(kSeedThreads) void seed_finish_kernel(Dev d, int unit_begin, int j0, int Q, int P, int W,
+                                                               const float* __restrict__ slg, const float* __restrict__ sml) {
+  extern __shared__ unsigned char smem[];
+  float* val = reinterpret_cast<float*>(smem);
+  uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
+  __shared__ __align__(16) float sM[kMaxGroup];
+  __shared__ __align__(16) float sInv[kMaxGroup];
+  __shared__ RedBuf rb;
+  __shared__ int sh[4 + kSeedThreads / 64];
+  __shared__ float s_tab[kTabLds];
+  const int tid = threadIdx.x;
+  const int urel = blockIdx.x, u = unit_begin + urel;
+  const int G = d.G, mc = d.max_chunks;
+  const int s_tab_n = min(kTabLds, d.tab_last + 1);
+  if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
+  int phase = 0;
+  for (int qi = 0; qi < Q; ++qi) {
+    const int t = P - W + j0 + qi;                        // the query's position = its time
+    const int n = t + 1;
+    const int nch = (n + kChunk - 1) / kChunk;
+    __syncthreads();                                      // the previous query's readers of sM / sInv are done
+    if (tid < G) {
+      const float* ml = sml + ((size_t)urel * mc * kSeedCols + (size_t)(qi * G + tid)) * 2;
+      float M = -INFINITY;
+      for (int c = 0; c < nch; ++c) M = fmaxf(M, ml[(size_t)c * kSeedCols * 2]);
+      float L = 0.f;
+      for (int c = 0; c < nch; ++c) {
+        const float m = ml[(size_t)c * kSeedCols * 2];
+        if (m > -INFINITY) L += ml[(size_t)c * kSeedCols * 2 + 1] * fast_exp2(m - M);
+      }
+      sM[tid] = M;
+      sInv[tid] = 1.0f / L;
+    }
+    __syncthreads();
+    const LgView lv{slg + (size_t)urel * (d.cap / kBlk) * (kSeedCols * kBlk) + (size_t)qi * G * kBlk, kSeedCols * kBlk};
+    unit_bookkeeping<kSeedThreads>(d, u, n, d.cap, t, lv, sM, sInv, false, val, evm, s_tab, s_tab_n, rb, phase, sh, tid);
+  }
 }
 
 // Alg. 1 Step 4 on its own: scores decayed to the unit's last step, no update.
@@ -1811,7 +1959,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, 
   int phase = 0;
   if (n > 0) {
     merge_partials(d, u, urel, (n + kChunk - 1) / kChunk, d.sc[SC_SEQ], sM, sInv, sW, nullptr, tid);
-    mean_weights(d, u, n, sM, sInv, val, tid);
+    mean_weights(d, unit_logits(d, u), n, sM, sInv, val, tid);
     const int kq = (3 * n) / 10;
     // order key: ascending = (weight asc, position desc); Crystal = kq largest, Slip = kq smallest
     u64 lo_cut = 0, hi_cut = ~0ull;

@@ -212,14 +212,17 @@ def test_path_selection_api():
 
 
 @pytest.mark.parametrize("hq,hkv,P,W,lam", [(8, 2, 45, 9, 0.5), (10, 2, 70, 32, 0.7), (2, 2, 33, 1, 0.5), (14, 2, 300, 17, 0.97),
-                                             (16, 2, 64, 64, 0.0), (8, 2, 610, 40, 1.0)])
+                                             (16, 2, 64, 64, 0.0), (8, 2, 610, 40, 1.0), (10, 2, 4105, 20, 0.7), (8, 2, 9000, 6, 0.5),
+                                             (2, 2, 16390, 21, 0.5)])
 def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam):
     """Scores of a loaded prompt from its last W queries (all of it for W = P, one query for W = 1; prompts
-    shorter and longer than a 256-entry chunk, not multiples of the 32-entry block): CRF bits and tau of
-    every entry equal the oracle's; the time and the Alg. 2 window are untouched (the decode steps and
-    the re-allocation that follow match the oracle as after any load)."""
-    cfg = _small("tiny", n_layers=2, n_q_heads=hq, n_kv_heads=hkv, prompt=P, decode_steps=max(W, 10), lam=lam,
-                 budget=P + 5, budget_min=8, budget_max=P + 30, seed=300 + W)
+    shorter and longer than a 256-entry chunk, not multiples of the 32-entry block; windows that are and are not
+    multiples of the number of queries a pass over the keys takes, floor(16 / G) = 4, 3, 16, 2, 2; windows across
+    the prompt lengths at which the replay's bookkeeping changes its code path, 8, 16 and 32 entries per thread
+    of a 512-thread workgroup): CRF bits and tau of every entry equal the oracle's; the time and the Alg. 2
+    window are untouched (the decode steps and the re-allocation that follow match the oracle as after any load)."""
+    cfg = _small("tiny", n_layers=2, batch=2 if P < 4000 else 1, n_q_heads=hq, n_kv_heads=hkv, prompt=P, decode_steps=max(W, 10),
+                 lam=lam, budget=P + 5, budget_min=8, budget_max=P + 30, seed=300 + W)
     st, o, g = _pair(cfg, cap=(P + 64) // 32 * 32)
     total0 = o.budgets().sum(axis=(0, 2))
     resync = 0
