@@ -376,6 +376,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.cap = layout->cap;
   d.units = c->units;
   d.unit0 = 0;
+  d.by_order = 1;
   d.max_chunks = (layout->cap + kChunk - 1) / kChunk;
   d.slots = d.max_chunks + 1;
   d.out_bf16 = layout->out_dtype == CKV_BF16;
@@ -518,9 +519,12 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (fv == &c->fused[2] && (flags & CKV_ATTENTION_ONLY)) fv = &c->fused[0];   // no bookkeeping to move aside
   const bool fused = fv != nullptr;
   if (int rc = join_side(c, s, layer)) return rc;
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                     (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? (layer >= 0 ? 7 : 3) : 1, INT_MAX, (const uint16_t*)q);
-  CKV_HIP(c, hipGetLastError());
+  // unit_kernel<W> appends by itself; the other kernels get the new entries (and their schedule or work list) from prep_kernel
+  if (!fused || fv == &c->fused[2]) {
+    hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
+                       (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? (layer >= 0 ? 7 : 3) : 1, INT_MAX, (const uint16_t*)q);
+    CKV_HIP(c, hipGetLastError());
+  }
 
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (c->profile) {
@@ -544,15 +548,17 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     dv.sched = c->dev.sched + (layer >= 0 ? begin : 0);
     dv.units = count;
     dv.unit0 = layer >= 0 ? begin : 0;
+    dv.by_order = layer >= 0 ? 0 : 1;
     const uint16_t* qb = (const uint16_t*)q;
     const uint16_t* vb = (const uint16_t*)v_new;
+    const uint16_t* kb = (const uint16_t*)k_new;
     void* ob = out;
     if (fv == &c->fused[2])
       hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
     else if (fv->waves == 4)
-      hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
+      hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb, kb);
     else
-      hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
+      hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb, kb);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
     return CKV_OK;

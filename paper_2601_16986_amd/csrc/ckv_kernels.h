@@ -40,7 +40,8 @@ constexpr int kTabLds = 256;              // decay-table entries kept in LDS by 
 
 struct Dev {
   int32_t L, Bz, Hq, Hkv, G, cap, units, max_chunks, slots, out_bf16;   // slots = partial slots per unit
-  int32_t unit0;         // fused kernel: unit whose rows come first in the call's q, v_new and out (a single layer's first unit)
+  int32_t unit0;         // fused kernel: unit whose rows come first in the call's q, k_new, v_new and out (a single layer's first unit)
+  int32_t by_order;      // fused kernel: schedule slot i holds unit order[i] (all layers), else unit unit0 + i (one layer)
   float scale_log2e;     // softmax_scale * log2(e): logits are kept in the base-2 domain
   float top_p;
   int32_t reward_mode, bmin, bmax, tab_last;
@@ -994,8 +995,8 @@ __device__ __forceinline__ void evict_one(const Dev& d, size_t base, int src, in
       d.crf[base + dst] = __int_as_float(sh[1]);
       d.tau[base + dst] = sh[2];
       d.pos[base + dst] = sh[3];
-      d.pos[base + src] = sh[4];
     }
+    d.pos[base + src] = sh[4];                 // the victim's position (the last slot's own if that is the victim)
     d.flags[base + src] = FLAG_SLIP;
   }
 }
@@ -1459,16 +1460,41 @@ struct NoHook {
   __device__ __forceinline__ void operator()() const {}
 };
 
+// The entry appended in this step when the caller has NOT written it to the cache (the fused kernel when
+// exactly one entry will be evicted): logically it is the unit's last entry, index n - 1, with CRF 0,
+// tau = t and position t; its key and value rows are the step's inputs.  Its per-slot state is supplied
+// here instead of being read, and if it survives the eviction its rows go straight from the inputs into
+// the victim's slot (one write instead of a write, a read and a write).  k_row == nullptr: the entry is in
+// the cache like any other (or nothing was appended).
+struct NewEntry {
+  const uint16_t* k_row;    // 128 bf16, or nullptr
+  const uint16_t* v_row;
+};
+
+template <int NT = kThreads>
+__device__ __forceinline__ EntryRow load_row_input(const NewEntry& ne, int tid) {
+  const int wave = tid >> 6, lane = tid & 63;
+  constexpr int W = NT / 64;
+  EntryRow r{{0u, 0u, 0u, 0u}, 0, 0};
+  if (wave == 0 && lane < 16) r.k = *reinterpret_cast<const u32x4*>(ne.k_row + lane * 8);
+  if (wave == (W > 1 ? 1 : 0)) {
+    r.v0 = ne.v_row[lane];
+    r.v1 = ne.v_row[lane + 64];
+  }
+  return r;
+}
+
 // `after_step1` runs once between Step 1 and the score update (the fused kernel
 // picks up its queue claim there).
 template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook, int SB = 0>
 __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
                                           i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
                                           int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
-                                          int tid, Hook after_step1 = Hook{}) {
+                                          int tid, Hook after_step1 = Hook{}, NewEntry ne = NewEntry{nullptr, nullptr}) {
   constexpr int C = R / 4;
   static_assert(C % CH == 0 && CP <= CH, "groups come in chunks of CH");
   const size_t base = (size_t)u * d.cap;
+  const bool new_in_regs = ne.k_row != nullptr;          // uniform; implies that exactly one entry is evicted below
 #pragma unroll
   for (int c = CP; c < CH; ++c) load_meta<NT>(d, base, n, t, c, tid, crf[c], tau[c], ps[c]);
   // what the end of the step would otherwise wait for: the unit's running sum, and the last slot's rows
@@ -1476,7 +1502,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
   const u64 window0 = d.window[u];
   const bool evict_single = evict && n - B == 1;
   EntryRow last_row{{0u, 0u, 0u, 0u}, 0, 0};
-  if (evict_single) last_row = load_row<NT>(d, base, n - 1, tid);
+  if (evict_single) last_row = new_in_regs ? load_row_input<NT>(ne, tid) : load_row<NT>(d, base, n - 1, tid);
   // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
   uint32_t theta = 0;
   bool ties_all = true;
@@ -1587,7 +1613,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
             int cnt = 0;
             for (int k = 0; k < R; ++k) {
               const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
-              if (__float_as_uint(a[k]) == theta && i < n && d.pos[base + i] < trial) ++cnt;
+              if (__float_as_uint(a[k]) == theta && i < n && ((new_in_regs && i == n - 1) ? t : d.pos[base + i]) < trial) ++cnt;
             }
             cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
@@ -1628,15 +1654,17 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     for (int e = 0; e < 4; ++e) {
       const int i = e0 + e;
       const bool ok = i < n;
-      const int pe = ps[c][e];
+      const bool fresh = new_in_regs & (i == n - 1);                 // the new entry, not in the cache: CRF 0, tau = position = t
+      const int pe = fresh ? t : ps[c][e];
       const float w = a[4 * cc + e];
-      const float dec = dec4[e];
+      const float dec = fresh ? 1.0f : dec4[e];
+      const float crf_old = fresh ? 0.0f : crf[c][e];
       const uint32_t b = __float_as_uint(w);
       const bool hit = topp & ((b > theta) | ((b == theta) & (ties_all | (pe <= pos_cut))) |
                                ((i == n - 1) & (pe == t)));          // the entry appended this step is always hit
       const bool store = ok & (hit | !topp);
       const float reward = topp ? (hit ? 1.0f : 0.0f) : w;
-      float tmp = __fadd_rn(__fmul_rn(dec, crf[c][e]), reward);
+      float tmp = __fadd_rn(__fmul_rn(dec, crf_old), reward);
       tmp = tmp < FLT_MIN ? 0.0f : tmp;
       ncrf[e] = store ? tmp : ncrf[e];
       ntau[e] = store ? t : ntau[e];

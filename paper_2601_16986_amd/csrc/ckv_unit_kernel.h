@@ -78,10 +78,20 @@ __global__ __launch_bounds__(1024) void schedule_kernel(Dev d) {
 }
 
 // W wavefronts per workgroup (and per unit), 8 / W workgroups per CU.
+//
+// The kernel also appends: there is no separate pass over the units before it.  The entry that arrives in this
+// step is never streamed from the cache.  Its logits are the dot products of the step's inputs (computed here),
+// it joins the merge as one more online-softmax state (max = its logit, sum = 1, accumulator = its value row),
+// and its logit is put where the bookkeeping looks for it.  In the steady state (exactly one entry evicted
+// per step) it is not even written to the slot behind the unit's entries first: if it survives the eviction its
+// rows go straight from the inputs into the victim's slot, otherwise only its position is logged.  In the
+// other cases (no eviction, several evictions, units too long for the register paths) it is written to
+// slot n at the start of the unit, before anything reads that slot.
 template <int W>
 __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* __restrict__ q, void* out,
                                                              uint32_t call_flags, int advance, int lds_main,
-                                                             const uint16_t* __restrict__ v_new) {
+                                                             const uint16_t* __restrict__ v_new,
+                                                             const uint16_t* __restrict__ k_new) {
   constexpr int NT = 64 * W;
   constexpr int kSlices = W / 2;             // LDS slices the accumulators are merged through, two waves each
   extern __shared__ unsigned char smem[];
@@ -116,19 +126,26 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   // result of the vector memory pipeline is a wait for all results requested before it).
   __shared__ int s_claim;
   const int grid = (int)gridDim.x, wg = (int)blockIdx.x;
-  // `lone`: the entry appended in this step opens a block of its own (a fixed budget that is a multiple of 32
-  // makes that the steady state).  Its logits come ready-made from prep_kernel and its value row from the step's
-  // input, so it joins the merge as one more online-softmax state and the block is never streamed.
-  auto fetch = [&](int slot, int& uu, int& nn, int& bb, int& ll) {      // uniform slot: scalar loads
-    const int4 e = d.sched[min(slot, n_units - 1)];
-    uu = slot < n_units ? e.x : -1;
-    nn = e.y;
-    bb = e.z;
-    ll = (e.w != 0 && ((e.y - 1) & (kBlk - 1)) == 0) ? 1 : 0;
+  // Which unit a schedule slot holds (all layers: the units by descending budget; one layer: its units in
+  // order) and what the unit holds: scalar loads, the unit two iterations and its state one iteration
+  // before they are needed.  `lone` = 1: an entry is appended in this step (0: the unit is full, which
+  // the status word reports); n counts it.
+  auto unit_of = [&](int slot) -> int {
+    const int sl = min(slot, n_units - 1);
+    const int uu = d.by_order ? d.order[sl] : d.unit0 + sl;
+    return slot < n_units ? uu : -1;
   };
-  int u, n, B, lone, u1, n1, B1, lone1;
-  fetch(wg, u, n, B, lone);
-  fetch(grid + wg, u1, n1, B1, lone1);
+  auto state_of = [&](int uu, int& nn, int& bb, int& ll) {
+    const int us = max(uu, 0);
+    const int n_old = d.n[us];
+    bb = d.budget[us];
+    ll = n_old < d.cap ? 1 : 0;
+    nn = n_old + ll;
+  };
+  int u, n, B, lone, u1, n1 = 0, B1 = 0, lone1 = 0;
+  u = unit_of(wg);
+  state_of(u, n, B, lone);
+  u1 = unit_of(grid + wg);
   int slot2 = 2 * grid + wg;                                   // slot of the unit after next
   // Per-lane values are re-derived, from a copy of the lane index the compiler cannot see through, at
   // the start of every phase that needs them: otherwise they are computed once, kept alive across the
@@ -159,19 +176,43 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     load_v(va, d.V + o);
     load_q(u);
   }
+  const bool evict = (call_flags & 1u) != 0;
 
   while (u >= 0) {
-    const int ns = n - lone;                       // entries that are streamed
+    const int ns = n - lone;                       // entries that are streamed: all but the one that arrives now
+    // the new entry stays out of the cache until the eviction has chosen its slot (see above); otherwise it is
+    // written to slot n - 1 now, by three wavefronts (key row, value row, per-slot state)
+    const bool new_in_regs = lone && evict && n - B == 1 && n <= 32 * NT;
+    if (lone && !new_in_regs) {
+      const size_t base = (size_t)u * d.cap;
+      const uint16_t* krow = k_new + (size_t)(u - d.unit0) * kDim;
+      const uint16_t* vrow = v_new + (size_t)(u - d.unit0) * kDim;
+      asm volatile("" : "+v"(slane));
+      if (wave == 0 && slane < 16)
+        *reinterpret_cast<u32x4*>(d.K + base * kDim + k_offset(n - 1, slane * 8)) = *reinterpret_cast<const u32x4*>(krow + slane * 8);
+      if (wave == (W > 1 ? 1 : 0)) {
+        d.V[base * kDim + v_offset(n - 1, slane)] = vrow[slane];
+        d.V[base * kDim + v_offset(n - 1, slane + 64)] = vrow[slane + 64];
+      }
+      if (wave == (W > 2 ? 2 : 0) && slane == 32) {
+        d.crf[base + n - 1] = 0.0f;
+        d.tau[base + n - 1] = t;
+        d.pos[base + n - 1] = t;
+        d.flags[base + n - 1] = 0;
+        d.n[u] = n;
+      }
+    }
+    if (!lone && tid == 0) atomicOr(&d.sc[SC_STATUS], 1);        // the unit is full: nothing was appended
     const int nblk = (ns + kBlk - 1) / kBlk;
     const int n_res = resident_entries(n, G, lds_main);
     const int res_blk = n_res / kBlk;
     const int my_cnt = wave < nblk ? (nblk - wave + W - 1) / W : 0;
 
     asm volatile("" : "+v"(slane));
-    // ---- schedule entry of the unit after next: scalar loads, waited for with the first LDS access
-    // below, a unit before they are needed
-    int u2, n2, B2, lone2;
-    fetch(slot2, u2, n2, B2, lone2);
+    // ---- the unit after next, and the state of the next one: scalar loads, waited for with the first LDS
+    // access below, long before they are needed
+    const int u2 = unit_of(slot2);
+    state_of(u1, n1, B1, lone1);
 
     // ---- stream this wave's blocks (wave + W i, i < my_cnt): while block i is computed, block i + 1 is
     // in flight; the last block's successor is the wave's first block of the next unit, so the loads
@@ -203,9 +244,13 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     const int u_next = have_next ? u1 : u;
     const int n_next = have_next ? n1 - lone1 : ns;
     const size_t o_next = first_off(u_next, n_next);
-    // the new entry's logit (threads below G) and value element, requested a block before they are used
-    const float snew = d.snew[(size_t)u * kMaxGroup + (slane & (kMaxGroup - 1))];
+    // the new entry's key as one more row for the matrix cores (what a lane holds of row 0 of a key tile: dims
+    // 32 s + 8 kg .. + 7) and its value element, requested a block before they are used
     const uint16_t vnew = v_new[(size_t)(u - d.unit0) * kDim + (slane & 63) + 64 * (wave & 1)];
+    u32x4 knew[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+      knew[s4] = *reinterpret_cast<const u32x4*>(k_new + (size_t)(u - d.unit0) * kDim + 32 * s4 + 8 * (slane >> 4));
     if (my_cnt > 0) {
       float sv[8];
       qk(wave + W * (my_cnt - 1), sv);
@@ -234,6 +279,21 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
+    // Scaled logits of the new entry, head g in lane g: the same matrix-core products as for a cached key (the
+    // key sits in row 0 of an otherwise empty tile), so that a key equal to a cached one gets the same bits
+    // and ties between them are broken by position, as the definition says.
+    float snew;
+    {
+      asm volatile("" : "+v"(slane));
+      const bool row0 = (slane & 15) == 0;
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        const u32x4 x = row0 ? knew[s4] : u32x4{0u, 0u, 0u, 0u};
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(x), qv[s4], s0, 0, 0, 0);
+      }
+      snew = s0[0] * d.scale_log2e;                   // lane (j, kg = 0) = lane j: row 0, head j
+    }
     asm volatile("" : "+v"(slane));
     const int j = slane & 15, kg = slane >> 4;
     if (j < G && kg == 0) {
@@ -243,15 +303,17 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     if (ftid < G) {
       s_ml[W][ftid][0] = lone ? snew : -INFINITY;
       s_ml[W][ftid][1] = lone ? 1.f : 0.f;
-      if (lone && !(call_flags & 2u)) {             // its logit where the bookkeeping looks for it: column 0 of its block
-        const int bn = (n - 1) / kBlk;
-        if (bn < res_blk)
-          lg[(size_t)bn * (G * kBlk) + ftid * kBlk] = snew;
-        else
-          d.logits[(size_t)u * d.cap * G + (size_t)bn * (G * kBlk) + ftid * kBlk] = snew;
-      }
     }
     __syncthreads();
+    // the new entry's logit where the bookkeeping looks for it: its column of its block.  After the barrier: the
+    // wavefront that streamed that block has written the block's rows (with the column masked) by now
+    if (ftid < G && lone && !(call_flags & 2u)) {
+      const int bn = (n - 1) / kBlk, col = (n - 1) & (kBlk - 1);
+      if (bn < res_blk)
+        lg[(size_t)bn * (G * kBlk) + ftid * kBlk + col] = snew;
+      else
+        d.logits[(size_t)u * d.cap * G + (size_t)bn * (G * kBlk) + ftid * kBlk + col] = snew;
+    }
 
     // ---- merge the four online-softmax states -> out.  Every thread derives the global max and
     // denominator of the heads it needs from s_ml (same fixed order everywhere); waves 0 and 1 deposit
@@ -317,8 +379,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     asm volatile("" : "+v"(ftid));
     int phase = 0;      // block reductions of different units are separated by barriers
     const ValFused val{lg, lg + (size_t)n_res * G, n_res, G * kBlk};
-    const bool evict = (call_flags & 1u) != 0;
     const float invG = 1.0f / (float)G;
+    const NewEntry ne{new_in_regs ? k_new + (size_t)(u - d.unit0) * kDim : nullptr, v_new + (size_t)(u - d.unit0) * kDim};
     const float* lgg = d.logits + (size_t)u * d.cap * G;
     // mean weights of the four consecutive entries e0 .. e0 + 3 (one 16-byte read per head; the heads'
     // maxima and reciprocal denominators are read as four 16-byte vectors per group, not once per use)
@@ -370,7 +432,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
         if (ftid == 0) s_claim = 3 * grid + claimed;
       };
       lrfu_regs<R, CH, CH, ValFused, NT>(d, u, n, B, t, a, crf, tau, ps, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4,
-                                         s_tab, s_tab_n, rb, phase, sh, ftid, publish);
+                                         s_tab, s_tab_n, rb, phase, sh, ftid, publish, ne);
     };
     if (call_flags & 2u) {               // attention only: no bookkeeping, just keep the stream and the queue going
       request_next();
@@ -408,11 +470,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     u = u1;
     n = n1;
     B = B1;
-    u1 = u2;
-    n1 = n2;
-    B1 = B2;
     lone = lone1;
-    lone1 = lone2;
+    u1 = u2;
     slot2 = __builtin_amdgcn_readfirstlane(s_claim);
   }
   step_epilogue(d, t, advance, tid, 0);
