@@ -28,9 +28,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-RING = 32                     # distinct synthetic step inputs, replayed cyclically.  Not fewer: entries with
-                              # identical keys tie in the top-p and eviction orders, and a cache that fills up
-                              # with copies of a few keys drifts into the (slow, unrealistic) tie-breaking paths
+RING = 32                     # distinct synthetic step inputs held at a time (and steps per HIP graph).  The timed
+                              # regions refill them with fresh draws between repeats: a replayed input inserts keys
+                              # that are exact duplicates of cached ones, identical keys tie in the top-p and
+                              # eviction orders, and a cache that fills up with copies drifts into the (slow,
+                              # unrealistic) tie-breaking paths
 
 
 def build_workload(cfg, device, budgets=None):
@@ -55,8 +57,23 @@ def build_workload(cfg, device, budgets=None):
         g.load_cache(layer, k, v, n, crf, tau, pos)
         torch.cuda.synchronize()
         del k, v, n, crf, tau, pos
-    ring = wl.torch_step_ring(cfg, RING, m, r_now, device)
+    ring, r_end = wl.torch_step_ring(cfg, RING, m, r_now, device, return_state=True)
+    g.refill = _refiller(cfg, ring, m, r_end, device)
     return g, budgets, ring
+
+
+def _refiller(cfg, ring, m, r_state, device):
+    """refill(): overwrite the ring's tensors in place (HIP graphs that read them stay valid) with the next
+    RING steps' inputs, drawn fresh, the drift continuing where the last batch ended."""
+    from paper_2601_16986_amd import workloads as wl
+    state = {"r": r_state, "epoch": 0}
+
+    def refill():
+        state["epoch"] += 1
+        fresh, state["r"] = wl.torch_step_ring(cfg, RING, m, state["r"], device, epoch=state["epoch"], return_state=True)
+        for dst, src in zip(ring, fresh):
+            dst.copy_(src)
+    return refill
 
 
 def build_fullkv(cfg, device, tokens, total_steps):
@@ -148,7 +165,7 @@ def algorithmic_bytes(cfg, budgets):
     U, G = n.size, cfg.group
     scan = int(n.sum()) * 512 + U * G * 256
     step = int(n.sum()) * 524 + U * (G * 256 + G * 512 + 512 + 2 * 524)
-    fused = step - U * 512                               # the fused kernel does everything but the append
+    fused = step                                         # the fused kernel does the whole step, the append included
     return scan, step, int(n.sum()), fused
 
 
@@ -328,23 +345,32 @@ def main():
             with torch.cuda.graph(g_tail):
                 eager_steps(n_tail)
         torch.cuda.synchronize()
+    # Every RING steps the ring is refilled with fresh inputs; the refills (input generation, not part of the
+    # path) are kept out of the clock: the K steps are timed in pieces of up to RING steps, each piece
+    # synchronised on both sides, and a repeat's time is the sum of its pieces.
+    refill = getattr(g, "refill", None)
     times = []
     for _ in range(repeats):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        if args.no_graph:
-            eager_steps(steps)
-        else:
-            for _ in range(n_full):
-                g_full.replay()
-            if n_tail:
-                g_tail.replay()
-        torch.cuda.synchronize()
-        times.append((time.perf_counter() - t0) * 1e3 / steps)
+        total = 0.0
+        pieces = [RING] * n_full + ([n_tail] if n_tail else [])
+        for k in pieces:
+            if refill is not None:
+                refill()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if args.no_graph:
+                eager_steps(k)
+            else:
+                (g_full if k == RING else g_tail).replay()
+            torch.cuda.synchronize()
+            total += time.perf_counter() - t0
+        times.append(total * 1e3 / steps)
     ms_steps_only = float(np.median(times))
     assert g.status() == 0
 
     # ---- roofline pass: eager, HIP events around every launch of the dominant kernel
+    if refill is not None:
+        refill()
     g.profile_enable(True)
     eager_steps(RING)
     scan_ms, launches = g.profile_read()
@@ -385,6 +411,8 @@ def main():
             torch.cuda.synchronize()
             tl = []
             for _ in range(3):
+                if refill is not None:
+                    refill()
                 torch.cuda.synchronize()
                 t1 = time.perf_counter()
                 gl.replay()
@@ -441,7 +469,7 @@ def main():
                     f"every cache holds all {args.fullkv} positions and grows by one per step"),
                    "units": int(cfg.n_units), "entries_per_step": entries,
                    "launch": ("all layers per call, eager" if args.no_graph else
-                              f"all layers per call, HIP graphs of up to {RING} steps, median of {repeats} timed regions of {steps} steps")},
+                              f"all layers per call, HIP graphs of up to {RING} steps, fresh inputs every {RING} steps, median of {repeats} timed regions of {steps} steps")},
         "rebudget": rebudget,
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

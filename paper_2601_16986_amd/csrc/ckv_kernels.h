@@ -1526,6 +1526,9 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     };
     constexpr int kListBit = 17;        // the rounds for the bits above this one run over all entries
     int bit = 29;
+    bool from_list = false;             // the tail ran on the short list, which also gave:
+    int list_ties = 0;                  //   entries equal to theta
+    float list_above = 0.f;             //   total weight of the entries above theta
     for (; bit > kListBit; bit -= 2) round(bit);
     // With the top 12 bits fixed, the weights that can still decide a candidate, those in
     // [theta, theta + 2^18), are usually a handful.  If at most 64, they are collected in LDS (in a fixed
@@ -1569,34 +1572,55 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
         }
         block_sync<NT, SB>(rb);
         if (wave == 0) {
+          // One candidate per lane.  The largest pattern theta with sum{a >= theta} > p is a candidate's own
+          // pattern: the largest one whose sum of candidates at least as large, on top of what lies above the
+          // bucket, exceeds p (what the remaining rounds of the bisection would arrive at).  Every entry
+          // equal to theta is in the list too, so the number of such ties and the weight above theta are
+          // known here as well, without two more reductions over all entries.
           const uint32_t bj = lane < m ? (uint32_t)lst[lane] : 0u;
           const float aj = __uint_as_float(bj);
-          for (; bit >= 1; bit -= 2) {
-            const uint32_t c1 = theta | (1u << (bit - 1)), c2 = theta | (1u << bit), c3 = c1 | c2;
-            const float p1 = above_bucket + wave_sum_f32(bj >= c1 ? aj : 0.f);
-            const float p2 = above_bucket + wave_sum_f32(bj >= c2 ? aj : 0.f);
-            const float p3 = above_bucket + wave_sum_f32(bj >= c3 ? aj : 0.f);
-            theta = p3 > d.top_p ? c3 : p2 > d.top_p ? c2 : p1 > d.top_p ? c1 : theta;
+          float sj = 0.f;
+          for (int k = 0; k < m; ++k) {                       // m is uniform; candidates in list order
+            const uint32_t bk = (uint32_t)__builtin_amdgcn_readlane((int)bj, k);
+            sj += (bk >= bj) ? __uint_as_float(bk) : 0.f;
           }
-          if (lane == 0) sh[7] = (int)theta;
+          const uint32_t mine_ok = (lane < m && above_bucket + sj > d.top_p) ? bj : 0u;
+          uint32_t th = mine_ok;
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) th = max(th, (uint32_t)__shfl_xor((int)th, o));
+          if (th != 0u) theta = th;
+          const int n_ties = __popcll(__ballot(lane < m && bj == theta));
+          const float above_l = above_bucket + wave_sum_f32((lane < m && bj > theta) ? aj : 0.f);
+          if (lane == 0) {
+            sh[7] = (int)theta;
+            sh[5] = n_ties;
+            sh[6] = __float_as_int(above_l);
+          }
         }
         block_sync<NT, SB>(rb);
         theta = (uint32_t)sh[7];
+        list_ties = sh[5];
+        list_above = __int_as_float(sh[6]);
+        from_list = true;
       } else {
         for (; bit >= 1; bit -= 2) round(bit);
       }
     }
     if (theta != 0) {
-      float above = 0.f;
-      int ties = 0;
+      float above = list_above;
+      int ties = list_ties;
+      if (!from_list) {
+        above = 0.f;
+        ties = 0;
 #pragma unroll
-      for (int k = 0; k < R; ++k) {
-        const uint32_t b = __float_as_uint(a[k]);
-        above += (b > theta) ? a[k] : 0.f;
-        ties += (b == theta) ? 1 : 0;
+        for (int k = 0; k < R; ++k) {
+          const uint32_t b = __float_as_uint(a[k]);
+          above += (b > theta) ? a[k] : 0.f;
+          ties += (b == theta) ? 1 : 0;
+        }
+        above = block_sum_f32<NT, SB>(above, rb, phase, tid);
+        ties = block_sum_int<NT, SB>(ties, rb, phase, tid);
       }
-      above = block_sum_f32<NT, SB>(above, rb, phase, tid);
-      ties = block_sum_int<NT, SB>(ties, rb, phase, tid);
       if (ties > 1) {
         const float th = __uint_as_float(theta);
         float c = above;

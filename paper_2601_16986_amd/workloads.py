@@ -329,12 +329,15 @@ def torch_steady_layer(cfg: Config, layer: int, lengths, t_now: int, m_layer, r_
             n.reshape(Bz, Hkv).int().contiguous(), crf.contiguous(), tau.contiguous(), pos.int().contiguous())
 
 
-def torch_step_ring(cfg: Config, n_slots: int, m, r_now, device):
+def torch_step_ring(cfg: Config, n_slots: int, m, r_now, device, epoch: int = 0, return_state: bool = False):
     """Inputs of `n_slots` consecutive decode steps for all layers, on the
     device: q [S][L][Bz][Hq][d], k_new, v_new [S][L][Bz][Hkv][d] (bf16).  The
-    drift continues from r_now [L][Bz][Hkv][d]."""
+    drift continues from r_now [L][Bz][Hkv][d].  `epoch` selects an independent
+    batch of steps (a benchmark that runs more steps than it holds inputs for draws
+    fresh ones instead of replaying old ones: replayed keys are exact duplicates of
+    cached ones and tie with them); return_state also returns the final drift state."""
     import torch
-    g = torch_generator(cfg, 7, device)
+    g = torch_generator(cfg, 7 + 1000 * int(epoch), device)
     L, Bz, Hq, Hkv, d, G = cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.group
     sig = float(np.sqrt(DRIFT_VAR))
     qs, ks, vs = [], [], []
@@ -349,4 +352,5 @@ def torch_step_ring(cfg: Config, n_slots: int, m, r_now, device):
         qs.append(q.to(torch.bfloat16))
         ks.append(k.to(torch.bfloat16))
         vs.append(v.to(torch.bfloat16))
-    return torch.stack(qs).contiguous(), torch.stack(ks).contiguous(), torch.stack(vs).contiguous()
+    ring = (torch.stack(qs).contiguous(), torch.stack(ks).contiguous(), torch.stack(vs).contiguous())
+    return (ring, r) if return_state else ring
