@@ -950,6 +950,60 @@ __device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, i
   }
 }
 
+// Up to four moves at once by one wavefront: move r0 + m takes the entry in slot lst[lst_cap - 1 - (r0 + m)]
+// to slot lst[r0 + m] (m < count), as move_entry does, but every load is issued before the first store, so
+// the moves' memory round trips overlap.  Lane l does the key piece l & 15 of move l >> 4; all lanes do two
+// value elements of every move; lanes 0..3 do the per-slot state of moves 0..3.
+__device__ __forceinline__ void move_entries4(const Dev& d, size_t base, const int* lst, int lst_cap, int r0, int count, int lane) {
+  uint16_t* K = d.K + base * kDim;
+  uint16_t* V = d.V + base * kDim;
+  const int mk = lane >> 4;
+  int src[4], dst[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int mm = min(m, count - 1);
+    src[m] = lst[lst_cap - 1 - (r0 + mm)];
+    dst[m] = lst[r0 + mm];
+  }
+  const int ks = mk == 0 ? src[0] : mk == 1 ? src[1] : mk == 2 ? src[2] : src[3];
+  const int kd = mk == 0 ? dst[0] : mk == 1 ? dst[1] : mk == 2 ? dst[2] : dst[3];
+  const u32x4 kx = *reinterpret_cast<const u32x4*>(K + k_offset(ks, (lane & 15) * 8));
+  uint16_t v0[4], v1[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    v0[m] = V[v_offset(src[m], lane)];
+    v1[m] = V[v_offset(src[m], lane + 64)];
+  }
+  float crf = 0.f;
+  int tau = 0, ps = 0, pd = 0;
+  uint8_t fl = 0;
+  const int ms = lane == 0 ? src[0] : lane == 1 ? src[1] : lane == 2 ? src[2] : src[3];
+  const int md = lane == 0 ? dst[0] : lane == 1 ? dst[1] : lane == 2 ? dst[2] : dst[3];
+  if (lane < count) {
+    crf = d.crf[base + ms];
+    tau = d.tau[base + ms];
+    ps = d.pos[base + ms];
+    pd = d.pos[base + md];
+    fl = d.flags[base + ms];
+  }
+  if (mk < count) *reinterpret_cast<u32x4*>(K + k_offset(kd, (lane & 15) * 8)) = kx;
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    if (m < count) {
+      V[v_offset(dst[m], lane)] = v0[m];
+      V[v_offset(dst[m], lane + 64)] = v1[m];
+    }
+  }
+  if (lane < count) {
+    d.crf[base + md] = crf;
+    d.tau[base + md] = tau;
+    d.pos[base + md] = ps;
+    d.pos[base + ms] = pd;
+    d.flags[base + md] = fl;
+    d.flags[base + ms] = FLAG_SLIP;
+  }
+}
+
 // Eviction of exactly one entry: the last slot's entry moves into the victim's
 // slot `dst`, whose position goes to the last slot, flagged as evicted.  The K
 // row, the V row and the per-slot state are handled by different wavefronts;
@@ -1052,20 +1106,58 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
       }
     }
   } else {
-    // k-th smallest key, most significant bit first (bit 63 is the score's sign: 0)
-    u64 X = 0;
-    for (int bit = 62; bit >= 0; --bit) {
-      const u64 trial = X | (1ull << bit);
-      int cnt = 0;
-      for (int i = tid; i < n; i += NT) cnt += evict_key(val(i), d.pos[base + i]) < trial ? 1 : 0;
-      cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
-      if (cnt < k) X = trial;
+    // The k smallest keys (score, then higher position first) in two stages, two bits per round (the three
+    // candidates' counts are nested, and they are small integers, exact as floats).  Stage 1: S = the k-th
+    // smallest score pattern, from the scores in LDS alone.  Stage 2, only if the entries equal to S are
+    // not all evicted: which of them, by position; only those entries' positions are read.
+    uint32_t S = 0;
+    for (int bit = 31; bit >= 1; bit -= 2) {
+      const uint32_t c1 = S | (1u << (bit - 1)), c2 = S | (1u << bit), c3 = c1 | c2;
+      float n1 = 0.f, n2 = 0.f, n3 = 0.f;
+      for (int i = tid; i < n; i += NT) {
+        const uint32_t b = __float_as_uint(val(i));
+        n1 += b < c1 ? 1.f : 0.f;
+        n2 += b < c2 ? 1.f : 0.f;
+        n3 += b < c3 ? 1.f : 0.f;
+      }
+      block_sum3_f32<NT, SB>(n1, n2, n3, rb, phase, tid);
+      const float kf = (float)k;
+      S = n3 < kf ? c3 : n2 < kf ? c2 : n1 < kf ? c1 : S;          // the largest pattern with fewer than k scores below it
+    }
+    float below = 0.f, equal = 0.f, unused = 0.f;
+    for (int i = tid; i < n; i += NT) {
+      const uint32_t b = __float_as_uint(val(i));
+      below += b < S ? 1.f : 0.f;
+      equal += b == S ? 1.f : 0.f;
+    }
+    block_sum3_f32<NT, SB>(below, equal, unused, rb, phase, tid);
+    const int r = k - (int)below;                                  // of the entries equal to S, the r highest positions go
+    uint32_t P = 0xFFFFFFFFu;                                      // ... those with ~position <= P
+    if (r < (int)equal) {
+      P = 0;
+      for (int bit = 31; bit >= 1; bit -= 2) {
+        const uint32_t c1 = P | (1u << (bit - 1)), c2 = P | (1u << bit), c3 = c1 | c2;
+        float n1 = 0.f, n2 = 0.f, n3 = 0.f;
+        for (int i = tid; i < n; i += NT) {
+          if (__float_as_uint(val(i)) == S) {
+            const uint32_t np = ~(uint32_t)d.pos[base + i];
+            n1 += np < c1 ? 1.f : 0.f;
+            n2 += np < c2 ? 1.f : 0.f;
+            n3 += np < c3 ? 1.f : 0.f;
+          }
+        }
+        block_sum3_f32<NT, SB>(n1, n2, n3, rb, phase, tid);
+        const float rf = (float)r;
+        P = n3 < rf ? c3 : n2 < rf ? c2 : n1 < rf ? c1 : P;
+      }
     }
     const int words = (n + 31) >> 5;
     for (int w = tid; w < words; w += NT) evm[w] = 0u;
     block_sync<NT, SB>(rb);
-    for (int i = tid; i < n; i += NT)
-      if (evict_key(val(i), d.pos[base + i]) <= X) atomicOr(&evm[i >> 5], 1u << (i & 31));
+    for (int i = tid; i < n; i += NT) {
+      const uint32_t b = __float_as_uint(val(i));
+      if (b < S || (b == S && (P == 0xFFFFFFFFu || ~(uint32_t)d.pos[base + i] <= P))) atomicOr(&evm[i >> 5], 1u << (i & 31));
+    }
     block_sync<NT, SB>(rb);
     // holes = evicted slots below B, movers = surviving slots at or above B (equal counts)
     const int wpt = (words + NT - 1) / NT;
@@ -1116,7 +1208,8 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, V
     // evicted entries that already sit at or above B just get their flag
     for (int i = B + tid; i < n; i += NT)
       if ((evm[i >> 5] >> (i & 31)) & 1u) d.flags[base + i] = FLAG_SLIP;
-    for (int r = wave; r < h; r += NT / 64) move_entry(d, base, lst[lst_cap - 1 - r], lst[r], lane);
+    // moves, four per wavefront at a time: all loads of a batch are issued before its stores
+    for (int r0 = 4 * wave; r0 < h; r0 += 4 * (NT / 64)) move_entries4(d, base, lst, lst_cap, r0, min(4, h - r0), lane);
   }
   if (tid == 0) {
     d.n[u] = B;
