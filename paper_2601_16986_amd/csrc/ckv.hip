@@ -20,6 +20,7 @@
 using namespace ckv;
 
 constexpr int kSide = 2;   // streams of the context's own for deferred bookkeeping
+constexpr int kBookGroup = 8;   // layers whose deferred bookkeeping goes out as one launch
 
 // Scratch of ckv_probe_noalloc: device memory the library owns from the moment it is loaded, so that the
 // call never needs a caller's workspace or an allocation.  In host code `scratch` is only a handle: the
@@ -59,11 +60,18 @@ struct ckv_ctx {
   // one of the `side` streams (layer l on side[l % kSide], so that the bookkeeping of consecutive layers, which
   // share nothing, can overlap), ordered by events against the caller's stream.  pending[l]: layer l's
   // bookkeeping has been queued there and nothing on the caller's side has waited for it yet.
+  // The bookkeeping of up to kBookGroup consecutive layers goes out as one launch (a fork from the caller's
+  // stream costs about as much as a small kernel, and more units per launch fill the chip better): after a
+  // deferred step, layers [group_first, group_first + group_count) have been scanned on group_stream and wait
+  // for theirs; the group goes out when it is full, with the last layer, and before anything else looks.
   hipStream_t side[kSide] = {};
   hipEvent_t ev_out = nullptr;
   std::vector<hipEvent_t> ev_book;
   std::vector<uint8_t> pending;
   bool any_pending = false;
+  int group_first = 0, group_count = 0, group_launches = 0;
+  uint32_t group_flags = 0;
+  hipStream_t group_stream = nullptr;
   std::string err;
   // scan timing
   bool profile = false;
@@ -137,7 +145,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, seedlg, seedml, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, msum, seedlg, seedml, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -166,6 +174,7 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.sched = take(U * 16);
   c.layer_ts = take((size_t)l->n_layers * 8);
   c.snew = take(U * kMaxGroup * 4);
+  c.msum = take(U * kMaxGroup * 2 * 4);
   // prompt replay (ckv_seed_prompt), one layer at a time: logits of 16 query columns per entry, softmax partials per chunk
   const size_t UL = (size_t)l->batch * l->n_kv_heads;
   c.seedlg = take(UL * (size_t)l->cap * kSeedCols * 4);
@@ -192,8 +201,43 @@ const ckv_ctx::Fused* fused_variant(const ckv_ctx* c) {
   return f->ok ? f : nullptr;
 }
 
+// A pair of timing events from the context's pool (ckv_profile_enable).
+int profile_events(ckv_ctx* c, hipEvent_t* e0, hipEvent_t* e1) {
+  if (c->ev_used + 2 > c->ev.size()) {
+    for (int i = 0; i < 2; ++i) {
+      hipEvent_t e;
+      CKV_HIP(c, hipEventCreate(&e));
+      c->ev.push_back(e);
+    }
+  }
+  *e0 = c->ev[c->ev_used];
+  *e1 = c->ev[c->ev_used + 1];
+  c->ev_used += 2;
+  return CKV_OK;
+}
+
+// Queue the bookkeeping of the layers scanned since the last group went out.
+int flush_group(ckv_ctx* c) {
+  if (c->group_count == 0) return CKV_OK;
+  const int first = c->group_first, count = c->group_count;
+  c->group_count = 0;
+  const int upl = c->lay.batch * c->lay.n_kv_heads;
+  CKV_HIP(c, hipEventRecord(c->ev_out, c->group_stream));
+  hipStream_t side = c->side[c->group_launches++ % kSide];
+  CKV_HIP(c, hipStreamWaitEvent(side, c->ev_out, 0));
+  hipLaunchKernelGGL(finish_kernel, dim3((unsigned)(count * upl)), dim3(kThreads), c->finish_lds, side, c->dev, first * upl,
+                     (void*)nullptr, c->group_flags, 0, INT_MAX, -1, 2, -2);
+  CKV_HIP(c, hipGetLastError());
+  CKV_HIP(c, hipEventRecord(c->ev_book[first], side));
+  for (int l = first; l < first + count; ++l) c->pending[l] = 1 + first;     // whose event to wait for
+  c->any_pending = true;
+  return CKV_OK;
+}
+
 // Order `s` after the deferred bookkeeping still in flight on the side streams (all layers, or one).
 int join_side(ckv_ctx* c, hipStream_t s, int layer = -1) {
+  if (c->group_count && (layer < 0 || (layer >= c->group_first && layer < c->group_first + c->group_count)))
+    if (int rc = flush_group(c)) return rc;
   if (!c->any_pending) return CKV_OK;
   bool left = false;
   for (int l = 0; l < c->lay.n_layers; ++l) {
@@ -202,7 +246,7 @@ int join_side(ckv_ctx* c, hipStream_t s, int layer = -1) {
       left = true;
       continue;
     }
-    CKV_HIP(c, hipStreamWaitEvent(s, c->ev_book[l], 0));
+    CKV_HIP(c, hipStreamWaitEvent(s, c->ev_book[c->pending[l] - 1], 0));
     c->pending[l] = 0;
   }
   c->any_pending = left;
@@ -412,6 +456,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.layer_ts = (int32_t*)(ws + cv.layer_ts);
   d.arrive = (int32_t*)(ws + cv.arrive);
   d.snew = (float*)(ws + cv.snew);
+  d.msum = (float*)(ws + cv.msum);
   c->seedlg = (float*)(ws + cv.seedlg);
   c->seedml = (float*)(ws + cv.seedml);
 
@@ -519,6 +564,34 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (fv == &c->fused[2] && (flags & CKV_ATTENTION_ONLY)) fv = &c->fused[0];   // no bookkeeping to move aside
   const bool fused = fv != nullptr;
   if (int rc = join_side(c, s, layer)) return rc;
+  if (flags & CKV_DEFER_BOOKKEEPING) {
+    // One kernel on the caller's stream: it appends, attends and writes the output; the bookkeeping (which also
+    // records the append) follows on a side stream, a group of layers at a time.
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->profile) {
+      if (int rc = profile_events(c, &e0, &e1)) return rc;
+      CKV_HIP(c, hipEventRecord(e0, s));
+    }
+    hipLaunchKernelGGL(layer_scan_kernel, dim3((unsigned)count, (unsigned)((c->dev.max_chunks + 3) / 4)), dim3(kThreads), 0, s, c->dev,
+                       begin, (const uint16_t*)q, (const uint16_t*)k_new, (const uint16_t*)v_new, out, (int)layer);
+    CKV_HIP(c, hipGetLastError());
+    if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
+    if (advance) {
+      hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(64), 0, s, c->dev);
+      CKV_HIP(c, hipGetLastError());
+    }
+    const uint32_t kflags = flags & CKV_FUSE_EVICT;
+    if (c->group_count && (c->group_flags != kflags || c->group_stream != s || c->group_first + c->group_count != layer))
+      if (int rc = flush_group(c)) return rc;
+    if (c->group_count == 0) {
+      c->group_first = layer;
+      c->group_flags = kflags;
+      c->group_stream = s;
+    }
+    c->group_count += 1;
+    if (c->group_count == kBookGroup || advance) return flush_group(c);
+    return CKV_OK;
+  }
   // unit_kernel<W> appends by itself; the other kernels get the new entries (and their schedule or work list) from prep_kernel
   if (!fused || fv == &c->fused[2]) {
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
@@ -528,16 +601,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
 
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (c->profile) {
-    if (c->ev_used + 2 > c->ev.size()) {
-      for (int i = 0; i < 2; ++i) {
-        hipEvent_t e;
-        CKV_HIP(c, hipEventCreate(&e));
-        c->ev.push_back(e);
-      }
-    }
-    e0 = c->ev[c->ev_used];
-    e1 = c->ev[c->ev_used + 1];
-    c->ev_used += 2;
+    if (int rc = profile_events(c, &e0, &e1)) return rc;
     CKV_HIP(c, hipEventRecord(e0, s));
   }
   if (fused) {
@@ -568,10 +632,10 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (blocks > (max_items + 3) / 4) blocks = (max_items + 3) / 4;
   const uint32_t kflags = flags & CKV_FUSE_EVICT;
   // when nothing but the output is due on the caller's stream, the scan merges its own partials and ends the step
-  const bool scan_merges = (flags & (CKV_DEFER_BOOKKEEPING | CKV_ATTENTION_ONLY)) != 0;
+  const bool scan_merges = (flags & CKV_ATTENTION_ONLY) != 0;
   if (scan_merges)
     hipLaunchKernelGGL(scan_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q, out,
-                       advance, (flags & CKV_DEFER_BOOKKEEPING) ? (int)layer : -1);
+                       advance, -1);
   else
     hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, c->dev, begin, (const uint16_t*)q,
                        (void*)nullptr, 0, -1);
@@ -579,19 +643,6 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
   if (flags & CKV_ATTENTION_ONLY) return CKV_OK;
 
-  if (flags & CKV_DEFER_BOOKKEEPING) {
-    // the caller waits for the scan alone; the scores and the eviction follow on a side stream
-    CKV_HIP(c, hipEventRecord(c->ev_out, s));
-    hipStream_t side = c->side[layer % kSide];
-    CKV_HIP(c, hipStreamWaitEvent(side, c->ev_out, 0));
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, side, c->dev, begin,
-                       (void*)nullptr, kflags, 0, INT_MAX, -1, 1, (int)layer);
-    CKV_HIP(c, hipGetLastError());
-    CKV_HIP(c, hipEventRecord(c->ev_book[layer], side));
-    c->pending[layer] = 1;
-    c->any_pending = true;
-    return CKV_OK;
-  }
   hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out,
                      kflags, advance, INT_MAX, -1, 0, 0);
   CKV_HIP(c, hipGetLastError());
@@ -750,6 +801,7 @@ int ckv_probe_noalloc(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* c
 
 int ckv_get_budgets(ckv_ctx* c, int32_t* budgets) {
   if (!c || !budgets) return CKV_EINVAL;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   CKV_HIP(c, hipMemcpy(budgets, c->dev.budget, (size_t)c->units * 4, hipMemcpyDeviceToHost));
   return CKV_OK;
@@ -757,6 +809,7 @@ int ckv_get_budgets(ckv_ctx* c, int32_t* budgets) {
 
 int ckv_get_lengths(ckv_ctx* c, int32_t* lengths) {
   if (!c || !lengths) return CKV_EINVAL;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   CKV_HIP(c, hipMemcpy(lengths, c->dev.n, (size_t)c->units * 4, hipMemcpyDeviceToHost));
   return CKV_OK;
@@ -765,12 +818,14 @@ int ckv_get_lengths(ckv_ctx* c, int32_t* lengths) {
 int ckv_set_budgets(ckv_ctx* c, const int32_t* budgets) {
   if (!c) return CKV_EINVAL;
   if (int rc = check_budgets(c, &c->lay, &c->par, budgets)) return rc;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   return upload_budgets(c, budgets, nullptr);
 }
 
 int ckv_get_time(ckv_ctx* c, int32_t* t) {
   if (!c || !t) return CKV_EINVAL;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   CKV_HIP(c, hipMemcpy(t, c->dev.sc + SC_T, 4, hipMemcpyDeviceToHost));
   return CKV_OK;
@@ -809,6 +864,7 @@ int ckv_export_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
     return fail(c, CKV_EINVAL, "unit index out of range");
   const size_t u = ((size_t)layer * c->lay.batch + seq) * c->lay.n_kv_heads + head;
   const size_t cap = (size_t)c->lay.cap, base = u * cap;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   int32_t n = 0, nev = 0, bud = 0;
   CKV_HIP(c, hipMemcpy(&n, c->dev.n + u, 4, hipMemcpyDeviceToHost));
@@ -854,6 +910,7 @@ int ckv_import_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
   if (n > 0 && (!K || !V || !crf || !tau || !pos)) return fail(c, CKV_EINVAL, "NULL state array");
   const size_t u = ((size_t)layer * c->lay.batch + seq) * c->lay.n_kv_heads + head;
   const size_t cap = (size_t)c->lay.cap, base = u * cap;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   const int nblk = (n + kBlk - 1) / kBlk;
   std::vector<uint16_t> tmp((size_t)nblk * kBlkElems);
@@ -883,6 +940,7 @@ int ckv_import_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
 
 int ckv_profile_enable(ckv_ctx* c, int32_t on) {
   if (!c) return CKV_EINVAL;
+  if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
   c->profile = on != 0;
   c->ev_used = 0;

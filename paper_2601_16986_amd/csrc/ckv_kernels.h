@@ -70,6 +70,7 @@ struct Dev {
   int32_t* layer_ts;     // [layers][2] time and launch sequence number of a layer's last deferred step (scan_kernel<true> -> finish_kernel with late = 1)
   int32_t* arrive;       // [units] runs of the unit published so far by a scan that also merges (zero between launches)
   float* snew;           // [units][8] scaled logits (base-2 domain) of the entry appended in this step, per query head
+  float* msum;           // [units][8][2] softmax maximum (base-2 domain) and 1 / sum per query head, left by layer_scan_kernel for its bookkeeping
 };
 
 
@@ -922,6 +923,260 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
     cur = nxt;
   }
   if (MERGE) wave_done();
+}
+
+// ------------------------------------------------------------------ single-layer scan that appends by itself
+// The shape a model imposes is one call per layer, a few hundred units at most: too few for the fused kernel
+// (one workgroup per unit) and too little work for the persistent scan above to amortise its work list.  Here
+// the grid itself is the work list: workgroup (x, y) takes chunks 4 y .. 4 y + 3 (256 entries each, one per
+// wavefront) of the layer's unit x and leaves at once if the unit is shorter.  (Units along x: consecutive
+// workgroups go to different XCDs, so the workgroups that have work - every unit's first, most units' second -
+// spread over all of them; with the chunk groups along x, and eight or a multiple of them, each XCD would get
+// one group index, the first few all the work, and a step takes 1.6 times as long.)  Nothing has to run before it:
+// every workgroup derives the unit's length after the append from the stored one (which stays as it is until
+// the bookkeeping that follows, finish_kernel with late = 2, has recorded the append), and the wavefront whose
+// chunk receives the new entry puts its key and value rows into the block it has just loaded (and into the
+// cache), so that the entry takes part like any cached one.  The four wavefronts combine their softmax states
+// in LDS; a unit of one workgroup (up to 1024 entries) is finished there and then, a longer one goes through
+// one partial per workgroup, merged by the workgroup that publishes the last (coherent stores and loads as in
+// scan_kernel<true>).  The unit's softmax maximum and 1 / sum per head stay in `msum` for the bookkeeping.
+// grid: (units of the layer, ceil(max_chunks / 4)), kThreads threads.
+__device__ __forceinline__ void inject_entry(KFrag& ka, VFrag& va, int rr, const u32x4 (&knew)[4], const uint32_t (&vnew)[8], int lane) {
+  const int j = lane & 15, kg = lane >> 4;
+  const int tt = rr >> 4;
+  const bool krow = j == (rr & 15);
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (krow && h == tt) ka.k[h * 4 + s] = knew[s];
+  const bool vrow = kg == ((rr & 15) >> 2);
+  const int e = tt * 4 + (rr & 3);
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {
+      const uint32_t old = va.v[dt][wi];
+      const uint32_t nw = (e & 1) ? ((old & 0x0000FFFFu) | (vnew[dt] << 16)) : ((old & 0xFFFF0000u) | vnew[dt]);
+      va.v[dt][wi] = (vrow && wi == (e >> 1)) ? nw : old;
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q,
+                                                                 const uint16_t* __restrict__ k_new,
+                                                                 const uint16_t* __restrict__ v_new, void* out, int layer) {
+  constexpr int kW = kThreads / 64;
+  __shared__ float s_lg[kW][kMaxGroup * kLgRow];
+  __shared__ float s_m[kW][kMaxGroup], s_l[kW][kMaxGroup];
+  __shared__ float s_acc[kW][kMaxGroup * kDim];
+  __shared__ int s_last;
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int urel = blockIdx.x, u = unit_begin + urel, cg = blockIdx.y;
+  const int G = d.G;
+  const int n_old = d.n[u];
+  const bool full = n_old >= d.cap;
+  const int n = n_old + (full ? 0 : 1);
+  const int nch = (n + kChunk - 1) / kChunk;
+  if (cg == 0 && tid == 0) {
+    if (urel == 0) d.layer_ts[2 * layer] = d.sc[SC_T];      // the bookkeeping runs later, perhaps after the time has moved on
+    if (full) atomicOr(&d.sc[SC_STATUS], 1);
+  }
+  if (cg * kW >= nch) return;
+  const int nwg = (nch + kW - 1) / kW;
+  const int j = lane & 15, kg = lane >> 4;
+  const bool head_lane = j < G;
+  const int c = cg * kW + w;
+  f32x4 acc[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+  if (c < nch) {
+    const int e0 = c * kChunk;
+    const int nv = min(n - e0, kChunk);
+    const int nb = (nv + kBlk - 1) / kBlk;
+    const bool inject = !full && n_old >= e0 && n_old < e0 + kChunk;     // the new entry is then the chunk's last: entry nv - 1
+    const size_t off = (size_t)u * d.cap * kDim + (size_t)c * kChunkBlocks * kBlkElems + lane * 8;
+    const uint16_t* kcur = d.K + off;
+    const uint16_t* vcur = d.V + off;
+    KFrag ka;
+    VFrag va;
+    load_k(ka, kcur);
+    load_v(va, vcur);
+    bf16x8 qv[4];
+    {
+      const uint16_t* qrow = q + ((size_t)urel * G + (head_lane ? j : 0)) * kDim + 8 * kg;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        u32x4 x = *reinterpret_cast<const u32x4*>(qrow + 32 * s);
+        if (!head_lane) x = u32x4{0u, 0u, 0u, 0u};
+        qv[s] = as_bf16x8(x);
+      }
+    }
+    u32x4 knew[4] = {};
+    uint32_t vnew[8] = {};
+    if (inject) {
+      const uint16_t* kr = k_new + (size_t)urel * kDim + 8 * kg;
+      const uint16_t* vr = v_new + (size_t)urel * kDim + j;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) knew[s] = *reinterpret_cast<const u32x4*>(kr + 32 * s);
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) vnew[dt] = vr[16 * dt];
+      // the rows also go into the cache, where the next step finds them
+      uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
+      uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+      if (j == 0) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) *reinterpret_cast<u32x4*>(kdst + k_offset(n_old, 32 * s + 8 * kg)) = knew[s];
+      }
+      if (kg == 0) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) vdst[v_offset(n_old, 16 * dt + j)] = (uint16_t)vnew[dt];
+      }
+    }
+    float* lds_lg = s_lg[w];
+    float* lg_dst = d.logits + ((size_t)u * d.cap + (size_t)e0) * G + 4 * min(lane, 8 * G - 1);
+    // one block ahead, as in scan_kernel (two ahead is slower here as well); the loads stay unconditional (the
+    // last block is read twice), so that the waits the compiler inserts are exact
+    for (int blk = 0; blk < nb; ++blk) {
+      const bool last = blk + 1 == nb;
+      const size_t nxt = (size_t)(last ? blk : blk + 1) * kBlkElems;
+      if (last && inject) inject_entry(ka, va, (n_old - e0) & 31, knew, vnew, lane);
+      float sv[8];
+      scan_qk(ka, qv, sv, d.scale_log2e, blk * kBlk, nv, lds_lg, kLgRow, lg_dst, G, lane);
+      load_k(ka, kcur + nxt);
+      scan_pv(sv, va, acc, m_run, l_run, lane);
+      load_v(va, vcur + nxt);
+    }
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+  }
+  // ---- the workgroup's four states into one
+  if (head_lane && kg == 0) {
+    s_m[w][j] = m_run;
+    s_l[w][j] = l_run;
+  }
+  if (c < nch) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int head = 4 * kg + v;
+      if (head < G) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) s_acc[w][head * kDim + 16 * dt + j] = acc[dt][v];
+      }
+    }
+  }
+  __syncthreads();
+  const size_t slot0 = (size_t)u * d.slots;
+  constexpr int kPer = (kMaxGroup * kDim) / kThreads;      // (head, dim) pairs per thread
+  float o[kPer], Mg[kPer], Lg[kPer];
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int e = tid + k * kThreads, g = e >> 7;
+    o[k] = 0.f;
+    Mg[k] = -INFINITY;
+    Lg[k] = 0.f;
+    if (g < G) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int ww = 0; ww < kW; ++ww) M = fmaxf(M, s_m[ww][g]);
+#pragma unroll
+      for (int ww = 0; ww < kW; ++ww) {
+        const float m = s_m[ww][g];
+        if (m > -INFINITY) {
+          const float wt = fast_exp2(m - M);
+          o[k] += s_acc[ww][e] * wt;
+          Lg[k] += s_l[ww][g] * wt;
+        }
+      }
+      Mg[k] = M;
+    }
+  }
+  auto write_out = [&](int k, float val, float M, float L) {
+    const int e = tid + k * kThreads, g = e >> 7, dim = e & 127;
+    const float inv = 1.0f / L;
+    const float ov = val * inv;
+    const size_t oi = ((size_t)urel * G + g) * kDim + dim;
+    if (d.out_bf16)
+      reinterpret_cast<__bf16*>(out)[oi] = (__bf16)ov;
+    else
+      reinterpret_cast<float*>(out)[oi] = ov;
+    if (dim == 0) {
+      d.msum[((size_t)u * kMaxGroup + g) * 2] = M;
+      d.msum[((size_t)u * kMaxGroup + g) * 2 + 1] = inv;
+    }
+  };
+  if (nwg == 1) {
+#pragma unroll
+    for (int k = 0; k < kPer; ++k)
+      if (((tid + k * kThreads) >> 7) < G) write_out(k, o[k], Mg[k], Lg[k]);
+    return;
+  }
+  // ---- one partial per workgroup; the workgroup that publishes the unit's last one merges them
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int e = tid + k * kThreads, g = e >> 7, dim = e & 127;
+    if (g < G) {
+      put<true>(&d.partial[((slot0 + cg) * G + g) * kDim + dim], o[k]);
+      if (dim == 0) {
+        put<true>(&d.ml[((slot0 + cg) * G + g) * 2], Mg[k]);
+        put<true>(&d.ml[((slot0 + cg) * G + g) * 2 + 1], Lg[k]);
+      }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the partial before the count (coherent stores: completed is enough)
+  __syncthreads();
+  if (tid == 0) {
+    const int lastone = atomicAdd(&d.arrive[u], 1) == nwg - 1;
+    if (lastone) __hip_atomic_store(&d.arrive[u], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = lastone;
+  }
+  __syncthreads();
+  if (!s_last) return;
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int e = tid + k * kThreads, g = e >> 7, dim = e & 127;
+    if (g >= G) continue;
+    // one pass with a running maximum: sixteen partials' values are requested at once, so that a unit of up
+    // to 16 K entries costs a single round trip
+    float M = -INFINITY, val = 0.f, L = 0.f;
+    for (int r0 = 0; r0 < nwg; r0 += 16) {
+      float m[16], l[16], x[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const size_t sl = slot0 + min(r0 + i, nwg - 1);
+        m[i] = get_coherent(&d.ml[(sl * G + g) * 2]);
+        l[i] = get_coherent(&d.ml[(sl * G + g) * 2 + 1]);
+        x[i] = get_coherent(&d.partial[(sl * G + g) * kDim + dim]);
+      }
+      float Mn = M;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (r0 + i < nwg) Mn = fmaxf(Mn, m[i]);
+      if (Mn > M) {
+        const float sc = fast_exp2(M - Mn);        // 0 the first time round (M = -inf)
+        val *= sc;
+        L *= sc;
+        M = Mn;
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (r0 + i < nwg && m[i] > -INFINITY) {
+          const float wt = fast_exp2(m[i] - M);
+          val += x[i] * wt;
+          L += l[i] * wt;
+        }
+      }
+    }
+    write_out(k, val, M, L);
+  }
+}
+
+// The step's time moves on after the last layer (the single-layer scan above leaves the step scalars alone).
+__global__ void advance_kernel(Dev d) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    d.sc[SC_T] = d.sc[SC_T] + 1;
+    d.sc[SC_WINDOW_STEPS] = d.sc[SC_WINDOW_STEPS] + 1;
+  }
 }
 
 // ------------------------------------------------------------------ eviction
@@ -1908,16 +2163,38 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   __shared__ float s_tab[kTabLds];
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
-  const int n = min(d.n[u], n_limit);
+  int n = min(d.n[u], n_limit);
+  if (layer == -2) layer = u / (d.Bz * d.Hkv);          // a launch over several layers: each unit looks up its own
   const int t = late ? d.layer_ts[2 * layer] : t_fixed >= 0 ? t_fixed : d.sc[SC_T];
-  const int seq = late ? d.layer_ts[2 * layer + 1] : d.sc[SC_SEQ];
+  const int seq = late == 1 ? d.layer_ts[2 * layer + 1] : d.sc[SC_SEQ];
   const int B = d.budget[u];
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
   if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
   int phase = 0;
+  if (late == 2) {
+    // after layer_scan_kernel: the new entry's rows are in the cache and its logits with the others, the
+    // unit's records still describe the step before.  Record the append, then go on as after any scan.
+    if (n < d.cap) {
+      if (tid == 0) {
+        const size_t s = (size_t)u * d.cap + n;
+        d.crf[s] = 0.0f;
+        d.tau[s] = t;
+        d.pos[s] = t;
+        d.flags[s] = 0;
+        d.n[u] = n + 1;
+      }
+      n += 1;
+    }
+    if (tid < d.G) {
+      sM[tid] = d.msum[((size_t)u * kMaxGroup + tid) * 2];
+      sInv[tid] = d.msum[((size_t)u * kMaxGroup + tid) * 2 + 1];
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
   if (n > 0) {
     const int nch = (n + kChunk - 1) / kChunk;
-    merge_partials(d, u, urel, nch, seq, sM, sInv, sW, late ? nullptr : out, tid);
+    if (late != 2) merge_partials(d, u, urel, nch, seq, sM, sInv, sW, late ? nullptr : out, tid);
     unit_bookkeeping(d, u, n, B, t, unit_logits(d, u), sM, sInv, (call_flags & 1u) != 0, val, evm, s_tab, s_tab_n, rb, phase, sh, tid);
   }
   if (!late) step_epilogue(d, t, advance, tid);
