@@ -64,12 +64,20 @@ enum { CKV_CLASS_SLIP = 0, CKV_CLASS_POTENTIAL = 1, CKV_CLASS_CRYSTAL = 2 };
 #define CKV_DEFER_BOOKKEEPING 4u /* ckv_decode_step of a single layer: only the attention output is ordered on the
                                   * caller's stream; scores and eviction follow on streams of the context (see there) */
 
-/* Geometry.  head_dim must be 128; n_q_heads = G * n_kv_heads with G <= 8;
- * `cap` = slots per unit, a multiple of 32, at most 32768. */
+/* Geometry.  head_dim must be 128; n_q_heads = G * n_kv_heads with G <= 8.
+ * `cap` = the most entries a unit can ever hold, a multiple of 32, at most 32768.
+ * Pool memory is handed to units in segments of 256 slots.  headroom = 0: every unit owns
+ * ceil(cap / 256) segments for good (pool_slots >= units * ceil(cap / 256) * 256).  headroom = h >= 1:
+ * the pools are shared, a unit owns the segments that budget + h entries need (h = the entries a unit may
+ * hold above its budget between evictions: 1 when every step evicts), the rest is spare; segments move
+ * between units and the spare list when budgets change (ckv_rebudget, ckv_set_budgets) or a prompt longer
+ * than the budget passes through (ckv_load_prompt), see ckv_rebalance.  ckv_pool_slots gives the need. */
 typedef struct {
   int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim;
   int32_t cap;
   int32_t out_dtype;      /* CKV_F32 or CKV_BF16: element type of `out` in ckv_decode_step */
+  int32_t headroom;
+  int64_t pool_slots;     /* slots in each pool, a multiple of 256 */
 } ckv_layout;
 
 /* Parameters of Alg. 1 / Alg. 2 (Sec. 6.4 recommends top_p = 0.9, lambda in [0.5, 0.7]). */

@@ -35,7 +35,7 @@ EXPORTS = [
 class Layout(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("cap", C.c_int32),
-                ("out_dtype", C.c_int32)]
+                ("out_dtype", C.c_int32), ("headroom", C.c_int32), ("pool_slots", C.c_int64)]
 
 
 class LrfuParams(C.Structure):
@@ -121,7 +121,10 @@ class CrystalKV:
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, budgets, *, lam=0.5, top_p=0.9,
                  softmax_scale=None, reward_mode=REWARD_TOPP_HIT, t0=0, budget_min=1, budget_max=None,
-                 out_dtype=F32, device="cuda:0"):
+                 out_dtype=F32, device="cuda:0", headroom=0, pool_slots=None):
+        """headroom = 0: every unit owns room for `cap` entries (pools of units * ceil(cap / 256) * 256 slots).
+        headroom >= 1: shared pools, a unit owns what budget + headroom entries need; pool_slots (a multiple of
+        256) then sizes the pools, by default what the budgets need plus a tenth."""
         import torch
         self.torch = torch
         self.lib = load()
@@ -130,7 +133,16 @@ class CrystalKV:
             softmax_scale = 1.0 / float(np.sqrt(head_dim))
         if budget_max is None:
             budget_max = cap - 1
-        self.layout = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype)
+        SEG = 256
+        b_all = np.asarray(budgets, dtype=np.int64).reshape(-1)
+        if pool_slots is None:
+            if headroom == 0:
+                pool_slots = n_layers * batch * n_kv_heads * ((cap + SEG - 1) // SEG) * SEG
+            else:
+                need = int(np.minimum((b_all + headroom + SEG - 1) // SEG, (cap + SEG - 1) // SEG).sum())
+                pool_slots = (need + need // 10 + 1) * SEG
+        self.headroom, self.pool_slots = headroom, int(pool_slots)
+        self.layout = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype, headroom, int(pool_slots))
         self.params = LrfuParams(lam, top_p, softmax_scale, reward_mode, t0, budget_min, budget_max)
         self.L, self.Bz, self.Hq, self.Hkv, self.d, self.cap = n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap
         self.G = n_q_heads // max(n_kv_heads, 1)
@@ -139,7 +151,7 @@ class CrystalKV:
         ws = self.lib.ckv_workspace_bytes(C.byref(self.layout), C.byref(self.params))
         if ws == 0:
             raise CkvError(EINVAL, "layout or parameters rejected")
-        S = self.units * cap
+        S = self.pool_slots
         dev = self.device
         self.k_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
         self.v_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)

@@ -52,8 +52,7 @@ struct ckv_ctx {
     int grid = 0;
     int lds_main = 0;           // bytes of the logits / values tile
     size_t lds = 0;             // dynamic LDS per workgroup
-  } fused[3];                   // [0]: 4 wavefronts, 2 workgroups per CU; [1]: 2 wavefronts, 4 workgroups per CU;
-                                // [2]: unit_kernel_split, 4 + 4 wavefronts, 1 workgroup per CU, lds_main = bytes of ONE of its two tiles
+  } fused[2];                   // [0]: 4 wavefronts, 2 workgroups per CU; [1]: 2 wavefronts, 4 workgroups per CU
   std::vector<uint8_t> prompt_loaded;
   std::vector<int32_t> prompt_len;   // per layer: length of a prompt loaded whole and untouched since, else -1
   // Deferred bookkeeping of single-layer steps (CKV_DEFER_BOOKKEEPING): finish_kernel (late = 1) runs on
@@ -114,6 +113,10 @@ bool layout_ok(const ckv_layout* l, std::string* why) {
   if (l->out_dtype != CKV_F32 && l->out_dtype != CKV_BF16) { *why = "out_dtype must be CKV_F32 or CKV_BF16"; return false; }
   long long units = (long long)l->n_layers * l->batch * l->n_kv_heads;
   if (units * l->cap > (1ll << 40) || units > (1ll << 24)) { *why = "geometry too large"; return false; }
+  const long long segs = (l->cap + kSeg - 1) / kSeg;
+  if (l->headroom < 0 || l->headroom >= l->cap) { *why = "headroom must be in [0, cap)"; return false; }
+  if (l->pool_slots <= 0 || l->pool_slots % kSeg != 0 || l->pool_slots > (1ll << 40)) { *why = "pool_slots must be a positive multiple of 256"; return false; }
+  if (l->headroom == 0 && l->pool_slots < units * segs * kSeg) { *why = "pool_slots too small: with headroom 0 every unit owns ceil(cap / 256) segments"; return false; }
   return true;
 }
 
@@ -145,7 +148,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, msum, seedlg, seedml, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, msum, tbl, owned, spare, seedlg, seedml, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -175,6 +178,9 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.layer_ts = take((size_t)l->n_layers * 8);
   c.snew = take(U * kMaxGroup * 4);
   c.msum = take(U * kMaxGroup * 2 * 4);
+  c.tbl = take(U * mc * 4);
+  c.owned = take(U * 4);
+  c.spare = take((size_t)(l->pool_slots / kSeg) * 4);
   // prompt replay (ckv_seed_prompt), one layer at a time: logits of 16 query columns per entry, softmax partials per chunk
   const size_t UL = (size_t)l->batch * l->n_kv_heads;
   c.seedlg = take(UL * (size_t)l->cap * kSeedCols * 4);
@@ -195,7 +201,6 @@ int check_budgets(ckv_ctx* c, const ckv_layout* l, const ckv_lrfu_params* p, con
 // The variant of the fused kernel the current path mode selects (nullptr: none fits or separate kernels).
 const ckv_ctx::Fused* fused_variant(const ckv_ctx* c) {
   if (c->path_mode == 1) return nullptr;
-  if (c->path_mode == 5) return c->fused[2].ok ? &c->fused[2] : nullptr;
   const ckv_ctx::Fused* f = c->path_mode == 3 ? &c->fused[0] : c->path_mode == 4 ? &c->fused[1]
                             : c->fused[0].ok ? &c->fused[0] : &c->fused[1];
   return f->ok ? f : nullptr;
@@ -385,32 +390,17 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     const int wgs = 8 / f.waves;
     const int static_lds = v == 0 ? 11 * 1024 : 6 * 1024;      // upper bounds of unit_kernel<W>'s static LDS
     const int evm_bytes = ((layout->cap + 31) / 32) * 4;
+    const int tbl_bytes = 2 * ((layout->cap + kSeg - 1) / kSeg) * 4;   // two rows of the segment table
     const int share = (160 * 1024 / wgs) & ~1023;
     const int per_wg = max_lds < share ? max_lds : share;
-    const int main_bytes = (per_wg - static_lds - evm_bytes) & ~127;
+    const int main_bytes = (per_wg - static_lds - evm_bytes - tbl_bytes) & ~127;
     f.grid = wgs * c->n_cu;
     f.ok = main_bytes >= 4 * layout->cap;                       // every entry's value must fit
     f.lds_main = main_bytes;
-    f.lds = (size_t)main_bytes + evm_bytes;
+    f.lds = (size_t)main_bytes + evm_bytes + tbl_bytes;
     const void* fn = v == 0 ? reinterpret_cast<const void*>(unit_kernel<4>) : reinterpret_cast<const void*>(unit_kernel<2>);
     if (f.ok && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)f.lds) != hipSuccess) f.ok = false;
   }
-  {                                                               // unit_kernel_split: two tiles per workgroup
-    ckv_ctx::Fused& f = c->fused[2];
-    f.waves = 4;
-    const int evm_bytes = ((layout->cap + 31) / 32) * 4;
-    const int share = 160 * 1024;                                 // one workgroup of eight wavefronts per CU
-    const int per_wg = max_lds < share ? max_lds : share;
-    const int tile = ((per_wg - 11 * 1024 - evm_bytes) / 2) & ~127;
-    f.grid = c->n_cu;
-    f.ok = tile >= 4 * layout->cap;
-    f.lds_main = tile;
-    f.lds = 2 * (size_t)tile + evm_bytes;
-    if (f.ok && hipFuncSetAttribute(reinterpret_cast<const void*>(unit_kernel_split), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)f.lds) != hipSuccess)
-      f.ok = false;
-  }
-
   Dev& d = c->dev;
   d.L = layout->n_layers;
   d.Bz = layout->batch;
@@ -457,6 +447,10 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.arrive = (int32_t*)(ws + cv.arrive);
   d.snew = (float*)(ws + cv.snew);
   d.msum = (float*)(ws + cv.msum);
+  d.tbl = (int32_t*)(ws + cv.tbl);
+  d.owned = (int32_t*)(ws + cv.owned);
+  d.spare = (int32_t*)(ws + cv.spare);
+  d.max_seg = (int32_t)((layout->cap + kSeg - 1) / kSeg);
   c->seedlg = (float*)(ws + cv.seedlg);
   c->seedml = (float*)(ws + cv.seedml);
 
@@ -473,7 +467,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
     if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return bail(CKV_EHIP);
     c->ev_book.push_back(e);
   }
-  const size_t S = (size_t)c->units * layout->cap;
+  const size_t S = (size_t)layout->pool_slots;
   int rc;
   if ((rc = fill32(c, d.K, 0u, S * kDim / 2, s))) return bail(rc);
   if ((rc = fill32(c, d.V, 0u, S * kDim / 2, s))) return bail(rc);
@@ -489,6 +483,30 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   if ((rc = fill32(c, d.sc + SC_QUEUE, 0u, 1, s))) return bail(rc);
   if (hipMemcpyAsync((void*)d.tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) return bail(CKV_EHIP);
   if ((rc = upload_budgets(c, budgets, s))) return bail(rc);
+  {
+    // Segment table.  headroom 0: every unit owns room for cap entries for good.  Otherwise a unit starts with
+    // the segments that budget + headroom entries need, handed out in unit order (so a unit's segments are
+    // contiguous to begin with); the rest of the pool is spare.
+    const int mseg = d.max_seg;
+    const long long pool_segs = layout->pool_slots / kSeg;
+    std::vector<int32_t> tbl((size_t)c->units * mseg, 0), owned((size_t)c->units, 0), spare;
+    long long next = 0;
+    for (long long u = 0; u < c->units; ++u) {
+      const int need = layout->headroom == 0 ? mseg : std::min<long long>(mseg, ((long long)budgets[u] + layout->headroom + kSeg - 1) / kSeg);
+      if (next + need > pool_segs) return bail(fail(c, CKV_EINVAL, "pool_slots too small for these budgets: see ckv_pool_slots"));
+      for (int j = 0; j < need; ++j) tbl[(size_t)u * mseg + j] = (int32_t)(next + j);
+      owned[u] = need;
+      next += need;
+    }
+    for (long long sg = pool_segs - 1; sg >= next; --sg) spare.push_back((int32_t)sg);     // popped from the end: lowest first
+    const int32_t nspare = (int32_t)spare.size();
+    if (hipMemcpyAsync(d.tbl, tbl.data(), tbl.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(d.owned, owned.data(), owned.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        (nspare && hipMemcpyAsync(d.spare, spare.data(), spare.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) ||
+        hipMemcpyAsync(d.sc + SC_SPARE, &nspare, 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+      return bail(CKV_EHIP);
+  }
   if (hipStreamSynchronize(s) != hipSuccess) return bail(CKV_EHIP);
   *out = c;
   return CKV_OK;
@@ -561,7 +579,6 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   // workgroup (a step with deferred bookkeeping always takes the separate kernels).
   const ckv_ctx::Fused* fv = (flags & CKV_DEFER_BOOKKEEPING) ? nullptr : fused_variant(c);
   if (fv && (c->path_mode == 0 || layer >= 0) && count < fv->grid) fv = nullptr;   // fewer units than workgroups: split the units instead
-  if (fv == &c->fused[2] && (flags & CKV_ATTENTION_ONLY)) fv = &c->fused[0];   // no bookkeeping to move aside
   const bool fused = fv != nullptr;
   if (int rc = join_side(c, s, layer)) return rc;
   if (flags & CKV_DEFER_BOOKKEEPING) {
@@ -593,7 +610,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     return CKV_OK;
   }
   // unit_kernel<W> appends by itself; the other kernels get the new entries (and their schedule or work list) from prep_kernel
-  if (!fused || fv == &c->fused[2]) {
+  if (!fused) {
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
                        (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? (layer >= 0 ? 7 : 3) : 1, INT_MAX, (const uint16_t*)q);
     CKV_HIP(c, hipGetLastError());
@@ -617,9 +634,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     const uint16_t* vb = (const uint16_t*)v_new;
     const uint16_t* kb = (const uint16_t*)k_new;
     void* ob = out;
-    if (fv == &c->fused[2])
-      hipLaunchKernelGGL(unit_kernel_split, dim3((unsigned)fv->grid), dim3(512), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb);
-    else if (fv->waves == 4)
+    if (fv->waves == 4)
       hipLaunchKernelGGL(unit_kernel<4>, dim3((unsigned)fv->grid), dim3(256), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb, kb);
     else
       hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb, kb);
@@ -760,14 +775,9 @@ int ckv_probe_noalloc(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* c
   // the layer's units as units 0 .. count-1 of a context of their own: caches and lengths from the real context,
   // work list, partials, logits and step counters from the scratch
   Dev ds = c->dev;
-  const size_t slot0 = (size_t)begin * c->dev.cap;
   ds.units = count;
-  ds.K += slot0 * kDim;
-  ds.V += slot0 * kDim;
-  ds.crf += slot0;
-  ds.tau += slot0;
-  ds.pos += slot0;
-  ds.flags += slot0;
+  ds.tbl += (size_t)begin * c->dev.max_seg;      // the rows name pool segments: the pools stay where they are
+  ds.owned += begin;
   ds.n += begin;
   ds.budget += begin;
   ds.t_unit += begin;
@@ -856,6 +866,15 @@ int ckv_status(ckv_ctx* c) {
   return CKV_OK;
 }
 
+// The unit's row of the segment table and the number of segments it owns (the device is idle).
+static int read_row(ckv_ctx* c, size_t u, std::vector<int32_t>* row, int32_t* own) {
+  row->resize((size_t)c->dev.max_seg);
+  CKV_HIP(c, hipMemcpy(row->data(), c->dev.tbl + u * c->dev.max_seg, row->size() * 4, hipMemcpyDeviceToHost));
+  CKV_HIP(c, hipMemcpy(own, c->dev.owned + u, 4, hipMemcpyDeviceToHost));
+  if (*own < 0 || *own > c->dev.max_seg) return fail(c, CKV_ESTATE, "corrupt segment table");
+  return CKV_OK;
+}
+
 int ckv_export_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_t* n_out, int32_t* nev_out,
                     int32_t* budget_out, uint16_t* K, uint16_t* V, float* crf, int32_t* tau, int32_t* pos,
                     uint8_t* flags) {
@@ -863,9 +882,22 @@ int ckv_export_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
   if (layer < 0 || layer >= c->lay.n_layers || seq < 0 || seq >= c->lay.batch || head < 0 || head >= c->lay.n_kv_heads)
     return fail(c, CKV_EINVAL, "unit index out of range");
   const size_t u = ((size_t)layer * c->lay.batch + seq) * c->lay.n_kv_heads + head;
-  const size_t cap = (size_t)c->lay.cap, base = u * cap;
+  const size_t cap = (size_t)c->lay.cap;
   if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
+  // the unit's slots, segment by segment (what it does not own stays zero on the host side)
+  std::vector<int32_t> row;
+  int32_t own = 0;
+  if (int rc = read_row(c, u, &row, &own)) return rc;
+  auto fetch = [&](void* host, const void* pool, size_t elem_bytes) -> int {      // per-slot array
+    std::memset(host, 0, cap * elem_bytes);
+    for (int j = 0; j < own; ++j) {
+      const size_t cnt = std::min<size_t>(kSeg, cap - (size_t)j * kSeg);
+      CKV_HIP(c, hipMemcpy((char*)host + (size_t)j * kSeg * elem_bytes, (const char*)pool + (size_t)row[j] * kSeg * elem_bytes,
+                           cnt * elem_bytes, hipMemcpyDeviceToHost));
+    }
+    return CKV_OK;
+  };
   int32_t n = 0, nev = 0, bud = 0;
   CKV_HIP(c, hipMemcpy(&n, c->dev.n + u, 4, hipMemcpyDeviceToHost));
   CKV_HIP(c, hipMemcpy(&nev, c->dev.nev + u, 4, hipMemcpyDeviceToHost));
@@ -877,23 +909,26 @@ int ckv_export_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
   for (int which = 0; which < 2; ++which) {
     uint16_t* dst = which == 0 ? K : V;
     if (!dst) continue;
-    tmp.resize(cap * kDim);
-    CKV_HIP(c, hipMemcpy(tmp.data(), (which == 0 ? c->dev.K : c->dev.V) + base * kDim, cap * kDim * 2, hipMemcpyDeviceToHost));
-    for (int r = 0; r < (int)cap; ++r)
-      for (int col = 0; col < kDim; ++col)
-        dst[(size_t)r * kDim + col] = tmp[which == 0 ? k_offset(r, col) : v_offset(r, col)];
+    tmp.resize(kSegElems);
+    std::memset(dst, 0, cap * kDim * 2);
+    for (int j = 0; j < own; ++j) {
+      CKV_HIP(c, hipMemcpy(tmp.data(), (which == 0 ? c->dev.K : c->dev.V) + (size_t)row[j] * kSegElems, (size_t)kSegElems * 2, hipMemcpyDeviceToHost));
+      for (int rr = 0; rr < kSeg && (size_t)j * kSeg + rr < cap; ++rr)
+        for (int col = 0; col < kDim; ++col)
+          dst[((size_t)j * kSeg + rr) * kDim + col] = tmp[which == 0 ? k_offset(rr, col) : v_offset(rr, col)];
+    }
   }
-  if (crf) CKV_HIP(c, hipMemcpy(crf, c->dev.crf + base, cap * 4, hipMemcpyDeviceToHost));
-  if (tau) CKV_HIP(c, hipMemcpy(tau, c->dev.tau + base, cap * 4, hipMemcpyDeviceToHost));
-  if (pos) CKV_HIP(c, hipMemcpy(pos, c->dev.pos + base, cap * 4, hipMemcpyDeviceToHost));
+  if (crf) if (int rc = fetch(crf, c->dev.crf, 4)) return rc;
+  if (tau) if (int rc = fetch(tau, c->dev.tau, 4)) return rc;
+  if (pos) if (int rc = fetch(pos, c->dev.pos, 4)) return rc;
   if (flags) {
-    CKV_HIP(c, hipMemcpy(flags, c->dev.flags + base, cap, hipMemcpyDeviceToHost));
+    if (int rc = fetch(flags, c->dev.flags, 1)) return rc;
     // the hit mark is not stored: in the top-p mode an entry was hit in the unit's last step iff its tau is that step
     int32_t tu = 0;
     CKV_HIP(c, hipMemcpy(&tu, c->dev.t_unit + u, 4, hipMemcpyDeviceToHost));
     if (c->dev.reward_mode == 0 && tu >= c->par.t0 && n > 0) {
-      std::vector<int32_t> th((size_t)n);
-      CKV_HIP(c, hipMemcpy(th.data(), c->dev.tau + base, (size_t)n * 4, hipMemcpyDeviceToHost));
+      std::vector<int32_t> th(cap);
+      if (int rc = fetch(th.data(), c->dev.tau, 4)) return rc;
       for (int i = 0; i < n; ++i)
         if (th[i] == tu) flags[i] |= CKV_FLAG_HIT;
     }
@@ -909,25 +944,34 @@ int ckv_import_unit(ckv_ctx* c, int32_t layer, int32_t seq, int32_t head, int32_
   if (n < 0 || n >= c->lay.cap) return fail(c, CKV_EINVAL, "need 0 <= n < cap");
   if (n > 0 && (!K || !V || !crf || !tau || !pos)) return fail(c, CKV_EINVAL, "NULL state array");
   const size_t u = ((size_t)layer * c->lay.batch + seq) * c->lay.n_kv_heads + head;
-  const size_t cap = (size_t)c->lay.cap, base = u * cap;
   if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
-  const int nblk = (n + kBlk - 1) / kBlk;
-  std::vector<uint16_t> tmp((size_t)nblk * kBlkElems);
+  std::vector<int32_t> row;
+  int32_t own = 0;
+  if (int rc = read_row(c, u, &row, &own)) return rc;
+  if (n >= std::min<long long>(c->lay.cap, (long long)own * kSeg)) return fail(c, CKV_ECAPACITY, "the unit's segments do not hold n + 1 entries");
+  const int nseg = (n + kSeg - 1) / kSeg;
+  std::vector<uint16_t> tmp((size_t)kSegElems);
   for (int which = 0; which < 2 && n > 0; ++which) {
     const uint16_t* src = which == 0 ? K : V;
-    std::fill(tmp.begin(), tmp.end(), (uint16_t)0);
-    for (int r = 0; r < n; ++r)
-      for (int col = 0; col < kDim; ++col)
-        tmp[which == 0 ? k_offset(r, col) : v_offset(r, col)] = src[(size_t)r * kDim + col];
-    CKV_HIP(c, hipMemcpy((which == 0 ? c->dev.K : c->dev.V) + base * kDim, tmp.data(), tmp.size() * 2, hipMemcpyHostToDevice));
+    for (int j = 0; j < nseg; ++j) {
+      std::fill(tmp.begin(), tmp.end(), (uint16_t)0);
+      for (int rr = 0; rr < kSeg && j * kSeg + rr < n; ++rr)
+        for (int col = 0; col < kDim; ++col)
+          tmp[which == 0 ? k_offset(rr, col) : v_offset(rr, col)] = src[((size_t)j * kSeg + rr) * kDim + col];
+      const size_t used = (size_t)((std::min(n - j * kSeg, kSeg) + kBlk - 1) / kBlk) * kBlkElems;      // whole blocks
+      CKV_HIP(c, hipMemcpy((which == 0 ? c->dev.K : c->dev.V) + (size_t)row[j] * kSegElems, tmp.data(), used * 2, hipMemcpyHostToDevice));
+    }
   }
   if (n > 0) {
-    std::vector<uint8_t> zf(n, 0);
-    CKV_HIP(c, hipMemcpy(c->dev.crf + base, crf, (size_t)n * 4, hipMemcpyHostToDevice));
-    CKV_HIP(c, hipMemcpy(c->dev.tau + base, tau, (size_t)n * 4, hipMemcpyHostToDevice));
-    CKV_HIP(c, hipMemcpy(c->dev.pos + base, pos, (size_t)n * 4, hipMemcpyHostToDevice));
-    CKV_HIP(c, hipMemcpy(c->dev.flags + base, zf.data(), (size_t)n, hipMemcpyHostToDevice));
+    std::vector<uint8_t> zf(kSeg, 0);
+    for (int j = 0; j < nseg; ++j) {
+      const size_t cnt = (size_t)std::min(n - j * kSeg, kSeg), s0 = (size_t)row[j] * kSeg, h0 = (size_t)j * kSeg;
+      CKV_HIP(c, hipMemcpy(c->dev.crf + s0, crf + h0, cnt * 4, hipMemcpyHostToDevice));
+      CKV_HIP(c, hipMemcpy(c->dev.tau + s0, tau + h0, cnt * 4, hipMemcpyHostToDevice));
+      CKV_HIP(c, hipMemcpy(c->dev.pos + s0, pos + h0, cnt * 4, hipMemcpyHostToDevice));
+      CKV_HIP(c, hipMemcpy(c->dev.flags + s0, zf.data(), cnt, hipMemcpyHostToDevice));
+    }
   }
   int32_t zero = 0;
   CKV_HIP(c, hipMemcpy(c->dev.n + u, &n, 4, hipMemcpyHostToDevice));
@@ -981,9 +1025,9 @@ int ckv_bandwidth_probe(const void* src, void* dst, size_t bytes, void* sink, vo
 }
 
 int ckv_set_path(ckv_ctx* c, int32_t mode) {
-  if (!c || mode < 0 || mode > 5) return CKV_EINVAL;
+  if (!c || mode < 0 || mode > 4) return CKV_EINVAL;
   const bool any = c->fused[0].ok || c->fused[1].ok;
-  if ((mode == 2 && !any) || (mode == 3 && !c->fused[0].ok) || (mode == 4 && !c->fused[1].ok) || (mode == 5 && !c->fused[2].ok))
+  if ((mode == 2 && !any) || (mode == 3 && !c->fused[0].ok) || (mode == 4 && !c->fused[1].ok))
     return fail(c, CKV_EINVAL, "cap too large for the fused kernel's LDS");
   c->path_mode = mode;
   return CKV_OK;

@@ -31,7 +31,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
 // SC_CLAIM is a 64-bit counter (8-byte aligned): low word = work items published, high word = their blocks
-enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_SEQ = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_QUEUE = 6, SC_CLAIM = 8, SC_COUNT = 64 };
+enum { SC_T = 0, SC_WINDOW_STEPS = 1, SC_SEQ = 2, SC_DONE = 3, SC_STATUS = 4, SC_DONE_RB = 5, SC_QUEUE = 6, SC_SPARE = 7, SC_CLAIM = 8, SC_COUNT = 64 };
 enum { FLAG_HIT = 1, FLAG_SLIP = 2 };
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 128;           // cap <= 32768
@@ -51,6 +51,10 @@ struct Dev {
   int32_t* tau;
   int32_t* pos;
   uint8_t* flags;
+  int32_t* tbl;          // [units][max_seg] segment table: the pool segments (256 slots each) a unit's entries live in, in order
+  int32_t max_seg;       // cap / 256, rounded up: columns of tbl
+  int32_t* owned;        // [units] segments the unit owns: the first owned[u] entries of its row (the others hold 0)
+  int32_t* spare;        // pool segments no unit owns, a stack of sc[SC_SPARE] entries
   int32_t* n;            // [units] entries held
   int32_t* budget;       // [units]
   int32_t* t_unit;       // [units] time of the unit's last decode step
@@ -74,6 +78,25 @@ struct Dev {
 };
 
 
+
+// Where a unit's entries live.  Pool memory (K, V and the per-slot arrays) is handed out in segments of 256
+// slots; row u of the segment table names unit u's segments in order, so entry i sits in pool slot
+// row[i / 256] * 256 + i % 256 and whole 256-entry chunks (what one scan work item, one wavefront of the
+// single-layer scan, eight blocks of the fused kernel's stream cover) are contiguous.  `row` may point to a
+// copy of the row in LDS.
+struct Slots {
+  const int32_t* row;
+  // pool slot of entry i (index into crf / tau / pos / flags)
+  __device__ __forceinline__ size_t operator+(int i) const { return (size_t)row[i >> 8] * kSeg + (size_t)(i & (kSeg - 1)); }
+  // element offset in the K / V pool of block b (32 entries) of the unit
+  __device__ __forceinline__ size_t blk(int b) const { return (size_t)row[b >> 3] * kSegElems + (size_t)(b & (kSegBlocks - 1)) * kBlkElems; }
+  // element offset in the K / V pool of K[entry r][dim c] / V[entry r][dim c]
+  __device__ __forceinline__ size_t k(int r, int c) const { return (size_t)row[r >> 8] * kSegElems + (size_t)k_offset(r & (kSeg - 1), c); }
+  __device__ __forceinline__ size_t v(int r, int c) const { return (size_t)row[r >> 8] * kSegElems + (size_t)v_offset(r & (kSeg - 1), c); }
+};
+__device__ __forceinline__ Slots slots_of(const Dev& d, int u) { return Slots{d.tbl + (size_t)u * d.max_seg}; }
+// entries unit u has room for: what its segments hold, `cap` at most
+__device__ __forceinline__ int unit_cap(const Dev& d, int u) { return min(d.cap, d.owned[u] * kSeg); }
 
 // ------------------------------------------------------------------ helpers
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -322,14 +345,15 @@ __global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_be
   if (r0 >= n) return;
   const uint16_t* ksrc = k + (size_t)urel * P * kDim;
   const uint16_t* vsrc = v + (size_t)urel * P * kDim;
-  uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
-  uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+  const Slots sl = slots_of(d, u);
+  uint16_t* kdst = d.K + sl.blk(blk);          // this block's 32 entries
+  uint16_t* vdst = d.V + sl.blk(blk);
   // K: 32 rows x 16 pieces of 16 bytes
   for (int p = tid; p < kBlk * 16; p += kThreads) {
     int rr = p >> 4, piece = p & 15, r = r0 + rr;
     u32x4 x = {0u, 0u, 0u, 0u};
     if (r < n) x = *reinterpret_cast<const u32x4*>(ksrc + (size_t)r * kDim + piece * 8);
-    *reinterpret_cast<u32x4*>(kdst + k_offset(r, piece * 8)) = x;
+    *reinterpret_cast<u32x4*>(kdst + k_offset(rr, piece * 8)) = x;
   }
   // V: stage the rows, then write 16-byte pieces of the entry-interleaved order
   for (int p = tid; p < kBlk * 16; p += kThreads) {
@@ -352,10 +376,10 @@ __global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_be
     x.y = e8[2] | ((uint32_t)e8[3] << 16);
     x.z = e8[4] | ((uint32_t)e8[5] << 16);
     x.w = e8[6] | ((uint32_t)e8[7] << 16);
-    *reinterpret_cast<u32x4*>(vdst + (size_t)blk * kBlkElems + (size_t)p * 8) = x;
+    *reinterpret_cast<u32x4*>(vdst + (size_t)p * 8) = x;
   }
   // per-slot state
-  const size_t base = (size_t)u * d.cap;
+  const Slots base = sl;
   for (int rr = tid; rr < kBlk; rr += kThreads) {
     int r = r0 + rr;
     if (r < n) {
@@ -380,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void seed_state_kernel(Dev d, int unit_be
     }
     return;
   }
-  const size_t base = (size_t)u * d.cap;
+  const Slots base = slots_of(d, u);
   for (int i = blockIdx.x * kThreads + threadIdx.x; i < P; i += gridDim.x * kThreads) {
     d.crf[base + i] = i < P - W ? 1.0f : 0.0f;
     d.tau[base + i] = i;
@@ -412,18 +436,17 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
     n_before = n;
     if (append & 1) {
       const int t = d.sc[SC_T];
-      if (n >= d.cap) {
+      if (n >= unit_cap(d, u)) {
         if (sub == 0) atomicOr(&d.sc[SC_STATUS], 1);
       } else {
-        uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
-        uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+        const Slots sl = slots_of(d, u);
         if (sub < 16)
-          *reinterpret_cast<u32x4*>(kdst + k_offset(n, sub * 8)) =
+          *reinterpret_cast<u32x4*>(d.K + sl.k(n, sub * 8)) =
               *reinterpret_cast<const u32x4*>(k_new + (size_t)w * kDim + sub * 8);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vdst[v_offset(n, sub * 4 + e)] = v_new[(size_t)w * kDim + sub * 4 + e];
+        for (int e = 0; e < 4; ++e) d.V[sl.v(n, sub * 4 + e)] = v_new[(size_t)w * kDim + sub * 4 + e];
         if (sub == 0) {
-          const size_t s = (size_t)u * d.cap + n;
+          const size_t s = sl + n;
           d.crf[s] = 0.0f;
           d.tau[s] = t;
           d.pos[s] = t;
@@ -825,14 +848,13 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
   const int G = d.G;
   const bool head_lane = j < G;
   const int jq = head_lane ? j : 0;
-  const size_t unit_elems = (size_t)d.cap * kDim;
 
   int it = find_item(d, n_items, b_cur, lane);
   Item cur = fetch_item(d, it);
   KFrag ka;
   VFrag va;
   {
-    const size_t off = (size_t)cur.u * unit_elems + ((size_t)cur.c * kChunk + (size_t)(b_cur - cur.blk_off) * kBlk) * kDim + lane * 8;
+    const size_t off = slots_of(d, cur.u).blk(cur.c * kChunkBlocks + (b_cur - cur.blk_off)) + lane * 8;
     load_k(ka, d.K + off);
     load_v(va, d.V + off);
   }
@@ -856,12 +878,23 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
         qv[s] = as_bf16x8(x);
       }
     }
-    const size_t run_off = (size_t)cur.u * unit_elems + (size_t)fb * kBlkElems + lane * 8;
-    const uint16_t* kcur = d.K + run_off;
-    const uint16_t* vcur = d.V + run_off;
-    // after the run's last block the stream continues with the next run, or re-reads this block at the very end
-    const size_t tail_off = have_next ? (size_t)nxt.u * unit_elems + (size_t)nxt.c * kChunk * kDim + lane * 8
-                                      : run_off + (size_t)(nblk - 1) * kBlkElems;
+    // The run's blocks are consecutive in the unit but contiguous in memory only inside a segment (8 blocks):
+    // lane i holds the pool segment of the unit's segment fb / 8 + i (reloaded every 64 segments), and a
+    // block's address comes from there without another trip to memory.
+    const int32_t* seg_row = d.tbl + (size_t)cur.u * d.max_seg;
+    int seg_first = fb >> 3;
+    int seg_reg = seg_row[min(seg_first + lane, d.max_seg - 1)];
+    auto block_off = [&](int b) -> size_t {            // element offset of the unit's block b (b >= fb)
+      if ((b >> 3) - seg_first >= 64) {
+        seg_first = b >> 3;
+        seg_reg = seg_row[min(seg_first + lane, d.max_seg - 1)];
+      }
+      return (size_t)__builtin_amdgcn_readlane(seg_reg, (b >> 3) - seg_first) * kSegElems + (size_t)(b & (kSegBlocks - 1)) * kBlkElems +
+             lane * 8;
+    };
+    // after the run's last block the stream continues with the next run (whose first segment is asked for now
+    // and looked at then), or re-reads this block at the very end
+    const int nxt_seg = d.tbl[(size_t)nxt.u * d.max_seg + nxt.c];
     // logits of a block are stored as [head][32 entries]: 128 G contiguous bytes, 16 per lane
     float* lg_dst = d.logits + ((size_t)cur.u * d.cap + (size_t)fb * kBlk) * G + 4 * min(lane, 8 * G - 1);
     f32x4 acc[8];
@@ -874,13 +907,12 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
     // right after block b's PV; at the end of the run both continue with the next run's first block
     while (true) {
       const bool last = blk + 1 == nblk;
-      const uint16_t* kn_ptr = last ? d.K + tail_off : kcur + (size_t)(blk + 1) * kBlkElems;
-      const uint16_t* vn_ptr = last ? d.V + tail_off : vcur + (size_t)(blk + 1) * kBlkElems;
+      const size_t n_off = !last ? block_off(fb + blk + 1) : have_next ? (size_t)nxt_seg * kSegElems + lane * 8 : block_off(fb + blk);
       float sv[8];
       scan_qk(ka, qv, sv, d.scale_log2e, blk * kBlk, run_valid, lds_lg, kLgRow, lg_dst, G, lane);
-      load_k(ka, kn_ptr);
+      load_k(ka, d.K + n_off);
       scan_pv(sv, va, acc, m_run, l_run, lane);
-      load_v(va, vn_ptr);
+      load_v(va, d.V + n_off);
       ++blk;
       if (last) break;
     }
@@ -974,7 +1006,9 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
   const int urel = blockIdx.x, u = unit_begin + urel, cg = blockIdx.y;
   const int G = d.G;
   const int n_old = d.n[u];
-  const bool full = n_old >= d.cap;
+  // this wavefront's chunk is one pool segment (asked for beside the length: neither waits for the other)
+  const int my_seg = d.tbl[(size_t)u * d.max_seg + min(cg * kW + w, d.max_seg - 1)];
+  const bool full = n_old >= unit_cap(d, u);
   const int n = n_old + (full ? 0 : 1);
   const int nch = (n + kChunk - 1) / kChunk;
   if (cg == 0 && tid == 0) {
@@ -995,7 +1029,7 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
     const int nv = min(n - e0, kChunk);
     const int nb = (nv + kBlk - 1) / kBlk;
     const bool inject = !full && n_old >= e0 && n_old < e0 + kChunk;     // the new entry is then the chunk's last: entry nv - 1
-    const size_t off = (size_t)u * d.cap * kDim + (size_t)c * kChunkBlocks * kBlkElems + lane * 8;
+    const size_t off = (size_t)my_seg * kSegElems + lane * 8;
     const uint16_t* kcur = d.K + off;
     const uint16_t* vcur = d.V + off;
     KFrag ka;
@@ -1022,15 +1056,15 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) vnew[dt] = vr[16 * dt];
       // the rows also go into the cache, where the next step finds them
-      uint16_t* kdst = d.K + (size_t)u * d.cap * kDim;
-      uint16_t* vdst = d.V + (size_t)u * d.cap * kDim;
+      uint16_t* kdst = d.K + (size_t)my_seg * kSegElems;         // n_old lies in this chunk
+      uint16_t* vdst = d.V + (size_t)my_seg * kSegElems;
       if (j == 0) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) *reinterpret_cast<u32x4*>(kdst + k_offset(n_old, 32 * s + 8 * kg)) = knew[s];
+        for (int s = 0; s < 4; ++s) *reinterpret_cast<u32x4*>(kdst + k_offset(n_old - e0, 32 * s + 8 * kg)) = knew[s];
       }
       if (kg == 0) {
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) vdst[v_offset(n_old, 16 * dt + j)] = (uint16_t)vnew[dt];
+        for (int dt = 0; dt < 8; ++dt) vdst[v_offset(n_old - e0, 16 * dt + j)] = (uint16_t)vnew[dt];
       }
     }
     float* lds_lg = s_lg[w];
@@ -1187,13 +1221,13 @@ __device__ __forceinline__ u64 evict_key(float tmp, int pos) {
 
 // One wavefront moves the entry in slot `src` to slot `dst` (both of unit
 // base slot `base`); dst's position goes to src, flagged as evicted.
-__device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, int dst, int lane) {
-  uint16_t* K = d.K + base * kDim;
-  uint16_t* V = d.V + base * kDim;
+__device__ __forceinline__ void move_entry(const Dev& d, Slots base, int src, int dst, int lane) {
+  uint16_t* K = d.K;
+  uint16_t* V = d.V;
   if (lane < 16)
-    *reinterpret_cast<u32x4*>(K + k_offset(dst, lane * 8)) = *reinterpret_cast<const u32x4*>(K + k_offset(src, lane * 8));
-  V[v_offset(dst, lane)] = V[v_offset(src, lane)];
-  V[v_offset(dst, lane + 64)] = V[v_offset(src, lane + 64)];
+    *reinterpret_cast<u32x4*>(K + base.k(dst, lane * 8)) = *reinterpret_cast<const u32x4*>(K + base.k(src, lane * 8));
+  V[base.v(dst, lane)] = V[base.v(src, lane)];
+  V[base.v(dst, lane + 64)] = V[base.v(src, lane + 64)];
   if (lane == 0) {
     d.crf[base + dst] = d.crf[base + src];
     d.tau[base + dst] = d.tau[base + src];
@@ -1209,9 +1243,9 @@ __device__ __forceinline__ void move_entry(const Dev& d, size_t base, int src, i
 // to slot lst[r0 + m] (m < count), as move_entry does, but every load is issued before the first store, so
 // the moves' memory round trips overlap.  Lane l does the key piece l & 15 of move l >> 4; all lanes do two
 // value elements of every move; lanes 0..3 do the per-slot state of moves 0..3.
-__device__ __forceinline__ void move_entries4(const Dev& d, size_t base, const int* lst, int lst_cap, int r0, int count, int lane) {
-  uint16_t* K = d.K + base * kDim;
-  uint16_t* V = d.V + base * kDim;
+__device__ __forceinline__ void move_entries4(const Dev& d, Slots base, const int* lst, int lst_cap, int r0, int count, int lane) {
+  uint16_t* K = d.K;
+  uint16_t* V = d.V;
   const int mk = lane >> 4;
   int src[4], dst[4];
 #pragma unroll
@@ -1222,12 +1256,12 @@ __device__ __forceinline__ void move_entries4(const Dev& d, size_t base, const i
   }
   const int ks = mk == 0 ? src[0] : mk == 1 ? src[1] : mk == 2 ? src[2] : src[3];
   const int kd = mk == 0 ? dst[0] : mk == 1 ? dst[1] : mk == 2 ? dst[2] : dst[3];
-  const u32x4 kx = *reinterpret_cast<const u32x4*>(K + k_offset(ks, (lane & 15) * 8));
+  const u32x4 kx = *reinterpret_cast<const u32x4*>(K + base.k(ks, (lane & 15) * 8));
   uint16_t v0[4], v1[4];
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
-    v0[m] = V[v_offset(src[m], lane)];
-    v1[m] = V[v_offset(src[m], lane + 64)];
+    v0[m] = V[base.v(src[m], lane)];
+    v1[m] = V[base.v(src[m], lane + 64)];
   }
   float crf = 0.f;
   int tau = 0, ps = 0, pd = 0;
@@ -1241,12 +1275,12 @@ __device__ __forceinline__ void move_entries4(const Dev& d, size_t base, const i
     pd = d.pos[base + md];
     fl = d.flags[base + ms];
   }
-  if (mk < count) *reinterpret_cast<u32x4*>(K + k_offset(kd, (lane & 15) * 8)) = kx;
+  if (mk < count) *reinterpret_cast<u32x4*>(K + base.k(kd, (lane & 15) * 8)) = kx;
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     if (m < count) {
-      V[v_offset(dst[m], lane)] = v0[m];
-      V[v_offset(dst[m], lane + 64)] = v1[m];
+      V[base.v(dst[m], lane)] = v0[m];
+      V[base.v(dst[m], lane + 64)] = v1[m];
     }
   }
   if (lane < count) {
@@ -1272,31 +1306,31 @@ struct EntryRow {
 };
 
 template <int NT = kThreads>
-__device__ __forceinline__ EntryRow load_row(const Dev& d, size_t base, int src, int tid) {
+__device__ __forceinline__ EntryRow load_row(const Dev& d, Slots base, int src, int tid) {
   const int wave = tid >> 6, lane = tid & 63;
   constexpr int W = NT / 64;
-  const uint16_t* K = d.K + base * kDim;
-  const uint16_t* V = d.V + base * kDim;
+  const uint16_t* K = d.K;
+  const uint16_t* V = d.V;
   EntryRow r{{0u, 0u, 0u, 0u}, 0, 0};
-  if (wave == 0 && lane < 16) r.k = *reinterpret_cast<const u32x4*>(K + k_offset(src, lane * 8));
+  if (wave == 0 && lane < 16) r.k = *reinterpret_cast<const u32x4*>(K + base.k(src, lane * 8));
   if (wave == (W > 1 ? 1 : 0)) {
-    r.v0 = V[v_offset(src, lane)];
-    r.v1 = V[v_offset(src, lane + 64)];
+    r.v0 = V[base.v(src, lane)];
+    r.v1 = V[base.v(src, lane + 64)];
   }
   return r;
 }
 
 template <int NT = kThreads>
-__device__ __forceinline__ void evict_one(const Dev& d, size_t base, int src, int dst, const int* sh, int tid, const EntryRow& row) {
+__device__ __forceinline__ void evict_one(const Dev& d, Slots base, int src, int dst, const int* sh, int tid, const EntryRow& row) {
   const int wave = tid >> 6, lane = tid & 63;
   constexpr int W = NT / 64;
-  uint16_t* K = d.K + base * kDim;
-  uint16_t* V = d.V + base * kDim;
+  uint16_t* K = d.K;
+  uint16_t* V = d.V;
   if (dst != src) {
-    if (wave == 0 && lane < 16) *reinterpret_cast<u32x4*>(K + k_offset(dst, lane * 8)) = row.k;
+    if (wave == 0 && lane < 16) *reinterpret_cast<u32x4*>(K + base.k(dst, lane * 8)) = row.k;
     if (wave == (W > 1 ? 1 : 0)) {
-      V[v_offset(dst, lane)] = row.v0;
-      V[v_offset(dst, lane + 64)] = row.v1;
+      V[base.v(dst, lane)] = row.v0;
+      V[base.v(dst, lane + 64)] = row.v1;
     }
   }
   if (wave == (W > 2 ? 2 : 0) && lane == 32) {
@@ -1322,9 +1356,8 @@ struct ValLinear {
 // evm = LDS bit mask of n bits, lst = LDS scratch of lst_cap >= n ints that may
 // overlap the storage behind `val` (the scores are dead by the time it is used).
 template <class Val, int NT = kThreads, int SB = 0>
-__device__ __forceinline__ void evict_phase(const Dev& d, int u, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
+__device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
                             int& phase, int* sh, int tid) {
-  const size_t base = (size_t)u * d.cap;
   const int lane = tid & 63, wave = tid >> 6;
   const int k = n - B;
   if (k == 1) {
@@ -1638,9 +1671,8 @@ __device__ __forceinline__ void mean_weights(const Dev& d, LgView lv, int n, con
 // aggregated CRF (2^-20 fixed point), summed over the block.  s_tab: the first
 // s_tab_n entries of the decay table in LDS.
 template <class Val, int NT = kThreads, int SB = 0>
-__device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
+__device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
                            int& phase, int tid) {
-  const size_t base = (size_t)u * d.cap;
   // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
   uint32_t theta = 0;
   bool ties_all = true;
@@ -1694,7 +1726,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, int n, int t, Va
   }
 
   // ---- Alg. 1 Steps 2-3: scores (4 entries per thread and round: loads, table lookups, then stores)
-  const bool has_new = d.pos[base + n - 1] == t;
+  const bool has_new = d.pos[base + (n - 1)] == t;
   const bool need_pos = d.reward_mode == 0 && !ties_all;
   u64 sfix = 0;
   for (int i0 = tid; i0 < n; i0 += 4 * NT) {
@@ -1783,14 +1815,15 @@ __device__ __forceinline__ void mean_weights_regs(const Dev& d, LgView lv, int n
 
 // CRF, tau and position of group c of thread tid.  The loads are unconditional
 // (a select on their result would wait for them on the spot): a group beyond
-// the unit reads the unit's last group instead (the arrays hold cap entries, a
-// multiple of 4), and nothing looks at the values of entries >= n.
+// the unit reads the unit's last group instead, and nothing looks at the values
+// of entries >= n.
 template <int NT = kThreads>
-__device__ __forceinline__ void load_meta(const Dev& d, size_t base, int n, int t, int c, int tid, f32x4& crf, i32x4& tau, i32x4& ps) {
-  const int e0 = min(4 * (tid + c * NT), d.cap - 4);
-  crf = *reinterpret_cast<const f32x4*>(d.crf + base + e0);
-  tau = *reinterpret_cast<const i32x4*>(d.tau + base + e0);
-  ps = *reinterpret_cast<const i32x4*>(d.pos + base + e0);
+__device__ __forceinline__ void load_meta(const Dev& d, Slots base, int n, int t, int c, int tid, f32x4& crf, i32x4& tau, i32x4& ps) {
+  const int e0 = min(4 * (tid + c * NT), (max(n, 1) - 1) & ~3);
+  const size_t s0 = base + e0;                 // four consecutive entries share a segment
+  crf = *reinterpret_cast<const f32x4*>(d.crf + s0);
+  tau = *reinterpret_cast<const i32x4*>(d.tau + s0);
+  ps = *reinterpret_cast<const i32x4*>(d.pos + s0);
 }
 
 // Alg. 1 Steps 1-4 for a unit of n <= R NT entries with the weights in
@@ -1835,13 +1868,12 @@ __device__ __forceinline__ EntryRow load_row_input(const NewEntry& ne, int tid) 
 // `after_step1` runs once between Step 1 and the score update (the fused kernel
 // picks up its queue claim there).
 template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook, int SB = 0>
-__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
+__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
                                           i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
                                           int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
                                           int tid, Hook after_step1 = Hook{}, NewEntry ne = NewEntry{nullptr, nullptr}) {
   constexpr int C = R / 4;
   static_assert(C % CH == 0 && CP <= CH, "groups come in chunks of CH");
-  const size_t base = (size_t)u * d.cap;
   const bool new_in_regs = ne.k_row != nullptr;          // uniform; implies that exactly one entry is evicted below
 #pragma unroll
   for (int c = CP; c < CH; ++c) load_meta<NT>(d, base, n, t, c, tid, crf[c], tau[c], ps[c]);
@@ -2058,14 +2090,15 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
     }
     if (e0 + 3 < n) {
       if (stored) {
-        *reinterpret_cast<f32x4*>(d.crf + base + e0) = ncrf;
-        *reinterpret_cast<i32x4*>(d.tau + base + e0) = ntau;
+        const size_t s0 = base + e0;
+        *reinterpret_cast<f32x4*>(d.crf + s0) = ncrf;
+        *reinterpret_cast<i32x4*>(d.tau + s0) = ntau;
       }
     } else if (e0 < n) {                     // the unit's last, partial group: entry by entry
       for (int e = 0; e < 4 && e0 + e < n; ++e) {
         if ((stored >> e) & 1u) {
-          d.crf[base + e0 + e] = ncrf[e];
-          d.tau[base + e0 + e] = t;
+          d.crf[base + (e0 + e)] = ncrf[e];
+          d.tau[base + (e0 + e)] = t;
         }
       }
     }
@@ -2099,7 +2132,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, int n, int B, int
       if (i < n) val(i) = a[k];
     }
     block_sync<NT, SB>(rb);
-    evict_phase<Val, NT, SB>(d, u, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
+    evict_phase<Val, NT, SB>(d, u, base, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
   }
 }
 
@@ -2111,36 +2144,37 @@ template <int NT = kThreads>
 __device__ __forceinline__ void unit_bookkeeping(const Dev& d, int u, int n, int B, int t, LgView lv, const float* sM,
                                                  const float* sInv, bool evict, float* val, uint32_t* evm, const float* s_tab,
                                                  int s_tab_n, RedBuf& rb, int& phase, int* sh, int tid) {
+  const Slots base = slots_of(d, u);
   if (n <= 8 * NT) {
     float a[8];
     mean_weights_regs<8, NT>(d, lv, n, sM, sInv, a, tid);
     f32x4 crf[2];
     i32x4 tau[2], ps[2];
-    lrfu_regs<8, 2, 0, ValLinear, NT>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+    lrfu_regs<8, 2, 0, ValLinear, NT>(d, u, base, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
                                       s_tab, s_tab_n, rb, phase, sh, tid);
   } else if (n <= 16 * NT) {
     float a[16];
     mean_weights_regs<16, NT>(d, lv, n, sM, sInv, a, tid);
     f32x4 crf[4];
     i32x4 tau[4], ps[4];
-    lrfu_regs<16, 4, 0, ValLinear, NT>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+    lrfu_regs<16, 4, 0, ValLinear, NT>(d, u, base, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
                                        s_tab, s_tab_n, rb, phase, sh, tid);
   } else if (n <= 32 * NT) {
     float a[32];
     mean_weights_regs<32, NT>(d, lv, n, sM, sInv, a, tid);
     f32x4 crf[8];
     i32x4 tau[8], ps[8];
-    lrfu_regs<32, 8, 0, ValLinear, NT>(d, u, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
+    lrfu_regs<32, 8, 0, ValLinear, NT>(d, u, base, n, B, t, a, crf, tau, ps, ValLinear{val}, evict, evm, reinterpret_cast<int*>(val), d.cap,
                                        s_tab, s_tab_n, rb, phase, sh, tid);
   } else {
     mean_weights<NT>(d, lv, n, sM, sInv, val, tid);
-    const u64 sfix = lrfu_update<ValLinear, NT>(d, u, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
+    const u64 sfix = lrfu_update<ValLinear, NT>(d, u, base, n, t, ValLinear{val}, s_tab, s_tab_n, rb, phase, tid);
     if (tid == 0) {
       d.window[u] += sfix;
       d.t_unit[u] = t;
     }
     if (evict && n > B)
-      evict_phase<ValLinear, NT>(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
+      evict_phase<ValLinear, NT>(d, u, base, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
     else if (tid == 0)
       d.nev[u] = 0;
   }
@@ -2174,9 +2208,9 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   if (late == 2) {
     // after layer_scan_kernel: the new entry's rows are in the cache and its logits with the others, the
     // unit's records still describe the step before.  Record the append, then go on as after any scan.
-    if (n < d.cap) {
+    if (n < unit_cap(d, u)) {
       if (tid == 0) {
-        const size_t s = (size_t)u * d.cap + n;
+        const size_t s = slots_of(d, u) + n;
         d.crf[s] = 0.0f;
         d.tau[s] = t;
         d.pos[s] = t;
@@ -2241,7 +2275,7 @@ __global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_beg
     }
   }
   const int nblk = min(kChunkBlocks, (n_max - e_chunk + kBlk - 1) / kBlk);
-  const uint16_t* kb = d.K + (size_t)u * d.cap * kDim + (size_t)chunk * kChunkBlocks * kBlkElems + lane * 8;
+  const uint16_t* kb = d.K + (size_t)d.tbl[(size_t)u * d.max_seg + chunk] * kSegElems + lane * 8;     // a chunk is one pool segment
   float* lgp = slg + ((size_t)urel * (d.cap / kBlk) + (size_t)chunk * kChunkBlocks) * (kSeedCols * kBlk) + j * kBlk + 4 * kg;
   float m_run = -INFINITY, l_run = 0.f;                   // this lane's entries only; the four lanes of a column meet at the end
   KFrag ka, kn;
@@ -2342,7 +2376,7 @@ __global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin, 
   const int tid = threadIdx.x;
   const int u = unit_begin + blockIdx.x;
   const int n = d.n[u], B = d.budget[u];
-  const size_t base = (size_t)u * d.cap;
+  const Slots base = slots_of(d, u);
   int phase = 0;
   if (n <= B) {
     if (tid == 0) d.nev[u] = 0;
@@ -2364,7 +2398,7 @@ __global__ __launch_bounds__(kThreads) void evict_kernel(Dev d, int unit_begin, 
     }
   }
   __syncthreads();
-  evict_phase(d, u, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
+  evict_phase(d, u, base, n, B, ValLinear{val}, evm, reinterpret_cast<int*>(val), d.cap, rb, phase, sh, tid);
 }
 
 // ------------------------------------------------------------------ probe
@@ -2377,7 +2411,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(Dev d, int unit_begin, 
   const int tid = threadIdx.x;
   const int urel = blockIdx.x, u = unit_begin + urel;
   const int n = d.n[u];
-  const size_t base = (size_t)u * d.cap;
+  const Slots base = slots_of(d, u);
   int phase = 0;
   if (n > 0) {
     merge_partials(d, u, urel, (n + kChunk - 1) / kChunk, d.sc[SC_SEQ], sM, sInv, sW, nullptr, tid);

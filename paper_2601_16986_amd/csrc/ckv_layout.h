@@ -35,8 +35,12 @@ constexpr int kBlkElems = kBlk * kDim;   // bf16 elements per block (4096)
 constexpr int kChunkBlocks = 8;    // blocks per scan work item
 constexpr int kChunk = kBlk * kChunkBlocks;   // 256 entries
 constexpr int kMaxGroup = 8;       // query heads per KV head
+constexpr int kSeg = kChunk;                // entries per segment, the unit in which pool memory is handed to units (64 KB of K, 64 KB of V)
+constexpr int kSegBlocks = kChunkBlocks;
+constexpr int kSegElems = kSeg * kDim;      // bf16 elements of one segment in the K (or V) pool
 
-// element offset (in bf16) of K[entry r][dim c] inside its unit
+// element offset (in bf16) of K[entry r][dim c] from the start of the run of blocks that holds entry 0
+// (a unit's entries are contiguous inside a segment of 256: callers pass r % 256 and add the segment's offset)
 CKV_HD int64_t k_offset(int r, int c) {
   int blk = r >> 5, rr = r & 31;
   int tt = rr >> 4, j = rr & 15;
@@ -44,7 +48,7 @@ CKV_HD int64_t k_offset(int r, int c) {
   return (int64_t)blk * kBlkElems + (((tt * 4 + s) * 64 + kg * 16 + j) << 3) + e;
 }
 
-// element offset (in bf16) of V[entry r][dim c] inside its unit
+// the same for V[entry r][dim c]
 CKV_HD int64_t v_offset(int r, int c) {
   int blk = r >> 5, rr = r & 31;
   int tt = rr >> 4, kg = (rr & 15) >> 2, e = tt * 4 + (rr & 3);

@@ -97,6 +97,8 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   extern __shared__ unsigned char smem[];
   float* lg = reinterpret_cast<float*>(smem);
   uint32_t* evm = reinterpret_cast<uint32_t*>(smem + lds_main);
+  // the segment-table rows of this unit and the next (max_seg entries each), behind the eviction mask
+  int32_t* s_tbl = reinterpret_cast<int32_t*>(smem + lds_main + ((d.cap + 31) / 32) * 4);
   // staging tiles for spilled logits while streaming, accumulator slices afterwards
   constexpr int kStageFloats = W * kMaxGroup * kLgRow, kOutFloats = kSlices * kMaxGroup * kDim;
   __shared__ float s_buf[kStageFloats > kOutFloats ? kStageFloats : kOutFloats];
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int G = d.G;
-  const size_t unit_elems = (size_t)d.cap * kDim;
+  const int max_seg = d.max_seg;
   const int n_units = d.units;
   const int t = d.sc[SC_T];
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
@@ -135,17 +137,23 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     const int uu = d.by_order ? d.order[sl] : d.unit0 + sl;
     return slot < n_units ? uu : -1;
   };
-  auto state_of = [&](int uu, int& nn, int& bb, int& ll) {
+  // sg0: the unit's first segment, where every wavefront's first block lies
+  auto state_of = [&](int uu, int& nn, int& bb, int& ll, int& sg0) {
     const int us = max(uu, 0);
     const int n_old = d.n[us];
     bb = d.budget[us];
-    ll = n_old < d.cap ? 1 : 0;
+    sg0 = d.tbl[(size_t)us * max_seg];
+    ll = n_old < unit_cap(d, us) ? 1 : 0;
     nn = n_old + ll;
   };
-  int u, n, B, lone, u1, n1 = 0, B1 = 0, lone1 = 0;
+  int u, n, B, lone, seg0, u1, n1 = 0, B1 = 0, lone1 = 0, seg01 = 0;
   u = unit_of(wg);
-  state_of(u, n, B, lone);
+  state_of(u, n, B, lone, seg0);
   u1 = unit_of(grid + wg);
+  // The table row of the unit in hand sits in LDS (s_tbl + cur * max_seg); the next unit's row is asked for at
+  // the top of the unit before it, into a register, and put into the other half when that unit is done.
+  int cur = 0;
+  if (tid < max_seg) s_tbl[tid] = d.tbl[(size_t)max(u, 0) * max_seg + tid];
   int slot2 = 2 * grid + wg;                                   // slot of the unit after next
   // Per-lane values are re-derived, from a copy of the lane index the compiler cannot see through, at
   // the start of every phase that needs them: otherwise they are computed once, kept alive across the
@@ -156,9 +164,9 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
   VFrag va;
   bf16x8 qv[4];
   // first block of wave `wave` in a unit of nb blocks (any valid block if the wave has none there)
-  auto first_off = [&](int uu, int nn) -> size_t {
+  auto first_off = [&](int sg, int nn) -> size_t {
     const int nb = (nn + kBlk - 1) / kBlk;
-    return (size_t)uu * unit_elems + (size_t)min(wave, max(nb - 1, 0)) * kBlkElems + slane * 8;
+    return (size_t)sg * kSegElems + (size_t)min(wave, max(nb - 1, 0)) * kBlkElems + slane * 8;
   };
   auto load_q = [&](int uu) {
     const int jh = slane & 7;       // columns 8..15 repeat the heads 0..7 (scan_pv<true>)
@@ -171,34 +179,39 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     }
   };
   if (u >= 0) {
-    const size_t o = first_off(u, n - lone);
+    const size_t o = first_off(seg0, n - lone);
     load_k(ka, d.K + o);
     load_v(va, d.V + o);
     load_q(u);
   }
   const bool evict = (call_flags & 1u) != 0;
 
+  __syncthreads();                                 // the first unit's table row is in place
   while (u >= 0) {
+    const int32_t* s_row = s_tbl + cur * max_seg;
+    const Slots base{s_row};
+    // the next unit's table row (this thread's entry of it): asked for first, looked at last
+    const int row_next = d.tbl[(size_t)max(u1, 0) * max_seg + min(tid, max_seg - 1)];
     const int ns = n - lone;                       // entries that are streamed: all but the one that arrives now
     // the new entry stays out of the cache until the eviction has chosen its slot (see above); otherwise it is
     // written to slot n - 1 now, by three wavefronts (key row, value row, per-slot state)
     const bool new_in_regs = lone && evict && n - B == 1 && n <= 32 * NT;
     if (lone && !new_in_regs) {
-      const size_t base = (size_t)u * d.cap;
       const uint16_t* krow = k_new + (size_t)(u - d.unit0) * kDim;
       const uint16_t* vrow = v_new + (size_t)(u - d.unit0) * kDim;
       asm volatile("" : "+v"(slane));
       if (wave == 0 && slane < 16)
-        *reinterpret_cast<u32x4*>(d.K + base * kDim + k_offset(n - 1, slane * 8)) = *reinterpret_cast<const u32x4*>(krow + slane * 8);
+        *reinterpret_cast<u32x4*>(d.K + base.k(n - 1, slane * 8)) = *reinterpret_cast<const u32x4*>(krow + slane * 8);
       if (wave == (W > 1 ? 1 : 0)) {
-        d.V[base * kDim + v_offset(n - 1, slane)] = vrow[slane];
-        d.V[base * kDim + v_offset(n - 1, slane + 64)] = vrow[slane + 64];
+        d.V[base.v(n - 1, slane)] = vrow[slane];
+        d.V[base.v(n - 1, slane + 64)] = vrow[slane + 64];
       }
       if (wave == (W > 2 ? 2 : 0) && slane == 32) {
-        d.crf[base + n - 1] = 0.0f;
-        d.tau[base + n - 1] = t;
-        d.pos[base + n - 1] = t;
-        d.flags[base + n - 1] = 0;
+        const size_t sn = base + (n - 1);
+        d.crf[sn] = 0.0f;
+        d.tau[sn] = t;
+        d.pos[sn] = t;
+        d.flags[sn] = 0;
         d.n[u] = n;
       }
     }
@@ -212,7 +225,7 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     // ---- the unit after next, and the state of the next one: scalar loads, waited for with the first LDS
     // access below, long before they are needed
     const int u2 = unit_of(slot2);
-    state_of(u1, n1, B1, lone1);
+    state_of(u1, n1, B1, lone1, seg01);
 
     // ---- stream this wave's blocks (wave + W i, i < my_cnt): while block i is computed, block i + 1 is
     // in flight; the last block's successor is the wave's first block of the next unit, so the loads
@@ -222,8 +235,10 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
-    const uint16_t* kcur = d.K + (size_t)u * unit_elems + slane * 8;
-    const uint16_t* vcur = d.V + (size_t)u * unit_elems + slane * 8;
+    // block b of the unit: segment b / 8 (from the row in LDS), block b % 8 inside it
+    auto blk_off = [&](int b) -> size_t {
+      return (size_t)s_row[b >> 3] * kSegElems + (size_t)(b & (kSegBlocks - 1)) * kBlkElems + slane * 8;
+    };
     float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(slane, 8 * G - 1);
     auto qk = [&](int blk, float (&sv)[8]) {
       const bool resident = blk < res_blk;
@@ -233,17 +248,18 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
     };
     for (int i = 0; i + 1 < my_cnt; ++i) {
       const int blk = wave + W * i;
+      const size_t o_blk = blk_off(blk + W);
       float sv[8];
       qk(blk, sv);
-      load_k(ka, kcur + (size_t)(blk + W) * kBlkElems);
+      load_k(ka, d.K + o_blk);
       scan_pv<true>(sv, va, acc, m_run, l_run, slane);
-      load_v(va, vcur + (size_t)(blk + W) * kBlkElems);
+      load_v(va, d.V + o_blk);
     }
     // without a next unit the prefetch reads this unit's first block again and is ignored
     const bool have_next = u1 >= 0;
     const int u_next = have_next ? u1 : u;
     const int n_next = have_next ? n1 - lone1 : ns;
-    const size_t o_next = first_off(u_next, n_next);
+    const size_t o_next = first_off(have_next ? seg01 : seg0, n_next);
     // the new entry's key as one more row for the matrix cores (what a lane holds of row 0 of a key tile: dims
     // 32 s + 8 kg .. + 7) and its value element, requested a block before they are used
     const uint16_t vnew = v_new[(size_t)(u - d.unit0) * kDim + (slane & 63) + 64 * (wave & 1)];
@@ -256,6 +272,9 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       qk(wave + W * (my_cnt - 1), sv);
       scan_pv<true>(sv, va, acc, m_run, l_run, slane);
     }
+    // the next unit's table row into the free half (every load of the stream has been consumed by now, so the
+    // wait for this one, the oldest, costs nothing); the barrier that ends the unit publishes it
+    if (tid < max_seg) s_tbl[(cur ^ 1) * max_seg + tid] = row_next;
     // The next unit's first block, its queries and the claim of the slot three units ahead are requested
     // once this unit's weights sit in registers (the block's 64 registers are free until then, which is
     // what lets units of up to 32 entries per thread stay in registers); they arrive during the
@@ -426,12 +445,12 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       f32x4 crf[CH];
       i32x4 tau[CH], ps[CH];
 #pragma unroll
-      for (int c = 0; c < CH; ++c) load_meta<NT>(d, (size_t)u * d.cap, n, t, c, ftid, crf[c], tau[c], ps[c]);
+      for (int c = 0; c < CH; ++c) load_meta<NT>(d, base, n, t, c, ftid, crf[c], tau[c], ps[c]);
       // the queue claim is picked up after the bisection: by then everything requested before it has arrived
       auto publish = [&]() {
         if (ftid == 0) s_claim = 3 * grid + claimed;
       };
-      lrfu_regs<R, CH, CH, ValFused, NT>(d, u, n, B, t, a, crf, tau, ps, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4,
+      lrfu_regs<R, CH, CH, ValFused, NT>(d, u, base, n, B, t, a, crf, tau, ps, val, evict, evm, reinterpret_cast<int*>(smem), lds_main / 4,
                                          s_tab, s_tab_n, rb, phase, sh, ftid, publish, ne);
     };
     if (call_flags & 2u) {               // attention only: no bookkeeping, just keep the stream and the queue going
@@ -454,365 +473,28 @@ __global__ __launch_bounds__(64 * W, 2) void unit_kernel(Dev d, const uint16_t* 
       request_next();
       if (ftid == 0) s_claim = 3 * grid + claimed;
       __syncthreads();
-      const u64 sfix = lrfu_update<ValFused, NT>(d, u, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
+      const u64 sfix = lrfu_update<ValFused, NT>(d, u, base, n, t, val, s_tab, s_tab_n, rb, phase, ftid);
       if (ftid == 0) {
         d.window[u] += sfix;
         d.t_unit[u] = t;
       }
       if (evict && n > B)
-        evict_phase<ValFused, NT>(d, u, n, B, val, evm, reinterpret_cast<int*>(smem), lds_main / 4, rb, phase, sh, ftid);
+        evict_phase<ValFused, NT>(d, u, base, n, B, val, evm, reinterpret_cast<int*>(smem), lds_main / 4, rb, phase, sh, ftid);
       else if (ftid == 0)
         d.nev[u] = 0;
     }
 
     // ---- next unit
     __syncthreads();          // LDS of this unit is dead before the next unit's logits overwrite it; s_claim is set
+    cur ^= 1;
     u = u1;
     n = n1;
     B = B1;
     lone = lone1;
+    seg0 = seg01;
     u1 = u2;
     slot2 = __builtin_amdgcn_readfirstlane(s_claim);
   }
-  step_epilogue(d, t, advance, tid, 0);
-}
-
-
-// The fused step with the two kinds of work on different wavefronts of one workgroup, one workgroup per
-// CU: four wavefronts stream (attention of unit r) and four do Alg. 1 Steps 1-4 of unit r - 1 from the
-// logits the streamers left in LDS, so a CU requests K and V nearly all of the time instead of while
-// neither of two workgroups happens to be book-keeping (four streaming wavefronts per CU reach the same
-// bandwidth as eight).  Two logits tiles of `lds_tile` bytes alternate between the roles.  The book-keepers
-// run the code of unit_kernel's bookkeeping phase with their own barrier (a counter in LDS, see block_sync)
-// and meet the streamers only at the four workgroup barriers that end a unit, which every wavefront
-// executes the same number of times; whoever is late is waited for there.  Schedule and queue as in
-// unit_kernel, one stage deeper: a slot is claimed four units ahead, so that the claim's result is never
-// waited for.
-__global__ __launch_bounds__(512, 2) void unit_kernel_split(Dev d, const uint16_t* __restrict__ q, void* out,
-                                                            uint32_t call_flags, int advance, int lds_tile,
-                                                            const uint16_t* __restrict__ v_new) {
-  constexpr int W = 4, NT = 256, kSlices = 2;
-  extern __shared__ unsigned char smem[];
-  uint32_t* evm = reinterpret_cast<uint32_t*>(smem + 2 * (size_t)lds_tile);
-  constexpr int kStageFloats = W * kMaxGroup * kLgRow, kOutFloats = kSlices * kMaxGroup * kDim;
-  __shared__ float s_buf[kStageFloats > kOutFloats ? kStageFloats : kOutFloats];
-  float* s_out = s_buf;
-  __shared__ float s_ml[W + 1][kMaxGroup][2];   // row W: a new entry alone in its block (as in unit_kernel)
-  __shared__ __align__(16) float sM[2][kMaxGroup];
-  __shared__ __align__(16) float sInv[2][kMaxGroup];
-  __shared__ float s_tab[kTabLds];
-  __shared__ RedBuf rb;
-  __shared__ int sh[8];
-  __shared__ int s_claim;
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const bool streamer = wave < W;
-  const int G = d.G;
-  const size_t unit_elems = (size_t)d.cap * kDim;
-  const int n_units = d.units;
-  const int t = d.sc[SC_T];
-  const int s_tab_n = min(kTabLds, d.tab_last + 1);
-  for (int i = tid; i < s_tab_n; i += 512) s_tab[i] = d.tab[i];
-  if (tid == 0) {
-    rb.soft = 0;
-    rb.soft_fail = 0;
-  }
-  __syncthreads();
-
-  const int grid = (int)gridDim.x, wg = (int)blockIdx.x;
-  auto fetch = [&](int slot, int& uu, int& nn, int& bb, int& ll) {      // uniform slot: scalar loads
-    const int4 e = d.sched[min(slot, n_units - 1)];
-    uu = slot < n_units ? e.x : -1;
-    nn = e.y;
-    bb = e.z;
-    ll = (e.w != 0 && ((e.y - 1) & (kBlk - 1)) == 0) ? 1 : 0;  // the new entry opens a block of its own
-  };
-  int u, n, B, lone, u1, n1, B1, lone1;
-  int up = -1, np_ = 0, Bp = 0;                                // the book-keeper's unit: the streamers' previous one
-  fetch(wg, u, n, B, lone);
-  fetch(grid + wg, u1, n1, B1, lone1);
-  int slot2 = 2 * grid + wg;
-  int par = 0, iter = 0;
-  int slane = lane;
-  asm volatile("" : "+v"(slane));
-  KFrag ka;
-  VFrag va;
-  bf16x8 qv[4];
-  auto first_off = [&](int uu, int nn) -> size_t {
-    const int nb = (nn + kBlk - 1) / kBlk;
-    return (size_t)uu * unit_elems + (size_t)min(wave, max(nb - 1, 0)) * kBlkElems + slane * 8;
-  };
-  auto load_q = [&](int uu) {
-    const int jh = slane & 7;       // columns 8..15 repeat the heads 0..7 (scan_pv<true>)
-    const uint16_t* qrow = q + ((size_t)(uu - d.unit0) * G + (jh < G ? jh : 0)) * kDim + 8 * (slane >> 4);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qv[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * s));
-  };
-  if (streamer && u >= 0) {
-    const size_t o = first_off(u, n - lone);
-    load_k(ka, d.K + o);
-    load_v(va, d.V + o);
-    load_q(u);
-  }
-
-  // The two roles run their own copy of the unit loop (same trip count, four barriers per iteration
-  // each): what one role keeps in registers across iterations must not count against the other.
-  auto rotate = [&](int u2, int n2, int B2, int lone2) {
-    up = u;
-    np_ = n;
-    Bp = B;
-    u = u1;
-    n = n1;
-    B = B1;
-    lone = lone1;
-    u1 = u2;
-    n1 = n2;
-    B1 = B2;
-    lone1 = lone2;
-    slot2 = __builtin_amdgcn_readfirstlane(s_claim);
-    par ^= 1;
-    ++iter;
-  };
-  if (streamer) {
-    int claimed_prev = -1;                                     // thread 0: the claim made one unit ago (-1: none)
-    while (u >= 0 || up >= 0) {
-      int u2, n2, B2, lone2;
-      fetch(slot2, u2, n2, B2, lone2);
-      float* lg = reinterpret_cast<float*>(smem + (size_t)par * lds_tile);
-      f32x4 acc[8];
-      uint16_t vnew = 0;
-      int claimed = -1;
-      const bool merge = u >= 0;
-      if (merge) {
-        // ---- stream unit u (as in unit_kernel)
-        const int ns = n - lone;                               // entries that are streamed
-        const int nblk = (ns + kBlk - 1) / kBlk;
-        const int res_blk = resident_entries(n, G, lds_tile) / kBlk;
-        const int my_cnt = wave < nblk ? (nblk - wave + W - 1) / W : 0;
-        asm volatile("" : "+v"(slane));
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        float m_run = -INFINITY, l_run = 0.f;
-        const uint16_t* kcur = d.K + (size_t)u * unit_elems + slane * 8;
-        const uint16_t* vcur = d.V + (size_t)u * unit_elems + slane * 8;
-        float* lg_glob = d.logits + (size_t)u * d.cap * G + 4 * min(slane, 8 * G - 1);
-        auto qk = [&](int blk, float (&sv)[8]) {
-          const bool resident = blk < res_blk;
-          float* lds_dst = resident ? lg + (size_t)blk * (G * kBlk) : s_buf + wave * (kMaxGroup * kLgRow);
-          scan_qk(ka, qv, sv, d.scale_log2e, 0, ns - blk * kBlk, lds_dst, resident ? kBlk : kLgRow,
-                  resident ? nullptr : lg_glob + (size_t)blk * (G * kBlk), G, slane);
-        };
-        for (int i = 0; i + 1 < my_cnt; ++i) {
-          const int blk = wave + W * i;
-          float sv[8];
-          qk(blk, sv);
-          load_k(ka, kcur + (size_t)(blk + W) * kBlkElems);
-          scan_pv<true>(sv, va, acc, m_run, l_run, slane);
-          load_v(va, vcur + (size_t)(blk + W) * kBlkElems);
-        }
-        // the new entry's logit (threads below G) and value element, requested a block before they are used
-        const float snew = d.snew[(size_t)u * kMaxGroup + (slane & (kMaxGroup - 1))];
-        vnew = v_new[(size_t)(u - d.unit0) * kDim + (slane & 63) + 64 * (wave & 1)];
-        if (my_cnt > 0) {
-          float sv[8];
-          qk(wave + W * (my_cnt - 1), sv);
-          scan_pv<true>(sv, va, acc, m_run, l_run, slane);
-        }
-        // the stream goes on with the next unit's first block (this unit's again if there is none)
-        const bool have_next = u1 >= 0;
-        const int u_next = have_next ? u1 : u;
-        const size_t o_next = first_off(u_next, have_next ? n1 - lone1 : ns);
-        load_k(ka, d.K + o_next);
-        load_v(va, d.V + o_next);
-        load_q(u_next);
-        if (tid == 0) claimed = atomicAdd(&d.sc[SC_QUEUE], 1);
-        // the low terms' rows (g + 8, 32 lanes up) join the high terms' rows g (scan_pv<true>)
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v) acc[dt][v] += __shfl_down(acc[dt][v], 32);
-        }
-        l_run += __shfl_xor(l_run, 16);
-        l_run += __shfl_xor(l_run, 32);
-        asm volatile("" : "+v"(slane));
-        const int j0 = slane & 15, kg0 = slane >> 4;
-        if (j0 < G && kg0 == 0) {
-          s_ml[wave][j0][0] = m_run;
-          s_ml[wave][j0][1] = l_run;
-        }
-        int t0 = tid;
-        asm volatile("" : "+v"(t0));
-        if (t0 < G) {
-          s_ml[W][t0][0] = lone ? snew : -INFINITY;
-          s_ml[W][t0][1] = lone ? 1.f : 0.f;
-          if (lone) {                                          // its logit where the book-keepers look for it
-            const int bn = (n - 1) / kBlk;
-            if (bn < res_blk)
-              lg[(size_t)bn * (G * kBlk) + t0 * kBlk] = snew;
-            else
-              d.logits[(size_t)u * d.cap * G + (size_t)bn * (G * kBlk) + t0 * kBlk] = snew;
-          }
-        }
-      }
-      __syncthreads();                                         // (1) s_ml of unit u complete
-
-      // ---- merge of the four online-softmax states -> out
-      int ftid = tid;
-      asm volatile("" : "+v"(ftid));
-      const int j = slane & 15, kg = slane >> 4;
-      float sc[4] = {0.f, 0.f, 0.f, 0.f};
-      float* slice = s_out + (wave & 1) * (kMaxGroup * kDim);
-      if (merge) {
-        if (ftid < G) {
-          float M = -INFINITY;
-          for (int w = 0; w < W + 1; ++w) M = fmaxf(M, s_ml[w][ftid][0]);
-          float L = 0.f;
-          for (int w = 0; w < W + 1; ++w) {
-            const float m = s_ml[w][ftid][0];
-            L += m > -INFINITY ? s_ml[w][ftid][1] * fast_exp2(m - M) : 0.f;
-          }
-          sM[par][ftid] = M;
-          sInv[par][ftid] = 1.0f / L;
-        }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int head = min(4 * kg + v, kMaxGroup - 1);
-          float M = -INFINITY;
-#pragma unroll
-          for (int w = 0; w < W + 1; ++w) M = fmaxf(M, s_ml[w][head][0]);
-          const float m = s_ml[wave][head][0];
-          sc[v] = m > -INFINITY ? fast_exp2(m - M) : 0.f;
-        }
-      }
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        if (merge && (wave >> 1) == half) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int head = 4 * kg + v;
-            if (head < G) {
-#pragma unroll
-              for (int dt = 0; dt < 8; ++dt) {
-                float* dst = &slice[head * kDim + 16 * dt + j];
-                const float x = acc[dt][v] * sc[v];
-                *dst = half == 0 ? x : *dst + x;
-              }
-            }
-          }
-        }
-        __syncthreads();                                       // (2), (3)
-      }
-      if (merge) {
-        for (int o = ftid; o < G * kDim; o += NT) {
-          const int g = o >> 7;
-          float y = s_out[o] + s_out[kMaxGroup * kDim + o];
-          if (lone) y += fast_exp2(s_ml[W][g][0] - sM[par][g]) * __uint_as_float((uint32_t)vnew << 16);
-          y *= sInv[par][g];
-          const size_t oi = (size_t)(u - d.unit0) * G * kDim + o;
-          if (d.out_bf16)
-            reinterpret_cast<__bf16*>(out)[oi] = (__bf16)y;
-          else
-            reinterpret_cast<float*>(out)[oi] = y;
-        }
-      }
-      // the claim made a unit ago has long arrived; this unit's is picked up a unit from now
-      if (tid == 0) s_claim = iter == 0 ? 3 * grid + wg : claimed_prev >= 0 ? 4 * grid + claimed_prev : n_units;
-      claimed_prev = claimed;
-      __syncthreads();                                         // (4) s_out and the staging tiles are free; s_claim is set
-      rotate(u2, n2, B2, lone2);
-    }
-  } else {
-    while (u >= 0 || up >= 0) {
-      int u2, n2, B2, lone2;
-      fetch(slot2, u2, n2, B2, lone2);
-      if (up >= 0) {
-        // ---- Alg. 1 Steps 1-4 of the previous unit, from the other tile (the code of unit_kernel's
-        // bookkeeping phase, 256 threads, with the book-keepers' own barrier)
-        float* lgp = reinterpret_cast<float*>(smem + (size_t)(par ^ 1) * lds_tile);
-        const float* hMp = sM[par ^ 1];
-        const float* hIp = sInv[par ^ 1];
-        const int n_res = resident_entries(np_, G, lds_tile);
-        const ValFused val{lgp, lgp + (size_t)n_res * G, n_res, G * kBlk};
-        const bool evict = (call_flags & 1u) != 0;
-        const float invG = 1.0f / (float)G;
-        const float* lgg = d.logits + (size_t)up * d.cap * G;
-        int phase = 0;
-        int ktid = tid - NT;
-        asm volatile("" : "+v"(ktid));
-        auto weights4 = [&](int e0, float* a4) {
-          f32x4 x[kMaxGroup];
-          const int off = (e0 >> 5) * (G * kBlk) + (e0 & 31);
-          const f32x4 ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-          if (e0 < n_res) {
-#pragma unroll
-            for (int g = 0; g < kMaxGroup; ++g) x[g] = g < G ? *reinterpret_cast<const f32x4*>(lgp + off + g * kBlk) : ninf;
-          } else {
-#pragma unroll
-            for (int g = 0; g < kMaxGroup; ++g)
-              x[g] = (g < G && e0 < np_) ? *reinterpret_cast<const f32x4*>(lgg + off + g * kBlk) : ninf;
-          }
-          const f32x4 hM[2] = {*reinterpret_cast<const f32x4*>(hMp), *reinterpret_cast<const f32x4*>(hMp + 4)};
-          const f32x4 hInv[2] = {*reinterpret_cast<const f32x4*>(hIp), *reinterpret_cast<const f32x4*>(hIp + 4)};
-          f32x4 w4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int g = 0; g < kMaxGroup; ++g) {
-            if (g < G) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) w4[e] += fast_exp2(x[g][e] - hM[g >> 2][g & 3]) * hInv[g >> 2][g & 3];
-            }
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) a4[e] = (e0 + e < np_) ? w4[e] * invG : 0.f;
-        };
-        auto regs_path = [&](auto rc) {
-          constexpr int R = decltype(rc)::value, C = R / 4, CH = C < 4 ? C : 4;
-          float a[R];
-#pragma unroll
-          for (int c = 0; c < C; ++c) {
-            weights4(4 * (ktid + c * NT), a + 4 * c);
-            __builtin_amdgcn_sched_barrier(0);
-          }
-          f32x4 crf[CH];
-          i32x4 tau[CH], ps[CH];
-          lrfu_regs<R, CH, 0, ValFused, NT, NoHook, 1>(d, up, np_, Bp, t, a, crf, tau, ps, val, evict, evm,
-                                                       reinterpret_cast<int*>(lgp), lds_tile / 4, s_tab, s_tab_n, rb, phase, sh, ktid);
-        };
-        if (np_ <= 8 * NT) {
-          regs_path(std::integral_constant<int, 8>{});
-        } else if (np_ <= 16 * NT) {
-          regs_path(std::integral_constant<int, 16>{});
-        } else if (np_ <= 32 * NT) {
-          regs_path(std::integral_constant<int, 32>{});
-        } else {
-          for (int e0 = 4 * ktid; e0 < np_; e0 += 4 * NT) {
-            float a4[4];
-            weights4(e0, a4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (e0 + e < np_) val(e0 + e) = a4[e];
-          }
-          block_sync<NT, 1>(rb);
-          const u64 sfix = lrfu_update<ValFused, NT, 1>(d, up, np_, t, val, s_tab, s_tab_n, rb, phase, ktid);
-          if (ktid == 0) {
-            d.window[up] += sfix;
-            d.t_unit[up] = t;
-          }
-          if (evict && np_ > Bp)
-            evict_phase<ValFused, NT, 1>(d, up, np_, Bp, val, evm, reinterpret_cast<int*>(lgp), lds_tile / 4, rb, phase, sh, ktid);
-          else if (ktid == 0)
-            d.nev[up] = 0;
-        }
-      }
-      __syncthreads();                                         // (1): the other tile is free again
-      __syncthreads();                                         // (2)
-      __syncthreads();                                         // (3)
-      __syncthreads();                                         // (4)
-      rotate(u2, n2, B2, lone2);
-    }
-  }
-  __syncthreads();
-  if (tid == 0 && rb.soft_fail) atomicOr(&d.sc[SC_STATUS], 2);    // a counter barrier gave up: results are invalid
   step_epilogue(d, t, advance, tid, 0);
 }
 

@@ -35,13 +35,14 @@ def test_workspace_bytes_validates_geometry_and_parameters():
     def ws(lay, par):
         return lib.ckv_workspace_bytes(C.byref(lay), C.byref(par))
 
-    lay = ckv.Layout(2, 2, 8, 2, 128, 256, ckv.F32)
+    lay = ckv.Layout(2, 2, 8, 2, 128, 256, ckv.F32, 0, 8 * 256)
     par = ckv.LrfuParams(0.5, 0.9, 0.0884, 0, 64, 1, 255)
     good = ws(lay, par)
     assert good > 0 and good % 256 == 0
     for field, bad in (("head_dim", 64), ("cap", 100), ("cap", 0), ("n_q_heads", 7), ("n_q_heads", 32),
-                       ("n_layers", 0), ("out_dtype", 9), ("cap", 65536)):
-        l2 = ckv.Layout(2, 2, 8, 2, 128, 256, ckv.F32)
+                       ("n_layers", 0), ("out_dtype", 9), ("cap", 65536), ("pool_slots", 7 * 256), ("pool_slots", 8 * 256 + 32),
+                       ("pool_slots", 0), ("headroom", -1), ("headroom", 256)):
+        l2 = ckv.Layout(2, 2, 8, 2, 128, 256, ckv.F32, 0, 8 * 256)
         setattr(l2, field, bad)
         assert ws(l2, par) == 0, (field, bad)
     for field, bad in (("lambda_", 1.5), ("lambda_", -0.1), ("top_p", 0.0), ("softmax_scale", 0.0),
@@ -49,13 +50,16 @@ def test_workspace_bytes_validates_geometry_and_parameters():
         p2 = ckv.LrfuParams(0.5, 0.9, 0.0884, 0, 64, 1, 255)
         setattr(p2, field, bad)
         assert ws(lay, p2) == 0, (field, bad)
+    # shared pools (headroom >= 1) may be smaller than units * cap: ckv_init checks them against the budgets
+    l3 = ckv.Layout(2, 2, 8, 2, 128, 256, ckv.F32, 1, 4 * 256)
+    assert ws(l3, par) > 0
     # a longer decay table (lambda closer to 1) needs a bigger workspace
     assert ws(lay, ckv.LrfuParams(0.99, 0.9, 0.0884, 0, 64, 1, 255)) > good
 
 
 def test_init_rejects_bad_arguments_without_touching_the_gpu():
     lib = ckv.load()
-    lay = ckv.Layout(1, 1, 8, 2, 128, 64, ckv.F32)
+    lay = ckv.Layout(1, 1, 8, 2, 128, 64, ckv.F32, 0, 2 * 256)
     par = ckv.LrfuParams(0.5, 0.9, 0.0884, 0, 0, 1, 63)
     ctx = C.c_void_p()
     budgets = np.full((1, 1, 2), 32, dtype=np.int32)

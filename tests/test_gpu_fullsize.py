@@ -22,9 +22,9 @@ N_STEPS = 8
 
 def _lds_resident_limit(cap, G):
     """Largest entry count whose logits all stay in the fused kernel's LDS tile (4 wavefronts per unit, two
-    workgroups per compute unit: 80 KB each less 11 KB of static arrays and the eviction bit mask).  The test
-    asserts below that the context reports the tile size assumed here."""
-    lds_main = (80 * 1024 - 11 * 1024 - (cap + 31) // 32 * 4) & ~127
+    workgroups per compute unit: 80 KB each less 11 KB of static arrays, the eviction bit mask and two rows of
+    the segment table).  The test asserts below that the context reports the tile size assumed here."""
+    lds_main = (80 * 1024 - 11 * 1024 - (cap + 31) // 32 * 4 - 2 * ((cap + 255) // 256) * 4) & ~127
     n = 32
     while (n + 32) * G * 4 <= lds_main:
         n += 32

@@ -42,7 +42,7 @@ def _small(name, **kw):
     return wl.scaled(wl.CONFIGS[name], **base)
 
 
-PATHS = [1, 3, 4, 5]  # separate kernels; fused kernel with 4 and with 2 wavefronts per unit; fused with a book-keeping wavefront
+PATHS = [1, 3, 4]  # separate kernels; fused kernel with 4 and with 2 wavefronts per unit
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -73,7 +73,7 @@ def test_units_longer_than_a_chunk_and_ragged_tails(path):
     g.close()
 
 
-@pytest.mark.parametrize("path", [3, 4, 5])
+@pytest.mark.parametrize("path", [3, 4])
 def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     """A unit of ~3000 entries with 8 query heads per KV head needs 96 KB of logits: more than the fused
     kernel's LDS tile, so the logits of its last blocks take the global-memory route; a second, small
@@ -90,7 +90,7 @@ def test_fused_kernel_with_logits_spilling_out_of_lds(path):
     g.close()
 
 
-@pytest.mark.parametrize("path", [3, 4, 5])
+@pytest.mark.parametrize("path", [3, 4])
 @pytest.mark.parametrize("hq", [2, 10, 16])
 def test_new_entry_alone_in_its_block(path, hq):
     """Budgets that are multiples of 32: in the steady state every unit holds B + 1 entries while it attends, the
@@ -122,7 +122,7 @@ def test_new_entry_alone_in_a_block_whose_logits_live_in_global_memory(path):
     g.close()
 
 
-@pytest.mark.parametrize("path,n_big", [(3, 4500), (3, 8300), (4, 2500), (4, 4400), (5, 1900), (5, 8300)])
+@pytest.mark.parametrize("path,n_big", [(3, 4500), (3, 8300), (4, 2500), (4, 4400)])
 def test_fused_kernel_large_units(path, n_big):
     """Units beyond 16 entries per thread: 17..32 per thread keep the weights in registers with the per-entry
     state loaded in chunks, more than 32 per thread go through the LDS-resident generic path.  (Path 3 has 256
@@ -201,10 +201,10 @@ def test_path_selection_api():
     cfg = _small("tiny", n_q_heads=8, n_kv_heads=2, seed=2)
     st, o, g = _pair(cfg, cap=96)
     assert g.path_info()[0] == 0                       # 4 units: separate kernels by default
-    for mode, waves in ((1, 0), (2, 4), (3, 4), (4, 2), (5, 4)):
+    for mode, waves in ((1, 0), (2, 4), (3, 4), (4, 2)):
         g.set_path(mode)
         assert g.path_info()[0] == waves
-    for bad in (-1, 6):
+    for bad in (-1, 5):
         with pytest.raises(ckv.CkvError) as e:
             g.set_path(bad)
         assert e.value.code == ckv.EINVAL
@@ -333,7 +333,7 @@ def test_per_layer_calls():
     g.close()
 
 
-@pytest.mark.parametrize("path", [0, 5])
+@pytest.mark.parametrize("path", [0, 3])
 def test_per_layer_calls_of_layers_with_a_unit_per_workgroup_take_the_fused_kernel(path):
     """A layer of 512 units (batch 64 x 8 KV heads) fills the fused kernel's grid, so single-layer steps run
     it on the layer's part of the schedule, with inputs and output addressed relative to the layer; all-layers
@@ -763,7 +763,7 @@ def test_hip_graph_replay_matches_eager(path):
     g.close(); g2.close()
 
 
-@pytest.mark.parametrize("path", [3, 5])
+@pytest.mark.parametrize("path", [3, 4])
 def test_probe_classes_on_multi_chunk_units_of_a_fused_path_context(path):
     """Sec. 3 classes on units of 300..700 entries (several 256-entry chunks, ragged last blocks, 7 query
     heads per KV head) in a context whose decode steps run the fused kernel: the probe shares the context's

@@ -84,7 +84,7 @@ def test_sweep_cells_equal_the_oracles_retention():
         print(f"sweep cell {name or (lam, p)}: heavy recall {hr_g:.3f}, Crystal recall {cr_g:.3f} (oracle {cr_o:.3f})", flush=True)
 
 
-@pytest.mark.parametrize("path", [1, 3, 4, 5])
+@pytest.mark.parametrize("path", [1, 3, 4])
 def test_accumulated_attention_policy_lockstep(path):
     """Sec. 2.3's accumulation of attention weights (the scoring of heavy-hitter schemes) = the
     attention-weighted reward with lambda = 1: every entry's score is the plain sum of its mean weights since
