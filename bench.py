@@ -35,7 +35,7 @@ RING = 32                     # distinct synthetic step inputs held at a time (a
                               # unrealistic) tie-breaking paths
 
 
-def build_workload(cfg, device, budgets=None):
+def build_workload(cfg, device, budgets=None, headroom=1, pool_factor=1.0, pools=None):
     """Steady-state caches of the workload on the device (every unit full at its budget), plus the ring of
     step inputs.  budgets: override of the workload's own draw (tests place units at chosen sizes)."""
     import numpy as np
@@ -46,9 +46,16 @@ def build_workload(cfg, device, budgets=None):
         budgets = wl.draw_budgets(cfg)
     cap = (cfg.budget_max + 1 + 31) // 32 * 32
     t_now = cfg.prompt + cfg.decode_steps // 2
+    pool_slots = None
+    if pool_factor != 1.0:
+        import ctypes as C
+        lay = ckv.Layout(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, ckv.F32, headroom, 0)
+        b32 = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32))
+        pool_slots = int(ckv.load().ckv_pool_slots(C.byref(lay), b32.ctypes.data_as(C.c_void_p), 0) * pool_factor) // 256 * 256
+    kwargs = dict(lam=cfg.lam, top_p=cfg.top_p, t0=t_now, budget_min=cfg.budget_min, budget_max=cfg.budget_max,
+                  headroom=headroom, pool_slots=pool_slots)     # headroom 1: shared pools, memory follows the budgets
     g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
-                      lam=cfg.lam, top_p=cfg.top_p, t0=t_now, budget_min=cfg.budget_min,
-                      budget_max=cfg.budget_max, device=device)
+                      device=device, pools=pools, **kwargs)
     m = wl.torch_mean_query(cfg, device)
     gen = wl.torch_generator(cfg, 9, device)
     r_now = math.sqrt(wl.DRIFT_VAR) * torch.randn(m.shape, generator=gen, device=device)
@@ -275,6 +282,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-layer", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    ap.add_argument("--headroom", type=int, default=1,
+                    help="1 (default): shared pools, a unit owns the 256-slot segments its budget + 1 entries need; "
+                         "0: every unit owns room for the largest budget")
+    ap.add_argument("--pool-factor", type=float, default=1.0, help="pools this many times what ckv_pool_slots asks for (measurement aid)")
     ap.add_argument("--path", type=int, default=0,
                     help="kernels of the all-layers step: 0 default, 1 separate scan/finish, 3 / 4 fused with 4 / 2 wavefronts per unit")
     ap.add_argument("--fullkv", type=int, default=0, metavar="TOKENS",
@@ -318,7 +329,7 @@ def main():
     if fullkv:
         g, budgets, (rq, rk, rv) = build_fullkv(cfg, device, args.fullkv, warm + (repeats + 2) * steps + 4 * RING)
     else:
-        g, budgets, (rq, rk, rv) = build_workload(cfg, device)
+        g, budgets, (rq, rk, rv) = build_workload(cfg, device, headroom=args.headroom, pool_factor=args.pool_factor)
     if args.path:
         g.set_path(args.path)
     out = torch.empty(rq.shape[1:], dtype=torch.float32, device=device)
@@ -470,7 +481,11 @@ def main():
                     f"every cache holds all {args.fullkv} positions and grows by one per step"),
                    "units": int(cfg.n_units), "entries_per_step": entries,
                    "launch": ("all layers per call, eager" if args.no_graph else
-                              f"all layers per call, HIP graphs of up to {RING} steps, fresh inputs every {RING} steps, median of {repeats} timed regions of {steps} steps")},
+                              f"all layers per call, HIP graphs of up to {RING} steps, fresh inputs every {RING} steps, median of {repeats} timed regions of {steps} steps"),
+                   "memory": (None if fullkv else
+                              {"pool_slots": int(g.pool_slots), "kv_pool_bytes": int(2 * g.pool_slots * 256),
+                               "budgeted_entry_bytes": int((np.asarray(budgets, dtype=np.int64) + 1).sum() * 512),
+                               "headroom": int(g.headroom)})},
         "rebudget": rebudget,
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

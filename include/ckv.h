@@ -223,6 +223,26 @@ int ckv_evict_window(ckv_ctx* ctx, int32_t layer, int32_t n_sink, void* stream);
  * eviction brings units down to shrunken budgets. */
 int ckv_rebudget(ckv_ctx* ctx, void* stream);
 
+/* Shared pools (headroom >= 1) only; a no-op otherwise.  Deals the pool segments out again: every unit ends up
+ * owning what max(budget + headroom, its entries) needs, surplus goes to the spare list first, deficits are
+ * served from it in unit order (deterministic).  The library calls this by itself: inside ckv_load_prompt and
+ * ckv_load_cache (the layer's units get room for the P entries and an append), and at the start of the first
+ * decode step (layer 0 or all layers) after an eviction that covered the last layer (a decode step with
+ * CKV_FUSE_EVICT, ckv_evict, ckv_evict_window) once budgets have changed (ckv_rebudget, ckv_set_budgets) or a
+ * prompt has passed through - not right behind that eviction, so that the record of what a unit evicted (the
+ * slots behind its entries) can still be exported.  Between a budget change and that point a grown unit still
+ * fits: it has room for headroom entries above its old budget.  If the spare list is short nobody is given anything and
+ * ckv_status() reports CKV_ECAPACITY; a unit that owns too little refuses appends the same way.
+ * Asynchronous on `stream`; one 1024-thread workgroup. */
+int ckv_rebalance(ckv_ctx* ctx, void* stream);
+
+/* Slots each pool needs (a multiple of 256; 0 on bad arguments).  headroom 0: units * ceil(cap / 256) * 256.
+ * Shared pools: what the budgets' total plus headroom per unit needs, one segment per unit on top (the most
+ * that rounding to segments can waste, however Alg. 2 redistributes the budgets), plus, if prompt_len > 0,
+ * one layer's units at prompt_len + headroom entries (a prompt on its way through ckv_load_prompt,
+ * ckv_seed_prompt and ckv_evict while the other layers sit at their budgets).  Host budgets as in ckv_init. */
+int64_t ckv_pool_slots(const ckv_layout* layout, const int32_t* budgets, int32_t prompt_len);
+
 /* Sec. 3 answer-probe classes for one layer: attention of `q_probe` (dev bf16
  * [batch][n_q_heads][128]) over the current caches, no state change; per slot
  * class (CKV_CLASS_*) written to classes (dev uint8, [batch][n_kv_heads][cap]):
@@ -247,6 +267,10 @@ int ckv_probe_noalloc(ckv_ctx* ctx, int32_t layer, const void* q_probe, uint8_t*
 int ckv_get_budgets(ckv_ctx* ctx, int32_t* budgets);
 int ckv_get_lengths(ckv_ctx* ctx, int32_t* lengths);
 int ckv_set_budgets(ckv_ctx* ctx, const int32_t* budgets);   /* same checks as ckv_init; B_total recomputed */
+/* The segment table: owned[units] = segments each unit owns, rows[units][ceil(cap / 256)] = their pool indices
+ * in order (0 in the columns behind them), spare[pool_slots / 256] = the first *n_spare entries are the pool
+ * segments nobody owns.  owned, rows and spare may be NULL. */
+int ckv_get_segments(ckv_ctx* ctx, int32_t* owned, int32_t* rows, int32_t* spare, int32_t* n_spare);
 int ckv_get_time(ckv_ctx* ctx, int32_t* t);
 int ckv_set_time(ckv_ctx* ctx, int32_t t);                   /* also restarts the Alg. 2 window */
 /* CKV_OK, or CKV_ECAPACITY if some append since the last call found its unit full. */

@@ -26,7 +26,7 @@ EXPORTS = [
     "ckv_workspace_bytes", "ckv_init", "ckv_destroy", "ckv_load_prompt", "ckv_seed_prompt", "ckv_load_cache", "ckv_decode_step",
     "ckv_evict",
     "ckv_evict_window",
-    "ckv_rebudget", "ckv_probe", "ckv_probe_noalloc", "ckv_get_budgets", "ckv_get_lengths", "ckv_set_budgets", "ckv_get_time",
+    "ckv_rebudget", "ckv_rebalance", "ckv_pool_slots", "ckv_probe", "ckv_probe_noalloc", "ckv_get_budgets", "ckv_get_lengths", "ckv_get_segments", "ckv_set_budgets", "ckv_get_time",
     "ckv_set_time", "ckv_status", "ckv_export_unit", "ckv_import_unit", "ckv_profile_enable",
     "ckv_profile_read", "ckv_set_path", "ckv_path_info", "ckv_join", "ckv_bandwidth_probe", "ckv_strerror", "ckv_last_error",
 ]
@@ -75,10 +75,14 @@ def load():
     lib.ckv_evict.argtypes = [vp, i32, vp]
     lib.ckv_evict_window.argtypes = [vp, i32, i32, vp]
     lib.ckv_rebudget.argtypes = [vp, vp]
+    lib.ckv_rebalance.argtypes = [vp, vp]
+    lib.ckv_pool_slots.restype = C.c_int64
+    lib.ckv_pool_slots.argtypes = [C.POINTER(Layout), vp, i32]
     lib.ckv_probe.argtypes = [vp, i32, vp, vp, vp]
     lib.ckv_probe_noalloc.argtypes = [vp, i32, vp, vp, vp]
     lib.ckv_get_budgets.argtypes = [vp, vp]
     lib.ckv_get_lengths.argtypes = [vp, vp]
+    lib.ckv_get_segments.argtypes = [vp, vp, vp, vp, C.POINTER(i32)]
     lib.ckv_set_budgets.argtypes = [vp, vp]
     lib.ckv_get_time.argtypes = [vp, C.POINTER(i32)]
     lib.ckv_set_time.argtypes = [vp, i32]
@@ -113,6 +117,32 @@ def _np_ptr(a):
     return a.ctypes.data_as(C.c_void_p)
 
 
+def _buffer_sizes(pool_slots, head_dim, ws):
+    """Bytes of the seven caller-owned device buffers: K pool, V pool, crf, tau, pos, flags, workspace."""
+    S = int(pool_slots)
+    return [S * head_dim * 2, S * head_dim * 2, S * 4, S * 4, S * 4, S, int(ws) + 256]
+
+
+def arena_bytes(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, budgets, *, lam=0.5, top_p=0.9, softmax_scale=None,
+                reward_mode=REWARD_TOPP_HIT, t0=0, budget_min=1, budget_max=None, out_dtype=F32, headroom=0, pool_slots=None,
+                prompt_len=0, **_):
+    """Bytes an `arena=` for a CrystalKV of these arguments must hold (each buffer rounded up to 2 MiB, one
+    2 MiB for the arena's own alignment)."""
+    lib = load()
+    b32 = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(n_layers, batch, n_kv_heads))
+    if pool_slots is None:
+        probe = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype, headroom, 0)
+        pool_slots = lib.ckv_pool_slots(C.byref(probe), _np_ptr(b32), int(prompt_len))
+    lay = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype, headroom, int(pool_slots))
+    par = LrfuParams(lam, top_p, softmax_scale if softmax_scale is not None else 1.0 / float(np.sqrt(head_dim)), reward_mode, t0,
+                     budget_min, budget_max if budget_max is not None else cap - 1)
+    ws = lib.ckv_workspace_bytes(C.byref(lay), C.byref(par))
+    if pool_slots <= 0 or ws == 0:
+        raise CkvError(EINVAL, "layout or parameters rejected")
+    al = 2 << 20
+    return sum((b_ + al - 1) // al * al for b_ in _buffer_sizes(pool_slots, head_dim, ws)) + al
+
+
 class CrystalKV:
     """One ckv context plus the torch tensors that back it.
 
@@ -121,10 +151,13 @@ class CrystalKV:
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, budgets, *, lam=0.5, top_p=0.9,
                  softmax_scale=None, reward_mode=REWARD_TOPP_HIT, t0=0, budget_min=1, budget_max=None,
-                 out_dtype=F32, device="cuda:0", headroom=0, pool_slots=None):
+                 out_dtype=F32, device="cuda:0", headroom=0, pool_slots=None, prompt_len=0, pools=None, arena=None):
         """headroom = 0: every unit owns room for `cap` entries (pools of units * ceil(cap / 256) * 256 slots).
         headroom >= 1: shared pools, a unit owns what budget + headroom entries need; pool_slots (a multiple of
-        256) then sizes the pools, by default what the budgets need plus a tenth."""
+        256) then sizes the pools, by default what ckv_pool_slots says for these budgets and a prompt of
+        prompt_len tokens passing through one layer at a time.
+        arena: a uint8 device tensor that all seven device buffers are carved from (at 2 MiB boundaries; see
+        arena_bytes) instead of seven allocations; pools: caller-owned K and V pools alone."""
         import torch
         self.torch = torch
         self.lib = load()
@@ -133,14 +166,12 @@ class CrystalKV:
             softmax_scale = 1.0 / float(np.sqrt(head_dim))
         if budget_max is None:
             budget_max = cap - 1
-        SEG = 256
-        b_all = np.asarray(budgets, dtype=np.int64).reshape(-1)
+        b32 = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(n_layers, batch, n_kv_heads))
         if pool_slots is None:
-            if headroom == 0:
-                pool_slots = n_layers * batch * n_kv_heads * ((cap + SEG - 1) // SEG) * SEG
-            else:
-                need = int(np.minimum((b_all + headroom + SEG - 1) // SEG, (cap + SEG - 1) // SEG).sum())
-                pool_slots = (need + need // 10 + 1) * SEG
+            probe = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype, headroom, 0)
+            pool_slots = self.lib.ckv_pool_slots(C.byref(probe), _np_ptr(b32), int(prompt_len))
+            if pool_slots <= 0:
+                raise CkvError(EINVAL, "layout rejected")
         self.headroom, self.pool_slots = headroom, int(pool_slots)
         self.layout = Layout(n_layers, batch, n_q_heads, n_kv_heads, head_dim, cap, out_dtype, headroom, int(pool_slots))
         self.params = LrfuParams(lam, top_p, softmax_scale, reward_mode, t0, budget_min, budget_max)
@@ -153,13 +184,34 @@ class CrystalKV:
             raise CkvError(EINVAL, "layout or parameters rejected")
         S = self.pool_slots
         dev = self.device
-        self.k_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
-        self.v_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
-        self.crf = torch.empty(S, dtype=torch.float32, device=dev)
-        self.tau = torch.empty(S, dtype=torch.int32, device=dev)
-        self.pos = torch.empty(S, dtype=torch.int32, device=dev)
-        self.flags = torch.empty(S, dtype=torch.uint8, device=dev)
-        self.workspace = torch.empty(ws + 256, dtype=torch.uint8, device=dev)
+        if arena is not None:
+            sizes = _buffer_sizes(S, head_dim, ws)
+            al = 2 << 20
+            offs, total = [], (-arena.data_ptr()) % al
+            for b_ in sizes:
+                offs.append(total)
+                total += (b_ + al - 1) // al * al
+            if arena.dtype != torch.uint8 or not arena.is_contiguous() or arena.numel() < total:
+                raise CkvError(EINVAL, f"arena must be a contiguous uint8 tensor of at least {total} bytes")
+            part = lambda i, dt: arena[offs[i]:offs[i] + sizes[i]].view(dt)
+            self.arena = arena
+            self.k_pool, self.v_pool = part(0, torch.bfloat16), part(1, torch.bfloat16)
+            self.crf, self.tau, self.pos = part(2, torch.float32), part(3, torch.int32), part(4, torch.int32)
+            self.flags, self.workspace = part(5, torch.uint8), part(6, torch.uint8)
+        elif pools is not None:                   # caller-owned K and V pools (bf16 tensors of S * head_dim elements each)
+            self.k_pool, self.v_pool = pools
+            for p_ in pools:
+                if p_.dtype != torch.bfloat16 or p_.numel() < S * head_dim or not p_.is_contiguous() or p_.data_ptr() % 256:
+                    raise CkvError(EINVAL, "pools must be contiguous, 256-byte aligned bf16 tensors of pool_slots * head_dim elements")
+        else:
+            self.k_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
+            self.v_pool = torch.empty(S * head_dim, dtype=torch.bfloat16, device=dev)
+        if arena is None:
+            self.crf = torch.empty(S, dtype=torch.float32, device=dev)
+            self.tau = torch.empty(S, dtype=torch.int32, device=dev)
+            self.pos = torch.empty(S, dtype=torch.int32, device=dev)
+            self.flags = torch.empty(S, dtype=torch.uint8, device=dev)
+            self.workspace = torch.empty(ws + 256, dtype=torch.uint8, device=dev)
         wptr = (self.workspace.data_ptr() + 255) // 256 * 256
         self.buffers = Buffers(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.crf.data_ptr(),
                                self.tau.data_ptr(), self.pos.data_ptr(), self.flags.data_ptr(), wptr, ws)
@@ -263,6 +315,9 @@ class CrystalKV:
     def rebudget(self):
         self._check(self.lib.ckv_rebudget(self.ctx, self._stream()))
 
+    def rebalance(self):
+        self._check(self.lib.ckv_rebalance(self.ctx, self._stream()))
+
     def probe(self, layer, q_probe):
         """Classes [Bz][Hkv][cap] (uint8 device tensor) of the layer's entries under q_probe [Bz][Hq][d]."""
         t = self.torch
@@ -284,6 +339,16 @@ class CrystalKV:
         b = np.zeros((self.L, self.Bz, self.Hkv), dtype=np.int32)
         self._check(self.lib.ckv_get_budgets(self.ctx, _np_ptr(b)))
         return b
+
+    def segment_table(self):
+        """Which pool segments (256 slots each) every unit owns, and the spare list."""
+        max_seg = (self.cap + 255) // 256
+        owned = np.zeros(self.units, dtype=np.int32)
+        rows = np.zeros((self.units, max_seg), dtype=np.int32)
+        spare = np.zeros(self.pool_slots // 256, dtype=np.int32)
+        n_spare = C.c_int32(0)
+        self._check(self.lib.ckv_get_segments(self.ctx, _np_ptr(owned), _np_ptr(rows), _np_ptr(spare), C.byref(n_spare)))
+        return dict(owned=owned, rows=rows, spare=spare[:n_spare.value].copy())
 
     def set_budgets(self, budgets):
         b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(self.L, self.Bz, self.Hkv))

@@ -68,6 +68,9 @@ struct ckv_ctx {
   std::vector<hipEvent_t> ev_book;
   std::vector<uint8_t> pending;
   bool any_pending = false;
+  // Shared pools: budgets (or a prompt) have changed what units should own (dirty); once an eviction over all
+  // layers has been issued since, the segments are dealt out again when the next step begins (due).
+  bool dirty = false, due = false;
   int group_first = 0, group_count = 0, group_launches = 0;
   uint32_t group_flags = 0;
   hipStream_t group_stream = nullptr;
@@ -256,6 +259,32 @@ int join_side(ckv_ctx* c, hipStream_t s, int layer = -1) {
   }
   c->any_pending = left;
   return CKV_OK;
+}
+
+// Deal the pool segments out again (shared pools only); units [x_begin, x_begin + x_count) get room for
+// x_entries entries whatever their budgets say.
+int launch_rebalance(ckv_ctx* c, hipStream_t s, int x_begin = 0, int x_count = 0, int x_entries = 0, const int32_t* x_len = nullptr) {
+  if (c->lay.headroom == 0) return CKV_OK;
+  hipLaunchKernelGGL(rebalance_kernel, dim3(1), dim3(kBalanceThreads), 0, s, c->dev, (int)c->lay.headroom, x_begin, x_count, x_entries, x_len);
+  CKV_HIP(c, hipGetLastError());
+  return CKV_OK;
+}
+
+// After an eviction that covered the last layer: the segments the shrunken units gave up can go to the others.
+// Not yet, though: the slots behind a unit's entries hold the record of what it has just evicted, which a
+// caller may still want to read, and with deferred bookkeeping the evictions have not even run.  The segments
+// move when the next step begins.
+int rebalance_after_eviction(ckv_ctx* c) {
+  if (c->lay.headroom > 0 && c->dirty) c->due = true;
+  return CKV_OK;
+}
+
+// Before a step begins: what a deferred eviction left to do.
+int rebalance_if_due(ckv_ctx* c, hipStream_t s) {
+  if (!c->due) return CKV_OK;
+  if (int rc = join_side(c, s)) return rc;
+  c->dirty = c->due = false;
+  return launch_rebalance(c, s);
 }
 
 // (Re)build the fused kernel's schedule (units by descending budget) from the budgets in device memory.
@@ -536,6 +565,13 @@ int ckv_load_cache(ckv_ctx* c, int32_t layer, const void* k, const void* v, int3
   c->prompt_loaded[layer] = 1;
   c->prompt_len[layer] = (!lengths && !pos0) ? P : -1;
   if (int rc = join_side(c, (hipStream_t)stream)) return rc;
+  if (c->lay.headroom > 0) {
+    // shared pools: the layer's units get room for what is loaded (and an append behind it) from the spare list,
+    // and whatever earlier layers no longer need goes back to it first; an eviction gives the surplus back
+    c->due = false;
+    c->dirty = true;
+    if (int rc = launch_rebalance(c, (hipStream_t)stream, layer * c->units_per_layer, c->units_per_layer, (int)P + c->lay.headroom, lengths)) return rc;
+  }
   dim3 grid((unsigned)((P + kBlk - 1) / kBlk), (unsigned)c->units_per_layer);
   hipLaunchKernelGGL(load_cache_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, c->dev,
                      layer * c->units_per_layer, (const uint16_t*)k, (const uint16_t*)v, (int)P, lengths, crf0, tau0,
@@ -580,6 +616,8 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   const ckv_ctx::Fused* fv = (flags & CKV_DEFER_BOOKKEEPING) ? nullptr : fused_variant(c);
   if (fv && (c->path_mode == 0 || layer >= 0) && count < fv->grid) fv = nullptr;   // fewer units than workgroups: split the units instead
   const bool fused = fv != nullptr;
+  if (layer <= 0)
+    if (int rc = rebalance_if_due(c, s)) return rc;
   if (int rc = join_side(c, s, layer)) return rc;
   if (flags & CKV_DEFER_BOOKKEEPING) {
     // One kernel on the caller's stream: it appends, attends and writes the output; the bookkeeping (which also
@@ -606,6 +644,8 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
       c->group_stream = s;
     }
     c->group_count += 1;
+    if (advance && (flags & CKV_FUSE_EVICT))
+      if (int rc = rebalance_after_eviction(c)) return rc;
     if (c->group_count == kBookGroup || advance) return flush_group(c);
     return CKV_OK;
   }
@@ -640,6 +680,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
       hipLaunchKernelGGL(unit_kernel<2>, dim3((unsigned)fv->grid), dim3(128), fv->lds, s, dv, qb, ob, flags, advance, fv->lds_main, vb, kb);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
+    if (advance && (flags & CKV_FUSE_EVICT)) return rebalance_after_eviction(c);
     return CKV_OK;
   }
   const long long max_items = (long long)count * c->dev.max_chunks;
@@ -661,6 +702,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
   hipLaunchKernelGGL(finish_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, s, c->dev, begin, out,
                      kflags, advance, INT_MAX, -1, 0, 0);
   CKV_HIP(c, hipGetLastError());
+  if (advance && kflags) return rebalance_after_eviction(c);
   return CKV_OK;
 }
 
@@ -704,6 +746,7 @@ int ckv_evict(ckv_ctx* c, int32_t layer, void* stream) {
   if (int rc = join_side(c, (hipStream_t)stream)) return rc;
   hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin, -1);
   CKV_HIP(c, hipGetLastError());
+  if (layer == -1 || layer == c->lay.n_layers - 1) return rebalance_after_eviction(c);
   return CKV_OK;
 }
 
@@ -717,6 +760,7 @@ int ckv_evict_window(ckv_ctx* c, int32_t layer, int32_t n_sink, void* stream) {
   hipLaunchKernelGGL(evict_kernel, dim3((unsigned)count), dim3(kThreads), c->finish_lds, (hipStream_t)stream, c->dev, begin,
                      (int)n_sink);
   CKV_HIP(c, hipGetLastError());
+  if (layer == -1 || layer == c->lay.n_layers - 1) return rebalance_after_eviction(c);
   return CKV_OK;
 }
 
@@ -726,7 +770,28 @@ int ckv_rebudget(ckv_ctx* c, void* stream) {
   if (int rc = join_side(c, (hipStream_t)stream)) return rc;
   hipLaunchKernelGGL(rebudget_kernel, dim3((unsigned)c->lay.batch), dim3(kThreads), 0, (hipStream_t)stream, c->dev);
   CKV_HIP(c, hipGetLastError());
+  c->dirty = true;             // shared pools: the segments follow once the shrunken units have evicted
   return launch_schedule(c, (hipStream_t)stream);
+}
+
+int ckv_rebalance(ckv_ctx* c, void* stream) {
+  if (!c) return CKV_EINVAL;
+  if (c->next_layer != 0) return fail(c, CKV_ESTATE, "a per-layer step is in progress");
+  if (int rc = join_side(c, (hipStream_t)stream)) return rc;
+  c->due = false;
+  return launch_rebalance(c, (hipStream_t)stream);
+}
+
+int64_t ckv_pool_slots(const ckv_layout* l, const int32_t* budgets, int32_t prompt_len) {
+  if (!l || !budgets || l->n_layers < 1 || l->batch < 1 || l->n_kv_heads < 1 || l->cap < kBlk || prompt_len < 0) return 0;
+  const long long units = (long long)l->n_layers * l->batch * l->n_kv_heads, mseg = (l->cap + kSeg - 1) / kSeg;
+  if (l->headroom <= 0) return units * mseg * kSeg;
+  long long total = 0;
+  for (long long u = 0; u < units; ++u) total += (long long)budgets[u] + l->headroom;
+  // whatever Alg. 2 makes of the budgets, rounding to segments wastes less than one segment per unit
+  long long segs = (total + kSeg - 1) / kSeg + units;
+  if (prompt_len > 0) segs += (long long)l->batch * l->n_kv_heads * std::min<long long>(mseg, ((long long)prompt_len + l->headroom + kSeg - 1) / kSeg);
+  return std::min(segs, units * mseg) * kSeg;
 }
 
 int ckv_probe(ckv_ctx* c, int32_t layer, const void* q_probe, uint8_t* classes, void* stream) {
@@ -825,11 +890,24 @@ int ckv_get_lengths(ckv_ctx* c, int32_t* lengths) {
   return CKV_OK;
 }
 
+int ckv_get_segments(ckv_ctx* c, int32_t* owned, int32_t* rows, int32_t* spare, int32_t* n_spare) {
+  if (!c || !n_spare) return CKV_EINVAL;
+  if (int rc = flush_group(c)) return rc;
+  CKV_HIP(c, hipDeviceSynchronize());
+  CKV_HIP(c, hipMemcpy(n_spare, c->dev.sc + SC_SPARE, 4, hipMemcpyDeviceToHost));
+  if (*n_spare < 0 || *n_spare > c->lay.pool_slots / kSeg) return fail(c, CKV_ESTATE, "corrupt spare list");
+  if (owned) CKV_HIP(c, hipMemcpy(owned, c->dev.owned, (size_t)c->units * 4, hipMemcpyDeviceToHost));
+  if (rows) CKV_HIP(c, hipMemcpy(rows, c->dev.tbl, (size_t)c->units * c->dev.max_seg * 4, hipMemcpyDeviceToHost));
+  if (spare && *n_spare > 0) CKV_HIP(c, hipMemcpy(spare, c->dev.spare, (size_t)*n_spare * 4, hipMemcpyDeviceToHost));
+  return CKV_OK;
+}
+
 int ckv_set_budgets(ckv_ctx* c, const int32_t* budgets) {
   if (!c) return CKV_EINVAL;
   if (int rc = check_budgets(c, &c->lay, &c->par, budgets)) return rc;
   if (int rc = flush_group(c)) return rc;
   CKV_HIP(c, hipDeviceSynchronize());
+  c->dirty = true;
   return upload_budgets(c, budgets, nullptr);
 }
 
@@ -861,6 +939,7 @@ int ckv_status(ckv_ctx* c) {
   if (st) {
     CKV_HIP(c, hipMemcpy(c->dev.sc + SC_STATUS, &zero, 4, hipMemcpyHostToDevice));
     if (st & 2) return fail(c, CKV_EHIP, "a wait between wavefronts of the fused kernel did not end: the last steps' results are invalid");
+    if (st & 4) return fail(c, CKV_ECAPACITY, "the spare list ran short when the pool segments were dealt out: some units own less than budget + headroom needs");
     return fail(c, CKV_ECAPACITY, "an append found its unit full");
   }
   return CKV_OK;

@@ -325,6 +325,85 @@ __global__ __launch_bounds__(kThreads) void probe_copy_kernel(const u32x4* __res
   for (; i < n_vec; i += stride) dst[i] = src[i];
 }
 
+// ------------------------------------------------------------------ pool segments between units
+// Shared pools (headroom >= 1): a unit should own the segments that budget + headroom entries need, never
+// fewer than its entries occupy, and for the units [x_begin, x_begin + x_count) at least what x_entries
+// entries need (a prompt on its way in; x_len, if given, holds the units' own lengths, headroom not included).  One workgroup walks all units twice: units that own more than
+// they should push the surplus (their last segments) onto the spare stack, then units that own less pop what
+// they lack.  Who gets which segment follows from prefix sums over the units in index order, so the result
+// does not depend on timing.  If the spare list is short nobody is given anything and bit 2 of the status
+// word is set; a unit that still holds more entries than its budget (its eviction has not run yet) keeps
+// its segments until a later call.  Unowned columns of a table row hold 0.
+constexpr int kBalanceThreads = 1024;
+__global__ __launch_bounds__(kBalanceThreads) void rebalance_kernel(Dev d, int headroom, int x_begin, int x_count, int x_entries,
+                                                                    const int32_t* x_len) {
+  __shared__ int s_part[kBalanceThreads / 64];
+  __shared__ int s_total;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (d.units + kBalanceThreads - 1) / kBalanceThreads;
+  const int u0 = min(d.units, tid * per), u1 = min(d.units, u0 + per);
+  // what this kernel writes and reads back (ownership, table cells, the spare stack) goes through accesses that
+  // are coherent one by one, whichever thread wrote them
+  auto ld = [](const int32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  auto st = [](int32_t* p, int32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  auto need_of = [&](int u) {
+    int e = max(d.budget[u] + headroom, d.n[u]);
+    if (u >= x_begin && u < x_begin + x_count) e = max(e, x_len ? min(max(x_len[u - x_begin], 0) + headroom, x_entries) : x_entries);
+    return min(d.max_seg, (e + kSeg - 1) / kSeg);
+  };
+  // exclusive prefix over the threads' ranges of a per-thread count; the total lands in s_total
+  auto scan = [&](int local) -> int {
+    int incl = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    __syncthreads();                       // the previous scan's readers are done
+    if (lane == 63) s_part[wave] = incl;
+    __syncthreads();
+    int before = incl - local;
+    for (int w = 0; w < wave; ++w) before += s_part[w];
+    if (tid == kBalanceThreads - 1) s_total = before + local;
+    __syncthreads();
+    return before;
+  };
+  int spare_n = d.sc[SC_SPARE];
+  // ---- release
+  int local = 0;
+  for (int u = u0; u < u1; ++u) local += max(0, ld(d.owned + u) - need_of(u));
+  int at = spare_n + scan(local);
+  for (int u = u0; u < u1; ++u) {
+    const int need = need_of(u), own = ld(d.owned + u);
+    for (int j = need; j < own; ++j) {
+      int32_t* cell = d.tbl + (size_t)u * d.max_seg + j;
+      st(d.spare + at++, ld(cell));
+      st(cell, 0);
+    }
+    if (own > need) st(d.owned + u, need);
+  }
+  spare_n += s_total;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the stack's new entries before anyone pops them
+  // ---- grant
+  local = 0;
+  for (int u = u0; u < u1; ++u) local += max(0, need_of(u) - ld(d.owned + u));
+  int from = scan(local);
+  const int wanted = s_total;
+  if (wanted > spare_n) {
+    if (tid == 0) {
+      atomicOr(&d.sc[SC_STATUS], 4);
+      d.sc[SC_SPARE] = spare_n;
+    }
+    return;
+  }
+  for (int u = u0; u < u1; ++u) {
+    const int need = need_of(u), own = ld(d.owned + u);
+    for (int j = own; j < need; ++j) st(d.tbl + (size_t)u * d.max_seg + j, ld(d.spare + (spare_n - 1 - from++)));
+    if (need > own) st(d.owned + u, need);
+  }
+  if (tid == 0) d.sc[SC_SPARE] = spare_n - wanted;
+}
+
 // ------------------------------------------------------------------ cache load
 // grid: (ceil(P/32), units of the layer); converts 32 row-major rows to one
 // tiled block.  k, v: [units][P][128]; unit `urel` holds len[urel] (or P)
@@ -337,7 +416,11 @@ __global__ __launch_bounds__(kThreads) void load_cache_kernel(Dev d, int unit_be
   const int tid = threadIdx.x;
   const int urel = blockIdx.y, u = unit_begin + urel;
   const int blk = blockIdx.x, r0 = blk * kBlk;
-  const int n = len ? min(max(len[urel], 0), P) : P;
+  int n = len ? min(max(len[urel], 0), P) : P;
+  if (n >= unit_cap(d, u)) {                     // the unit's segments do not hold it (shared pools that ran short)
+    n = max(unit_cap(d, u) - 1, 0);
+    if (blk == 0 && tid == 0) atomicOr(&d.sc[SC_STATUS], 1);
+  }
   if (blk == 0 && tid == 0) {
     d.n[u] = n;
     d.nev[u] = 0;

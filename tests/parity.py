@@ -118,6 +118,8 @@ def compare_unit(g, o, key, rec, stats, *, check_kv=False, allow_resync=True, ev
             msg.append(f"tau differs at pos {gp[order_g][badt].tolist()}")
             badh = np.nonzero((e["flags"][order_g] & 1).astype(bool) != u.hit[order_o])[0][:10]
             msg.append(f"hit differs at pos {gp[order_g][badh].tolist()}")
+            if rec is not None:
+                msg.append(f"evicted gpu {np.asarray(e['evicted_pos']).tolist()[:20]} oracle {np.asarray(rec.evicted_pos).tolist()[:20]}")
         raise AssertionError("\n".join(msg))
     # sub-margin: the GPU's state must be what Alg. 1 gives when only edge entries' hit bits differ
     gs = dict(pos=gp[order_g], crf=e["crf"][order_g].view(np.uint32), tau=e["tau"][order_g],

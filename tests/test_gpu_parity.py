@@ -19,7 +19,7 @@ def _pair(cfg, cap, budgets=None, stream=None, n_steps=None, load=True, path=0, 
     ok, ckv, wl = _mods()
     st = stream if stream is not None else wl.make_stream(cfg, n_steps)
     budgets = wl.draw_budgets(cfg) if budgets is None else budgets
-    okw = {k: v for k, v in kw.items() if k != "out_dtype"}
+    okw = {k: v for k, v in kw.items() if k not in ("out_dtype", "headroom", "pool_slots", "prompt_len")}   # the rest is the GPU side's own business
     o = ok.CrystalKVOracle(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, budgets,
                            lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min,
                            budget_max=cfg.budget_max, **okw)
