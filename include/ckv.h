@@ -91,9 +91,11 @@ typedef struct {
   int32_t budget_max;
 } ckv_lrfu_params;
 
-/* Caller-owned device buffers.  With S = n_layers*batch*n_kv_heads*cap slots:
- *   k_pool, v_pool : S * 128 bf16 each.  Unit u owns slots [u*cap, (u+1)*cap).
- *                    Inside a unit, entries are stored in blocks of 32 entries
+/* Caller-owned device buffers.  With S = ckv_layout.pool_slots:
+ *   k_pool, v_pool : S * 128 bf16 each, in segments of 256 slots (64 KB).  Which
+ *                    segments hold a unit's entries, in which order, is recorded
+ *                    in the segment table in the workspace (ckv_get_segments).
+ *                    Inside a segment, entries are stored in blocks of 32 entries
  *                    (8 KB) in a tiled order chosen so that a 64-lane wavefront
  *                    reads 1 KB contiguous per load and gets MFMA operands
  *                    directly; use ckv_load_prompt / ckv_import_unit /
@@ -138,7 +140,10 @@ void ckv_destroy(ckv_ctx* ctx);
  * crf0 / tau0: dev [batch][n_kv_heads][P] or NULL (then CRF = 1, tau = P-1:
  * referenced once, at the end of the prompt; the paper is silent on prompt
  * scores).  Requires 0 < P < cap, P <= t0 and the layer's units empty
- * (CKV_ESTATE otherwise). */
+ * (CKV_ESTATE otherwise).  With shared pools the layer's units first get the
+ * segments that P + headroom entries need from the spare list (see
+ * ckv_rebalance); a unit for which they are not there is loaded as far as it has
+ * room, and ckv_status() reports CKV_ECAPACITY. */
 int ckv_load_prompt(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, int32_t P,
                     const float* crf0, const int32_t* tau0, void* stream);
 
@@ -182,15 +187,19 @@ int ckv_load_cache(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, in
  * hit entries' stored CRF and tau (tau = t marks the hit), accumulates the unit's
  * aggregated CRF for Alg. 2, and with CKV_FUSE_EVICT evicts down to the budget
  * (as ckv_evict).  Layers must be stepped in order 0..n_layers-1; t advances
- * after the last one.  A unit that is already full (n == cap) is not
- * appended to: the step still runs and ckv_status() reports CKV_ECAPACITY.
+ * after the last one.  A unit that is already full (n == cap, or with shared
+ * pools n == 256 * the segments it owns) is not appended to: the step still
+ * runs and ckv_status() reports CKV_ECAPACITY.
  * With CKV_ATTENTION_ONLY the stored scores, taus and the Alg. 2 window are left
  * alone (the new entry is still appended with CRF 0, tau t).
  * With CKV_DEFER_BOOKKEEPING (single-layer calls only) the call puts on `stream`
- * only what the next operation of a model needs, the append and the attention
- * output; the hit set, the scores and the eviction of that layer run afterwards
- * on one of two streams the context owns, beside whatever `stream` does next (the
- * next layer's step, the model's other work).  Results are the same.  Every later
+ * only what the next operation of a model needs: one kernel that attends over the
+ * cache and the new entry and writes the output (and the new entry's rows into
+ * the cache).  The append's records, the hit set, the scores and the eviction of
+ * that layer follow on one of two streams the context owns, up to eight
+ * consecutive layers per launch, beside whatever `stream` does next (the next
+ * layers' steps, the model's other work).  Results are the same up to
+ * floating-point summation order.  Every later
  * ckv_* call that takes a stream orders itself after the bookkeeping it depends
  * on (the next step of the same layer after that layer's, everything else after
  * all of it); the host-side getters wait for the whole device.  ckv_join orders
@@ -273,14 +282,17 @@ int ckv_set_budgets(ckv_ctx* ctx, const int32_t* budgets);   /* same checks as c
 int ckv_get_segments(ckv_ctx* ctx, int32_t* owned, int32_t* rows, int32_t* spare, int32_t* n_spare);
 int ckv_get_time(ckv_ctx* ctx, int32_t* t);
 int ckv_set_time(ckv_ctx* ctx, int32_t t);                   /* also restarts the Alg. 2 window */
-/* CKV_OK, or CKV_ECAPACITY if some append since the last call found its unit full. */
+/* CKV_OK; CKV_ECAPACITY if, since the last call, some append found its unit full or the spare list ran short when
+ * pool segments were dealt out; CKV_EHIP if a bounded wait inside a kernel gave up (results invalid).  Reported once. */
 int ckv_status(ckv_ctx* ctx);
 
 /* Synchronous state transfer of one unit, row-major on the host side (tests,
  * checkpointing).  Export: *n entries, *n_evicted log slots after them; the
  * host arrays must hold `cap` slots (K, V: cap*128 bf16 as uint16).  Any
- * output pointer may be NULL.  Import: replaces the unit's entries (n < cap)
- * and sets its last-step time to t_unit. */
+ * output pointer may be NULL; slots in segments the unit does not own read as
+ * zero.  Import: replaces the unit's entries (n < cap, and with shared pools
+ * n < 256 * the segments the unit owns: CKV_ECAPACITY otherwise) and sets its
+ * last-step time to t_unit. */
 int ckv_export_unit(ckv_ctx* ctx, int32_t layer, int32_t seq, int32_t head, int32_t* n,
                     int32_t* n_evicted, int32_t* budget, uint16_t* K, uint16_t* V, float* crf,
                     int32_t* tau, int32_t* pos, uint8_t* flags);
@@ -300,14 +312,11 @@ int ckv_profile_read(ckv_ctx* ctx, double* scan_ms, int32_t* launches);
 /* Which kernels ckv_decode_step uses: 0 = choose by unit count (default),
  * 1 = separate scan and finish kernels, 2 = the fused per-unit kernel, which
  * keeps the logits in LDS, in the widest variant that fits; 3 / 4 = the fused
- * kernel with 4 / 2 wavefronts per unit (2 / 4 workgroups per compute unit);
- * 5 = the fused kernel with four streaming wavefronts and four that do the
- * bookkeeping of the previous unit meanwhile (two logits tiles per workgroup).
+ * kernel with 4 / 2 wavefronts per unit (2 / 4 workgroups per compute unit).
  * Whatever the mode, a single-layer call takes the separate kernels if the
  * layer has fewer units than the fused kernel has workgroups or if its
  * bookkeeping is deferred.  A variant needs 4 * cap
- * bytes of LDS in its workgroup's share, mode 5 in each of its two tiles
- * (CKV_EINVAL otherwise).  Results do not depend on the choice beyond
+ * bytes of LDS in its workgroup's share (CKV_EINVAL otherwise).  Results do not depend on the choice beyond
  * floating-point summation order.
  * ckv_path_info reports what all-layer steps use under the current mode:
  * *fused_waves = wavefronts per unit of the fused variant (0: separate

@@ -151,7 +151,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, rank, sched, layer_ts, arrive, snew, msum, tbl, owned, spare, seedlg, seedml, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, layer_ts, arrive, msum, tbl, owned, spare, seedlg, seedml, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -176,10 +176,7 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.logits = take(U * G * (size_t)l->cap * 4);
   c.btotal = take((size_t)l->batch * 8);
   c.order = take(U * 4);
-  c.rank = take(U * 4);
-  c.sched = take(U * 16);
   c.layer_ts = take((size_t)l->n_layers * 8);
-  c.snew = take(U * kMaxGroup * 4);
   c.msum = take(U * kMaxGroup * 2 * 4);
   c.tbl = take(U * mc * 4);
   c.owned = take(U * 4);
@@ -470,11 +467,8 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.logits = (float*)(ws + cv.logits);
   d.btotal = (long long*)(ws + cv.btotal);
   d.order = (int32_t*)(ws + cv.order);
-  d.rank = (int32_t*)(ws + cv.rank);
-  d.sched = (int4*)(ws + cv.sched);
   d.layer_ts = (int32_t*)(ws + cv.layer_ts);
   d.arrive = (int32_t*)(ws + cv.arrive);
-  d.snew = (float*)(ws + cv.snew);
   d.msum = (float*)(ws + cv.msum);
   d.tbl = (int32_t*)(ws + cv.tbl);
   d.owned = (int32_t*)(ws + cv.owned);
@@ -649,10 +643,10 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     if (c->group_count == kBookGroup || advance) return flush_group(c);
     return CKV_OK;
   }
-  // unit_kernel<W> appends by itself; the other kernels get the new entries (and their schedule or work list) from prep_kernel
+  // unit_kernel<W> appends by itself; the separate kernels get the new entries and their work list from prep_kernel
   if (!fused) {
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((count + kPrepUnits - 1) / kPrepUnits)), dim3(kPrepThreads), 0, s, c->dev, begin, count,
-                       (const uint16_t*)k_new, (const uint16_t*)v_new, fused ? (layer >= 0 ? 7 : 3) : 1, INT_MAX, (const uint16_t*)q);
+                       (const uint16_t*)k_new, (const uint16_t*)v_new, 1, INT_MAX, (const uint16_t*)q);
     CKV_HIP(c, hipGetLastError());
   }
 
@@ -662,11 +656,9 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
     CKV_HIP(c, hipEventRecord(e0, s));
   }
   if (fused) {
-    // The kernel indexes the schedule by slot and its inputs and output by unit: for a single layer it gets
-    // the layer's part of the schedule (which prep_kernel has just filled in unit order) as if it were all
-    // there is, and the layer's first unit, whose rows come first in q, v_new and out.
+    // The kernel takes its units from the schedule (all layers: by descending budget) or, for a single layer, in
+    // the layer's own order starting at its first unit, whose rows come first in q, k_new, v_new and out.
     Dev dv = c->dev;
-    dv.sched = c->dev.sched + (layer >= 0 ? begin : 0);
     dv.units = count;
     dv.unit0 = layer >= 0 ? begin : 0;
     dv.by_order = layer >= 0 ? 0 : 1;

@@ -69,11 +69,8 @@ struct Dev {
   float* logits;         // [units][cap/32][G][32] scaled logits (base-2 domain)
   long long* btotal;     // [Bz] budget total per sequence
   int32_t* order;        // [units] unit indices by descending budget (schedule of the fused kernel)
-  int32_t* rank;         // [units] inverse of `order`
-  int4* sched;           // [units] schedule entry i: {unit order[i], its entry count after this step's append, its budget, 0}
   int32_t* layer_ts;     // [layers][2] time and launch sequence number of a layer's last deferred step (scan_kernel<true> -> finish_kernel with late = 1)
   int32_t* arrive;       // [units] runs of the unit published so far by a scan that also merges (zero between launches)
-  float* snew;           // [units][8] scaled logits (base-2 domain) of the entry appended in this step, per query head
   float* msum;           // [units][8][2] softmax maximum (base-2 domain) and 1 / sum per query head, left by layer_scan_kernel for its bookkeeping
 };
 
@@ -496,7 +493,7 @@ __global__ __launch_bounds__(kThreads) void seed_state_kernel(Dev d, int unit_be
 
 // ------------------------------------------------------------------ prep
 // 32 threads per unit, 32 units per workgroup: append the new entry (unless
-// bit 0 of `append` is clear) and, unless bit 1 is set, publish the unit's scan work items {unit, chunk, entries
+// bit 0 of `append` is clear) and publish the unit's scan work items {unit, chunk, entries
 // from the chunk's start to the unit's end, blocks in the list before this
 // item}.  One 64-bit atomic per workgroup claims the list range and the block
 // range together, so the list is sorted by block offset and unit-major (its
@@ -539,29 +536,6 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Dev d, int unit_begi
         n += 1;
       }
     }
-  }
-  if (append & 2) {                       // the fused kernel schedules whole units: one schedule entry per unit, no work list
-    // It also gets the new entry's logits ready-made (fp32 dot products of the bf16 inputs): a new entry that
-    // opens a block of its own then needs no pass over that block.  Entry .w says whether one was appended.
-    const bool appended = active && n > n_before;
-    if (appended) {
-      const uint16_t* kr = k_new + (size_t)w * kDim + 4 * sub;
-      float kf[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) kf[e] = __uint_as_float((uint32_t)kr[e] << 16);
-      for (int g = 0; g < d.G; ++g) {
-        const uint16_t* qr = q + ((size_t)w * d.G + g) * kDim + 4 * sub;
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc += __uint_as_float((uint32_t)qr[e] << 16) * kf[e];
-#pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 32);
-        if (sub == 0) d.snew[(size_t)u * kMaxGroup + g] = acc * d.scale_log2e;
-      }
-    }
-    // all layers: the slot the budget order gives the unit; one layer (append & 4): the units in their own order
-    if (active && sub == 0) d.sched[(append & 4) ? u : d.rank[u]] = make_int4(u, n, d.budget[u], appended ? 1 : 0);
-    return;
   }
   const int nch = active ? (n + kChunk - 1) / kChunk : 0;
   const int nblk = active ? (n + kBlk - 1) / kBlk : 0;

@@ -8,7 +8,7 @@
 // Here two workgroups share a CU, so while one does a unit's bookkeeping the
 // other keeps the memory pipeline busy.
 //
-// Work: schedule slots (units in order of descending budget, `d.sched`) are
+// Work: schedule slots (units in order of descending budget, `d.order`) are
 // taken three rounds statically, then from a shared queue.  The W wavefronts of
 // a workgroup split a unit's 32-entry blocks round robin (wave w takes blocks
 // w, w+W, ...), each with its own online softmax state; the states are merged
@@ -51,9 +51,8 @@ __device__ __forceinline__ int resident_entries(int n, int G, int lds_main_bytes
 
 // Schedule of the fused kernel: the units sorted by descending budget (counting
 // sort over budget / 32, one workgroup; the order inside a class is arbitrary,
-// it only affects scheduling).  Unit u gets slot rank[u] of `sched`, whose
-// entries {unit, entries, budget} prep_kernel refreshes every step.  Workgroups
-// take the slots in order, largest units first.
+// it only affects scheduling) in `order`.  Workgroups take the slots in order,
+// largest units first.
 __global__ __launch_bounds__(1024) void schedule_kernel(Dev d) {
   __shared__ int hist[1025];
   const int tid = threadIdx.x;
@@ -73,7 +72,6 @@ __global__ __launch_bounds__(1024) void schedule_kernel(Dev d) {
   for (int u = tid; u < d.units; u += 1024) {
     const int slot = atomicAdd(&hist[1023 - min(1023, d.budget[u] >> 5)], 1);
     d.order[slot] = u;
-    d.rank[u] = slot;
   }
 }
 
