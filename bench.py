@@ -28,7 +28,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-LARGE_POOL_BYTES = 54 << 30   # each pool of the secondary measurement: K and V together 3/8 of the device's memory
 RING = 32                     # distinct synthetic step inputs held at a time (and steps per HIP graph).  The timed
                               # regions refill them with fresh draws between repeats: a replayed input inserts keys
                               # that are exact duplicates of cached ones, identical keys tie in the top-p and
@@ -55,8 +54,22 @@ def build_workload(cfg, device, budgets=None, headroom=1, pool_factor=1.0, pools
         pool_slots = int(ckv.load().ckv_pool_slots(C.byref(lay), b32.ctypes.data_as(C.c_void_p), 0) * pool_factor) // 256 * 256
     kwargs = dict(lam=cfg.lam, top_p=cfg.top_p, t0=t_now, budget_min=cfg.budget_min, budget_max=cfg.budget_max,
                   headroom=headroom, pool_slots=pool_slots)     # headroom 1: shared pools, memory follows the budgets
+    placement = None
+    if pools == "place":
+        # Where the pools lie in physical memory moves the step by a tenth on this hardware: once, at start-up,
+        # try allocations across the device's memory and keep the one decode steps run fastest on.
+        import ctypes as C
+        lay = ckv.Layout(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, ckv.F32, headroom, 0)
+        b32 = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32))
+        ps = pool_slots or int(ckv.load().ckv_pool_slots(C.byref(lay), b32.ctypes.data_as(C.c_void_p), 0))
+        kwargs["pool_slots"] = ps
+        rest_bytes = ckv.arena_bytes(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets, **kwargs) - 2 * ps * 256
+        kp, vp, rest, placement = ckv.place_pools(ps * 256, device, rest_bytes=rest_bytes)
+        pools = (kp[:ps * 128], vp[:ps * 128])
+        kwargs["arena"] = rest
     g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
                       device=device, pools=pools, **kwargs)
+    g.placement = placement
     m = wl.torch_mean_query(cfg, device)
     gen = wl.torch_generator(cfg, 9, device)
     r_now = math.sqrt(wl.DRIFT_VAR) * torch.randn(m.shape, generator=gen, device=device)
@@ -286,7 +299,9 @@ def main():
     ap.add_argument("--headroom", type=int, default=1,
                     help="1 (default): shared pools, a unit owns the 256-slot segments its budget + 1 entries need; "
                          "0: every unit owns room for the largest budget")
-    ap.add_argument("--no-large-pool", action="store_true", help="skip the secondary measurement in pools of 54 GiB each")
+    ap.add_argument("--no-placement", action="store_true",
+                    help="take the buffers wherever the allocator puts them instead of choosing their place by the start-up "
+                         "calibration (ckv.place_pools)")
     ap.add_argument("--pool-factor", type=float, default=1.0, help="pools this many times what ckv_pool_slots asks for (measurement aid)")
     ap.add_argument("--path", type=int, default=0,
                     help="kernels of the all-layers step: 0 default, 1 separate scan/finish, 3 / 4 fused with 4 / 2 wavefronts per unit")
@@ -331,7 +346,8 @@ def main():
     if fullkv:
         g, budgets, (rq, rk, rv) = build_fullkv(cfg, device, args.fullkv, warm + (repeats + 2) * steps + 4 * RING)
     else:
-        g, budgets, (rq, rk, rv) = build_workload(cfg, device, headroom=args.headroom, pool_factor=args.pool_factor)
+        g, budgets, (rq, rk, rv) = build_workload(cfg, device, headroom=args.headroom, pool_factor=args.pool_factor,
+                                                      pools=None if (args.no_placement or fullkv) else "place")
     if args.path:
         g.set_path(args.path)
     out = torch.empty(rq.shape[1:], dtype=torch.float32, device=device)
@@ -487,7 +503,7 @@ def main():
                    "memory": (None if fullkv else
                               {"pool_slots": int(g.pool_slots), "kv_pool_bytes": int(2 * g.pool_slots * 256),
                                "budgeted_entry_bytes": int((np.asarray(budgets, dtype=np.int64) + 1).sum() * 512),
-                               "headroom": int(g.headroom)})},
+                               "headroom": int(g.headroom), "placement": getattr(g, "placement", None)})},
         "rebudget": rebudget,
         "kv_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -505,39 +521,6 @@ def main():
     if cpu is not None:
         res["cpu_baseline"] = cpu
     g.close()
-    # ---- secondary: the same workload in pools sized as a serving process sizes them (a share of the device's
-    # memory, not what this one workload needs).  Where the buffers lie in physical memory moves the step by up
-    # to a tenth on this hardware, and on most boxes large pools land better than tight ones; reported beside
-    # the headline, never instead of it.
-    if plain and not args.no_graph and not args.no_large_pool and args.pool_factor == 1.0:
-        del g_full, g_tail, g, rq, rk, rv, out
-        torch.cuda.empty_cache()
-        tight = res["config"]["memory"]["kv_pool_bytes"] / 2
-        factor = max(1.0, LARGE_POOL_BYTES / tight)
-        g, _, (rq, rk, rv) = build_workload(cfg, device, headroom=args.headroom, pool_factor=factor)
-        out = torch.empty((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device=device)
-        for i in range(RING):
-            g.decode_step(rq[i], rk[i], rv[i], out=out)
-        torch.cuda.synchronize()
-        gl = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gl):
-            for i in range(RING):
-                g.decode_step(rq[i], rk[i], rv[i], out=out)
-        tl = []
-        for _ in range(5):
-            g.refill()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            gl.replay()
-            torch.cuda.synchronize()
-            tl.append((time.perf_counter() - t1) * 1e3 / RING)
-        ms_l = float(np.median(tl))
-        res["large_pools"] = {"kv_pool_bytes": int(2 * g.pool_slots * 256), "ms_per_step_steps_only": ms_l,
-                              "kv_gbps": step_bytes / (ms_l * 1e-3) / 1e9, "hbm_frac": step_bytes / (ms_l * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                              "tight_pools_ms_per_step_steps_only": ms_steps_only}
-        assert g.status() == 0
-        del gl
-        g.close()
     print(json.dumps(res))
 
 

@@ -186,6 +186,8 @@ class CrystalKV:
         dev = self.device
         if arena is not None:
             sizes = _buffer_sizes(S, head_dim, ws)
+            if pools is not None:                 # K and V from `pools`, the other five buffers from the arena
+                sizes[0] = sizes[1] = 0
             al = 2 << 20
             offs, total = [], (-arena.data_ptr()) % al
             for b_ in sizes:
@@ -195,7 +197,7 @@ class CrystalKV:
                 raise CkvError(EINVAL, f"arena must be a contiguous uint8 tensor of at least {total} bytes")
             part = lambda i, dt: arena[offs[i]:offs[i] + sizes[i]].view(dt)
             self.arena = arena
-            self.k_pool, self.v_pool = part(0, torch.bfloat16), part(1, torch.bfloat16)
+            self.k_pool, self.v_pool = (part(0, torch.bfloat16), part(1, torch.bfloat16)) if pools is None else pools
             self.crf, self.tau, self.pos = part(2, torch.float32), part(3, torch.int32), part(4, torch.int32)
             self.flags, self.workspace = part(5, torch.uint8), part(6, torch.uint8)
         elif pools is not None:                   # caller-owned K and V pools (bf16 tensors of S * head_dim elements each)
@@ -420,6 +422,98 @@ class CrystalKV:
         ms, n = C.c_double(0.0), C.c_int32(0)
         self._check(self.lib.ckv_profile_read(self.ctx, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+
+def place_pools(pool_bytes, device="cuda:0", max_fraction=0.92, verbose=False, rest_bytes=0):
+    """Device memory for the K and V pools (`pool_bytes` each), chosen by measurement; returns (k_pool, v_pool,
+    rest, report): bf16 tensors to pass as `pools=` to CrystalKV and, if rest_bytes > 0, a uint8 tensor of at least
+    rest_bytes to pass as `arena=` beside them (the per-slot arrays and the workspace are then carved from it).
+
+    On MI355X the decode kernels run about a tenth slower or faster depending on where their buffers lie in
+    physical memory (regions tens of GB wide; plain streaming reads do not see them).  Where an allocation lands
+    is the driver's business, but consecutive allocations of a process walk through the memory.  So, once, at
+    start-up: allocate buffers of twice the pool size one after another without freeing any, until
+    `max_fraction` of the device's memory is in use (each is a different piece of memory); time a few
+    attention-only decode steps of a synthetic context whose K and V pools are the buffer's halves (random keys,
+    units of 2048 entries, as many as fit; its other buffers lie wherever the allocator puts them); keep the
+    fastest buffer whose neighbours in allocation order are about as fast (a buffer that straddles a boundary is
+    not wanted) for the pools.  What was measured on this hardware, and is not understood, is that the step is
+    fastest when the other buffers lie in memory of the *other* kind: so the buffer on which the calibration ran
+    slowest is kept for them.  Everything else is freed."""
+    import torch
+    dev = torch.device(device)
+    pool_bytes = (int(pool_bytes) + (2 << 20) - 1) // (2 << 20) * (2 << 20)
+    L, Hq, Hkv, n_ent, cap = 1, 32, 8, 2048, 2304
+    Bz = int(min(8192, pool_bytes // (cap * 256)) // Hkv)
+    if Bz < 64:
+        k = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
+        v = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
+        rest = torch.empty(int(rest_bytes), dtype=torch.uint8, device=dev) if rest_bytes > 0 else None
+        return k, v, rest, dict(candidates=0, note="pools too small to matter: not placed")
+    need = Bz * Hkv * cap * 256
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    q = torch.randn((L, Bz, Hq, 128), generator=gen, device=dev).to(torch.bfloat16)
+    kn = torch.randn((L, Bz, Hkv, 128), generator=gen, device=dev).to(torch.bfloat16)
+    kc = torch.randn((Bz, Hkv, n_ent, 128), generator=gen, device=dev).to(torch.bfloat16)
+    budgets = np.full((L, Bz, Hkv), cap - 1, dtype=np.int32)
+    out = torch.empty((L, Bz, Hq, 128), dtype=torch.float32, device=dev)
+    torch.cuda.empty_cache()              # what torch holds in reserve counts as in use otherwise
+    cands, times, spacers = [], [], []
+    # at most 48 candidates: small pools are tried at even distances, with spacers (freed afterwards) between them
+    free_b, total_b = torch.cuda.mem_get_info(dev)
+    span = max(0, int(max_fraction * total_b) - (total_b - free_b))
+    spacer_bytes = max(0, span // 48 - max(2 * pool_bytes, int(rest_bytes))) // (2 << 20) * (2 << 20)
+    while True:
+        free_b, total_b = torch.cuda.mem_get_info(dev)
+        one = max(2 * pool_bytes, int(rest_bytes))
+        if free_b < one + (4 << 30) or (total_b - free_b + one) > max_fraction * total_b:
+            break
+        buf = torch.empty(one, dtype=torch.uint8, device=dev)
+        cands.append(buf)
+        g = CrystalKV(L, Bz, Hq, Hkv, 128, cap, budgets, t0=n_ent, device=dev,
+                      pools=(buf[:need].view(torch.bfloat16), buf[pool_bytes:pool_bytes + need].view(torch.bfloat16)))
+        g.set_path(3)
+        g.load_prompt(0, kc, kc)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+        g.decode_step(q, kn, kn, out=out, attention_only=True, evict=False)
+        ev[0].record()
+        for j in range(6):
+            g.decode_step(q, kn, kn, out=out, attention_only=True, evict=False)
+            ev[j + 1].record()
+        torch.cuda.synchronize(dev)
+        times.append(float(np.median([ev[j].elapsed_time(ev[j + 1]) for j in range(6)])))
+        g.close()
+        del g
+        free_b, _ = torch.cuda.mem_get_info(dev)
+        if spacer_bytes and free_b > spacer_bytes + one + (4 << 30):
+            spacers.append(torch.empty(spacer_bytes, dtype=torch.uint8, device=dev))
+    del kc, q, kn, out, spacers
+    if not cands:
+        k = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
+        v = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
+        rest = torch.empty(int(rest_bytes), dtype=torch.uint8, device=dev) if rest_bytes > 0 else None
+        return k, v, rest, dict(candidates=0, note="no room to try placements")
+    t = np.asarray(times)
+    fastest = float(t.min())
+    # settled = both neighbours within 1 % of the candidate itself (the ends count their one neighbour)
+    ok = [i for i in range(len(t)) if all(abs(t[j] - t[i]) <= 0.01 * t[i] for j in (i - 1, i + 1) if 0 <= j < len(t))]
+    pick = min(ok, key=lambda i: t[i]) if ok and min(t[i] for i in ok) <= 1.01 * fastest else int(np.argmin(t))
+    buf = cands[pick]
+    k = buf[:pool_bytes].view(torch.bfloat16)
+    v = buf[pool_bytes:].view(torch.bfloat16)
+    slowest = int(np.argmax(t))
+    rest = cands[slowest] if rest_bytes > 0 and slowest != pick else None
+    report = dict(candidates=len(cands), calibration_units=L * Bz * Hkv, step_ms_min=round(fastest, 4),
+                  step_ms_max=round(float(t.max()), 4), step_ms_first=round(float(t[0]), 4), chosen=int(pick),
+                  step_ms_chosen=round(float(t[pick]), 4), rest_in=slowest if rest is not None else None)
+    if verbose:
+        print("place_pools:", report, [round(float(x), 3) for x in t], flush=True)
+    del cands, buf
+    torch.cuda.empty_cache()
+    if rest is None and rest_bytes > 0:
+        rest = torch.empty(int(rest_bytes), dtype=torch.uint8, device=dev)
+    return k, v, rest, report
 
 
 def bandwidth_probe(n_bytes=4 << 30, copy=False, reps=5, device="cuda:0"):

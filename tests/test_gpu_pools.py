@@ -240,3 +240,35 @@ def test_caller_owned_pools_and_a_single_arena_give_the_same_results():
     for g in ctxs:
         assert g.status() == 0
         g.close()
+
+
+def test_place_pools_returns_usable_buffers_and_a_report():
+    """The start-up calibration: buffers of the requested sizes come back (K and V pools, and memory for the other
+    five buffers), the report says what was tried, and a context built on them gives the bits of a context with
+    buffers of its own.  Pools too small to matter are simply allocated."""
+    import torch
+    _, ckv, wl = _mods()
+    k, v, rest, rep = ckv.place_pools(8 << 20, rest_bytes=1 << 20)
+    assert rep["candidates"] == 0 and k.numel() * 2 >= 8 << 20 and rest.numel() >= 1 << 20
+    cfg = _small("qwen7b", n_layers=2, batch=64, n_q_heads=8, n_kv_heads=8, prompt=300, decode_steps=4, budget=2040,
+                 budget_min=100, budget_max=2047, seed=21)
+    st = wl.make_stream(cfg)
+    budgets = wl.draw_budgets(cfg)
+    geom = (cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 2048, budgets)
+    kw = dict(lam=cfg.lam, top_p=cfg.top_p, t0=cfg.prompt, budget_min=cfg.budget_min, budget_max=cfg.budget_max, headroom=1)
+    plain = ckv.CrystalKV(*geom, **kw)
+    ps = plain.pool_slots
+    rest_bytes = ckv.arena_bytes(*geom, **kw) - 2 * ps * 256
+    k, v, rest, rep = ckv.place_pools(ps * 256, rest_bytes=rest_bytes, max_fraction=0.4)
+    assert 2 <= rep["candidates"] <= 48 and rep["step_ms_min"] <= rep["step_ms_chosen"] <= rep["step_ms_max"]
+    assert k.numel() >= ps * 128 and v.numel() >= ps * 128 and rest.numel() >= rest_bytes
+    placed = ckv.CrystalKV(*geom, pools=(k[:ps * 128], v[:ps * 128]), arena=rest, **kw)
+    for g in (plain, placed):
+        for l in range(cfg.n_layers):
+            g.load_prompt(l, st.prompt_k[l], st.prompt_v[l])
+    for s in range(cfg.decode_steps):
+        a = plain.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        b = placed.decode_step(st.q[s], st.k_new[s], st.v_new[s])
+        assert torch.equal(a, b)
+    assert plain.status() == 0 and placed.status() == 0
+    plain.close(); placed.close()
