@@ -621,7 +621,7 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
       if (int rc = profile_events(c, &e0, &e1)) return rc;
       CKV_HIP(c, hipEventRecord(e0, s));
     }
-    hipLaunchKernelGGL(layer_scan_kernel, dim3((unsigned)count, (unsigned)((c->dev.max_chunks + 3) / 4)), dim3(kThreads), 0, s, c->dev,
+    hipLaunchKernelGGL((layer_scan_kernel<4, 1>), dim3((unsigned)count, (unsigned)((c->dev.max_chunks + 3) / 4)), dim3(256), 0, s, c->dev,
                        begin, (const uint16_t*)q, (const uint16_t*)k_new, (const uint16_t*)v_new, out, (int)layer);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));

@@ -1029,7 +1029,11 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
 // in LDS; a unit of one workgroup (up to 1024 entries) is finished there and then, a longer one goes through
 // one partial per workgroup, merged by the workgroup that publishes the last (coherent stores and loads as in
 // scan_kernel<true>).  The unit's softmax maximum and 1 / sum per head stay in `msum` for the bookkeeping.
-// grid: (units of the layer, ceil(max_chunks / 4)), kThreads threads.
+// kW wavefronts per workgroup, each over 1 / kSplit of a chunk; the text above describes <4, 1>, the shape in
+// use.  Measured beside it on 128 units of 257 .. 8193 entries: fewer wavefronts per workgroup (<2, 1>, <1, 1>)
+// 2 % and 15 % slower per step, more (<8, 1>) 8 %, shorter spans (<4, 2>, <8, 2>, <8, 4>) 8 %, 23 % and 49 %;
+// rotating the units against the chunk groups, or the long units' last chunks first: no difference.
+// grid: (units of the layer, ceil(max_chunks * kSplit / kW)), 64 kW threads.
 __device__ __forceinline__ void inject_entry(KFrag& ka, VFrag& va, int rr, const u32x4 (&knew)[4], const uint32_t (&vnew)[8], int lane) {
   const int j = lane & 15, kg = lane >> 4;
   const int tt = rr >> 4;
@@ -1051,23 +1055,27 @@ __device__ __forceinline__ void inject_entry(KFrag& ka, VFrag& va, int rr, const
     }
 }
 
-__global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q,
-                                                                 const uint16_t* __restrict__ k_new,
-                                                                 const uint16_t* __restrict__ v_new, void* out, int layer) {
-  constexpr int kW = kThreads / 64;
+template <int kW, int kSplit>
+__global__ __launch_bounds__(64 * kW, 1) void layer_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q,
+                                                                const uint16_t* __restrict__ k_new,
+                                                                const uint16_t* __restrict__ v_new, void* out, int layer) {
+  constexpr int kT = 64 * kW;
+  constexpr int kSpanBlk = kChunkBlocks / kSplit, kSpan = kSpanBlk * kBlk;      // blocks and entries one wavefront takes
   __shared__ float s_lg[kW][kMaxGroup * kLgRow];
   __shared__ float s_m[kW][kMaxGroup], s_l[kW][kMaxGroup];
   __shared__ float s_acc[kW][kMaxGroup * kDim];
+  __shared__ float s_w[2 * kMaxChunks * kMaxGroup], s_M[kMaxGroup], s_L[kMaxGroup];
   __shared__ int s_last;
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int urel = blockIdx.x, u = unit_begin + urel, cg = blockIdx.y;
   const int G = d.G;
   const int n_old = d.n[u];
-  // this wavefront's chunk is one pool segment (asked for beside the length: neither waits for the other)
-  const int my_seg = d.tbl[(size_t)u * d.max_seg + min(cg * kW + w, d.max_seg - 1)];
+  // this wavefront's span lies in one pool segment (asked for beside the length: neither waits for the other)
+  const int c = cg * kW + w;
+  const int my_seg = d.tbl[(size_t)u * d.max_seg + min(c / kSplit, d.max_seg - 1)];
   const bool full = n_old >= unit_cap(d, u);
   const int n = n_old + (full ? 0 : 1);
-  const int nch = (n + kChunk - 1) / kChunk;
+  const int nch = (n + kSpan - 1) / kSpan;          // spans of the unit
   if (cg == 0 && tid == 0) {
     if (urel == 0) d.layer_ts[2 * layer] = d.sc[SC_T];      // the bookkeeping runs later, perhaps after the time has moved on
     if (full) atomicOr(&d.sc[SC_STATUS], 1);
@@ -1076,17 +1084,17 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
   const int nwg = (nch + kW - 1) / kW;
   const int j = lane & 15, kg = lane >> 4;
   const bool head_lane = j < G;
-  const int c = cg * kW + w;
   f32x4 acc[8];
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
   if (c < nch) {
-    const int e0 = c * kChunk;
-    const int nv = min(n - e0, kChunk);
+    const int e0 = c * kSpan;
+    const int s0 = (c % kSplit) * kSpan;                                  // the span's first slot within its segment
+    const int nv = min(n - e0, kSpan);
     const int nb = (nv + kBlk - 1) / kBlk;
-    const bool inject = !full && n_old >= e0 && n_old < e0 + kChunk;     // the new entry is then the chunk's last: entry nv - 1
-    const size_t off = (size_t)my_seg * kSegElems + lane * 8;
+    const bool inject = !full && n_old >= e0 && n_old < e0 + kSpan;      // the new entry is then the span's last: entry nv - 1
+    const size_t off = (size_t)my_seg * kSegElems + (size_t)(c % kSplit) * kSpanBlk * kBlkElems + lane * 8;
     const uint16_t* kcur = d.K + off;
     const uint16_t* vcur = d.V + off;
     KFrag ka;
@@ -1113,15 +1121,15 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) vnew[dt] = vr[16 * dt];
       // the rows also go into the cache, where the next step finds them
-      uint16_t* kdst = d.K + (size_t)my_seg * kSegElems;         // n_old lies in this chunk
+      uint16_t* kdst = d.K + (size_t)my_seg * kSegElems;         // n_old lies in this span
       uint16_t* vdst = d.V + (size_t)my_seg * kSegElems;
       if (j == 0) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) *reinterpret_cast<u32x4*>(kdst + k_offset(n_old - e0, 32 * s + 8 * kg)) = knew[s];
+        for (int s = 0; s < 4; ++s) *reinterpret_cast<u32x4*>(kdst + k_offset(s0 + n_old - e0, 32 * s + 8 * kg)) = knew[s];
       }
       if (kg == 0) {
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) vdst[v_offset(n_old - e0, 16 * dt + j)] = (uint16_t)vnew[dt];
+        for (int dt = 0; dt < 8; ++dt) vdst[v_offset(s0 + n_old - e0, 16 * dt + j)] = (uint16_t)vnew[dt];
       }
     }
     float* lds_lg = s_lg[w];
@@ -1158,11 +1166,11 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
   }
   __syncthreads();
   const size_t slot0 = (size_t)u * d.slots;
-  constexpr int kPer = (kMaxGroup * kDim) / kThreads;      // (head, dim) pairs per thread
+  constexpr int kPer = (kMaxGroup * kDim) / kT;      // (head, dim) pairs per thread
   float o[kPer], Mg[kPer], Lg[kPer];
 #pragma unroll
   for (int k = 0; k < kPer; ++k) {
-    const int e = tid + k * kThreads, g = e >> 7;
+    const int e = tid + k * kT, g = e >> 7;
     o[k] = 0.f;
     Mg[k] = -INFINITY;
     Lg[k] = 0.f;
@@ -1183,7 +1191,7 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
     }
   }
   auto write_out = [&](int k, float val, float M, float L) {
-    const int e = tid + k * kThreads, g = e >> 7, dim = e & 127;
+    const int e = tid + k * kT, g = e >> 7, dim = e & 127;
     const float inv = 1.0f / L;
     const float ov = val * inv;
     const size_t oi = ((size_t)urel * G + g) * kDim + dim;
@@ -1199,13 +1207,13 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
   if (nwg == 1) {
 #pragma unroll
     for (int k = 0; k < kPer; ++k)
-      if (((tid + k * kThreads) >> 7) < G) write_out(k, o[k], Mg[k], Lg[k]);
+      if (((tid + k * kT) >> 7) < G) write_out(k, o[k], Mg[k], Lg[k]);
     return;
   }
   // ---- one partial per workgroup; the workgroup that publishes the unit's last one merges them
 #pragma unroll
   for (int k = 0; k < kPer; ++k) {
-    const int e = tid + k * kThreads, g = e >> 7, dim = e & 127;
+    const int e = tid + k * kT, g = e >> 7, dim = e & 127;
     if (g < G) {
       put<true>(&d.partial[((slot0 + cg) * G + g) * kDim + dim], o[k]);
       if (dim == 0) {
@@ -1223,42 +1231,70 @@ __global__ __launch_bounds__(kThreads, 2) void layer_scan_kernel(Dev d, int unit
   }
   __syncthreads();
   if (!s_last) return;
+  // the partials' values are asked for first, kRound partials at a time; their maxima and sums go through LDS,
+  // where every head's overall maximum, the partials' weights and the sum's reciprocal are formed once
+  constexpr int kRound = 64 / kPer < 16 ? 64 / kPer : 16;
+  static_assert(kW >= kSplit, "a unit has one partial slot per chunk");
+  float x[kRound][kPer];
+  auto request = [&](int r0) {
 #pragma unroll
-  for (int k = 0; k < kPer; ++k) {
-    const int e = tid + k * kThreads, g = e >> 7, dim = e & 127;
-    if (g >= G) continue;
-    // one pass with a running maximum: sixteen partials' values are requested at once, so that a unit of up
-    // to 16 K entries costs a single round trip
-    float M = -INFINITY, val = 0.f, L = 0.f;
-    for (int r0 = 0; r0 < nwg; r0 += 16) {
-      float m[16], l[16], x[16];
+    for (int i = 0; i < kRound; ++i) {
+      const size_t sl = slot0 + min(r0 + i, nwg - 1);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const size_t sl = slot0 + min(r0 + i, nwg - 1);
-        m[i] = get_coherent(&d.ml[(sl * G + g) * 2]);
-        l[i] = get_coherent(&d.ml[(sl * G + g) * 2 + 1]);
-        x[i] = get_coherent(&d.partial[(sl * G + g) * kDim + dim]);
+      for (int k = 0; k < kPer; ++k) {
+        const int e = tid + k * kT, g = e >> 7, dim = e & 127;
+        x[i][k] = get_coherent(&d.partial[(sl * G + min(g, G - 1)) * kDim + dim]);
       }
-      float Mn = M;
+    }
+  };
+  request(0);
+  float* sW = s_w;
+  float* sL = s_w + kMaxChunks * kMaxGroup;
+  for (int i = tid; i < nwg * kMaxGroup; i += kT) {
+    const int sidx = i >> 3, g = i & 7;
+    const float* mlp = d.ml + ((slot0 + sidx) * G + min(g, G - 1)) * 2;
+    const float m = get_coherent(mlp), l = get_coherent(mlp + 1);
+    sW[i] = g < G ? m : -INFINITY;
+    sL[i] = g < G ? l : 0.f;
+  }
+  __syncthreads();
+  if (tid < kMaxGroup) {
+    float M = -INFINITY;
+    for (int r = 0; r < nwg; ++r) M = fmaxf(M, sW[r * kMaxGroup + tid]);
+    s_M[tid] = M;
+  }
+  __syncthreads();
+  for (int i = tid; i < nwg * kMaxGroup; i += kT) {
+    const float m = sW[i];
+    sW[i] = m > -INFINITY ? fast_exp2(m - s_M[i & 7]) : 0.f;
+  }
+  __syncthreads();
+  if (tid < kMaxGroup) {
+    float L = 0.f;
+    for (int r = 0; r < nwg; ++r) L += sL[r * kMaxGroup + tid] * sW[r * kMaxGroup + tid];
+    s_L[tid] = L;
+  }
+  __syncthreads();
+  float val[kPer];
 #pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if (r0 + i < nwg) Mn = fmaxf(Mn, m[i]);
-      if (Mn > M) {
-        const float sc = fast_exp2(M - Mn);        // 0 the first time round (M = -inf)
-        val *= sc;
-        L *= sc;
-        M = Mn;
-      }
+  for (int k = 0; k < kPer; ++k) val[k] = 0.f;
+  for (int r0 = 0; r0 < nwg; r0 += kRound) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (r0 + i < nwg && m[i] > -INFINITY) {
-          const float wt = fast_exp2(m[i] - M);
-          val += x[i] * wt;
-          L += l[i] * wt;
+    for (int i = 0; i < kRound; ++i) {
+      if (r0 + i < nwg) {
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+          const float wt = sW[(r0 + i) * kMaxGroup + ((tid + k * kT) >> 7)];
+          if (wt != 0.f) val[k] += x[i][k] * wt;
         }
       }
     }
-    write_out(k, val, M, L);
+    if (r0 + kRound < nwg) request(r0 + kRound);
+  }
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int g = (tid + k * kT) >> 7;
+    if (g < G) write_out(k, val[k], s_M[g], s_L[g]);
   }
 }
 
@@ -2265,6 +2301,9 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
   if (late == 2) {
     // after layer_scan_kernel: the new entry's rows are in the cache and its logits with the others, the
     // unit's records still describe the step before.  Record the append, then go on as after any scan.
+    // (Every wavefront has read the stored length before the first thread replaces it: a wavefront that
+    // started late would otherwise count the new entry twice and part ways with the others.)
+    __syncthreads();
     if (n < unit_cap(d, u)) {
       if (tid == 0) {
         const size_t s = slots_of(d, u) + n;
