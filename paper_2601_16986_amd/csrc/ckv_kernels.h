@@ -1763,10 +1763,18 @@ __device__ __forceinline__ void mean_weights(const Dev& d, LgView lv, int n, con
 // score update, flags.  Leaves CRF_temp in val(i) and returns the unit's
 // aggregated CRF (2^-20 fixed point), summed over the block.  s_tab: the first
 // s_tab_n entries of the decay table in LDS.
+// Alg. 1 Step 1 as a rule: an entry of weight pattern b and position pe is hit if b > theta, or b == theta and
+// (ties_all or pe <= pos_cut).  (The entry appended in the step is hit whatever its weight: the callers add that.)
+struct HitRule {
+  uint32_t theta;
+  bool ties_all;
+  int pos_cut;
+  __device__ __forceinline__ bool operator()(uint32_t b, int pe) const { return (b > theta) | ((b == theta) & (ties_all | (pe <= pos_cut))); }
+};
+
+// Step 1 over weights in val(0 .. n - 1) (LDS), any n
 template <class Val, int NT = kThreads, int SB = 0>
-__device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
-                           int& phase, int tid) {
-  // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
+__device__ __forceinline__ HitRule top_p_lds(const Dev& d, Slots base, int n, Val val, RedBuf& rb, int& phase, int tid) {
   uint32_t theta = 0;
   bool ties_all = true;
   int pos_cut = 0x7FFFFFFF;
@@ -1817,6 +1825,15 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int 
       }
     }
   }
+  return HitRule{theta, ties_all, pos_cut};
+}
+
+template <class Val, int NT = kThreads, int SB = 0>
+__device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
+                           int& phase, int tid) {
+  // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
+  const HitRule rule = top_p_lds<Val, NT, SB>(d, base, n, val, rb, phase, tid);
+  const bool ties_all = rule.ties_all;
 
   // ---- Alg. 1 Steps 2-3: scores (4 entries per thread and round: loads, table lookups, then stores)
   const bool has_new = d.pos[base + (n - 1)] == t;
@@ -1848,7 +1865,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int 
         float reward;
         if (d.reward_mode == 0) {
           const uint32_t b = __float_as_uint(a);
-          hit = (b > theta) || (b == theta && (ties_all || ps[r] <= pos_cut));
+          hit = rule(b, ps[r]);
           if (i == n - 1 && has_new) hit = true;
           store = hit;
           reward = hit ? 1.0f : 0.0f;
@@ -1958,25 +1975,12 @@ __device__ __forceinline__ EntryRow load_row_input(const NewEntry& ne, int tid) 
   return r;
 }
 
-// `after_step1` runs once between Step 1 and the score update (the fused kernel
-// picks up its queue claim there).
-template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook, int SB = 0>
-__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
-                                          i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
-                                          int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
-                                          int tid, Hook after_step1 = Hook{}, NewEntry ne = NewEntry{nullptr, nullptr}) {
-  constexpr int C = R / 4;
-  static_assert(C % CH == 0 && CP <= CH, "groups come in chunks of CH");
-  const bool new_in_regs = ne.k_row != nullptr;          // uniform; implies that exactly one entry is evicted below
-#pragma unroll
-  for (int c = CP; c < CH; ++c) load_meta<NT>(d, base, n, t, c, tid, crf[c], tau[c], ps[c]);
-  // what the end of the step would otherwise wait for: the unit's running sum, and the last slot's rows
-  // (the entry that moves if exactly one entry is evicted)
-  const u64 window0 = d.window[u];
-  const bool evict_single = evict && n - B == 1;
-  EntryRow last_row{{0u, 0u, 0u, 0u}, 0, 0};
-  if (evict_single) last_row = new_in_regs ? load_row_input<NT>(ne, tid) : load_row<NT>(d, base, n - 1, tid);
-  // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
+// Step 1 over weights in registers (a[4 c + e] = mean weight of entry 4 (tid + c NT) + e, 0 beyond n).  lst: 64 ints of
+// LDS (lst_cap >= 64, or the short list is not used); sh: the callers' exchange words (5 .. 7 are used here).
+// new_last_t >= 0: the unit's last entry is not in the cache and has this position.
+template <int R, int NT = kThreads, int SB = 0>
+__device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, const float (&a)[R], int* lst, int lst_cap, int new_last_t,
+                                              RedBuf& rb, int& phase, int* sh, int tid) {
   uint32_t theta = 0;
   bool ties_all = true;
   int pos_cut = 0x7FFFFFFF;
@@ -2110,7 +2114,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
             int cnt = 0;
             for (int k = 0; k < R; ++k) {
               const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
-              if (__float_as_uint(a[k]) == theta && i < n && ((new_in_regs && i == n - 1) ? t : d.pos[base + i]) < trial) ++cnt;
+              if (__float_as_uint(a[k]) == theta && i < n && ((new_last_t >= 0 && i == n - 1) ? new_last_t : d.pos[base + i]) < trial) ++cnt;
             }
             cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
@@ -2120,6 +2124,29 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
       }
     }
   }
+  return HitRule{theta, ties_all, pos_cut};
+}
+
+// `after_step1` runs once between Step 1 and the score update (the fused kernel
+// picks up its queue claim there).
+template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook, int SB = 0>
+__device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
+                                          i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
+                                          int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
+                                          int tid, Hook after_step1 = Hook{}, NewEntry ne = NewEntry{nullptr, nullptr}) {
+  constexpr int C = R / 4;
+  static_assert(C % CH == 0 && CP <= CH, "groups come in chunks of CH");
+  const bool new_in_regs = ne.k_row != nullptr;          // uniform; implies that exactly one entry is evicted below
+#pragma unroll
+  for (int c = CP; c < CH; ++c) load_meta<NT>(d, base, n, t, c, tid, crf[c], tau[c], ps[c]);
+  // what the end of the step would otherwise wait for: the unit's running sum, and the last slot's rows
+  // (the entry that moves if exactly one entry is evicted)
+  const u64 window0 = d.window[u];
+  const bool evict_single = evict && n - B == 1;
+  EntryRow last_row{{0u, 0u, 0u, 0u}, 0, 0};
+  if (evict_single) last_row = new_in_regs ? load_row_input<NT>(ne, tid) : load_row<NT>(d, base, n - 1, tid);
+  // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
+  const HitRule rule = top_p_regs<R, NT, SB>(d, base, n, a, lst, lst_cap, new_in_regs ? t : -1, rb, phase, sh, tid);
   after_step1();
   // ---- Steps 2-3: scores; a[k] becomes CRF_temp.  The candidate for Step 4 (lowest score, then
   // highest position) is tracked on the way.
@@ -2157,8 +2184,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
       const float dec = fresh ? 1.0f : dec4[e];
       const float crf_old = fresh ? 0.0f : crf[c][e];
       const uint32_t b = __float_as_uint(w);
-      const bool hit = topp & ((b > theta) | ((b == theta) & (ties_all | (pe <= pos_cut))) |
-                               ((i == n - 1) & (pe == t)));          // the entry appended this step is always hit
+      const bool hit = topp & (rule(b, pe) | ((i == n - 1) & (pe == t)));          // the entry appended this step is always hit
       const bool store = ok & (hit | !topp);
       const float reward = topp ? (hit ? 1.0f : 0.0f) : w;
       float tmp = __fadd_rn(__fmul_rn(dec, crf_old), reward);
@@ -2331,131 +2357,311 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
 }
 
 // ------------------------------------------------------------------ prompt replay (scores of a loaded prompt)
-// The prompt's last W queries, Q = 16 / G of them per pass over the keys: the matrix-core tile has 16 query
-// columns, of which a decode step fills G.  Column c of a pass holds head c % G of query j0 + c / G.  Only the
-// weights are wanted (no output), so V is never read.
+// The prompt's last W queries in three kernels per batch of queries.  What a query does to the scores splits
+// into a part that does not depend on the scores - its mean attention weights over the entries it sees and,
+// from them, the reward of every entry (Alg. 1 Steps 1-2: hit or not; or the weight itself) - and the score
+// recurrence (Step 3), which is sequential over the queries but independent per entry.  So:
+//   seed_scan_kernel   one pass over the keys for all queries of the batch: scaled logits and softmax partials
+//   seed_hits_kernel   per (unit, query): mean weights, hit rule, rewards
+//   seed_crf_kernel    per entry: the queries' rewards applied in order
+// Only the weights are wanted (no output), so V is never read.
 //
-// seed_scan_kernel: one wavefront per 256-entry chunk of a unit.  Per block of 32 entries the scaled logits of
-// all 16 columns go to `slg` ([unit][block][column][32]); query j sees the entries of positions <= its own,
-// i.e. indices < P - W + j + 1 (the prompt's entries sit in position order), the rest is masked.  Per chunk and
-// column the running maximum and sum of the softmax go to `sml`.
-// grid: (ceil(chunks / 4), units of the layer), kThreads threads.
+// Columns: the matrix-core tile has 16 query columns, of which a decode step fills G; here a tile holds the G
+// heads of Q = 16 / G queries (column c = head c % G of the tile's query c / G), and a batch is up to
+// kSeedTiles tiles.  Buffers of a batch of nt tiles, nq queries, for the UL units of a layer:
+//   slg [tile][unit][block][column][32]   scaled logits (base-2 domain), -inf where the query does not see the entry
+//   sml [tile][unit][chunk][column][2]    running maximum and sum of the softmax per 256-entry chunk
+//   srw [query][unit][cap]                rewards
 constexpr int kSeedCols = 16;
+constexpr int kSeedTiles = 16;
 
+// seed_scan_kernel: one wavefront per 256-entry chunk of a unit; the tiles' queries sit in LDS (per tile and
+// 32-dim slice one 16-byte operand piece per lane), each block of keys is loaded once and multiplied with every
+// tile.  Query j of the window sees the entries of positions <= its own, i.e. indices < P - W + j + 1 (the
+// prompt's entries sit in position order).
+// grid: (ceil(chunks / 4), units of the layer), kThreads threads, nt * 4096 bytes of dynamic LDS.
 __global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q_obs, int j0,
-                                                             int Q, int P, int W, float* __restrict__ slg,
+                                                             int nq, int Q, int P, int W, float* __restrict__ slg,
                                                              float* __restrict__ sml) {
+  extern __shared__ unsigned char smem[];
+  u32x4* s_q = reinterpret_cast<u32x4*>(smem);            // [tile][slice][lane]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int urel = blockIdx.y, u = unit_begin + urel;
+  const int UL = gridDim.y;
   const int chunk = blockIdx.x * (kThreads / 64) + wave;
   const int G = d.G;
   const int j = lane & 15, kg = lane >> 4;
-  const int qi = min(j / G, Q - 1);                       // the column's query within the pass (columns beyond Q G: unused)
-  const bool col_ok = j < Q * G;
-  const int n_first = P - W + j0 + 1;                     // entries the pass's first query sees
-  const int lim = col_ok ? n_first + qi : 0;              // entries this column's query sees
-  const int n_max = n_first + Q - 1;                      // ... and the pass's last query
-  const int e_chunk = chunk * kChunk;
+  const int nt = (nq + Q - 1) / Q;
   const int mc = d.max_chunks;
-  if (e_chunk >= n_max) return;
-  // queries: B operand, lane (j, kg) holds dims 32 s + 8 kg .. + 7 of its column's head
-  bf16x8 qv[4];
+  const int n_first = P - W + j0 + 1;                     // entries the batch's first query sees
+  const int n_last = n_first + nq - 1;                    // ... and its last
   {
+    // this thread's piece (slice = wave, lane) of every tile's operand
     const int b = urel / d.Hkv, h = urel % d.Hkv;
-    const uint16_t* qrow = q_obs + ((((size_t)(j0 + qi) * d.Bz + b) * d.Hq) + (size_t)h * G + (j % G)) * kDim + 8 * kg;
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-      u32x4 x = *reinterpret_cast<const u32x4*>(qrow + 32 * s4);
-      if (!col_ok) x = u32x4{0u, 0u, 0u, 0u};
-      qv[s4] = as_bf16x8(x);
+    for (int tl = 0; tl < nt; ++tl) {
+      const int qn = min(Q, nq - tl * Q);                 // queries in this tile
+      const int qi = min(j / G, qn - 1);
+      const uint16_t* qrow = q_obs + ((((size_t)(j0 + tl * Q + qi) * d.Bz + b) * d.Hq) + (size_t)h * G + (j % G)) * kDim + 8 * kg;
+      u32x4 x = *reinterpret_cast<const u32x4*>(qrow + 32 * wave);
+      if (j >= qn * G) x = u32x4{0u, 0u, 0u, 0u};
+      s_q[(tl * 4 + wave) * 64 + lane] = x;
     }
   }
-  const int nblk = min(kChunkBlocks, (n_max - e_chunk + kBlk - 1) / kBlk);
+  __syncthreads();
+  const int e_chunk = chunk * kChunk;
+  if (e_chunk >= n_last) return;
+  const int nblk = min(kChunkBlocks, (n_last - e_chunk + kBlk - 1) / kBlk);
   const uint16_t* kb = d.K + (size_t)d.tbl[(size_t)u * d.max_seg + chunk] * kSegElems + lane * 8;     // a chunk is one pool segment
+  const size_t lg_tile = (size_t)UL * (d.cap / kBlk) * (kSeedCols * kBlk);
   float* lgp = slg + ((size_t)urel * (d.cap / kBlk) + (size_t)chunk * kChunkBlocks) * (kSeedCols * kBlk) + j * kBlk + 4 * kg;
-  float m_run = -INFINITY, l_run = 0.f;                   // this lane's entries only; the four lanes of a column meet at the end
+  float m_run[kSeedTiles], l_run[kSeedTiles];             // this lane's entries only; the four lanes of a column meet at the end
+#pragma unroll
+  for (int tl = 0; tl < kSeedTiles; ++tl) {
+    m_run[tl] = -INFINITY;
+    l_run[tl] = 0.f;
+  }
   KFrag ka, kn;
   load_k(ka, kb);
   for (int blk = 0; blk < nblk; ++blk) {
     if (blk + 1 < nblk) load_k(kn, kb + (size_t)(blk + 1) * kBlkElems);
-    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[s4]), qv[s4], s0, 0, 0, 0);
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[4 + s4]), qv[s4], s1, 0, 0, 0);
     const int e0 = e_chunk + blk * kBlk + 4 * kg;
-    float sv[8];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      sv[v] = (e0 + v < lim) ? s0[v] * d.scale_log2e : -INFINITY;
-      sv[4 + v] = (e0 + 16 + v < lim) ? s1[v] * d.scale_log2e : -INFINITY;
-    }
-    *reinterpret_cast<f32x4*>(lgp + (size_t)blk * (kSeedCols * kBlk)) = f32x4{sv[0], sv[1], sv[2], sv[3]};
-    *reinterpret_cast<f32x4*>(lgp + (size_t)blk * (kSeedCols * kBlk) + 16) = f32x4{sv[4], sv[5], sv[6], sv[7]};
-    float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-    if (bm > m_run) {
-      l_run *= fast_exp2(m_run - bm);                     // exp2(-inf) = 0 the first time
-      m_run = bm;
-    }
-    if (m_run > -INFINITY) {
+    for (int tl = 0; tl < kSeedTiles; ++tl) {
+      if (tl < nt) {
+        const int qn = min(Q, nq - tl * Q);
+        // entries this column's query sees (columns beyond the tile's queries: none)
+        const int lim = j < qn * G ? n_first + tl * Q + j / G : 0;
+        if (e_chunk + blk * kBlk < n_first + tl * Q + qn - 1) {         // the tile's last query sees the block (uniform)
+          bf16x8 qv[4];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) l_run += fast_exp2(sv[i] - m_run);
+          for (int s4 = 0; s4 < 4; ++s4) qv[s4] = as_bf16x8(s_q[(tl * 4 + s4) * 64 + lane]);
+          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s4 = 0; s4 < 4; ++s4) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[s4]), qv[s4], s0, 0, 0, 0);
+#pragma unroll
+          for (int s4 = 0; s4 < 4; ++s4) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[4 + s4]), qv[s4], s1, 0, 0, 0);
+          float sv[8];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            sv[v] = (e0 + v < lim) ? s0[v] * d.scale_log2e : -INFINITY;
+            sv[4 + v] = (e0 + 16 + v < lim) ? s1[v] * d.scale_log2e : -INFINITY;
+          }
+          float* dst = lgp + (size_t)tl * lg_tile + (size_t)blk * (kSeedCols * kBlk);
+          *reinterpret_cast<f32x4*>(dst) = f32x4{sv[0], sv[1], sv[2], sv[3]};
+          *reinterpret_cast<f32x4*>(dst + 16) = f32x4{sv[4], sv[5], sv[6], sv[7]};
+          const float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+          if (bm > m_run[tl]) {
+            l_run[tl] *= fast_exp2(m_run[tl] - bm);         // exp2(-inf) = 0 the first time
+            m_run[tl] = bm;
+          }
+          if (m_run[tl] > -INFINITY) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) l_run[tl] += fast_exp2(sv[i] - m_run[tl]);
+          }
+        }
+      }
     }
     if (blk + 1 < nblk) ka = kn;
   }
-  // the column's four lanes (kg = 0..3): maximum, then the sums rescaled to it, in a fixed order
-  float M = fmaxf(m_run, __shfl_xor(m_run, 16));
-  M = fmaxf(M, __shfl_xor(M, 32));
-  const float mine = m_run > -INFINITY ? l_run * fast_exp2(m_run - M) : 0.f;
-  const float l0 = __shfl(mine, j), l1 = __shfl(mine, j + 16), l2 = __shfl(mine, j + 32), l3 = __shfl(mine, j + 48);
-  if (kg == 0) {
-    float* dst = sml + (((size_t)urel * mc + chunk) * kSeedCols + j) * 2;
-    dst[0] = M;
-    dst[1] = (l0 + l1) + (l2 + l3);
+  // per tile, the column's four lanes (kg = 0..3): maximum, then the sums rescaled to it, in a fixed order
+#pragma unroll
+  for (int tl = 0; tl < kSeedTiles; ++tl) {
+    if (tl < nt) {
+      float M = fmaxf(m_run[tl], __shfl_xor(m_run[tl], 16));
+      M = fmaxf(M, __shfl_xor(M, 32));
+      const float mine = m_run[tl] > -INFINITY ? l_run[tl] * fast_exp2(m_run[tl] - M) : 0.f;
+      const float l0 = __shfl(mine, j), l1 = __shfl(mine, j + 16), l2 = __shfl(mine, j + 32), l3 = __shfl(mine, j + 48);
+      if (kg == 0) {
+        float* dst = sml + ((((size_t)tl * UL + urel) * mc + chunk) * kSeedCols + j) * 2;
+        dst[0] = M;
+        dst[1] = (l0 + l1) + (l2 + l3);
+      }
+    }
   }
 }
 
-// seed_finish_kernel: one workgroup per unit; the pass's queries in order, each one a decode step's
-// bookkeeping without eviction at its own time over the entries it sees (Alg. 1 Steps 1-3): softmax maxima
-// and denominators of its G columns from the chunks' partials, mean weights from the logits, hit set, scores.
-constexpr int kSeedThreads = 512;      // twice a decode step's workgroup: prompts are long, and a layer has few units
+// seed_hits_kernel: one workgroup per (query of the batch, unit).  Softmax maxima and denominators of the
+// query's G columns from the chunks' partials, mean weights from the logits, hit rule, rewards: 1 or 0 under the
+// top-p rule (the query's own entry, the last it sees, is always hit), the weight itself otherwise.
+// grid: (queries of the batch, units of the layer), kSeedThreads threads, dynamic LDS as finish_kernel.
+constexpr int kSeedThreads = 512;      // twice a decode step's workgroup: prompts are long
 
-__global__ __launch_bounds__(kSeedThreads) void seed_finish_kernel(Dev d, int unit_begin, int j0, int Q, int P, int W,
-                                                               const float* __restrict__ slg, const float* __restrict__ sml) {
+template <int R>
+__device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int n, int t, LgView lv, const float* sM, const float* sInv,
+                                                  float* rw, int* lst, int lst_cap, RedBuf& rb, int& phase, int* sh, int tid) {
+  float a[R];
+  {
+    // mean_weights_regs with the next group's logits requested before the current group's are used (the same
+    // operations in the same order per entry)
+    const int G = d.G;
+    const float invG = 1.0f / (float)G;
+    f32x4 x[2][kMaxGroup];
+    auto request = [&](int c, f32x4 (&xx)[kMaxGroup]) {
+      const int e0 = 4 * (tid + c * kSeedThreads);
+      const float* row = lv.p + (size_t)(e0 >> 5) * lv.blk_stride + (e0 & 31);
+#pragma unroll
+      for (int g = 0; g < kMaxGroup; ++g)
+        xx[g] = (e0 < n && g < G) ? *reinterpret_cast<const f32x4*>(row + g * kBlk) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    };
+    request(0, x[0]);
+#pragma unroll
+    for (int c = 0; c < R / 4; ++c) {
+      if (c + 1 < R / 4) request(c + 1, x[(c + 1) & 1]);
+      const int e0 = 4 * (tid + c * kSeedThreads);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float acc = 0.f;
+#pragma unroll
+        for (int g = 0; g < kMaxGroup; ++g)
+          if (g < G) acc += fast_exp2(x[c & 1][g][e] - sM[g]) * sInv[g];
+        a[4 * c + e] = (e0 + e < n) ? acc * invG : 0.f;
+      }
+    }
+  }
+  const HitRule rule = top_p_regs<R, kSeedThreads>(d, base, n, a, lst, lst_cap, -1, rb, phase, sh, tid);
+  const bool topp = d.reward_mode == 0;
+  const bool last_new = d.pos[base + (n - 1)] == t;
+#pragma unroll
+  for (int c = 0; c < R / 4; ++c) {
+    const int e0 = 4 * (tid + c * kSeedThreads);
+    if (e0 < n) {
+      i32x4 ps = {0, 0, 0, 0};
+      if (topp && !rule.ties_all) ps = *reinterpret_cast<const i32x4*>(d.pos + (base + e0));      // rare
+      f32x4 r;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float w = a[4 * c + e];
+        const bool hit = rule(__float_as_uint(w), ps[e]) | ((e0 + e == n - 1) & last_new);
+        r[e] = topp ? (hit ? 1.0f : 0.0f) : w;
+      }
+      *reinterpret_cast<f32x4*>(rw + e0) = r;              // entries >= n of the group: written, never read
+    }
+  }
+}
+
+__global__ __launch_bounds__(kSeedThreads, 4) void seed_hits_kernel(Dev d, int unit_begin, int j0, int Q, int P, int W,
+                                                             const float* __restrict__ slg, const float* __restrict__ sml,
+                                                             float* __restrict__ srw) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
-  uint32_t* evm = reinterpret_cast<uint32_t*>(smem + (size_t)d.cap * 4);
   __shared__ __align__(16) float sM[kMaxGroup];
   __shared__ __align__(16) float sInv[kMaxGroup];
   __shared__ RedBuf rb;
   __shared__ int sh[4 + kSeedThreads / 64];
+  __shared__ float s_pm[kMaxChunks * kMaxGroup], s_pl[kMaxChunks * kMaxGroup];
+  const int tid = threadIdx.x;
+  const int ql = blockIdx.x, urel = blockIdx.y, u = unit_begin + urel;
+  const int UL = gridDim.y;
+  const int G = d.G, mc = d.max_chunks;
+  const int tl = ql / Q, qi = ql % Q;
+  const int t = P - W + j0 + ql;                          // the query's position = its time
+  const int n = t + 1;
+  const int nch = (n + kChunk - 1) / kChunk;
+  int phase = 0;
+  // the chunks' partials of the query's G columns through LDS (every thread fetches one), then per head the
+  // maximum and the sum in chunk order
+  for (int i = tid; i < nch * kMaxGroup; i += kSeedThreads) {
+    const int c = i >> 3, g = i & 7;
+    const float2 p = *reinterpret_cast<const float2*>(sml + (((((size_t)tl * UL + urel) * mc) + c) * kSeedCols + (size_t)(qi * G + min(g, G - 1))) * 2);
+    s_pm[i] = p.x;
+    s_pl[i] = p.y;
+  }
+  __syncthreads();
+  if (tid < G) {
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, s_pm[c * kMaxGroup + tid]);
+    float L = 0.f;
+    for (int c = 0; c < nch; ++c) {
+      const float m = s_pm[c * kMaxGroup + tid];
+      if (m > -INFINITY) L += s_pl[c * kMaxGroup + tid] * fast_exp2(m - M);
+    }
+    sM[tid] = M;
+    sInv[tid] = 1.0f / L;
+  }
+  __syncthreads();
+  const Slots base = slots_of(d, u);
+  const LgView lv{slg + ((size_t)tl * UL + urel) * (d.cap / kBlk) * (kSeedCols * kBlk) + (size_t)qi * G * kBlk, kSeedCols * kBlk};
+  float* rw = srw + ((size_t)ql * UL + urel) * d.cap;
+  int* lst = reinterpret_cast<int*>(val);
+  if (n <= 8 * kSeedThreads) {
+    seed_rewards_regs<8>(d, base, n, t, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+  } else if (n <= 16 * kSeedThreads) {
+    seed_rewards_regs<16>(d, base, n, t, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+  } else if (n <= 32 * kSeedThreads) {
+    seed_rewards_regs<32>(d, base, n, t, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+  } else {
+    mean_weights<kSeedThreads>(d, lv, n, sM, sInv, val, tid);
+    const HitRule rule = top_p_lds<ValLinear, kSeedThreads>(d, base, n, ValLinear{val}, rb, phase, tid);
+    const bool topp = d.reward_mode == 0;
+    const bool last_new = d.pos[base + (n - 1)] == t;
+    for (int i = tid; i < n; i += kSeedThreads) {
+      const float w = val[i];
+      const int pe = (topp && !rule.ties_all) ? d.pos[base + i] : 0;
+      const bool hit = rule(__float_as_uint(w), pe) | ((i == n - 1) & last_new);
+      rw[i] = topp ? (hit ? 1.0f : 0.0f) : w;
+    }
+  }
+}
+
+// seed_crf_kernel: Alg. 1 Step 3 for the batch's queries in order, four consecutive entries per thread: an entry
+// takes part from the query of its own position on; under the top-p rule only a hit replaces (CRF, tau).
+// grid: (ceil(P / (4 kThreads)), units of the layer), kThreads threads.
+__global__ __launch_bounds__(kThreads) void seed_crf_kernel(Dev d, int unit_begin, int j0, int nq, int P, int W,
+                                                            const float* __restrict__ srw) {
   __shared__ float s_tab[kTabLds];
   const int tid = threadIdx.x;
-  const int urel = blockIdx.x, u = unit_begin + urel;
-  const int G = d.G, mc = d.max_chunks;
+  const int urel = blockIdx.y, u = unit_begin + urel;
+  const int UL = gridDim.y;
   const int s_tab_n = min(kTabLds, d.tab_last + 1);
   if (tid < s_tab_n) s_tab[tid] = d.tab[tid];
-  int phase = 0;
-  for (int qi = 0; qi < Q; ++qi) {
-    const int t = P - W + j0 + qi;                        // the query's position = its time
-    const int n = t + 1;
-    const int nch = (n + kChunk - 1) / kChunk;
-    __syncthreads();                                      // the previous query's readers of sM / sInv are done
-    if (tid < G) {
-      const float* ml = sml + ((size_t)urel * mc * kSeedCols + (size_t)(qi * G + tid)) * 2;
-      float M = -INFINITY;
-      for (int c = 0; c < nch; ++c) M = fmaxf(M, ml[(size_t)c * kSeedCols * 2]);
-      float L = 0.f;
-      for (int c = 0; c < nch; ++c) {
-        const float m = ml[(size_t)c * kSeedCols * 2];
-        if (m > -INFINITY) L += ml[(size_t)c * kSeedCols * 2 + 1] * fast_exp2(m - M);
+  __syncthreads();
+  const int e0 = 4 * (blockIdx.x * kThreads + tid);
+  if (e0 >= P) return;
+  const Slots base = slots_of(d, u);
+  const size_t s0 = base + e0;                            // four consecutive entries share a segment
+  f32x4 crf = *reinterpret_cast<const f32x4*>(d.crf + s0);
+  i32x4 tau = *reinterpret_cast<const i32x4*>(d.tau + s0);
+  const bool topp = d.reward_mode == 0;
+  const float* rw = srw + (size_t)urel * d.cap + e0;
+  const size_t q_stride = (size_t)UL * d.cap;
+  const int t_first = P - W + j0;
+  bool changed = false;
+  for (int q0 = 0; q0 < nq; q0 += 8) {
+    f32x4 r[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) r[k] = *reinterpret_cast<const f32x4*>(rw + (size_t)min(q0 + k, nq - 1) * q_stride);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int t = t_first + q0 + k;
+      if (q0 + k < nq) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (e0 + e <= t) {                              // the query sees positions 0 .. t
+            int delta = t - tau[e];
+            delta = delta < 0 ? 0 : (delta > d.tab_last ? d.tab_last : delta);
+            const float dec = decay_of(d, delta, s_tab, s_tab_n);
+            const float reward = r[k][e];
+            float tmp = __fadd_rn(__fmul_rn(dec, crf[e]), reward);
+            if (tmp < FLT_MIN) tmp = 0.0f;
+            if (!topp || reward != 0.0f) {
+              crf[e] = tmp;
+              tau[e] = t;
+              changed = true;
+            }
+          }
+        }
       }
-      sM[tid] = M;
-      sInv[tid] = 1.0f / L;
     }
-    __syncthreads();
-    const LgView lv{slg + (size_t)urel * (d.cap / kBlk) * (kSeedCols * kBlk) + (size_t)qi * G * kBlk, kSeedCols * kBlk};
-    unit_bookkeeping<kSeedThreads>(d, u, n, d.cap, t, lv, sM, sInv, false, val, evm, s_tab, s_tab_n, rb, phase, sh, tid);
+  }
+  if (!changed) return;
+  if (e0 + 3 < P) {
+    *reinterpret_cast<f32x4*>(d.crf + s0) = crf;
+    *reinterpret_cast<i32x4*>(d.tau + s0) = tau;
+  } else {
+    for (int e = 0; e < 4 && e0 + e < P; ++e) {
+      d.crf[s0 + e] = crf[e];
+      d.tau[s0 + e] = tau[e];
+    }
   }
 }
 

@@ -211,17 +211,20 @@ def test_path_selection_api():
     g.close()
 
 
-@pytest.mark.parametrize("hq,hkv,P,W,lam", [(8, 2, 45, 9, 0.5), (10, 2, 70, 32, 0.7), (2, 2, 33, 1, 0.5), (14, 2, 300, 17, 0.97),
-                                             (16, 2, 64, 64, 0.0), (8, 2, 610, 40, 1.0), (10, 2, 4105, 20, 0.7), (8, 2, 9000, 6, 0.5),
-                                             (2, 2, 16390, 21, 0.5)])
-def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam):
+@pytest.mark.parametrize("hq,hkv,P,W,lam,L", [(8, 2, 45, 9, 0.5, 2), (10, 2, 70, 32, 0.7, 2), (2, 2, 33, 1, 0.5, 2), (14, 2, 300, 17, 0.97, 2),
+                                               (16, 2, 64, 64, 0.0, 2), (8, 2, 610, 40, 1.0, 2), (10, 2, 4105, 20, 0.7, 2),
+                                               (8, 2, 9000, 6, 0.5, 2), (2, 2, 16390, 21, 0.5, 2),
+                                               (10, 2, 300, 40, 0.7, 24), (8, 2, 8300, 10, 0.5, 12), (4, 2, 530, 64, 0.9, 36)])
+def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam, L):
     """Scores of a loaded prompt from its last W queries (all of it for W = P, one query for W = 1; prompts
     shorter and longer than a 256-entry chunk, not multiples of the 32-entry block; windows that are and are not
     multiples of the number of queries a pass over the keys takes, floor(16 / G) = 4, 3, 16, 2, 2; windows across
     the prompt lengths at which the replay's bookkeeping changes its code path, 8, 16 and 32 entries per thread
-    of a 512-thread workgroup): CRF bits and tau of every entry equal the oracle's; the time and the Alg. 2
+    of a 512-thread workgroup; contexts of two layers, whose replay takes one tile of queries at a time in its own
+    buffers, and of more, whose replay takes batches of 6, 2 and 3 tiles in the decode workspace): CRF bits and
+    tau of every entry equal the oracle's; the time and the Alg. 2
     window are untouched (the decode steps and the re-allocation that follow match the oracle as after any load)."""
-    cfg = _small("tiny", n_layers=2, batch=2 if P < 4000 else 1, n_q_heads=hq, n_kv_heads=hkv, prompt=P, decode_steps=max(W, 10),
+    cfg = _small("tiny", n_layers=L, batch=2 if P < 4000 else 1, n_q_heads=hq, n_kv_heads=hkv, prompt=P, decode_steps=max(W, 10),
                  lam=lam, budget=P + 5, budget_min=8, budget_max=P + 30, seed=300 + W)
     st, o, g = _pair(cfg, cap=(P + 64) // 32 * 32)
     total0 = o.budgets().sum(axis=(0, 2))
@@ -242,7 +245,7 @@ def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam):
             assert sub and differ <= may, (key, sorted(differ), sorted(may))
             parity.sync_unit_to_gpu(g, o, key)
             resync += 1
-    assert resync <= 1
+    assert resync <= 1 + len(o.units) * W // 4000          # sub-margin decisions are rare, not absent
     assert g.time() == P and g.status() == 0
     stats = parity.lockstep(g, o, st, 10, check_kv_every=5)
     assert stats.resynced <= 1, stats.notes
