@@ -432,81 +432,108 @@ def place_pools(pool_bytes, device="cuda:0", max_fraction=0.92, verbose=False, r
     On MI355X the decode kernels run about a tenth slower or faster depending on where their buffers lie in
     physical memory (regions tens of GB wide; plain streaming reads do not see them).  Where an allocation lands
     is the driver's business, but consecutive allocations of a process walk through the memory.  So, once, at
-    start-up: allocate buffers of twice the pool size one after another without freeing any, until
-    `max_fraction` of the device's memory is in use (each is a different piece of memory); time a few
-    attention-only decode steps of a synthetic context whose K and V pools are the buffer's halves (random keys,
-    units of 2048 entries, as many as fit; its other buffers lie wherever the allocator puts them); keep the
-    fastest buffer whose neighbours in allocation order are about as fast (a buffer that straddles a boundary is
-    not wanted) for the pools.  What was measured on this hardware, and is not understood, is that the step is
-    fastest when the other buffers lie in memory of the *other* kind: so the buffer on which the calibration ran
-    slowest is kept for them.  Everything else is freed."""
+    start-up, in two stages.  First: allocate buffers of twice the pool size one after another without freeing
+    any, until `max_fraction` of the device's memory is in use (each is a different piece of memory), and time
+    a few attention-only decode steps of a synthetic context whose K and V pools are the buffer's halves (random
+    keys, units of 2048 entries, as many as fit; its other buffers lie wherever the allocator puts them); the
+    fastest buffers whose neighbours in allocation order are about as fast (a buffer that straddles a boundary
+    is not wanted) are the candidates for the pools.  Second (if rest_bytes > 0): where the other buffers lie
+    matters as well, and not in a way the first stage shows (beside pools in a fast buffer, some fast buffers
+    are bad places for them and the slow ones good ones), so whole decode steps (attention, scores, one
+    eviction per unit) of the synthetic context are timed with the pools in each of the two best candidates and
+    the other buffers in each of up to ten of the rest (the slowest, the fastest, eight at even distances in
+    allocation order), and the fastest pair is kept.  Everything else is freed."""
     import torch
     dev = torch.device(device)
     pool_bytes = (int(pool_bytes) + (2 << 20) - 1) // (2 << 20) * (2 << 20)
     L, Hq, Hkv, n_ent, cap = 1, 32, 8, 2048, 2304
     Bz = int(min(8192, pool_bytes // (cap * 256)) // Hkv)
-    if Bz < 64:
+
+    def unplaced(note):
         k = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
         v = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
         rest = torch.empty(int(rest_bytes), dtype=torch.uint8, device=dev) if rest_bytes > 0 else None
-        return k, v, rest, dict(candidates=0, note="pools too small to matter: not placed")
+        return k, v, rest, dict(candidates=0, note=note)
+
+    if Bz < 64:
+        return unplaced("pools too small to matter: not placed")
     need = Bz * Hkv * cap * 256
     gen = torch.Generator(device=dev)
     gen.manual_seed(1)
     q = torch.randn((L, Bz, Hq, 128), generator=gen, device=dev).to(torch.bfloat16)
     kn = torch.randn((L, Bz, Hkv, 128), generator=gen, device=dev).to(torch.bfloat16)
     kc = torch.randn((Bz, Hkv, n_ent, 128), generator=gen, device=dev).to(torch.bfloat16)
-    budgets = np.full((L, Bz, Hkv), cap - 1, dtype=np.int32)
     out = torch.empty((L, Bz, Hq, 128), dtype=torch.float32, device=dev)
+    b_roomy = np.full((L, Bz, Hkv), cap - 1, dtype=np.int32)       # attention-only steps: nothing is ever evicted
+    b_full = np.full((L, Bz, Hkv), n_ent, dtype=np.int32)         # whole steps: every unit at its budget, one eviction per step
+    own_rest = arena_bytes(L, Bz, Hq, Hkv, 128, cap, b_full, t0=n_ent) - 2 * need      # the synthetic context's other buffers
+
+    def trial(buf, rest=None, whole=False):
+        g = CrystalKV(L, Bz, Hq, Hkv, 128, cap, b_full if whole else b_roomy, t0=n_ent, device=dev, arena=rest,
+                      pools=(buf[:need].view(torch.bfloat16), buf[pool_bytes:pool_bytes + need].view(torch.bfloat16)))
+        g.set_path(3)
+        g.load_prompt(0, kc, kc)
+        reps = 8 if whole else 6
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        step = (lambda: g.decode_step(q, kn, kn, out=out, evict=True)) if whole else \
+               (lambda: g.decode_step(q, kn, kn, out=out, attention_only=True, evict=False))
+        step()
+        ev[0].record()
+        for j in range(reps):
+            step()
+            ev[j + 1].record()
+        torch.cuda.synchronize(dev)
+        ms = float(np.median([ev[j].elapsed_time(ev[j + 1]) for j in range(reps)]))
+        g.close()
+        return ms
+
     torch.cuda.empty_cache()              # what torch holds in reserve counts as in use otherwise
     cands, times, spacers = [], [], []
     # at most 48 candidates: small pools are tried at even distances, with spacers (freed afterwards) between them
+    one = max(2 * pool_bytes, int(rest_bytes))
     free_b, total_b = torch.cuda.mem_get_info(dev)
     span = max(0, int(max_fraction * total_b) - (total_b - free_b))
-    spacer_bytes = max(0, span // 48 - max(2 * pool_bytes, int(rest_bytes))) // (2 << 20) * (2 << 20)
+    spacer_bytes = max(0, span // 48 - one) // (2 << 20) * (2 << 20)
     while True:
         free_b, total_b = torch.cuda.mem_get_info(dev)
-        one = max(2 * pool_bytes, int(rest_bytes))
         if free_b < one + (4 << 30) or (total_b - free_b + one) > max_fraction * total_b:
             break
         buf = torch.empty(one, dtype=torch.uint8, device=dev)
         cands.append(buf)
-        g = CrystalKV(L, Bz, Hq, Hkv, 128, cap, budgets, t0=n_ent, device=dev,
-                      pools=(buf[:need].view(torch.bfloat16), buf[pool_bytes:pool_bytes + need].view(torch.bfloat16)))
-        g.set_path(3)
-        g.load_prompt(0, kc, kc)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
-        g.decode_step(q, kn, kn, out=out, attention_only=True, evict=False)
-        ev[0].record()
-        for j in range(6):
-            g.decode_step(q, kn, kn, out=out, attention_only=True, evict=False)
-            ev[j + 1].record()
-        torch.cuda.synchronize(dev)
-        times.append(float(np.median([ev[j].elapsed_time(ev[j + 1]) for j in range(6)])))
-        g.close()
-        del g
+        times.append(trial(buf))
         free_b, _ = torch.cuda.mem_get_info(dev)
         if spacer_bytes and free_b > spacer_bytes + one + (4 << 30):
             spacers.append(torch.empty(spacer_bytes, dtype=torch.uint8, device=dev))
-    del kc, q, kn, out, spacers
+    del spacers
     if not cands:
-        k = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
-        v = torch.empty(pool_bytes // 2, dtype=torch.bfloat16, device=dev)
-        rest = torch.empty(int(rest_bytes), dtype=torch.uint8, device=dev) if rest_bytes > 0 else None
-        return k, v, rest, dict(candidates=0, note="no room to try placements")
+        del kc, q, kn, out
+        return unplaced("no room to try placements")
     t = np.asarray(times)
     fastest = float(t.min())
     # settled = both neighbours within 1 % of the candidate itself (the ends count their one neighbour)
     ok = [i for i in range(len(t)) if all(abs(t[j] - t[i]) <= 0.01 * t[i] for j in (i - 1, i + 1) if 0 <= j < len(t))]
-    pick = min(ok, key=lambda i: t[i]) if ok and min(t[i] for i in ok) <= 1.01 * fastest else int(np.argmin(t))
+    ranked = sorted((i for i in ok if t[i] <= 1.01 * fastest), key=lambda i: t[i]) or [int(np.argmin(t))]
+    pick, rest_at, pairs = ranked[0], None, []
+    if rest_bytes > 0 and len(cands) > 1 and own_rest <= one:
+        by_time = [int(i) for i in np.argsort(t)]
+        for kv in ranked[:2]:
+            others = [i for i in by_time if i != kv]
+            tried = []
+            spread = [sorted(others)[j * (len(others) - 1) // 7] for j in range(8)] if len(others) > 1 else []
+            for r in [others[-1], others[0]] + spread:
+                if r not in tried:
+                    tried.append(r)
+                    pairs.append((kv, r, trial(cands[kv], cands[r], whole=True)))
+        pick, rest_at, _ = min(pairs, key=lambda x: x[2])
+    del kc, q, kn, out
     buf = cands[pick]
     k = buf[:pool_bytes].view(torch.bfloat16)
-    v = buf[pool_bytes:].view(torch.bfloat16)
-    slowest = int(np.argmax(t))
-    rest = cands[slowest] if rest_bytes > 0 and slowest != pick else None
+    v = buf[pool_bytes:2 * pool_bytes].view(torch.bfloat16)
+    rest = cands[rest_at] if rest_at is not None else None
     report = dict(candidates=len(cands), calibration_units=L * Bz * Hkv, step_ms_min=round(fastest, 4),
                   step_ms_max=round(float(t.max()), 4), step_ms_first=round(float(t[0]), 4), chosen=int(pick),
-                  step_ms_chosen=round(float(t[pick]), 4), rest_in=slowest if rest is not None else None)
+                  step_ms_chosen=round(float(t[pick]), 4), rest_in=rest_at,
+                  whole_step_ms={f"{kv}+{r}": round(ms, 4) for kv, r, ms in pairs})
     if verbose:
         print("place_pools:", report, [round(float(x), 3) for x in t], flush=True)
     del cands, buf
