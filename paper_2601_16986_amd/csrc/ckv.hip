@@ -21,6 +21,7 @@ using namespace ckv;
 
 constexpr int kSide = 2;   // streams of the context's own for deferred bookkeeping
 constexpr int kBookGroup = 8;   // layers whose deferred bookkeeping goes out as one launch
+constexpr size_t kLayerScanPad = 48 << 10;      // dynamic LDS of layer_scan_kernel: with its 32 KB of static LDS, two workgroups per 160 KB
 
 // Scratch of ckv_probe_noalloc: device memory the library owns from the moment it is loaded, so that the
 // call never needs a caller's workspace or an allocation.  In host code `scratch` is only a handle: the
@@ -630,8 +631,11 @@ int ckv_decode_step(ckv_ctx* c, int32_t layer, const void* q, const void* k_new,
       if (int rc = profile_events(c, &e0, &e1)) return rc;
       CKV_HIP(c, hipEventRecord(e0, s));
     }
-    hipLaunchKernelGGL((layer_scan_kernel<4, 1>), dim3((unsigned)count, (unsigned)((c->dev.max_chunks + 3) / 4)), dim3(256), 0, s, c->dev,
-                       begin, (const uint16_t*)q, (const uint16_t*)k_new, (const uint16_t*)v_new, out, (int)layer);
+    // At most two of its workgroups fit on a compute unit (the unused dynamic LDS sees to that): the kernel's
+    // registers would allow three, and the dispatcher then crowds some compute units while others idle
+    // (2.43 against 2.11 ms per step of 48 layers of 128 units; one per compute unit: 2.22).
+    hipLaunchKernelGGL((layer_scan_kernel<4, 1>), dim3((unsigned)count, (unsigned)((c->dev.max_chunks + 3) / 4)), dim3(256), kLayerScanPad, s,
+                       c->dev, begin, (const uint16_t*)q, (const uint16_t*)k_new, (const uint16_t*)v_new, out, (int)layer);
     CKV_HIP(c, hipGetLastError());
     if (c->profile) CKV_HIP(c, hipEventRecord(e1, s));
     if (advance) {

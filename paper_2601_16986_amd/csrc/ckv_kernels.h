@@ -1031,32 +1031,39 @@ __global__ __launch_bounds__(kThreads, 2) void scan_kernel(Dev d, int unit_begin
 // scan_kernel<true>).  The unit's softmax maximum and 1 / sum per head stay in `msum` for the bookkeeping.
 // kW wavefronts per workgroup, each over 1 / kSplit of a chunk; the text above describes <4, 1>, the shape in
 // use.  Measured beside it on 128 units of 257 .. 8193 entries: fewer wavefronts per workgroup (<2, 1>, <1, 1>)
-// 2 % and 15 % slower per step, more (<8, 1>) 8 %, shorter spans (<4, 2>, <8, 2>, <8, 4>) 8 %, 23 % and 49 %;
-// rotating the units against the chunk groups, or the long units' last chunks first: no difference.
+// 2 % and 15 % slower per step, more (<8, 1>) 8 %, shorter spans (<4, 2>, <8, 2>, <8, 4>) 8 %, 23 % and 49 %
+// (also with three wavefronts per SIMD); rotating the units against the chunk groups, or the long units' last
+// chunks first: no difference.  What does matter is how many workgroups a compute unit may hold: see the launch.
 // grid: (units of the layer, ceil(max_chunks * kSplit / kW)), 64 kW threads.
-__device__ __forceinline__ void inject_entry(KFrag& ka, VFrag& va, int rr, const u32x4 (&knew)[4], const uint32_t (&vnew)[8], int lane) {
+// Entry rr of the block in (ka, va) is replaced by the rows in `rows` (LDS: 128 bf16 of the key, then 128 of the
+// value), piece by piece, so that few registers are live at a time.
+__device__ __forceinline__ void inject_entry(KFrag& ka, VFrag& va, int rr, const uint16_t* rows, int lane) {
   const int j = lane & 15, kg = lane >> 4;
   const int tt = rr >> 4;
   const bool krow = j == (rr & 15);
 #pragma unroll
-  for (int h = 0; h < 2; ++h)
+  for (int s = 0; s < 4; ++s) {
+    const u32x4 kn = *reinterpret_cast<const u32x4*>(rows + 32 * s + 8 * kg);
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      if (krow && h == tt) ka.k[h * 4 + s] = knew[s];
+    for (int h = 0; h < 2; ++h)
+      if (krow && h == tt) ka.k[h * 4 + s] = kn;
+  }
   const bool vrow = kg == ((rr & 15) >> 2);
   const int e = tt * 4 + (rr & 3);
 #pragma unroll
-  for (int dt = 0; dt < 8; ++dt)
+  for (int dt = 0; dt < 8; ++dt) {
+    const uint32_t vn = rows[kDim + 16 * dt + j];
 #pragma unroll
     for (int wi = 0; wi < 4; ++wi) {
       const uint32_t old = va.v[dt][wi];
-      const uint32_t nw = (e & 1) ? ((old & 0x0000FFFFu) | (vnew[dt] << 16)) : ((old & 0xFFFF0000u) | vnew[dt]);
+      const uint32_t nw = (e & 1) ? ((old & 0x0000FFFFu) | (vn << 16)) : ((old & 0xFFFF0000u) | vn);
       va.v[dt][wi] = (vrow && wi == (e >> 1)) ? nw : old;
     }
+  }
 }
 
 template <int kW, int kSplit>
-__global__ __launch_bounds__(64 * kW, 1) void layer_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(64 * kW, 3) void layer_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q,
                                                                 const uint16_t* __restrict__ k_new,
                                                                 const uint16_t* __restrict__ v_new, void* out, int layer) {
   constexpr int kT = 64 * kW;
@@ -1065,6 +1072,7 @@ __global__ __launch_bounds__(64 * kW, 1) void layer_scan_kernel(Dev d, int unit_
   __shared__ float s_m[kW][kMaxGroup], s_l[kW][kMaxGroup];
   __shared__ float s_acc[kW][kMaxGroup * kDim];
   __shared__ float s_w[2 * kMaxChunks * kMaxGroup], s_M[kMaxGroup], s_L[kMaxGroup];
+  __shared__ __align__(16) uint16_t s_new[kW][2 * kDim];
   __shared__ int s_last;
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int urel = blockIdx.x, u = unit_begin + urel, cg = blockIdx.y;
@@ -1111,26 +1119,22 @@ __global__ __launch_bounds__(64 * kW, 1) void layer_scan_kernel(Dev d, int unit_
         qv[s] = as_bf16x8(x);
       }
     }
-    u32x4 knew[4] = {};
-    uint32_t vnew[8] = {};
+    // The new entry's rows wait in LDS for their block's turn (the span's last): held in registers through the
+    // loop they would cost the kernel a third wavefront per SIMD.  They also go into the cache, where the next
+    // step finds them.
     if (inject) {
-      const uint16_t* kr = k_new + (size_t)urel * kDim + 8 * kg;
-      const uint16_t* vr = v_new + (size_t)urel * kDim + j;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) knew[s] = *reinterpret_cast<const u32x4*>(kr + 32 * s);
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) vnew[dt] = vr[16 * dt];
-      // the rows also go into the cache, where the next step finds them
-      uint16_t* kdst = d.K + (size_t)my_seg * kSegElems;         // n_old lies in this span
+      const int row = s0 + n_old - e0;                          // n_old lies in this span
+      if (lane < 32) {
+        const int piece = lane & 15;
+        const uint16_t* src = (lane < 16 ? k_new : v_new) + (size_t)urel * kDim + piece * 8;
+        const u32x4 x = *reinterpret_cast<const u32x4*>(src);
+        *reinterpret_cast<u32x4*>(&s_new[w][(lane < 16 ? 0 : kDim) + piece * 8]) = x;
+        if (lane < 16) *reinterpret_cast<u32x4*>(d.K + (size_t)my_seg * kSegElems + k_offset(row, piece * 8)) = x;
+      }
       uint16_t* vdst = d.V + (size_t)my_seg * kSegElems;
-      if (j == 0) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) *reinterpret_cast<u32x4*>(kdst + k_offset(s0 + n_old - e0, 32 * s + 8 * kg)) = knew[s];
-      }
-      if (kg == 0) {
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) vdst[v_offset(s0 + n_old - e0, 16 * dt + j)] = (uint16_t)vnew[dt];
-      }
+      vdst[v_offset(row, lane)] = v_new[(size_t)urel * kDim + lane];
+      vdst[v_offset(row, lane + 64)] = v_new[(size_t)urel * kDim + lane + 64];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     }
     float* lds_lg = s_lg[w];
     float* lg_dst = d.logits + ((size_t)u * d.cap + (size_t)e0) * G + 4 * min(lane, 8 * G - 1);
@@ -1139,7 +1143,10 @@ __global__ __launch_bounds__(64 * kW, 1) void layer_scan_kernel(Dev d, int unit_
     for (int blk = 0; blk < nb; ++blk) {
       const bool last = blk + 1 == nb;
       const size_t nxt = (size_t)(last ? blk : blk + 1) * kBlkElems;
-      if (last && inject) inject_entry(ka, va, (n_old - e0) & 31, knew, vnew, lane);
+      if (last && inject) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        inject_entry(ka, va, (n_old - e0) & 31, s_new[w], lane);
+      }
       float sv[8];
       scan_qk(ka, qv, sv, d.scale_log2e, blk * kBlk, nv, lds_lg, kLgRow, lg_dst, G, lane);
       load_k(ka, kcur + nxt);
@@ -1233,7 +1240,7 @@ __global__ __launch_bounds__(64 * kW, 1) void layer_scan_kernel(Dev d, int unit_
   if (!s_last) return;
   // the partials' values are asked for first, kRound partials at a time; their maxima and sums go through LDS,
   // where every head's overall maximum, the partials' weights and the sum's reciprocal are formed once
-  constexpr int kRound = 64 / kPer < 16 ? 64 / kPer : 16;
+  constexpr int kRound = 32 / kPer < 8 ? 32 / kPer : 8;
   static_assert(kW >= kSplit, "a unit has one partial slot per chunk");
   float x[kRound][kPer];
   auto request = [&](int r0) {
