@@ -244,8 +244,8 @@ def test_caller_owned_pools_and_a_single_arena_give_the_same_results():
 
 def test_place_pools_returns_usable_buffers_and_a_report():
     """The start-up calibration: buffers of the requested sizes come back (K and V pools, and memory for the other
-    five buffers), the report says what was tried, and a context built on them gives the bits of a context with
-    buffers of its own.  Pools too small to matter are simply allocated."""
+    five buffers), the report says what was tried in both stages, and a context built on them gives the bits of a
+    context with buffers of its own.  Pools too small to matter are simply allocated."""
     import torch
     _, ckv, wl = _mods()
     k, v, rest, rep = ckv.place_pools(8 << 20, rest_bytes=1 << 20)
@@ -262,6 +262,10 @@ def test_place_pools_returns_usable_buffers_and_a_report():
     k, v, rest, rep = ckv.place_pools(ps * 256, rest_bytes=rest_bytes, max_fraction=0.4)
     assert 2 <= rep["candidates"] <= 48 and rep["step_ms_min"] <= rep["step_ms_chosen"] <= rep["step_ms_max"]
     assert k.numel() >= ps * 128 and v.numel() >= ps * 128 and rest.numel() >= rest_bytes
+    # second stage: whole steps over pairs (pools, other buffers); the fastest pair is the one returned
+    pairs = rep["whole_step_ms"]
+    assert len(pairs) >= 2 and rep["rest_in"] is not None and rep["rest_in"] != rep["chosen"]
+    assert pairs[f"{rep['chosen']}+{rep['rest_in']}"] == min(pairs.values())
     placed = ckv.CrystalKV(*geom, pools=(k[:ps * 128], v[:ps * 128]), arena=rest, **kw)
     for g in (plain, placed):
         for l in range(cfg.n_layers):
