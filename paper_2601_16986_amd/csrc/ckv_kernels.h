@@ -172,43 +172,16 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
 // Barrier among the NT threads that work on one unit.  NT = 64: a single wavefront, which may be one of
 // several in its workgroup and must not touch the workgroup barrier: its LDS and memory operations
 // already execute in program order, only the compiler has to keep them so.
-//
-// SB = 1: the NT threads are some of the wavefronts of a workgroup whose other wavefronts do something
-// else meanwhile (unit_kernel_split's book-keepers), so the workgroup barrier is not theirs to use.  They
-// meet at a counter in LDS instead: every wavefront adds one on arrival and leaves when the count reaches
-// the next multiple of NT / 64.  All of them are resident and none waits for anything else, so the wait
-// ends; it is bounded all the same (kSoftLimit polls, then `soft_fail` is raised and the kernel reports
-// it through the context's status word instead of hanging).
 struct alignas(16) RedBuf {
   u64 v[2][8];          // one slot per wavefront: up to 512 threads
   float t[2][8][4];
-  int soft;         // arrivals at the counter barrier since the kernel began
-  int soft_fail;    // a counter barrier gave up waiting
 };
-constexpr int kSoftLimit = 1 << 20;
 
-template <int NT, int SB = 0>
+template <int NT>
 __device__ __forceinline__ void block_sync(RedBuf& rb) {
   if constexpr (NT == 64) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-  } else if constexpr (SB == 1) {
-    constexpr int kWaves = NT / 64;
-    static_assert((kWaves & (kWaves - 1)) == 0, "power of two");
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    int old = 0;
-    if ((threadIdx.x & 63) == 0) old = __hip_atomic_fetch_add(&rb.soft, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    const int target = (__builtin_amdgcn_readfirstlane(old) & ~(kWaves - 1)) + kWaves;
-    int polls = 0;
-    while (__hip_atomic_load(&rb.soft, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target) {
-      __builtin_amdgcn_s_sleep(1);
-      // give up after kSoftLimit polls, and at once if a barrier has given up before (then nothing is in step any more)
-      if (++polls > kSoftLimit || __hip_atomic_load(&rb.soft_fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0) {
-        __hip_atomic_store(&rb.soft_fail, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        break;
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   } else {
     __syncthreads();
   }
@@ -217,12 +190,12 @@ __device__ __forceinline__ void block_sync(RedBuf& rb) {
 // Block-wide reductions over NT threads with a fixed combination order
 // (deterministic).  `rb` is a [2][NT/64] LDS array used alternately, so one
 // barrier per call suffices.  NT = 64: the wavefront's own reduction, nothing else.
-template <int NT = kThreads, int SB = 0>
+template <int NT = kThreads>
 __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_u64(v);
   if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
-  block_sync<NT, SB>(rb);
+  block_sync<NT>(rb);
   u64 r = rb.v[phase][0];
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r += rb.v[phase][w];
@@ -230,12 +203,12 @@ __device__ __forceinline__ u64 block_sum_u64(u64 v, RedBuf& rb, int& phase, int 
   return r;
 }
 
-template <int NT = kThreads, int SB = 0>
+template <int NT = kThreads>
 __device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_i32(v);
   if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)(uint32_t)v;
-  block_sync<NT, SB>(rb);
+  block_sync<NT>(rb);
   int r = (int)(uint32_t)rb.v[phase][0];
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r += (int)(uint32_t)rb.v[phase][w];
@@ -243,12 +216,12 @@ __device__ __forceinline__ int block_sum_int(int v, RedBuf& rb, int& phase, int 
   return r;
 }
 
-template <int NT = kThreads, int SB = 0>
+template <int NT = kThreads>
 __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, int tid) {
   v = wave_sum_f32(v);
   if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = (u64)__float_as_uint(v);
-  block_sync<NT, SB>(rb);
+  block_sync<NT>(rb);
   float r = __uint_as_float((uint32_t)rb.v[phase][0]);
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r += __uint_as_float((uint32_t)rb.v[phase][w]);
@@ -257,14 +230,14 @@ __device__ __forceinline__ float block_sum_f32(float v, RedBuf& rb, int& phase, 
 }
 
 // Three sums at once (one barrier).
-template <int NT = kThreads, int SB = 0>
+template <int NT = kThreads>
 __device__ __forceinline__ void block_sum3_f32(float& x, float& y, float& z, RedBuf& rb, int& phase, int tid) {
   x = wave_sum_f32(x);
   y = wave_sum_f32(y);
   z = wave_sum_f32(z);
   if constexpr (NT == 64) return;
   if ((tid & 63) == 0) *reinterpret_cast<f32x4*>(rb.t[phase][tid >> 6]) = f32x4{x, y, z, 0.f};
-  block_sync<NT, SB>(rb);
+  block_sync<NT>(rb);
   f32x4 r = *reinterpret_cast<const f32x4*>(rb.t[phase][0]);
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) {
@@ -279,12 +252,12 @@ __device__ __forceinline__ void block_sum3_f32(float& x, float& y, float& z, Red
   phase ^= 1;
 }
 
-template <int NT = kThreads, int SB = 0>
+template <int NT = kThreads>
 __device__ __forceinline__ u64 block_min_u64(u64 v, RedBuf& rb, int& phase, int tid) {
   v = wave_min_u64(v);
   if constexpr (NT == 64) return v;
   if ((tid & 63) == 0) rb.v[phase][tid >> 6] = v;
-  block_sync<NT, SB>(rb);
+  block_sync<NT>(rb);
   u64 r = rb.v[phase][0];
 #pragma unroll
   for (int w = 1; w < NT / 64; ++w) r = rb.v[phase][w] < r ? rb.v[phase][w] : r;
@@ -1455,7 +1428,7 @@ struct ValLinear {
 // Alg. 1 Step 4 for one unit with n > B.  val(i) = CRF_temp of slot i (LDS),
 // evm = LDS bit mask of n bits, lst = LDS scratch of lst_cap >= n ints that may
 // overlap the storage behind `val` (the scores are dead by the time it is used).
-template <class Val, int NT = kThreads, int SB = 0>
+template <class Val, int NT = kThreads>
 __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int n, int B, Val val, uint32_t* evm, int* lst, int lst_cap, RedBuf& rb,
                             int& phase, int* sh, int tid) {
   const int lane = tid & 63, wave = tid >> 6;
@@ -1482,9 +1455,9 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int
         }
       }
     }
-    const u64 gbest = block_min_u64<NT, SB>(best, rb, phase, tid);
+    const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
     if (best == gbest && best_i >= 0) sh[0] = best_i;     // keys are unique: one writer
-    block_sync<NT, SB>(rb);
+    block_sync<NT>(rb);
     const int e = sh[0];
     if (wave == 0) {
       if (e != n - 1) {
@@ -1508,7 +1481,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int
         n2 += b < c2 ? 1.f : 0.f;
         n3 += b < c3 ? 1.f : 0.f;
       }
-      block_sum3_f32<NT, SB>(n1, n2, n3, rb, phase, tid);
+      block_sum3_f32<NT>(n1, n2, n3, rb, phase, tid);
       const float kf = (float)k;
       S = n3 < kf ? c3 : n2 < kf ? c2 : n1 < kf ? c1 : S;          // the largest pattern with fewer than k scores below it
     }
@@ -1518,7 +1491,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int
       below += b < S ? 1.f : 0.f;
       equal += b == S ? 1.f : 0.f;
     }
-    block_sum3_f32<NT, SB>(below, equal, unused, rb, phase, tid);
+    block_sum3_f32<NT>(below, equal, unused, rb, phase, tid);
     const int r = k - (int)below;                                  // of the entries equal to S, the r highest positions go
     uint32_t P = 0xFFFFFFFFu;                                      // ... those with ~position <= P
     if (r < (int)equal) {
@@ -1534,19 +1507,19 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int
             n3 += np < c3 ? 1.f : 0.f;
           }
         }
-        block_sum3_f32<NT, SB>(n1, n2, n3, rb, phase, tid);
+        block_sum3_f32<NT>(n1, n2, n3, rb, phase, tid);
         const float rf = (float)r;
         P = n3 < rf ? c3 : n2 < rf ? c2 : n1 < rf ? c1 : P;
       }
     }
     const int words = (n + 31) >> 5;
     for (int w = tid; w < words; w += NT) evm[w] = 0u;
-    block_sync<NT, SB>(rb);
+    block_sync<NT>(rb);
     for (int i = tid; i < n; i += NT) {
       const uint32_t b = __float_as_uint(val(i));
       if (b < S || (b == S && (P == 0xFFFFFFFFu || ~(uint32_t)d.pos[base + i] <= P))) atomicOr(&evm[i >> 5], 1u << (i & 31));
     }
-    block_sync<NT, SB>(rb);
+    block_sync<NT>(rb);
     // holes = evicted slots below B, movers = surviving slots at or above B (equal counts)
     const int wpt = (words + NT - 1) / NT;
     const int w0 = min(words, tid * wpt), w1 = min(words, w0 + wpt);
@@ -1567,7 +1540,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int
       if (lane >= o) incl += y;
     }
     if (lane == 63) sh[4 + wave] = (int)incl;
-    block_sync<NT, SB>(rb);
+    block_sync<NT>(rb);
     uint32_t prefix = 0, total = 0;
 #pragma unroll
     for (int w = 0; w < NT / 64; ++w) {
@@ -1592,7 +1565,7 @@ __device__ __forceinline__ void evict_phase(const Dev& d, int u, Slots base, int
         mm &= mm - 1;
       }
     }
-    block_sync<NT, SB>(rb);
+    block_sync<NT>(rb);
     // evicted entries that already sit at or above B just get their flag
     for (int i = B + tid; i < n; i += NT)
       if ((evm[i >> 5] >> (i & 31)) & 1u) d.flags[base + i] = FLAG_SLIP;
@@ -1780,7 +1753,7 @@ struct HitRule {
 };
 
 // Step 1 over weights in val(0 .. n - 1) (LDS), any n
-template <class Val, int NT = kThreads, int SB = 0>
+template <class Val, int NT = kThreads>
 __device__ __forceinline__ HitRule top_p_lds(const Dev& d, Slots base, int n, Val val, RedBuf& rb, int& phase, int tid) {
   uint32_t theta = 0;
   bool ties_all = true;
@@ -1793,7 +1766,7 @@ __device__ __forceinline__ HitRule top_p_lds(const Dev& d, Slots base, int n, Va
         const float a = val(i);
         part += (__float_as_uint(a) >= cand) ? a : 0.f;
       }
-      const float tot = block_sum_f32<NT, SB>(part, rb, phase, tid);
+      const float tot = block_sum_f32<NT>(part, rb, phase, tid);
       if (tot > d.top_p) theta = cand;
     }
     if (theta != 0) {
@@ -1806,8 +1779,8 @@ __device__ __forceinline__ HitRule top_p_lds(const Dev& d, Slots base, int n, Va
         above += (b > theta) ? a : 0.f;
         ties += (b == theta) ? 1 : 0;
       }
-      above = block_sum_f32<NT, SB>(above, rb, phase, tid);
-      ties = block_sum_int<NT, SB>(ties, rb, phase, tid);
+      above = block_sum_f32<NT>(above, rb, phase, tid);
+      ties = block_sum_int<NT>(ties, rb, phase, tid);
       if (ties > 1) {
         const float th = __uint_as_float(theta);
         float c = above;
@@ -1824,7 +1797,7 @@ __device__ __forceinline__ HitRule top_p_lds(const Dev& d, Slots base, int n, Va
             int cnt = 0;
             for (int i = tid; i < n; i += NT)
               cnt += (__float_as_uint(val(i)) == theta && d.pos[base + i] < trial) ? 1 : 0;
-            cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
+            cnt = block_sum_int<NT>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
           }
           pos_cut = X;
@@ -1835,11 +1808,11 @@ __device__ __forceinline__ HitRule top_p_lds(const Dev& d, Slots base, int n, Va
   return HitRule{theta, ties_all, pos_cut};
 }
 
-template <class Val, int NT = kThreads, int SB = 0>
+template <class Val, int NT = kThreads>
 __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int n, int t, Val val, const float* s_tab, int s_tab_n, RedBuf& rb,
                            int& phase, int tid) {
   // ---- Alg. 1 Step 1: top-p hit set as a threshold on the weight's bit pattern
-  const HitRule rule = top_p_lds<Val, NT, SB>(d, base, n, val, rb, phase, tid);
+  const HitRule rule = top_p_lds<Val, NT>(d, base, n, val, rb, phase, tid);
   const bool ties_all = rule.ties_all;
 
   // ---- Alg. 1 Steps 2-3: scores (4 entries per thread and round: loads, table lookups, then stores)
@@ -1891,7 +1864,7 @@ __device__ __forceinline__ u64 lrfu_update(const Dev& d, int u, Slots base, int 
       }
     }
   }
-  return block_sum_u64<NT, SB>(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
+  return block_sum_u64<NT>(sfix, rb, phase, tid);   // its barrier also completes val() for what follows
 }
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -1985,7 +1958,7 @@ __device__ __forceinline__ EntryRow load_row_input(const NewEntry& ne, int tid) 
 // Step 1 over weights in registers (a[4 c + e] = mean weight of entry 4 (tid + c NT) + e, 0 beyond n).  lst: 64 ints of
 // LDS (lst_cap >= 64, or the short list is not used); sh: the callers' exchange words (5 .. 7 are used here).
 // new_last_t >= 0: the unit's last entry is not in the cache and has this position.
-template <int R, int NT = kThreads, int SB = 0>
+template <int R, int NT = kThreads>
 __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, const float (&a)[R], int* lst, int lst_cap, int new_last_t,
                                               RedBuf& rb, int& phase, int* sh, int tid) {
   uint32_t theta = 0;
@@ -2005,7 +1978,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
         p2 += (b >= c2) ? a[k] : 0.f;
         p3 += (b >= c3) ? a[k] : 0.f;
       }
-      block_sum3_f32<NT, SB>(p1, p2, p3, rb, phase, tid);
+      block_sum3_f32<NT>(p1, p2, p3, rb, phase, tid);
       theta = p3 > d.top_p ? c3 : p2 > d.top_p ? c2 : p1 > d.top_p ? c1 : theta;
     };
     constexpr int kListBit = 17;        // the rounds for the bits above this one run over all entries
@@ -2032,7 +2005,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
       ab = wave_sum_f32(ab);
       mine = wave_sum_i32(mine);
       if (lane == 0) *reinterpret_cast<f32x4*>(rb.t[phase][wave]) = f32x4{ab, __int_as_float(mine), 0.f, 0.f};
-      block_sync<NT, SB>(rb);
+      block_sync<NT>(rb);
       float above_bucket = 0.f;
       int m = 0, off = 0;
 #pragma unroll
@@ -2054,7 +2027,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
           if (in) lst[r] = (int)b;
           off += __popcll(mask);
         }
-        block_sync<NT, SB>(rb);
+        block_sync<NT>(rb);
         if (wave == 0) {
           // One candidate per lane.  The largest pattern theta with sum{a >= theta} > p is a candidate's own
           // pattern: the largest one whose sum of candidates at least as large, on top of what lies above the
@@ -2081,7 +2054,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
             sh[6] = __float_as_int(above_l);
           }
         }
-        block_sync<NT, SB>(rb);
+        block_sync<NT>(rb);
         theta = (uint32_t)sh[7];
         list_ties = sh[5];
         list_above = __int_as_float(sh[6]);
@@ -2102,8 +2075,8 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
           above += (b > theta) ? a[k] : 0.f;
           ties += (b == theta) ? 1 : 0;
         }
-        above = block_sum_f32<NT, SB>(above, rb, phase, tid);
-        ties = block_sum_int<NT, SB>(ties, rb, phase, tid);
+        above = block_sum_f32<NT>(above, rb, phase, tid);
+        ties = block_sum_int<NT>(ties, rb, phase, tid);
       }
       if (ties > 1) {
         const float th = __uint_as_float(theta);
@@ -2123,7 +2096,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
               const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
               if (__float_as_uint(a[k]) == theta && i < n && ((new_last_t >= 0 && i == n - 1) ? new_last_t : d.pos[base + i]) < trial) ++cnt;
             }
-            cnt = block_sum_int<NT, SB>(cnt, rb, phase, tid);
+            cnt = block_sum_int<NT>(cnt, rb, phase, tid);
             if (cnt < r) X = trial;
           }
           pos_cut = X;
@@ -2136,7 +2109,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
 
 // `after_step1` runs once between Step 1 and the score update (the fused kernel
 // picks up its queue claim there).
-template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook, int SB = 0>
+template <int R, int CH, int CP, class Val, int NT = kThreads, class Hook = NoHook>
 __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n, int B, int t, float (&a)[R], f32x4 (&crf)[CH],
                                           i32x4 (&tau)[CH], i32x4 (&ps)[CH], Val val, bool evict, uint32_t* evm, int* lst,
                                           int lst_cap, const float* s_tab, int s_tab_n, RedBuf& rb, int& phase, int* sh,
@@ -2153,7 +2126,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
   EntryRow last_row{{0u, 0u, 0u, 0u}, 0, 0};
   if (evict_single) last_row = new_in_regs ? load_row_input<NT>(ne, tid) : load_row<NT>(d, base, n - 1, tid);
   // ---- Step 1: top-p hit set as a threshold on the weight's bit pattern
-  const HitRule rule = top_p_regs<R, NT, SB>(d, base, n, a, lst, lst_cap, new_in_regs ? t : -1, rb, phase, sh, tid);
+  const HitRule rule = top_p_regs<R, NT>(d, base, n, a, lst, lst_cap, new_in_regs ? t : -1, rb, phase, sh, tid);
   after_step1();
   // ---- Steps 2-3: scores; a[k] becomes CRF_temp.  The candidate for Step 4 (lowest score, then
   // highest position) is tracked on the way.
@@ -2229,7 +2202,7 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
       }
     }
   }
-  sfix = block_sum_u64<NT, SB>(sfix, rb, phase, tid);
+  sfix = block_sum_u64<NT>(sfix, rb, phase, tid);
   if (tid == 0) {
     d.window[u] = window0 + sfix;
     d.t_unit[u] = t;
@@ -2240,12 +2213,12 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
     return;
   }
   if (evict_single) {
-    const u64 gbest = block_min_u64<NT, SB>(best, rb, phase, tid);
+    const u64 gbest = block_min_u64<NT>(best, rb, phase, tid);
     if (best == gbest && best_i >= 0) {     // keys are unique: one writer
       sh[0] = best_i;
       sh[4] = ~(int)(uint32_t)best;         // the victim's position
     }
-    block_sync<NT, SB>(rb);
+    block_sync<NT>(rb);
     evict_one<NT>(d, base, n - 1, sh[0], sh, tid, last_row);
     if (tid == 0) {
       d.n[u] = B;
@@ -2257,8 +2230,8 @@ __device__ __forceinline__ void lrfu_regs(const Dev& d, int u, Slots base, int n
       const int i = 4 * (tid + (k >> 2) * NT) + (k & 3);
       if (i < n) val(i) = a[k];
     }
-    block_sync<NT, SB>(rb);
-    evict_phase<Val, NT, SB>(d, u, base, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
+    block_sync<NT>(rb);
+    evict_phase<Val, NT>(d, u, base, n, B, val, evm, lst, lst_cap, rb, phase, sh, tid);
   }
 }
 
