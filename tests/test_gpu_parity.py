@@ -256,14 +256,15 @@ def test_seed_prompt_matches_oracle_then_decodes(hq, hkv, P, W, lam, L):
     g.close()
 
 
-def test_seed_prompt_with_the_attention_weighted_reward():
-    """The labelled reward variant through the prompt replay: every entry's score accumulates its mean
-    weights (within 1e-5 relative of the oracle's, as for decode steps), tau = P - 1 for every entry."""
+@pytest.mark.parametrize("L,P,W", [(1, 77, 12), (24, 300, 20)])
+def test_seed_prompt_with_the_attention_weighted_reward(L, P, W):
+    """The labelled reward variant through the prompt replay (one tile of queries at a time in a context of one
+    layer, a batch of several tiles in one of 24): every entry's score accumulates its mean weights (within
+    1e-5 relative of the oracle's, as for decode steps), tau = P - 1 for every entry."""
     ok, _, _ = _mods()
-    P, W = 77, 12
-    cfg = _small("tiny", n_layers=1, n_q_heads=10, n_kv_heads=2, prompt=P, decode_steps=W, budget=P + 5, budget_min=8,
+    cfg = _small("tiny", n_layers=L, n_q_heads=10, n_kv_heads=2, prompt=P, decode_steps=W, budget=P + 5, budget_min=8,
                  budget_max=P + 30, seed=91)
-    st, o, g = _pair(cfg, cap=128, reward_mode=ok.REWARD_ATTN_WEIGHTED)
+    st, o, g = _pair(cfg, cap=(P + 64) // 32 * 32, reward_mode=ok.REWARD_ATTN_WEIGHTED)
     o.seed_prompt(0, st.q[:W, 0])
     g.seed_prompt(0, st.q[:W, 0])
     for key, u in o.units.items():
