@@ -1958,7 +1958,9 @@ __device__ __forceinline__ EntryRow load_row_input(const NewEntry& ne, int tid) 
 // Step 1 over weights in registers (a[4 c + e] = mean weight of entry 4 (tid + c NT) + e, 0 beyond n).  lst: 64 ints of
 // LDS (lst_cap >= 64, or the short list is not used); sh: the callers' exchange words (5 .. 7 are used here).
 // new_last_t >= 0: the unit's last entry is not in the cache and has this position.
-template <int R, int NT = kThreads>
+// kList: candidates the short list may hold (64: one per lane of the wavefront that finishes the bisection;
+// 128, 256: two or four per lane, for long units with flat weights, whose bucket holds more).
+template <int R, int NT = kThreads, int kList = 64>
 __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, const float (&a)[R], int* lst, int lst_cap, int new_last_t,
                                               RedBuf& rb, int& phase, int* sh, int tid) {
   uint32_t theta = 0;
@@ -1988,7 +1990,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
     float list_above = 0.f;             //   total weight of the entries above theta
     for (; bit > kListBit; bit -= 2) round(bit);
     // With the top 12 bits fixed, the weights that can still decide a candidate, those in
-    // [theta, theta + 2^18), are usually a handful.  If at most 64, they are collected in LDS (in a fixed
+    // [theta, theta + 2^18), are usually a handful.  If at most kList, they are collected in LDS (in a fixed
     // order: by wavefront, register index, lane) and one wavefront finishes the bisection on them alone:
     // nine rounds without barriers over one register instead of R.
     {
@@ -2017,7 +2019,7 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
         m += cw;
       }
       phase ^= 1;
-      if (m <= 64 && lst_cap >= 64) {
+      if (m <= kList && lst_cap >= kList) {
 #pragma unroll
         for (int k = 0; k < R; ++k) {
           const uint32_t b = __float_as_uint(a[k]);
@@ -2034,24 +2036,62 @@ __device__ __forceinline__ HitRule top_p_regs(const Dev& d, Slots base, int n, c
           // bucket, exceeds p (what the remaining rounds of the bisection would arrive at).  Every entry
           // equal to theta is in the list too, so the number of such ties and the weight above theta are
           // known here as well, without two more reductions over all entries.
-          const uint32_t bj = lane < m ? (uint32_t)lst[lane] : 0u;
-          const float aj = __uint_as_float(bj);
-          float sj = 0.f;
-          for (int k = 0; k < m; ++k) {                       // m is uniform; candidates in list order
-            const uint32_t bk = (uint32_t)__builtin_amdgcn_readlane((int)bj, k);
-            sj += (bk >= bj) ? __uint_as_float(bk) : 0.f;
-          }
-          const uint32_t mine_ok = (lane < m && above_bucket + sj > d.top_p) ? bj : 0u;
-          uint32_t th = mine_ok;
+          if constexpr (kList == 64) {
+            const uint32_t bj = lane < m ? (uint32_t)lst[lane] : 0u;
+            const float aj = __uint_as_float(bj);
+            float sj = 0.f;
+            for (int k = 0; k < m; ++k) {                       // m is uniform; candidates in list order
+              const uint32_t bk = (uint32_t)__builtin_amdgcn_readlane((int)bj, k);
+              sj += (bk >= bj) ? __uint_as_float(bk) : 0.f;
+            }
+            const uint32_t mine_ok = (lane < m && above_bucket + sj > d.top_p) ? bj : 0u;
+            uint32_t th = mine_ok;
 #pragma unroll
-          for (int o = 32; o > 0; o >>= 1) th = max(th, (uint32_t)__shfl_xor((int)th, o));
-          if (th != 0u) theta = th;
-          const int n_ties = __popcll(__ballot(lane < m && bj == theta));
-          const float above_l = above_bucket + wave_sum_f32((lane < m && bj > theta) ? aj : 0.f);
-          if (lane == 0) {
-            sh[7] = (int)theta;
-            sh[5] = n_ties;
-            sh[6] = __float_as_int(above_l);
+            for (int o = 32; o > 0; o >>= 1) th = max(th, (uint32_t)__shfl_xor((int)th, o));
+            if (th != 0u) theta = th;
+            const int n_ties = __popcll(__ballot(lane < m && bj == theta));
+            const float above_l = above_bucket + wave_sum_f32((lane < m && bj > theta) ? aj : 0.f);
+            if (lane == 0) {
+              sh[7] = (int)theta;
+              sh[5] = n_ties;
+              sh[6] = __float_as_int(above_l);
+            }
+          } else {
+            // the same with kList / 64 candidates per lane (candidate lane + 64 c), the others read from LDS
+            constexpr int kC = kList / 64;
+            uint32_t bj[kC];
+            float sj[kC];
+#pragma unroll
+            for (int c = 0; c < kC; ++c) {
+              bj[c] = lane + 64 * c < m ? (uint32_t)lst[lane + 64 * c] : 0u;
+              sj[c] = 0.f;
+            }
+            for (int k = 0; k < m; ++k) {                     // candidates in list order
+              const uint32_t bk = (uint32_t)lst[k];
+              const float ak = __uint_as_float(bk);
+#pragma unroll
+              for (int c = 0; c < kC; ++c) sj[c] += (bk >= bj[c]) ? ak : 0.f;
+            }
+            uint32_t th = 0u;
+#pragma unroll
+            for (int c = 0; c < kC; ++c) th = max(th, (lane + 64 * c < m && above_bucket + sj[c] > d.top_p) ? bj[c] : 0u);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) th = max(th, (uint32_t)__shfl_xor((int)th, o));
+            if (th != 0u) theta = th;
+            int n_ties = 0;
+            float mine_above = 0.f;
+#pragma unroll
+            for (int c = 0; c < kC; ++c) {
+              const bool in = lane + 64 * c < m;
+              n_ties += __popcll(__ballot(in && bj[c] == theta));
+              mine_above += (in && bj[c] > theta) ? __uint_as_float(bj[c]) : 0.f;
+            }
+            const float above_l = above_bucket + wave_sum_f32(mine_above);
+            if (lane == 0) {
+              sh[7] = (int)theta;
+              sh[5] = n_ties;
+              sh[6] = __float_as_int(above_l);
+            }
           }
         }
         block_sync<NT>(rb);
@@ -2498,7 +2538,7 @@ __device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int 
       }
     }
   }
-  const HitRule rule = top_p_regs<R, kSeedThreads>(d, base, n, a, lst, lst_cap, -1, rb, phase, sh, tid);
+  const HitRule rule = top_p_regs<R, kSeedThreads, 256>(d, base, n, a, lst, lst_cap, -1, rb, phase, sh, tid);
   const bool topp = d.reward_mode == 0;
   const bool last_new = d.pos[base + (n - 1)] == t;
 #pragma unroll
