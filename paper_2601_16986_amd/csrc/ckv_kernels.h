@@ -2507,7 +2507,7 @@ __global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_beg
 constexpr int kSeedThreads = 512;      // twice a decode step's workgroup: prompts are long
 
 template <int R>
-__device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int n, int t, LgView lv, const float* sM, const float* sInv,
+__device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int n, bool last_new, LgView lv, const float* sM, const float* sInv,
                                                   float* rw, int* lst, int lst_cap, RedBuf& rb, int& phase, int* sh, int tid) {
   float a[R];
   {
@@ -2540,7 +2540,6 @@ __device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int 
   }
   const HitRule rule = top_p_regs<R, kSeedThreads, 256>(d, base, n, a, lst, lst_cap, -1, rb, phase, sh, tid);
   const bool topp = d.reward_mode == 0;
-  const bool last_new = d.pos[base + (n - 1)] == t;
 #pragma unroll
   for (int c = 0; c < R / 4; ++c) {
     const int e0 = 4 * (tid + c * kSeedThreads);
@@ -2577,6 +2576,8 @@ __global__ __launch_bounds__(kSeedThreads, 4) void seed_hits_kernel(Dev d, int u
   const int t = P - W + j0 + ql;                          // the query's position = its time
   const int n = t + 1;
   const int nch = (n + kChunk - 1) / kChunk;
+  const Slots base = slots_of(d, u);
+  const bool last_new = d.pos[base + (n - 1)] == t;       // the query's own entry (asked for early: nothing waits for it until the end)
   int phase = 0;
   // the chunks' partials of the query's G columns through LDS (every thread fetches one), then per head the
   // maximum and the sum in chunk order
@@ -2599,21 +2600,19 @@ __global__ __launch_bounds__(kSeedThreads, 4) void seed_hits_kernel(Dev d, int u
     sInv[tid] = 1.0f / L;
   }
   __syncthreads();
-  const Slots base = slots_of(d, u);
   const LgView lv{slg + ((size_t)tl * UL + urel) * (d.cap / kBlk) * (kSeedCols * kBlk) + (size_t)qi * G * kBlk, kSeedCols * kBlk};
   float* rw = srw + ((size_t)ql * UL + urel) * d.cap;
   int* lst = reinterpret_cast<int*>(val);
   if (n <= 8 * kSeedThreads) {
-    seed_rewards_regs<8>(d, base, n, t, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+    seed_rewards_regs<8>(d, base, n, last_new, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
   } else if (n <= 16 * kSeedThreads) {
-    seed_rewards_regs<16>(d, base, n, t, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+    seed_rewards_regs<16>(d, base, n, last_new, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
   } else if (n <= 32 * kSeedThreads) {
-    seed_rewards_regs<32>(d, base, n, t, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+    seed_rewards_regs<32>(d, base, n, last_new, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
   } else {
     mean_weights<kSeedThreads>(d, lv, n, sM, sInv, val, tid);
     const HitRule rule = top_p_lds<ValLinear, kSeedThreads>(d, base, n, ValLinear{val}, rb, phase, tid);
     const bool topp = d.reward_mode == 0;
-    const bool last_new = d.pos[base + (n - 1)] == t;
     for (int i = tid; i < n; i += kSeedThreads) {
       const float w = val[i];
       const int pe = (topp && !rule.ties_all) ? d.pos[base + i] : 0;
