@@ -251,3 +251,64 @@ def test_qwen14b_full_size_one_call_per_layer_with_deferred_bookkeeping():
     print(f"steps 3..{rq.shape[0] - 1}: max err {worst:.2e}", flush=True)
     g.close()
     g_ref.close()
+
+
+def test_seed_prompt_at_the_bench_geometry_sampled_units():
+    """ckv_seed_prompt in the configuration `bench.py --seed-prompt 9350,32` times (14B geometry: 48 layers, so
+    the replay takes all 11 query tiles of the window in one batch and one pass over the keys; 128 units per
+    layer; 9350 entries per unit, i.e. 32 entries per thread of the rewards kernel and a short list of more
+    than 64 candidates): eight units of the layer, spread over it, against the oracle entry by entry (CRF bits
+    and tau; entries at the edge of a sub-margin top-p decision of the window may differ), every other unit's
+    scores finite, non-negative and with tau within the window or at the entry's own position."""
+    import math
+    import torch
+    from oracle import crystal_kv as ok
+    from paper_2601_16986_amd import ckv, workloads as wl
+    cfg = wl.CONFIGS["qwen14b"]
+    dev = torch.device("cuda:0")
+    P, W, layer = 9350, 32, 0
+    G = cfg.group
+    budgets = np.full((cfg.n_layers, cfg.batch, cfg.n_kv_heads), P, dtype=np.int32)
+    cap = (P + 64) // 32 * 32
+    g = ckv.CrystalKV(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cap, budgets,
+                      lam=cfg.lam, top_p=cfg.top_p, t0=P, budget_min=1, budget_max=cap - 1, device=dev)
+    m = wl.torch_mean_query(cfg, dev)
+    gen = wl.torch_generator(cfg, 9, dev)
+    r_now = math.sqrt(wl.DRIFT_VAR) * torch.randn(m.shape, generator=gen, device=dev)
+    k, v, *_ = wl.torch_steady_layer(cfg, layer, budgets[layer], P, m[layer], r_now[layer], dev)
+    g.load_prompt(layer, k, v)
+    q_obs = (torch.randn((W, cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=gen, device=dev)
+             + m[layer].repeat_interleave(G, dim=1)[None]).to(torch.bfloat16)
+    g.seed_prompt(layer, q_obs)
+    torch.cuda.synchronize()
+    assert g.status() == 0 and g.time() == P
+    # the sampled units in an oracle of their own: one sequence whose KV heads are the sampled units
+    units = [(int(u) // cfg.n_kv_heads, int(u) % cfg.n_kv_heads) for u in np.linspace(0, cfg.batch * cfg.n_kv_heads - 1, 8).astype(int)]
+    S = len(units)
+    o = ok.CrystalKVOracle(1, 1, S * G, S, cfg.head_dim, np.full((1, 1, S), P, dtype=np.int32), lam=cfg.lam, top_p=cfg.top_p,
+                           t0=P, budget_min=1, budget_max=cap - 1)
+    kh, vh, qh = k.float().cpu().numpy(), v.float().cpu().numpy(), q_obs.float().cpu().numpy()
+    q_o = np.zeros((W, 1, S * G, cfg.head_dim), dtype=np.float32)
+    for i, (b, h) in enumerate(units):
+        o.set_unit((0, 0, i), kh[b, h], vh[b, h], np.arange(P), np.ones(P, np.float32), np.full(P, P - 1))
+        q_o[:, 0, i * G:(i + 1) * G] = qh[:, b, h * G:(h + 1) * G]
+    decs = o.seed_prompt(0, q_o)
+    n_sub = 0
+    for i, (b, h) in enumerate(units):
+        u, e = o.units[(0, 0, i)], g.export_unit(layer, b, h, with_kv=False)
+        assert e["n"] == P and np.array_equal(e["pos"], u.pos)
+        if np.array_equal(e["crf"].view(np.uint32), u.crf.view(np.uint32)) and np.array_equal(e["tau"], u.tau):
+            continue
+        sub = [d for d in decs[(0, 0, i)] if min(d.sum_margin, d.edge_gap) < parity.MARGIN_TOL]
+        may = set(j for d in sub for j in parity.edge_entries(d))
+        differ = set(np.nonzero((e["crf"].view(np.uint32) != u.crf.view(np.uint32)) | (e["tau"] != u.tau))[0].tolist())
+        assert sub and differ <= may, ((b, h), sorted(differ)[:20], sorted(may)[:20])
+        n_sub += 1
+    print(f"seed at the bench geometry: {S} units equal the oracle ({n_sub} through a sub-margin decision)")
+    assert n_sub <= 2
+    for b in range(cfg.batch):
+        for h in range(cfg.n_kv_heads):
+            e = g.export_unit(layer, b, h, with_kv=False)
+            assert e["n"] == P and np.isfinite(e["crf"]).all() and (e["crf"] >= 0).all()
+            assert np.all((e["tau"] == np.arange(P)) | ((e["tau"] >= P - W) & (e["tau"] <= P - 1)))
+    g.close()
