@@ -441,8 +441,8 @@ def place_pools(pool_bytes, device="cuda:0", max_fraction=0.92, verbose=False, r
     matters as well, and not in a way the first stage shows (beside pools in a fast buffer, some fast buffers
     are bad places for them and the slow ones good ones), so whole decode steps (attention, scores, one
     eviction per unit) of the synthetic context are timed with the pools in each of the two best candidates and
-    the other buffers in each of up to ten of the rest (the slowest, the fastest, eight at even distances in
-    allocation order), and the fastest pair is kept.  Everything else is freed."""
+    the other buffers in each of the others, and the fastest pair is kept (two times 47 trials of about 15 ms at
+    most).  Everything else is freed."""
     import torch
     dev = torch.device(device)
     pool_bytes = (int(pool_bytes) + (2 << 20) - 1) // (2 << 20) * (2 << 20)
@@ -518,12 +518,8 @@ def place_pools(pool_bytes, device="cuda:0", max_fraction=0.92, verbose=False, r
         by_time = [int(i) for i in np.argsort(t)]
         for kv in ranked[:2]:
             others = [i for i in by_time if i != kv]
-            tried = []
-            spread = [sorted(others)[j * (len(others) - 1) // 7] for j in range(8)] if len(others) > 1 else []
-            for r in [others[-1], others[0]] + spread:
-                if r not in tried:
-                    tried.append(r)
-                    pairs.append((kv, r, trial(cands[kv], cands[r], whole=True)))
+            for r in sorted(others):
+                pairs.append((kv, r, trial(cands[kv], cands[r], whole=True)))
         pick, rest_at, _ = min(pairs, key=lambda x: x[2])
     del kc, q, kn, out
     buf = cands[pick]
