@@ -1,17 +1,29 @@
 // Device code of the Crystal-KV decode path for gfx950 (64-lane wavefronts,
-// v_mfma_f32_16x16x32_bf16).  Kernels, in launch order of one decode step:
+// v_mfma_f32_16x16x32_bf16).  One decode step runs as one of
 //
-//   prep_kernel    append (k_new, v_new) into the tiled cache, build the list
-//                  of scan work items (unit, chunk of 256 entries)
-//   scan_kernel    the HBM-bound pass: stream K and V once, QK^T and PV on the
-//                  matrix cores, online softmax per work item; leaves the
-//                  scaled logits and one partial (max, sum, acc) per item;
-//                  on request also merges the partials -> out and ends the step
-//   finish_kernel  one workgroup per unit: merge partials -> out, mean
-//                  attention weight per entry, top-p hit mask, CRF update,
-//                  aggregated CRF, and (optionally) eviction + compaction
-//   evict_kernel   eviction + compaction on its own
+//   unit_kernel<W> (ckv_unit_kernel.h)  everything in one persistent kernel, a workgroup per unit at a time
+//   layer_scan_kernel + finish_kernel   one layer: append, attention and output in one kernel on the caller's
+//                  stream, the bookkeeping (finish_kernel, late = 2) afterwards on a stream of the context's
+//   prep_kernel, scan_kernel, finish_kernel   the separate path:
+//     prep_kernel    append (k_new, v_new) into the tiled cache, build the list
+//                    of scan work items (unit, chunk of 256 entries)
+//     scan_kernel    the HBM-bound pass: stream K and V once, QK^T and PV on the
+//                    matrix cores, online softmax per work item; leaves the
+//                    scaled logits and one partial (max, sum, acc) per item;
+//                    on request also merges the partials -> out and ends the step
+//     finish_kernel  one workgroup per unit: merge partials -> out, mean
+//                    attention weight per entry, top-p hit mask, CRF update,
+//                    aggregated CRF, and (optionally) eviction + compaction
+//
+// and beside the step:
+//
+//   load_cache_kernel, seed_state_kernel   fill a layer's caches
+//   seed_scan_kernel, seed_hits_kernel, seed_crf_kernel   scores of a loaded prompt from its last queries
+//   evict_kernel     eviction + compaction on its own (Alg. 1 Step 4, or the sink + recent window policy)
+//   probe_kernel     answer-probe classes
 //   rebudget_kernel  Alg. 2 with integer apportionment, one workgroup/sequence
+//   rebalance_kernel pool segments between units after budgets have changed
+//   schedule_kernel  (ckv_unit_kernel.h) the fused kernel's order of units
 //
 // All floating-point code is compiled with -ffp-contract=off: the CRF update
 // and Alg. 2 must round exactly as their definitions say.
