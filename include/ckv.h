@@ -201,7 +201,9 @@ int ckv_load_cache(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, in
  * that layer follow on one of two streams the context owns, up to eight
  * consecutive layers per launch, beside whatever `stream` does next (the next
  * layers' steps, the model's other work).  Results are the same up to
- * floating-point summation order.  Every later
+ * floating-point summation order.  (A layer with at least two units per compute
+ * unit is finished sooner by the fused kernel, bookkeeping included: there the
+ * flag has no effect.)  Every later
  * ckv_* call that takes a stream orders itself after the bookkeeping it depends
  * on (the next step of the same layer after that layer's, everything else after
  * all of it); the host-side getters wait for the whole device.  ckv_join orders
