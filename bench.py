@@ -297,7 +297,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
-    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=256)
     ap.add_argument("--repeats", type=int, default=5, help="the K timed steps are run this many times; the median is reported")
     ap.add_argument("--config", default="qwen14b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -364,7 +364,15 @@ def main():
         for i in range(k):
             g.decode_step(rq[i % RING], rk[i % RING], rv[i % RING], out=out, evict=not fullkv, attention_only=fullkv)
 
-    eager_steps(warm)
+    # warm-up, with fresh inputs every RING steps like the timed region (replayed inputs fill the caches with
+    # duplicate keys, see RING)
+    done = 0
+    while done < warm:
+        if done and getattr(g, "refill", None) is not None:
+            g.refill()
+        k = min(RING, warm - done)
+        eager_steps(k)
+        done += k
     torch.cuda.synchronize()
     assert g.status() == 0, "a unit overflowed during warm-up"
 
