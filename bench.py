@@ -159,16 +159,16 @@ def seed_prompt_bench(cfg, device, P, W):
     # what the replay needs at the least: every key row once (weights only, so no values), the queries, and the
     # scores read and written once per query
     # as built: a tile of 16 query columns holds Q = 16 // G queries; a batch of tiles (as many as the decode
-    # workspace holds, at most 16) makes one pass over the keys, writes its logits (64 B per entry and tile) and
-    # reads them back (4 G B per entry and query), writes and reads the rewards (4 B per entry and query); the
-    # scores are read and written once per batch
+    # workspace holds, at most 16) makes two passes over the keys (softmax partials, then mean weights: 4 B per
+    # entry and query written); the rewards kernel reads the weights and writes the rewards in their place, the
+    # recurrence reads them; the scores are read and written once per batch
     Q = max(1, 16 // cfg.group)
     tiles = (W + Q - 1) // Q
-    fit = min(cfg.n_layers * cfg.group * 4 // (64 + 4 * Q), 16)
+    fit = min(cfg.n_layers * cfg.group // Q, 16)
     per_batch = fit if fit >= 2 else 1
     passes = (tiles + per_batch - 1) // per_batch
     min_bytes = upl * (P * 256 + W * cfg.group * 256 + W * P * 16)
-    pass_bytes = upl * (passes * P * (256 + 16) + W * cfg.group * 256 + tiles * P * 64 + W * P * (4 * cfg.group + 8))
+    pass_bytes = upl * (passes * P * (2 * 256 + 16) + 2 * W * cfg.group * 256 + W * P * 16)
     sec = ms / cfg.n_layers * 1e-3
     assert g.status() == 0
     g.close()
@@ -176,7 +176,7 @@ def seed_prompt_bench(cfg, device, P, W):
             "n_gpus": 1, "ms_per_layer": ms / cfg.n_layers, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": f"{cfg.name} geometry: {cfg.n_layers} layers, batch {cfg.batch}, {cfg.n_q_heads}/{cfg.n_kv_heads} heads, "
                                    f"prompt of {P} tokens, window of {W} queries", "units_per_layer": upl,
-                       "entries_scanned_per_layer": entries, "queries_per_tile": Q, "tiles": tiles, "passes_over_the_keys": passes},
+                       "entries_scanned_per_layer": entries, "queries_per_tile": Q, "tiles": tiles, "batches": passes, "passes_over_the_keys": 2 * passes},
             # K and V of the W visible prefixes, the bytes a query-by-query replay of decode steps moves (the figure of
             # the first version, kept for comparison; the replay as built reads far less, so this can exceed 1)
             "decode_replay_equivalent_gbps": bytes_layer / sec / 1e9,

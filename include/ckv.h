@@ -159,11 +159,11 @@ int ckv_load_prompt(ckv_ctx* ctx, int32_t layer, const void* k, const void* v, i
  * output, the time stays t0, and the replay leaves no trace in the aggregated
  * CRF that ckv_rebudget consumes.  Requires a layer filled by ckv_load_prompt
  * and not touched since (CKV_ESTATE otherwise) and 1 <= W <= P.  The keys are read
- * once per batch of queries (up to 16 floor(16 / G) of them, G = n_q_heads /
+ * twice per batch of queries (up to 16 floor(16 / G) of them, G = n_q_heads /
  * n_kv_heads; fewer when the workspace of a context with few layers holds less),
  * the values not at all (only weights are needed); the workspace's logits and
  * partials of the decode paths serve as scratch (their contents are dead between
- * calls).  Three kernel launches per batch plus two on `stream`; asynchronous. */
+ * calls).  Five kernel launches per batch plus two on `stream`; asynchronous. */
 int ckv_seed_prompt(ckv_ctx* ctx, int32_t layer, const void* q_obs, int32_t W, void* stream);
 
 /* Fill the empty caches of one layer with entries from the middle of a

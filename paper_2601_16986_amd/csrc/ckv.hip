@@ -40,7 +40,7 @@ struct ckv_ctx {
   int units_per_layer = 0;
   int next_layer = 0;
   int n_cu = 256;
-  float* seedlg = nullptr;      // workspace of the prompt replay
+  float* seedmi = nullptr;      // workspace of the prompt replay
   float* seedml = nullptr;
   float* seedrw = nullptr;
   int device = 0;               // the HIP device the context was created on
@@ -153,7 +153,7 @@ std::vector<float> make_decay_table(float lambda) {
 }
 
 struct Carve {
-  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, layer_ts, arrive, msum, tbl, owned, spare, seedlg, seedml, seedrw, total;
+  size_t n, budget, t_unit, nev, window, sc, stamp, tab, items, partial, ml, logits, btotal, order, layer_ts, arrive, msum, tbl, owned, spare, seedml, seedmi, seedrw, total;
 };
 
 Carve carve(const ckv_layout* l, size_t tab_len) {
@@ -183,11 +183,11 @@ Carve carve(const ckv_layout* l, size_t tab_len) {
   c.tbl = take(U * mc * 4);
   c.owned = take(U * 4);
   c.spare = take((size_t)(l->pool_slots / kSeg) * 4);
-  // prompt replay (ckv_seed_prompt), one layer at a time, for contexts whose decode workspace is too small to
-  // lend it room for several tiles of queries: logits of one tile (16 query columns per entry), its softmax
-  // partials per chunk, and the rewards of its up to 16 queries
+  // prompt replay (ckv_seed_prompt), one layer at a time: softmax maximum and 1 / sum per query column of a
+  // batch; and, for contexts whose decode workspace is too small to lend the replay room for several tiles of
+  // queries, one tile's softmax partials per chunk and the weights (then rewards) of its up to 16 queries
   const size_t UL = (size_t)l->batch * l->n_kv_heads;
-  c.seedlg = take(UL * (size_t)l->cap * kSeedCols * 4);
+  c.seedmi = take((size_t)kSeedTiles * UL * kSeedCols * 2 * 4);
   c.seedml = take(UL * mc * kSeedCols * 2 * 4);
   c.seedrw = take(UL * (size_t)l->cap * kSeedCols * 4);
   c.total = off;
@@ -407,7 +407,8 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   }
   const void* lds_kernels[4] = {reinterpret_cast<const void*>(finish_kernel), reinterpret_cast<const void*>(evict_kernel),
                                 reinterpret_cast<const void*>(probe_kernel), reinterpret_cast<const void*>(seed_hits_kernel)};
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(seed_scan_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSeedTiles * 4096) != hipSuccess) {
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(seed_scan_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, kSeedTiles * 4096) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(seed_scan_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, kSeedTiles * 4096) != hipSuccess) {
     delete c;
     return CKV_EHIP;
   }
@@ -483,7 +484,7 @@ int ckv_init(ckv_ctx** out, const ckv_layout* layout, const int32_t* budgets, co
   d.owned = (int32_t*)(ws + cv.owned);
   d.spare = (int32_t*)(ws + cv.spare);
   d.max_seg = (int32_t)((layout->cap + kSeg - 1) / kSeg);
-  c->seedlg = (float*)(ws + cv.seedlg);
+  c->seedmi = (float*)(ws + cv.seedmi);
   c->seedml = (float*)(ws + cv.seedml);
   c->seedrw = (float*)(ws + cv.seedrw);
 
@@ -727,33 +728,43 @@ int ckv_seed_prompt(ckv_ctx* c, int32_t layer, const void* q_obs, int32_t W, voi
   const dim3 sgrid((unsigned)std::min((P + kThreads - 1) / kThreads, 64), (unsigned)count);
   hipLaunchKernelGGL(seed_state_kernel, sgrid, dim3(kThreads), 0, s, c->dev, begin, P, (int)W, 0, 0);
   CKV_HIP(c, hipGetLastError());
-  // A tile of 16 query columns holds the G heads of Q queries.  Per batch of tiles: one pass over the keys for
-  // all its queries, the queries' rewards, the score recurrence.  The batch's logits, softmax partials and
-  // rewards live in the decode paths' logits and partials (idle here, rewritten by the next scan before anything
-  // reads them) when those hold at least two tiles, else in the replay's own one-tile buffers.
+  // A tile of 16 query columns holds the G heads of Q queries.  Per batch of tiles: a pass over the keys for the
+  // softmax partials of all its queries, their maxima and sums, a second pass for the mean weights, the
+  // rewards (top-p rule), the score recurrence.  The batch's weights and softmax partials live in the decode
+  // paths' logits and partials (idle here, rewritten by the next scan before anything reads them) when those
+  // hold at least two tiles, else in the replay's own one-tile buffers.
   const int G = c->dev.G, Q = kSeedCols / G;
   const size_t UL = (size_t)count, cap = (size_t)c->lay.cap, mc = (size_t)c->dev.max_chunks;
-  const size_t tile_lg = UL * cap * kSeedCols * 4, tile_rw = (size_t)Q * UL * cap * 4, tile_ml = UL * mc * kSeedCols * 2 * 4;
+  const size_t tile_rw = (size_t)Q * UL * cap * 4, tile_ml = UL * mc * kSeedCols * 2 * 4;
   const size_t big_lg = (size_t)c->units * cap * (size_t)G * 4, big_ml = (size_t)c->units * (size_t)c->dev.slots * (size_t)G * kDim * 4;
-  const int fit = (int)std::min<size_t>({big_lg / (tile_lg + tile_rw), big_ml / tile_ml, (size_t)kSeedTiles});
-  float *lg = c->seedlg, *ml = c->seedml, *rw = c->seedrw;
+  const int fit = (int)std::min<size_t>({big_lg / tile_rw, big_ml / tile_ml, (size_t)kSeedTiles});
+  float *ml = c->seedml, *rw = c->seedrw, *mi = c->seedmi;
   int tiles = 1;
   if (fit >= 2) {
     tiles = fit;
-    lg = c->dev.logits;
-    rw = reinterpret_cast<float*>(reinterpret_cast<char*>(c->dev.logits) + (size_t)fit * tile_lg);
+    rw = c->dev.logits;
     ml = c->dev.partial;
   }
+  const bool topp = c->par.reward_mode == CKV_REWARD_TOPP_HIT;
   for (int j0 = 0; j0 < W; j0 += tiles * Q) {
     const int nq = std::min(tiles * Q, (int)W - j0), nt = (nq + Q - 1) / Q;
     const int n_last = P - W + j0 + nq;                    // entries the batch's last query sees
     const int chunks = (n_last + kChunk - 1) / kChunk;
-    hipLaunchKernelGGL(seed_scan_kernel, dim3((unsigned)((chunks + kThreads / 64 - 1) / (kThreads / 64)), (unsigned)count), dim3(kThreads),
-                       (size_t)nt * 4096, s, c->dev, begin, (const uint16_t*)q_obs, j0, nq, Q, P, (int)W, lg, ml);
+    const dim3 sgrid2((unsigned)((chunks + kThreads / 64 - 1) / (kThreads / 64)), (unsigned)count);
+    hipLaunchKernelGGL(seed_scan_kernel<false>, sgrid2, dim3(kThreads), (size_t)nt * 4096, s, c->dev, begin, (const uint16_t*)q_obs, j0,
+                       nq, Q, P, (int)W, ml, (const float*)mi, rw);
     CKV_HIP(c, hipGetLastError());
-    hipLaunchKernelGGL(seed_hits_kernel, dim3((unsigned)nq, (unsigned)count), dim3(kSeedThreads), c->finish_lds, s, c->dev, begin, j0, Q, P,
-                       (int)W, (const float*)lg, (const float*)ml, rw);
+    hipLaunchKernelGGL(seed_stats_kernel, dim3((unsigned)count), dim3(kSeedTiles * kSeedCols), 0, s, c->dev, j0, nq, Q, P, (int)W,
+                       (const float*)ml, mi);
     CKV_HIP(c, hipGetLastError());
+    hipLaunchKernelGGL(seed_scan_kernel<true>, sgrid2, dim3(kThreads), (size_t)nt * 4096, s, c->dev, begin, (const uint16_t*)q_obs, j0,
+                       nq, Q, P, (int)W, ml, (const float*)mi, rw);
+    CKV_HIP(c, hipGetLastError());
+    if (topp) {
+      hipLaunchKernelGGL(seed_hits_kernel, dim3((unsigned)nq, (unsigned)count), dim3(kSeedThreads), c->finish_lds, s, c->dev, begin, j0, P,
+                         (int)W, rw);
+      CKV_HIP(c, hipGetLastError());
+    }
     hipLaunchKernelGGL(seed_crf_kernel, dim3((unsigned)((P + 4 * kThreads - 1) / (4 * kThreads)), (unsigned)count), dim3(kThreads), 0, s,
                        c->dev, begin, j0, nq, P, (int)W, (const float*)rw);
     CKV_HIP(c, hipGetLastError());

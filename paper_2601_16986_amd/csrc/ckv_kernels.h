@@ -18,7 +18,7 @@
 // and beside the step:
 //
 //   load_cache_kernel, seed_state_kernel   fill a layer's caches
-//   seed_scan_kernel, seed_hits_kernel, seed_crf_kernel   scores of a loaded prompt from its last queries
+//   seed_scan_kernel, seed_stats_kernel, seed_hits_kernel, seed_crf_kernel   scores of a loaded prompt from its last queries
 //   evict_kernel     eviction + compaction on its own (Alg. 1 Step 4, or the sink + recent window policy)
 //   probe_kernel     answer-probe classes
 //   rebudget_kernel  Alg. 2 with integer apportionment, one workgroup/sequence
@@ -121,6 +121,21 @@ __device__ __forceinline__ T wave_sum(T v) {
 template <int kCtrl>
 __device__ __forceinline__ int dpp_i32(int v) {
   return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xF, 0xF, true);
+}
+// value of the lane `by` places further up in this lane's row of 16 (0 beyond the row's end); by = 1 .. 7
+__device__ __forceinline__ float row_shl_f32(float v, int by) {
+  const int x = __float_as_int(v);
+  int r = 0;
+  switch (by) {
+    case 1: r = __builtin_amdgcn_update_dpp(0, x, 0x101, 0xF, 0xF, true); break;
+    case 2: r = __builtin_amdgcn_update_dpp(0, x, 0x102, 0xF, 0xF, true); break;
+    case 3: r = __builtin_amdgcn_update_dpp(0, x, 0x103, 0xF, 0xF, true); break;
+    case 4: r = __builtin_amdgcn_update_dpp(0, x, 0x104, 0xF, 0xF, true); break;
+    case 5: r = __builtin_amdgcn_update_dpp(0, x, 0x105, 0xF, 0xF, true); break;
+    case 6: r = __builtin_amdgcn_update_dpp(0, x, 0x106, 0xF, 0xF, true); break;
+    default: r = __builtin_amdgcn_update_dpp(0, x, 0x107, 0xF, 0xF, true); break;
+  }
+  return __int_as_float(r);
 }
 constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
 constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
@@ -2389,34 +2404,43 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(Dev d, int unit_begin,
 }
 
 // ------------------------------------------------------------------ prompt replay (scores of a loaded prompt)
-// The prompt's last W queries in three kernels per batch of queries.  What a query does to the scores splits
+// The prompt's last W queries in a few kernels per batch of queries.  What a query does to the scores splits
 // into a part that does not depend on the scores - its mean attention weights over the entries it sees and,
 // from them, the reward of every entry (Alg. 1 Steps 1-2: hit or not; or the weight itself) - and the score
 // recurrence (Step 3), which is sequential over the queries but independent per entry.  So:
-//   seed_scan_kernel   one pass over the keys for all queries of the batch: scaled logits and softmax partials
-//   seed_hits_kernel   per (unit, query): mean weights, hit rule, rewards
-//   seed_crf_kernel    per entry: the queries' rewards applied in order
-// Only the weights are wanted (no output), so V is never read.
+//   seed_scan_kernel<false>  a pass over the keys for all queries of the batch: softmax partials per chunk
+//   seed_stats_kernel        per query head: softmax maximum and 1 / sum over the entries the query sees
+//   seed_scan_kernel<true>   a second pass: the logits again, normalised, the mean over the heads -> weights
+//   seed_hits_kernel         per (unit, query): hit rule, rewards in place of the weights (top-p rule only)
+//   seed_crf_kernel          per entry: the queries' rewards applied in order
+// (Two passes over the keys, 256 B per entry each, instead of the logits of every query head going through
+// memory, 4 G B per entry and query written and read back.)  Only the weights are wanted (no output), so V is
+// never read.
 //
 // Columns: the matrix-core tile has 16 query columns, of which a decode step fills G; here a tile holds the G
 // heads of Q = 16 / G queries (column c = head c % G of the tile's query c / G), and a batch is up to
 // kSeedTiles tiles.  Buffers of a batch of nt tiles, nq queries, for the UL units of a layer:
-//   slg [tile][unit][block][column][32]   scaled logits (base-2 domain), -inf where the query does not see the entry
 //   sml [tile][unit][chunk][column][2]    running maximum and sum of the softmax per 256-entry chunk
-//   srw [query][unit][cap]                rewards
+//   smi [tile][unit][column][2]           maximum and 1 / sum over all the entries the column's query sees
+//   srw [query][unit][cap]                mean weights, then rewards
 constexpr int kSeedCols = 16;
 constexpr int kSeedTiles = 16;
 
 // seed_scan_kernel: one wavefront per 256-entry chunk of a unit; the tiles' queries sit in LDS (per tile and
 // 32-dim slice one 16-byte operand piece per lane), each block of keys is loaded once and multiplied with every
 // tile.  Query j of the window sees the entries of positions <= its own, i.e. indices < P - W + j + 1 (the
-// prompt's entries sit in position order).
+// prompt's entries sit in position order).  WEIGHTS = false: per chunk and column the running maximum and sum
+// of the softmax go to `sml`.  WEIGHTS = true: every logit is normalised with its column's maximum and 1 / sum
+// from `smi`, and the mean over a query's G heads (summed in head order, as the decode path's mean weights
+// are) goes to `srw`; entries a query does not see get 0.
 // grid: (ceil(chunks / 4), units of the layer), kThreads threads, nt * 4096 bytes of dynamic LDS.
+template <bool WEIGHTS>
 __global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_begin, const uint16_t* __restrict__ q_obs, int j0,
-                                                             int nq, int Q, int P, int W, float* __restrict__ slg,
-                                                             float* __restrict__ sml) {
+                                                             int nq, int Q, int P, int W, float* __restrict__ sml,
+                                                             const float* __restrict__ smi, float* __restrict__ srw) {
   extern __shared__ unsigned char smem[];
   u32x4* s_q = reinterpret_cast<u32x4*>(smem);            // [tile][slice][lane]
+  __shared__ float2 s_mi[WEIGHTS ? kSeedTiles * kSeedCols : 1];      // WEIGHTS: every column's maximum and 1 / sum
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int urel = blockIdx.y, u = unit_begin + urel;
   const int UL = gridDim.y;
@@ -2427,6 +2451,10 @@ __global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_beg
   const int mc = d.max_chunks;
   const int n_first = P - W + j0 + 1;                     // entries the batch's first query sees
   const int n_last = n_first + nq - 1;                    // ... and its last
+  if constexpr (WEIGHTS) {
+    if ((int)threadIdx.x < nt * kSeedCols)
+      s_mi[threadIdx.x] = *reinterpret_cast<const float2*>(smi + (((size_t)(threadIdx.x / kSeedCols) * UL + urel) * kSeedCols + threadIdx.x % kSeedCols) * 2);
+  }
   {
     // this thread's piece (slice = wave, lane) of every tile's operand
     const int b = urel / d.Hkv, h = urel % d.Hkv;
@@ -2444,192 +2472,210 @@ __global__ __launch_bounds__(kThreads) void seed_scan_kernel(Dev d, int unit_beg
   if (e_chunk >= n_last) return;
   const int nblk = min(kChunkBlocks, (n_last - e_chunk + kBlk - 1) / kBlk);
   const uint16_t* kb = d.K + (size_t)d.tbl[(size_t)u * d.max_seg + chunk] * kSegElems + lane * 8;     // a chunk is one pool segment
-  const size_t lg_tile = (size_t)UL * (d.cap / kBlk) * (kSeedCols * kBlk);
-  float* lgp = slg + ((size_t)urel * (d.cap / kBlk) + (size_t)chunk * kChunkBlocks) * (kSeedCols * kBlk) + j * kBlk + 4 * kg;
-  float m_run[kSeedTiles], l_run[kSeedTiles];             // this lane's entries only; the four lanes of a column meet at the end
+  // WEIGHTS = false: this lane's running maximum and sum per tile (its entries only; the four lanes of a column
+  // meet at the end)
+  constexpr int kStat = WEIGHTS ? 1 : kSeedTiles;
+  float m_run[kStat], l_run[kStat];
 #pragma unroll
-  for (int tl = 0; tl < kSeedTiles; ++tl) {
+  for (int tl = 0; tl < kStat; ++tl) {
     m_run[tl] = -INFINITY;
     l_run[tl] = 0.f;
   }
+  const float invG = 1.0f / (float)G;
   KFrag ka, kn;
   load_k(ka, kb);
   for (int blk = 0; blk < nblk; ++blk) {
     if (blk + 1 < nblk) load_k(kn, kb + (size_t)(blk + 1) * kBlkElems);
     const int e0 = e_chunk + blk * kBlk + 4 * kg;
+    auto tile = [&](int tl, float& m_t, float& l_t) {
+      const int qn = min(Q, nq - tl * Q);
+      const bool col_ok = j < qn * G;
+      // entries this column's query sees (columns beyond the tile's queries: none)
+      const int lim = col_ok ? n_first + tl * Q + j / G : 0;
+      if (e_chunk + blk * kBlk >= n_first + tl * Q + qn - 1) return;     // the tile's last query does not see the block (uniform)
+      bf16x8 qv[4];
 #pragma unroll
-    for (int tl = 0; tl < kSeedTiles; ++tl) {
-      if (tl < nt) {
-        const int qn = min(Q, nq - tl * Q);
-        // entries this column's query sees (columns beyond the tile's queries: none)
-        const int lim = j < qn * G ? n_first + tl * Q + j / G : 0;
-        if (e_chunk + blk * kBlk < n_first + tl * Q + qn - 1) {         // the tile's last query sees the block (uniform)
-          bf16x8 qv[4];
+      for (int s4 = 0; s4 < 4; ++s4) qv[s4] = as_bf16x8(s_q[(tl * 4 + s4) * 64 + lane]);
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int s4 = 0; s4 < 4; ++s4) qv[s4] = as_bf16x8(s_q[(tl * 4 + s4) * 64 + lane]);
-          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+      for (int s4 = 0; s4 < 4; ++s4) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[s4]), qv[s4], s0, 0, 0, 0);
 #pragma unroll
-          for (int s4 = 0; s4 < 4; ++s4) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[s4]), qv[s4], s0, 0, 0, 0);
+      for (int s4 = 0; s4 < 4; ++s4) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[4 + s4]), qv[s4], s1, 0, 0, 0);
+      float sv[8];
 #pragma unroll
-          for (int s4 = 0; s4 < 4; ++s4) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.k[4 + s4]), qv[s4], s1, 0, 0, 0);
-          float sv[8];
+      for (int v = 0; v < 4; ++v) {
+        sv[v] = (e0 + v < lim) ? s0[v] * d.scale_log2e : -INFINITY;
+        sv[4 + v] = (e0 + 16 + v < lim) ? s1[v] * d.scale_log2e : -INFINITY;
+      }
+      if constexpr (!WEIGHTS) {
+        const float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+        if (bm > m_t) {
+          l_t *= fast_exp2(m_t - bm);                       // exp2(-inf) = 0 the first time
+          m_t = bm;
+        }
+        if (m_t > -INFINITY) {
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            sv[v] = (e0 + v < lim) ? s0[v] * d.scale_log2e : -INFINITY;
-            sv[4 + v] = (e0 + 16 + v < lim) ? s1[v] * d.scale_log2e : -INFINITY;
-          }
-          float* dst = lgp + (size_t)tl * lg_tile + (size_t)blk * (kSeedCols * kBlk);
-          *reinterpret_cast<f32x4*>(dst) = f32x4{sv[0], sv[1], sv[2], sv[3]};
-          *reinterpret_cast<f32x4*>(dst + 16) = f32x4{sv[4], sv[5], sv[6], sv[7]};
-          const float bm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-          if (bm > m_run[tl]) {
-            l_run[tl] *= fast_exp2(m_run[tl] - bm);         // exp2(-inf) = 0 the first time
-            m_run[tl] = bm;
-          }
-          if (m_run[tl] > -INFINITY) {
+          for (int i = 0; i < 8; ++i) l_t += fast_exp2(sv[i] - m_t);
+        }
+      } else {
+        // this head's share of the weight of its 4 + 4 entries, then the query's heads in order
+        const float2 mi = s_mi[tl * kSeedCols + j];
+        float term[8], mean[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) l_run[tl] += fast_exp2(sv[i] - m_run[tl]);
+        for (int i = 0; i < 8; ++i) {
+          term[i] = sv[i] > -INFINITY ? fast_exp2(sv[i] - mi.x) * mi.y : 0.f;
+        }
+        // lane c + g of the row holds head g of the query whose first head sits in lane c: the sum of a
+        // query's heads, in head order, forms in its first head's lane (row_shl:g brings lane + g's value)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mean[i] = term[i];
+#pragma unroll
+        for (int g = 1; g < kMaxGroup; ++g) {
+          if (g < G) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mean[i] += row_shl_f32(term[i], g);
           }
         }
+        if (col_ok && j % G == 0) {
+          float* dst = srw + ((size_t)(tl * Q + j / G) * UL + urel) * d.cap + e0;
+          *reinterpret_cast<f32x4*>(dst) = f32x4{mean[0] * invG, mean[1] * invG, mean[2] * invG, mean[3] * invG};
+          *reinterpret_cast<f32x4*>(dst + 16) = f32x4{mean[4] * invG, mean[5] * invG, mean[6] * invG, mean[7] * invG};
+        }
       }
+    };
+    if constexpr (WEIGHTS) {
+#pragma unroll 1
+      for (int tl = 0; tl < nt; ++tl) tile(tl, m_run[0], l_run[0]);
+    } else {
+#pragma unroll
+      for (int tl = 0; tl < kSeedTiles; ++tl)
+        if (tl < nt) tile(tl, m_run[tl], l_run[tl]);
     }
     if (blk + 1 < nblk) ka = kn;
   }
-  // per tile, the column's four lanes (kg = 0..3): maximum, then the sums rescaled to it, in a fixed order
+  if constexpr (!WEIGHTS) {
+    // per tile, the column's four lanes (kg = 0..3): maximum, then the sums rescaled to it, in a fixed order
 #pragma unroll
-  for (int tl = 0; tl < kSeedTiles; ++tl) {
-    if (tl < nt) {
-      float M = fmaxf(m_run[tl], __shfl_xor(m_run[tl], 16));
-      M = fmaxf(M, __shfl_xor(M, 32));
-      const float mine = m_run[tl] > -INFINITY ? l_run[tl] * fast_exp2(m_run[tl] - M) : 0.f;
-      const float l0 = __shfl(mine, j), l1 = __shfl(mine, j + 16), l2 = __shfl(mine, j + 32), l3 = __shfl(mine, j + 48);
-      if (kg == 0) {
-        float* dst = sml + ((((size_t)tl * UL + urel) * mc + chunk) * kSeedCols + j) * 2;
-        dst[0] = M;
-        dst[1] = (l0 + l1) + (l2 + l3);
+    for (int tl = 0; tl < kSeedTiles; ++tl) {
+      if (tl < nt) {
+        float M = fmaxf(m_run[tl], __shfl_xor(m_run[tl], 16));
+        M = fmaxf(M, __shfl_xor(M, 32));
+        const float mine = m_run[tl] > -INFINITY ? l_run[tl] * fast_exp2(m_run[tl] - M) : 0.f;
+        const float l0 = __shfl(mine, j), l1 = __shfl(mine, j + 16), l2 = __shfl(mine, j + 32), l3 = __shfl(mine, j + 48);
+        if (kg == 0) {
+          float* dst = sml + ((((size_t)tl * UL + urel) * mc + chunk) * kSeedCols + j) * 2;
+          dst[0] = M;
+          dst[1] = (l0 + l1) + (l2 + l3);
+        }
       }
     }
   }
 }
 
-// seed_hits_kernel: one workgroup per (query of the batch, unit).  Softmax maxima and denominators of the
-// query's G columns from the chunks' partials, mean weights from the logits, hit rule, rewards: 1 or 0 under the
-// top-p rule (the query's own entry, the last it sees, is always hit), the weight itself otherwise.
+// seed_stats_kernel: thread (tile, column) of a unit: maximum and 1 / sum of the column's softmax over the chunks
+// its query sees, in chunk order.  grid: units of the layer, kSeedTiles * kSeedCols threads.
+__global__ __launch_bounds__(kSeedTiles * kSeedCols) void seed_stats_kernel(Dev d, int j0, int nq, int Q, int P, int W,
+                                                                         const float* __restrict__ sml, float* __restrict__ smi) {
+  const int urel = blockIdx.x, UL = gridDim.x;
+  const int tl = threadIdx.x / kSeedCols, col = threadIdx.x % kSeedCols;
+  const int G = d.G, mc = d.max_chunks;
+  const int nt = (nq + Q - 1) / Q;
+  if (tl >= nt) return;
+  const int qn = min(Q, nq - tl * Q);
+  float M = -INFINITY, inv = 0.f;
+  if (col < qn * G) {
+    const int n = P - W + j0 + tl * Q + col / G + 1;      // entries the column's query sees
+    const int nch = (n + kChunk - 1) / kChunk;
+    const float* ml = sml + ((((size_t)tl * UL + urel) * mc) * kSeedCols + col) * 2;
+    // eight chunks' partials are asked for at a time; maxima, then sums, in chunk order
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+      float2 p[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) p[k] = *reinterpret_cast<const float2*>(ml + (size_t)min(c0 + k, nch - 1) * kSeedCols * 2);
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (c0 + k < nch) M = fmaxf(M, p[k].x);
+    }
+    float L = 0.f;
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+      float2 p[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) p[k] = *reinterpret_cast<const float2*>(ml + (size_t)min(c0 + k, nch - 1) * kSeedCols * 2);
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (c0 + k < nch && p[k].x > -INFINITY) L += p[k].y * fast_exp2(p[k].x - M);
+    }
+    inv = 1.0f / L;
+  }
+  float* dst = smi + (((size_t)tl * UL + urel) * kSeedCols + col) * 2;
+  dst[0] = M;
+  dst[1] = inv;
+}
+
+// seed_hits_kernel (top-p rule only): one workgroup per (query of the batch, unit).  The query's mean weights
+// from `srw`, the hit rule, and in their place the rewards: 1 or 0 (the query's own entry, the last it sees, is
+// always hit).
 // grid: (queries of the batch, units of the layer), kSeedThreads threads, dynamic LDS as finish_kernel.
 constexpr int kSeedThreads = 512;      // twice a decode step's workgroup: prompts are long
 
 template <int R>
-__device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int n, bool last_new, LgView lv, const float* sM, const float* sInv,
-                                                  float* rw, int* lst, int lst_cap, RedBuf& rb, int& phase, int* sh, int tid) {
+__device__ __forceinline__ void seed_rewards_regs(const Dev& d, Slots base, int n, bool last_new, float* rw, int* lst, int lst_cap,
+                                                  RedBuf& rb, int& phase, int* sh, int tid) {
   float a[R];
-  {
-    // mean_weights_regs with the next group's logits requested before the current group's are used (the same
-    // operations in the same order per entry)
-    const int G = d.G;
-    const float invG = 1.0f / (float)G;
-    f32x4 x[2][kMaxGroup];
-    auto request = [&](int c, f32x4 (&xx)[kMaxGroup]) {
-      const int e0 = 4 * (tid + c * kSeedThreads);
-      const float* row = lv.p + (size_t)(e0 >> 5) * lv.blk_stride + (e0 & 31);
 #pragma unroll
-      for (int g = 0; g < kMaxGroup; ++g)
-        xx[g] = (e0 < n && g < G) ? *reinterpret_cast<const f32x4*>(row + g * kBlk) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    };
-    request(0, x[0]);
+  for (int c = 0; c < R / 4; ++c) {
+    const int e0 = 4 * (tid + c * kSeedThreads);
+    const f32x4 x = e0 < n ? *reinterpret_cast<const f32x4*>(rw + e0) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < R / 4; ++c) {
-      if (c + 1 < R / 4) request(c + 1, x[(c + 1) & 1]);
-      const int e0 = 4 * (tid + c * kSeedThreads);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float acc = 0.f;
-#pragma unroll
-        for (int g = 0; g < kMaxGroup; ++g)
-          if (g < G) acc += fast_exp2(x[c & 1][g][e] - sM[g]) * sInv[g];
-        a[4 * c + e] = (e0 + e < n) ? acc * invG : 0.f;
-      }
-    }
+    for (int e = 0; e < 4; ++e) a[4 * c + e] = (e0 + e < n) ? x[e] : 0.f;
   }
   const HitRule rule = top_p_regs<R, kSeedThreads, 256>(d, base, n, a, lst, lst_cap, -1, rb, phase, sh, tid);
-  const bool topp = d.reward_mode == 0;
 #pragma unroll
   for (int c = 0; c < R / 4; ++c) {
     const int e0 = 4 * (tid + c * kSeedThreads);
     if (e0 < n) {
       i32x4 ps = {0, 0, 0, 0};
-      if (topp && !rule.ties_all) ps = *reinterpret_cast<const i32x4*>(d.pos + (base + e0));      // rare
+      if (!rule.ties_all) ps = *reinterpret_cast<const i32x4*>(d.pos + (base + e0));      // rare
       f32x4 r;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float w = a[4 * c + e];
-        const bool hit = rule(__float_as_uint(w), ps[e]) | ((e0 + e == n - 1) & last_new);
-        r[e] = topp ? (hit ? 1.0f : 0.0f) : w;
+        const bool hit = rule(__float_as_uint(a[4 * c + e]), ps[e]) | ((e0 + e == n - 1) & last_new);
+        r[e] = hit ? 1.0f : 0.0f;
       }
       *reinterpret_cast<f32x4*>(rw + e0) = r;              // entries >= n of the group: written, never read
     }
   }
 }
 
-__global__ __launch_bounds__(kSeedThreads, 4) void seed_hits_kernel(Dev d, int unit_begin, int j0, int Q, int P, int W,
-                                                             const float* __restrict__ slg, const float* __restrict__ sml,
-                                                             float* __restrict__ srw) {
+__global__ __launch_bounds__(kSeedThreads, 4) void seed_hits_kernel(Dev d, int unit_begin, int j0, int P, int W, float* __restrict__ srw) {
   extern __shared__ unsigned char smem[];
   float* val = reinterpret_cast<float*>(smem);
-  __shared__ __align__(16) float sM[kMaxGroup];
-  __shared__ __align__(16) float sInv[kMaxGroup];
   __shared__ RedBuf rb;
   __shared__ int sh[4 + kSeedThreads / 64];
-  __shared__ float s_pm[kMaxChunks * kMaxGroup], s_pl[kMaxChunks * kMaxGroup];
   const int tid = threadIdx.x;
   const int ql = blockIdx.x, urel = blockIdx.y, u = unit_begin + urel;
   const int UL = gridDim.y;
-  const int G = d.G, mc = d.max_chunks;
-  const int tl = ql / Q, qi = ql % Q;
   const int t = P - W + j0 + ql;                          // the query's position = its time
   const int n = t + 1;
-  const int nch = (n + kChunk - 1) / kChunk;
   const Slots base = slots_of(d, u);
   const bool last_new = d.pos[base + (n - 1)] == t;       // the query's own entry (asked for early: nothing waits for it until the end)
   int phase = 0;
-  // the chunks' partials of the query's G columns through LDS (every thread fetches one), then per head the
-  // maximum and the sum in chunk order
-  for (int i = tid; i < nch * kMaxGroup; i += kSeedThreads) {
-    const int c = i >> 3, g = i & 7;
-    const float2 p = *reinterpret_cast<const float2*>(sml + (((((size_t)tl * UL + urel) * mc) + c) * kSeedCols + (size_t)(qi * G + min(g, G - 1))) * 2);
-    s_pm[i] = p.x;
-    s_pl[i] = p.y;
-  }
-  __syncthreads();
-  if (tid < G) {
-    float M = -INFINITY;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, s_pm[c * kMaxGroup + tid]);
-    float L = 0.f;
-    for (int c = 0; c < nch; ++c) {
-      const float m = s_pm[c * kMaxGroup + tid];
-      if (m > -INFINITY) L += s_pl[c * kMaxGroup + tid] * fast_exp2(m - M);
-    }
-    sM[tid] = M;
-    sInv[tid] = 1.0f / L;
-  }
-  __syncthreads();
-  const LgView lv{slg + ((size_t)tl * UL + urel) * (d.cap / kBlk) * (kSeedCols * kBlk) + (size_t)qi * G * kBlk, kSeedCols * kBlk};
   float* rw = srw + ((size_t)ql * UL + urel) * d.cap;
   int* lst = reinterpret_cast<int*>(val);
   if (n <= 8 * kSeedThreads) {
-    seed_rewards_regs<8>(d, base, n, last_new, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+    seed_rewards_regs<8>(d, base, n, last_new, rw, lst, d.cap, rb, phase, sh, tid);
   } else if (n <= 16 * kSeedThreads) {
-    seed_rewards_regs<16>(d, base, n, last_new, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+    seed_rewards_regs<16>(d, base, n, last_new, rw, lst, d.cap, rb, phase, sh, tid);
   } else if (n <= 32 * kSeedThreads) {
-    seed_rewards_regs<32>(d, base, n, last_new, lv, sM, sInv, rw, lst, d.cap, rb, phase, sh, tid);
+    seed_rewards_regs<32>(d, base, n, last_new, rw, lst, d.cap, rb, phase, sh, tid);
   } else {
-    mean_weights<kSeedThreads>(d, lv, n, sM, sInv, val, tid);
+    for (int i = tid; i < n; i += kSeedThreads) val[i] = rw[i];
+    __syncthreads();
     const HitRule rule = top_p_lds<ValLinear, kSeedThreads>(d, base, n, ValLinear{val}, rb, phase, tid);
-    const bool topp = d.reward_mode == 0;
     for (int i = tid; i < n; i += kSeedThreads) {
-      const float w = val[i];
-      const int pe = (topp && !rule.ties_all) ? d.pos[base + i] : 0;
-      const bool hit = rule(__float_as_uint(w), pe) | ((i == n - 1) & last_new);
-      rw[i] = topp ? (hit ? 1.0f : 0.0f) : w;
+      const int pe = !rule.ties_all ? d.pos[base + i] : 0;
+      const bool hit = rule(__float_as_uint(val[i]), pe) | ((i == n - 1) & last_new);
+      rw[i] = hit ? 1.0f : 0.0f;
     }
   }
 }
